@@ -1,0 +1,192 @@
+"""ctypes front end of the fp64 CPU oracle (earn_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg; never by the product package.  Arrays in and out are numpy fp64 / int32.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "earn_oracle.c")
+_LIB = os.path.join(_HERE, "libearn_oracle.so")
+_lib = None
+
+c_dp = ctypes.POINTER(ctypes.c_double)
+c_ip = ctypes.POINTER(ctypes.c_int32)
+c_bp = ctypes.POINTER(ctypes.c_uint8)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP). Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.oracle_cache_entries.restype = ctypes.c_int64
+        L.oracle_cache_entries.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
+                                           ctypes.c_int64]
+        L.oracle_gamma_cache.restype = ctypes.c_double
+        L.oracle_gamma_cache.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_double]
+        L.oracle_flops_layer.restype = ctypes.c_double
+        L.oracle_flops_layer.argtypes = [ctypes.c_double] * 5
+        L.oracle_gamma_attn.restype = ctypes.c_double
+        L.oracle_gamma_attn.argtypes = [ctypes.c_int32, ctypes.c_int32] + [ctypes.c_double] * 6
+        L.oracle_causal_attn_flops.restype = ctypes.c_double
+        L.oracle_causal_attn_flops.argtypes = [c_ip, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        _lib = L
+    return _lib
+
+
+def _d(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(c_dp)
+
+
+def _i(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(c_ip)
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def _i32(a) -> Optional[np.ndarray]:
+    return None if a is None else np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"{what}: oracle returned {rc}")
+
+
+def rope(x, pos, base: float = 10000.0) -> np.ndarray:
+    """Rotate x [rows, heads, d] at integer positions pos [rows]."""
+    x = _f64(x)
+    pos = _i32(pos)
+    rows, heads, d = x.shape
+    y = np.empty_like(x)
+    _check(lib().oracle_rope(_d(x), _i(pos), ctypes.c_int64(rows), heads, d, ctypes.c_double(base), _d(y)), "rope")
+    return y
+
+
+def prefill_attn(q, k, v, cu_seqlens, positions=None, q_to_kv: Optional[Sequence[int]] = None, scale: float = 0.0,
+                 rope_base: float = 10000.0, row_sel=None, want_probs: Optional[tuple] = None) -> dict:
+    """Causal attention over a packed ragged batch.
+
+    Returns dict(out [T,Hq,d], k_rot [T,Hkv,d], lse [T,Hq], rowsum [T,Hq], probs [n,n] if want_probs=(seq, head)).
+    Rows not selected by row_sel hold NaN in out/lse/rowsum.
+    """
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    cu = _i32(cu_seqlens)
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    assert k.shape == (T, hkv, d) and v.shape == (T, hkv, d) and cu[-1] == T
+    batch = len(cu) - 1
+    pos = _i32(positions)
+    mp = _i32(q_to_kv)
+    sel = None if row_sel is None else np.ascontiguousarray(np.asarray(row_sel, dtype=np.uint8))
+    out = np.full((T, hq, d), np.nan)
+    k_rot = np.empty((T, hkv, d))
+    lse = np.full((T, hq), np.nan)
+    rowsum = np.full((T, hq), np.nan)
+    probs = None
+    ps, ph = (-1, -1)
+    if want_probs is not None:
+        ps, ph = want_probs
+        n = int(cu[ps + 1] - cu[ps])
+        probs = np.zeros((n, n))
+    rc = lib().oracle_prefill_attn(_d(q), _d(k), _d(v), _i(cu), _i(pos), batch, hq, hkv, d, _i(mp),
+                                   ctypes.c_double(scale), ctypes.c_double(rope_base),
+                                   None if sel is None else sel.ctypes.data_as(c_bp), _d(out), _d(k_rot), _d(lse),
+                                   _d(rowsum), _d(probs), ps, ph)
+    _check(rc, "prefill_attn")
+    res = {"out": out, "k_rot": k_rot, "lse": lse, "rowsum": rowsum}
+    if probs is not None:
+        res["probs"] = probs
+    return res
+
+
+def compact_registers(src: Optional[np.ndarray], cu_seqlens, n_head_reg: int, n_tail_reg: int) -> dict:
+    """Gather the register rows of a packed [T, ...] array (any dtype, bytes are copied).
+
+    Returns dict(dst, idx [B*r], pos [B*r], cu [B+1]); dst is None when src is None.
+    """
+    cu = _i32(cu_seqlens)
+    batch = len(cu) - 1
+    r = n_head_reg + n_tail_reg
+    idx = np.empty(max(batch * r, 1), dtype=np.int32)
+    pos = np.empty(max(batch * r, 1), dtype=np.int32)
+    cu_out = np.empty(batch + 1, dtype=np.int32)
+    dst = None
+    sp = dp = None
+    row_bytes = 0
+    if src is not None:
+        src = np.ascontiguousarray(src)
+        assert src.shape[0] == cu[-1]
+        row_bytes = src.nbytes // max(src.shape[0], 1)
+        dst = np.empty((batch * r,) + src.shape[1:], dtype=src.dtype)
+        sp = src.ctypes.data_as(c_bp)
+        dp = dst.ctypes.data_as(c_bp)
+    rc = lib().oracle_compact_registers(sp, ctypes.c_int64(row_bytes), _i(cu), batch, n_head_reg, n_tail_reg, dp,
+                                        _i(idx), _i(pos), _i(cu_out))
+    _check(rc, "compact_registers")
+    return {"dst": dst, "idx": idx[: batch * r], "pos": pos[: batch * r], "cu": cu_out}
+
+
+def decode_attn(q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k: np.ndarray,
+                gen_v: np.ndarray, gen_len, q_to_kv=None, scale: float = 0.0, rope_base: float = 10000.0) -> dict:
+    """One decode step; gen_k/gen_v [S,gen_cap,Hkv,d] fp64 are updated in place (slot gen_len[u])."""
+    q, k_new, v_new = _f64(q), _f64(k_new), _f64(v_new)
+    shared_k, shared_v = _f64(shared_k), _f64(shared_v)
+    S, hq, d = q.shape
+    hkv = k_new.shape[1]
+    assert gen_k.dtype == np.float64 and gen_v.dtype == np.float64
+    assert gen_k.flags.c_contiguous and gen_v.flags.c_contiguous
+    gen_cap = gen_k.shape[1]
+    assert gen_k.shape == (S, gen_cap, hkv, d) and gen_v.shape == gen_k.shape
+    cu = _i32(shared_cu)
+    batch = len(cu) - 1
+    assert shared_k.shape[0] == cu[-1]
+    out = np.empty((S, hq, d))
+    lse = np.empty((S, hq))
+    rowsum = np.empty((S, hq))
+    rc = lib().oracle_decode_attn(_d(q), _d(k_new), _d(v_new), _i(_i32(q_pos)), _d(shared_k), _d(shared_v), _i(cu),
+                                  _i(_i32(stream_to_seq)), _d(gen_k), _d(gen_v), _i(_i32(gen_len)), gen_cap, S, batch,
+                                  hq, hkv, d, _i(_i32(q_to_kv)), ctypes.c_double(scale), ctypes.c_double(rope_base),
+                                  _d(out), _d(lse), _d(rowsum))
+    _check(rc, "decode_attn")
+    return {"out": out, "lse": lse, "rowsum": rowsum}
+
+
+def cache_entries(n_layers: int, split_k: int, n: int, r: int, gen: int = 0) -> int:
+    return int(lib().oracle_cache_entries(n_layers, split_k, n, r, gen))
+
+
+def gamma_cache(n_layers: int, split_k: int, L: float, r: float) -> float:
+    return float(lib().oracle_gamma_cache(n_layers, split_k, L, r))
+
+
+def flops_layer(L: float, n_h: float, d_a: float, d_h: float, d_f: float) -> float:
+    return float(lib().oracle_flops_layer(L, n_h, d_a, d_h, d_f))
+
+
+def gamma_attn(n_layers: int, split_k: int, L: float, r: float, n_h: float, d_a: float, d_h: float,
+               d_f: float) -> float:
+    return float(lib().oracle_gamma_attn(n_layers, split_k, L, r, n_h, d_a, d_h, d_f))
+
+
+def causal_attn_flops(lengths, hq: int, d: int) -> float:
+    ln = _i32(lengths)
+    return float(lib().oracle_causal_attn_flops(_i(ln), len(ln), hq, d))
