@@ -1,0 +1,168 @@
+/*
+ * libearn — the attention hot path of EARN's register-token inference scheme on one MI355X (gfx950).
+ *
+ * EARN places register tokens at the head and tail of every prompt, runs the first k layers over the whole
+ * sequence, gathers the register rows at the input of layer k, and from then on (later layers of the prefill and
+ * every decode step) attends over registers plus generated tokens only (paper Section 3.2, "Inference").
+ *
+ * Conventions for every entry point
+ *   - plain C ABI; every pointer is DEVICE memory owned by the caller unless marked "host";
+ *   - the library owns no memory, never allocates and never synchronises: a call validates its scalar arguments
+ *     on the host, enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the null stream) and returns;
+ *   - tensors are row-major, packed ragged over the batch: [tokens, heads, head_dim], element type bf16 or fp32
+ *     (earn_attn_desc.dtype); softmax statistics and accumulators are fp32; lengths and indices are int32;
+ *   - scalars the host needs for grid sizing (batch, total_tokens, max_seqlen, ...) are passed by value so that no
+ *     device-to-host read is needed.  Conditions that live in device memory (monotone cu_seqlens, n_s >= h+t,
+ *     gen_len < gen_cap, positions >= 0) are PRECONDITIONS; kernels clamp their loops to the sizes passed by value so
+ *     that a violated precondition gives wrong values, not an out-of-bounds access beyond the stated extents;
+ *   - return value: EARN_OK or a negative error code; earn_last_error() returns a thread-local message.
+ *
+ * The split layer k and the layer count N are not kernel arguments: the caller expresses them by which cache and
+ * which cu_seqlens it hands to which call (first k layers: the full-length tensors; remaining N-k layers: the
+ * compacted ones).
+ */
+#ifndef EARN_H
+#define EARN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EARN_OK 0
+#define EARN_ERR_INVALID_ARG (-1)
+#define EARN_ERR_UNSUPPORTED (-2)
+#define EARN_ERR_WORKSPACE_TOO_SMALL (-3)
+#define EARN_ERR_HIP (-4)
+
+#define EARN_F32 0
+#define EARN_BF16 1
+
+/* Largest number of tensors one earn_compact_registers call gathers. */
+#define EARN_MAX_COMPACT_TENSORS 112
+
+/* Attention description shared by prefill and decode (host struct, read during the call only). */
+typedef struct {
+  int32_t dtype;          /* EARN_F32 | EARN_BF16: element type of q, k, v, out and the caches */
+  int32_t n_q_heads;      /* Hq */
+  int32_t n_kv_heads;     /* Hkv; Hq % Hkv == 0; query head a reads kv head a / (Hq/Hkv) (grouped-query attention) */
+  int32_t head_dim;       /* d: 64 or 128 */
+  float softmax_scale;    /* <= 0 means 1/sqrt(head_dim) (Eq. 3) */
+  float rope_base;        /* rotary base (10000); <= 0 disables the rotation */
+} earn_attn_desc;
+
+/* Message of the last error on the calling thread ("" if none). Never NULL. */
+const char* earn_last_error(void);
+
+/* Library version string and the GPU architecture the kernels were built for. */
+const char* earn_version(void);
+
+/*
+ * Causal prefill attention over a packed ragged batch (paper Section 2.2, Eq. 3; used for the "full computation"
+ * layers 0..k-1 on all tokens and, with compacted inputs and explicit positions, for the "register-focused" layers
+ * k..N-1 — Section 3.2, Inference).
+ *
+ * For each sequence s (tokens cu_seqlens[s] .. cu_seqlens[s+1]-1), query head a and its kv head c:
+ *   q'_i = RoPE(q_i, p_i), k'_j = RoPE(k_j, p_j)   rotary embedding on half-split pairs (e, e + d/2),
+ *                                                   theta_e = rope_base^(-2e/d), p = the token's ORIGINAL position
+ *   out_i = sum_{j <= i} softmax_j(q'_i . k'_j * scale) v_j
+ *
+ *   q              [total_tokens, Hq, d]
+ *   k, v           [total_tokens, Hkv, d]
+ *   cu_seqlens     [batch+1] int32, cu_seqlens[0] = 0, non-decreasing, cu_seqlens[batch] = total_tokens
+ *   positions      [total_tokens] int32 or NULL; NULL means p_i = i - cu_seqlens[s]. Compacted layers pass the
+ *                  pos_out of earn_compact_registers so that suffix registers keep position h + L_s + j.
+ *   max_seqlen     upper bound on any sequence length (grid sizing)
+ *   out            [total_tokens, Hq, d]
+ *   k_rot_out      [total_tokens, Hkv, d] or NULL: receives k' (this is what the layer's KV cache stores)
+ *   lse_out        [total_tokens, Hq] fp32 or NULL: natural-log-sum-exp of each softmax row
+ *   workspace      at least earn_prefill_workspace_bytes(...) bytes, 256-byte aligned; may be NULL when that is 0
+ *
+ * Errors: NULL required pointer, batch <= 0, total_tokens < 0, max_seqlen <= 0, Hq % Hkv != 0 -> INVALID_ARG;
+ * head_dim not in {64,128} or unknown dtype -> UNSUPPORTED; workspace_bytes too small -> WORKSPACE_TOO_SMALL.
+ * total_tokens == 0 is a no-op.
+ */
+int earn_prefill_attn(const earn_attn_desc* desc, const void* q, const void* k, const void* v,
+                      const int32_t* cu_seqlens, const int32_t* positions, int32_t batch, int32_t total_tokens,
+                      int32_t max_seqlen, void* out, void* k_rot_out, float* lse_out, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/* Workspace earn_prefill_attn needs (bytes); depends on whether k_rot_out is supplied. 0 on invalid desc. */
+size_t earn_prefill_workspace_bytes(const earn_attn_desc* desc, int32_t batch, int32_t total_tokens,
+                                    int32_t max_seqlen, int32_t have_k_rot_out);
+
+/*
+ * Register compaction at the input of layer k (paper Section 3.2, Inference item 2, prefilling bullet:
+ * X = [X_prefix; X_prompt; X_suffix] -> X' = [X_prefix; X_suffix]).
+ *
+ * For every sequence keeps rows [0, h) and [n_s - t, n_s) in order; row m of the result (m in [0, batch*(h+t)))
+ * comes from source row idx = cu_seqlens[s] + p with s = m / r, j = m % r, p = j < h ? j : n_s - t + (j - h).
+ * The gather is a pure byte copy (bit-exact), applied to n_tensors tensors that share the packed row index
+ * (the hidden state, or K/V of the layers that follow) in one launch.
+ *
+ *   src, dst       HOST arrays of n_tensors device pointers; src[i] is [total_tokens, row_bytes[i]] bytes,
+ *                  dst[i] is [batch*(h+t), row_bytes[i]] bytes; 16-byte aligned; n_tensors may be 0 (indices only)
+ *   row_bytes      HOST array, each a positive multiple of 16
+ *   cu_seqlens     [batch+1] int32 (device)
+ *   idx_out        [batch*(h+t)] int32 or NULL: source row of every kept row
+ *   pos_out        [batch*(h+t)] int32 or NULL: original position p of every kept row
+ *   cu_out         [batch+1] int32 or NULL: cu_out[s] = s*(h+t)
+ *
+ * Precondition (device data): n_s >= h + t for every s.  n_s == h + t is the identity permutation.
+ * Errors: batch <= 0, h < 0, t < 0, h + t == 0, n_tensors < 0 or > EARN_MAX_COMPACT_TENSORS, NULL src/dst/row_bytes
+ * with n_tensors > 0, a NULL or misaligned tensor pointer, row_bytes not a positive multiple of 16 -> INVALID_ARG.
+ */
+int earn_compact_registers(int32_t n_tensors, const void* const* src, void* const* dst, const int64_t* row_bytes,
+                           const int32_t* cu_seqlens, int32_t batch, int32_t n_head_reg, int32_t n_tail_reg,
+                           int32_t* idx_out, int32_t* pos_out, int32_t* cu_out, void* stream);
+
+/*
+ * One decode step of attention (paper Section 2.2, Eq. 4: append K_t, V_t to the cache, then Q_t K_{1:t}^T;
+ * Section 3.2, Inference, decoding bullet: layers >= k see [prefix; suffix; generated] only).
+ *
+ * There are n_streams decode streams (beams); stream u belongs to sequence s = stream_to_seq[u] and shares that
+ * sequence's prefill cache rows shared_cu[s] .. shared_cu[s+1]-1 with the other beams of s.  For each stream:
+ *   q' = RoPE(q_u, q_pos[u]);  k' = RoPE(k_new_u, q_pos[u]);
+ *   gen_k[u, gen_len[u]] = k';  gen_v[u, gen_len[u]] = v_new_u            (cache append)
+ *   out_u = softmax over { shared rows of s } ++ { gen rows 0 .. gen_len[u] } of (q' . key * scale), times values.
+ * No mask: every key is in the past.  The same call serves layers < k (shared_* = the full-length cache of the
+ * layer) and layers >= k (shared_* = the compacted register cache).
+ *
+ *   q                  [n_streams, Hq, d]
+ *   k_new, v_new       [n_streams, Hkv, d], k_new NOT yet rotated
+ *   q_pos              [n_streams] int32: original position of the new token (n_s + step)
+ *   shared_k, shared_v [shared_total, Hkv, d]; shared_k already rotated (k_rot_out of the prefill)
+ *   shared_cu          [batch+1] int32
+ *   stream_to_seq      [n_streams] int32 or NULL (= identity, requires n_streams == batch)
+ *   gen_k, gen_v       [n_streams, gen_cap, Hkv, d]; slot gen_len[u] of stream u is written by this call
+ *   gen_len            [n_streams] int32, 0 <= gen_len[u] < gen_cap
+ *   max_shared_len     upper bound on shared_cu[s+1] - shared_cu[s]
+ *   out                [n_streams, Hq, d]
+ *   workspace          at least earn_decode_workspace_bytes(...) bytes, 256-byte aligned
+ *
+ * Errors: as for earn_prefill_attn, plus gen_cap <= 0, n_streams <= 0, stream_to_seq == NULL with
+ * n_streams != batch, max_shared_len < 0 -> INVALID_ARG.
+ */
+int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
+                     const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
+                     const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int32_t gen_cap,
+                     int32_t n_streams, int32_t batch, int32_t max_shared_len, void* out, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
+/* Workspace earn_decode_attn needs (bytes) for split-key partial results. 0 on invalid desc. */
+size_t earn_decode_workspace_bytes(const earn_attn_desc* desc, int32_t n_streams, int32_t batch,
+                                   int32_t max_shared_len, int32_t gen_cap);
+
+/*
+ * KV-cache entries per attention head one sequence holds under EARN (paper Section 3.3, "KV Cache Size":
+ * N_KV = n_h (k L + (N-k) r), here per head and with L = the length the first k layers see, plus `gen`
+ * generated tokens kept by every layer).  Used for allocation and as an invariant.
+ */
+int64_t earn_cache_entries(int32_t n_layers, int32_t split_k, int64_t seq_len, int32_t n_registers, int64_t gen);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EARN_H */

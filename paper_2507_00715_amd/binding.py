@@ -1,0 +1,141 @@
+"""Thin ctypes binding over libearn.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs in the HIP kernels; torch is used for device memory and the current stream.
+There is no CPU fallback: if the library is missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libearn.so")
+_lib = None
+
+EARN_OK = 0
+EARN_ERR_INVALID_ARG = -1
+EARN_ERR_UNSUPPORTED = -2
+EARN_ERR_WORKSPACE_TOO_SMALL = -3
+EARN_ERR_HIP = -4
+EARN_F32, EARN_BF16 = 0, 1
+EARN_MAX_COMPACT_TENSORS = 112
+
+EXPORTS = ["earn_last_error", "earn_version", "earn_prefill_attn", "earn_prefill_workspace_bytes",
+           "earn_compact_registers", "earn_decode_attn", "earn_decode_workspace_bytes", "earn_cache_entries"]
+
+
+class EarnError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libearn error {code}: {msg}")
+        self.code = code
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("rope_base", ctypes.c_float)]
+
+
+def lib():
+    """Load libearn.so (built in-tree by build.py / __graft_entry__.build()). Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2507_00715_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        L.earn_last_error.restype = ctypes.c_char_p
+        L.earn_version.restype = ctypes.c_char_p
+        L.earn_prefill_attn.restype = ctypes.c_int
+        L.earn_prefill_attn.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.earn_prefill_workspace_bytes.restype = sz
+        L.earn_prefill_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), i32, i32, i32, i32]
+        L.earn_compact_registers.restype = ctypes.c_int
+        L.earn_compact_registers.argtypes = [i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                             ctypes.POINTER(ctypes.c_int64), vp, i32, i32, i32, vp, vp, vp, vp]
+        L.earn_decode_attn.restype = ctypes.c_int
+        L.earn_decode_attn.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
+                                       i32, i32, vp, vp, sz, vp]
+        L.earn_decode_workspace_bytes.restype = sz
+        L.earn_decode_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), i32, i32, i32, i32]
+        L.earn_cache_entries.restype = ctypes.c_int64
+        L.earn_cache_entries.argtypes = [i32, i32, ctypes.c_int64, i32, ctypes.c_int64]
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().earn_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != EARN_OK:
+        raise EarnError(rc, last_error())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "libearn takes contiguous device tensors"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_desc(dtype: torch.dtype, n_q_heads: int, n_kv_heads: int, head_dim: int, softmax_scale: float = 0.0,
+              rope_base: float = 10000.0) -> AttnDesc:
+    code = {torch.float32: EARN_F32, torch.bfloat16: EARN_BF16}.get(dtype, 99)
+    return AttnDesc(code, n_q_heads, n_kv_heads, head_dim, softmax_scale, rope_base)
+
+
+def earn_prefill_workspace_bytes(desc: AttnDesc, batch: int, total_tokens: int, max_seqlen: int,
+                                 have_k_rot_out: bool) -> int:
+    return int(lib().earn_prefill_workspace_bytes(ctypes.byref(desc), batch, total_tokens, max_seqlen,
+                                                  int(have_k_rot_out)))
+
+
+def earn_prefill_attn(desc: AttnDesc, q, k, v, cu_seqlens, positions, batch: int, total_tokens: int, max_seqlen: int,
+                      out, k_rot_out=None, lse_out=None, workspace=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().earn_prefill_attn(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens), _ptr(positions),
+                                   batch, total_tokens, max_seqlen, _ptr(out), _ptr(k_rot_out), _ptr(lse_out),
+                                   _ptr(workspace), ws_bytes, _stream()))
+
+
+def earn_compact_registers(src: Sequence[torch.Tensor], dst: Sequence[torch.Tensor], cu_seqlens, batch: int,
+                           n_head_reg: int, n_tail_reg: int, idx_out=None, pos_out=None, cu_out=None,
+                           row_bytes: Optional[Sequence[int]] = None) -> None:
+    n = len(src)
+    assert len(dst) == n
+    vp = ctypes.c_void_p
+    src_arr = (vp * max(n, 1))(*[t.data_ptr() for t in src])
+    dst_arr = (vp * max(n, 1))(*[t.data_ptr() for t in dst])
+    if row_bytes is None:
+        row_bytes = [t[0].numel() * t.element_size() if t.shape[0] > 0 else 16 for t in src]
+    rb_arr = (ctypes.c_int64 * max(n, 1))(*row_bytes)
+    for t in list(src) + list(dst):
+        assert t.is_cuda and t.is_contiguous()
+    _check(lib().earn_compact_registers(n, src_arr, dst_arr, rb_arr, _ptr(cu_seqlens), batch, n_head_reg, n_tail_reg,
+                                        _ptr(idx_out), _ptr(pos_out), _ptr(cu_out), _stream()))
+
+
+def earn_decode_workspace_bytes(desc: AttnDesc, n_streams: int, batch: int, max_shared_len: int, gen_cap: int) -> int:
+    return int(lib().earn_decode_workspace_bytes(ctypes.byref(desc), n_streams, batch, max_shared_len, gen_cap))
+
+
+def earn_decode_attn(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k,
+                     gen_v, gen_len, gen_cap: int, n_streams: int, batch: int, max_shared_len: int, out,
+                     workspace=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().earn_decode_attn(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos), _ptr(shared_k),
+                                  _ptr(shared_v), _ptr(shared_cu), _ptr(stream_to_seq), _ptr(gen_k), _ptr(gen_v),
+                                  _ptr(gen_len), gen_cap, n_streams, batch, max_shared_len, _ptr(out),
+                                  _ptr(workspace), ws_bytes, _stream()))
+
+
+def earn_cache_entries(n_layers: int, split_k: int, seq_len: int, n_registers: int, gen: int = 0) -> int:
+    return int(lib().earn_cache_entries(n_layers, split_k, seq_len, n_registers, gen))

@@ -1,0 +1,158 @@
+// C ABI of libearn: argument validation on the host, then kernel launches on the caller's stream.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace earn {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+RopeTable make_rope_table(float base, int head_dim) {
+  RopeTable t;
+  memset(&t, 0, sizeof(t));
+  t.enabled = base > 0.f ? 1 : 0;
+  if (!t.enabled) return t;
+  const double two_pi = 6.283185307179586476925286766559;
+  for (int e = 0; e < head_dim / 2 && e < kMaxHalfDim; ++e) {
+    double turns = pow((double)base, -2.0 * (double)e / (double)head_dim) / two_pi;
+    float hi = (float)turns;
+    t.hi[e] = hi;
+    t.lo[e] = (float)(turns - (double)hi);
+  }
+  return t;
+}
+
+int launch_compact(int n_tensors, const void* const* src, void* const* dst, const int64_t* row_bytes,
+                   const int32_t* cu_seqlens, int batch, int h, int t, int32_t* idx_out, int32_t* pos_out,
+                   int32_t* cu_out, hipStream_t stream);
+int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                   const int32_t* positions, int batch, int total_tokens, int max_seqlen, void* out, void* k_rot_out,
+                   float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t stream);
+size_t prefill_workspace_bytes(const earn_attn_desc* desc, int total_tokens, int have_k_rot_out);
+int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
+                  const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
+                  const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
+                  int n_streams, int batch, int max_shared_len, void* out, void* workspace, size_t workspace_bytes,
+                  hipStream_t stream);
+size_t decode_workspace_bytes(int hq, int hkv, int d, int n_streams, int max_total_len);
+
+static int check_desc(const earn_attn_desc* d, const char* who) {
+  if (!d) { set_error("%s: desc is NULL", who); return EARN_ERR_INVALID_ARG; }
+  if (d->dtype != EARN_F32 && d->dtype != EARN_BF16) { set_error("%s: unknown dtype %d", who, d->dtype); return EARN_ERR_UNSUPPORTED; }
+  if (d->n_q_heads <= 0 || d->n_kv_heads <= 0) { set_error("%s: head counts must be positive", who); return EARN_ERR_INVALID_ARG; }
+  if (d->n_q_heads % d->n_kv_heads != 0) {
+    set_error("%s: n_q_heads (%d) is not a multiple of n_kv_heads (%d)", who, d->n_q_heads, d->n_kv_heads);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (d->head_dim != 64 && d->head_dim != 128) { set_error("%s: head_dim %d not in {64,128}", who, d->head_dim); return EARN_ERR_UNSUPPORTED; }
+  return EARN_OK;
+}
+
+}  // namespace earn
+
+using namespace earn;
+
+extern "C" {
+
+const char* earn_last_error(void) { return g_err; }
+
+const char* earn_version(void) { return "libearn 0.1 (gfx950)"; }
+
+size_t earn_prefill_workspace_bytes(const earn_attn_desc* desc, int32_t batch, int32_t total_tokens,
+                                    int32_t max_seqlen, int32_t have_k_rot_out) {
+  (void)batch; (void)max_seqlen;
+  if (check_desc(desc, "earn_prefill_workspace_bytes") != EARN_OK || total_tokens < 0) return 0;
+  return prefill_workspace_bytes(desc, total_tokens, have_k_rot_out);
+}
+
+int earn_prefill_attn(const earn_attn_desc* desc, const void* q, const void* k, const void* v,
+                      const int32_t* cu_seqlens, const int32_t* positions, int32_t batch, int32_t total_tokens,
+                      int32_t max_seqlen, void* out, void* k_rot_out, float* lse_out, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  int rc = check_desc(desc, "earn_prefill_attn");
+  if (rc != EARN_OK) return rc;
+  if (batch <= 0 || total_tokens < 0 || max_seqlen <= 0) {
+    set_error("earn_prefill_attn: batch (%d) and max_seqlen (%d) must be positive, total_tokens (%d) non-negative", batch, max_seqlen, total_tokens);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (!cu_seqlens) { set_error("earn_prefill_attn: cu_seqlens is NULL"); return EARN_ERR_INVALID_ARG; }
+  if (total_tokens == 0) return EARN_OK;
+  if (!q || !k || !v || !out) { set_error("earn_prefill_attn: q, k, v and out must not be NULL"); return EARN_ERR_INVALID_ARG; }
+  if (max_seqlen > total_tokens) max_seqlen = total_tokens;
+  return launch_prefill(desc, q, k, v, cu_seqlens, positions, batch, total_tokens, max_seqlen, out, k_rot_out, lse_out,
+                        workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int earn_compact_registers(int32_t n_tensors, const void* const* src, void* const* dst, const int64_t* row_bytes,
+                           const int32_t* cu_seqlens, int32_t batch, int32_t n_head_reg, int32_t n_tail_reg,
+                           int32_t* idx_out, int32_t* pos_out, int32_t* cu_out, void* stream) {
+  g_err[0] = 0;
+  if (batch <= 0) { set_error("earn_compact_registers: batch must be positive"); return EARN_ERR_INVALID_ARG; }
+  if (n_head_reg < 0 || n_tail_reg < 0 || n_head_reg + n_tail_reg == 0) {
+    set_error("earn_compact_registers: register counts must be non-negative and not both zero (h=%d, t=%d)", n_head_reg, n_tail_reg);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (n_tensors < 0 || n_tensors > EARN_MAX_COMPACT_TENSORS) {
+    set_error("earn_compact_registers: n_tensors %d outside [0, %d]", n_tensors, EARN_MAX_COMPACT_TENSORS);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (!cu_seqlens) { set_error("earn_compact_registers: cu_seqlens is NULL"); return EARN_ERR_INVALID_ARG; }
+  if ((long long)batch * (n_head_reg + n_tail_reg) > 0x7fffffffLL) { set_error("earn_compact_registers: too many rows"); return EARN_ERR_INVALID_ARG; }
+  if (n_tensors > 0 && (!src || !dst || !row_bytes)) { set_error("earn_compact_registers: src, dst and row_bytes must not be NULL"); return EARN_ERR_INVALID_ARG; }
+  for (int i = 0; i < n_tensors; ++i) {
+    if (!src[i] || !dst[i]) { set_error("earn_compact_registers: tensor %d has a NULL pointer", i); return EARN_ERR_INVALID_ARG; }
+    if (((uintptr_t)src[i] | (uintptr_t)dst[i]) & 15) { set_error("earn_compact_registers: tensor %d is not 16-byte aligned", i); return EARN_ERR_INVALID_ARG; }
+    if (row_bytes[i] <= 0 || row_bytes[i] % 16 != 0 || row_bytes[i] / 16 > 0x7fffffffLL) {
+      set_error("earn_compact_registers: row_bytes[%d] = %lld is not a positive multiple of 16", i, (long long)row_bytes[i]);
+      return EARN_ERR_INVALID_ARG;
+    }
+  }
+  return launch_compact(n_tensors, src, dst, row_bytes, cu_seqlens, batch, n_head_reg, n_tail_reg, idx_out, pos_out,
+                        cu_out, (hipStream_t)stream);
+}
+
+size_t earn_decode_workspace_bytes(const earn_attn_desc* desc, int32_t n_streams, int32_t batch,
+                                   int32_t max_shared_len, int32_t gen_cap) {
+  (void)batch;
+  if (check_desc(desc, "earn_decode_workspace_bytes") != EARN_OK || n_streams <= 0 || max_shared_len < 0 || gen_cap <= 0) return 0;
+  return decode_workspace_bytes(desc->n_q_heads, desc->n_kv_heads, desc->head_dim, n_streams, max_shared_len + gen_cap);
+}
+
+int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
+                     const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
+                     const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int32_t gen_cap,
+                     int32_t n_streams, int32_t batch, int32_t max_shared_len, void* out, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  int rc = check_desc(desc, "earn_decode_attn");
+  if (rc != EARN_OK) return rc;
+  if (n_streams <= 0 || batch <= 0 || gen_cap <= 0 || max_shared_len < 0) {
+    set_error("earn_decode_attn: n_streams (%d), batch (%d), gen_cap (%d) must be positive and max_shared_len (%d) non-negative", n_streams, batch, gen_cap, max_shared_len);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (!q || !k_new || !v_new || !q_pos || !shared_cu || !gen_k || !gen_v || !gen_len || !out) {
+    set_error("earn_decode_attn: a required pointer is NULL");
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (max_shared_len > 0 && (!shared_k || !shared_v)) { set_error("earn_decode_attn: shared_k/shared_v are NULL but max_shared_len > 0"); return EARN_ERR_INVALID_ARG; }
+  if (!stream_to_seq && n_streams != batch) { set_error("earn_decode_attn: stream_to_seq is NULL but n_streams (%d) != batch (%d)", n_streams, batch); return EARN_ERR_INVALID_ARG; }
+  return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
+                       gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int64_t earn_cache_entries(int32_t n_layers, int32_t split_k, int64_t seq_len, int32_t n_registers, int64_t gen) {
+  return (int64_t)split_k * seq_len + (int64_t)(n_layers - split_k) * n_registers + (int64_t)n_layers * gen;
+}
+
+}  // extern "C"

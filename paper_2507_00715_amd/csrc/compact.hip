@@ -1,0 +1,95 @@
+// Register compaction: X = [X_prefix; X_prompt; X_suffix] -> X' = [X_prefix; X_suffix] at the input of layer k
+// (paper Section 3.2, Inference item 2).  A pure byte gather: HBM-bound, so the kernel is organised around the
+// OUTPUT, which is contiguous: every lane owns 16-byte units of the compacted tensor, a wave stores 1 KiB of
+// consecutive bytes per instruction, and the source of a unit is found with integer arithmetic only.  Source rows
+// of one register group (h head rows, t tail rows) are consecutive in memory as well, so loads coalesce too.
+#include "common.h"
+
+namespace earn {
+
+struct CompactArgs {
+  const u32x4* src[EARN_MAX_COMPACT_TENSORS];
+  u32x4* dst[EARN_MAX_COMPACT_TENSORS];
+  unsigned int units_per_row[EARN_MAX_COMPACT_TENSORS];  // row_bytes / 16
+};
+
+constexpr int kCompactThreads = 256;
+constexpr int kCompactUnroll = 4;  // 16-byte units per lane: 4 loads in flight before the first store
+
+// source row of compacted row m
+__device__ __forceinline__ int source_row(const int32_t* __restrict__ cu, int m, int r, int h, int t, int* pos) {
+  int s = m / r, j = m - s * r;
+  int b0 = cu[s], n = cu[s + 1] - b0;
+  int p = j < h ? j : n - t + (j - h);
+  *pos = p;
+  return b0 + p;
+}
+
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactArgs args, const int32_t* __restrict__ cu,
+                                                                  int batch, int h, int t, int rows_out,
+                                                                  int32_t* __restrict__ idx_out,
+                                                                  int32_t* __restrict__ pos_out,
+                                                                  int32_t* __restrict__ cu_out, int n_tensors) {
+  const int r = h + t;
+  const int tensor = blockIdx.y;
+  if (tensor == n_tensors) {  // the extra grid row writes the index outputs
+    for (int m = blockIdx.x * kCompactThreads + threadIdx.x; m < rows_out; m += gridDim.x * kCompactThreads) {
+      int pos;
+      int idx = source_row(cu, m, r, h, t, &pos);
+      if (idx_out) idx_out[m] = idx;
+      if (pos_out) pos_out[m] = pos;
+    }
+    if (cu_out)
+      for (int s = blockIdx.x * kCompactThreads + threadIdx.x; s <= batch; s += gridDim.x * kCompactThreads)
+        cu_out[s] = s * r;
+    return;
+  }
+  const u32x4* __restrict__ src = args.src[tensor];
+  u32x4* __restrict__ dst = args.dst[tensor];
+  const unsigned int upr = args.units_per_row[tensor];
+  const long long total_units = (long long)rows_out * upr;
+  const long long stride = (long long)gridDim.x * kCompactThreads * kCompactUnroll;
+  for (long long base = (long long)blockIdx.x * kCompactThreads * kCompactUnroll; base < total_units; base += stride) {
+    u32x4 v[kCompactUnroll];
+    long long u[kCompactUnroll];
+#pragma unroll
+    for (int i = 0; i < kCompactUnroll; ++i) {
+      u[i] = base + (long long)i * kCompactThreads + threadIdx.x;
+      if (u[i] < total_units) {
+        int m = (int)(u[i] / upr);
+        unsigned int off = (unsigned int)(u[i] - (long long)m * upr);
+        int pos;
+        long long row = source_row(cu, m, r, h, t, &pos);
+        v[i] = __builtin_nontemporal_load(src + row * upr + off);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kCompactUnroll; ++i)
+      if (u[i] < total_units) __builtin_nontemporal_store(v[i], dst + u[i]);
+  }
+}
+
+int launch_compact(int n_tensors, const void* const* src, void* const* dst, const int64_t* row_bytes,
+                   const int32_t* cu_seqlens, int batch, int h, int t, int32_t* idx_out, int32_t* pos_out,
+                   int32_t* cu_out, hipStream_t stream) {
+  CompactArgs args;
+  const long long rows_out = (long long)batch * (h + t);
+  long long max_units = 0;
+  for (int i = 0; i < n_tensors; ++i) {
+    args.src[i] = (const u32x4*)src[i];
+    args.dst[i] = (u32x4*)dst[i];
+    args.units_per_row[i] = (unsigned int)(row_bytes[i] / 16);
+    long long units = rows_out * (row_bytes[i] / 16);
+    if (units > max_units) max_units = units;
+  }
+  const long long per_block = (long long)kCompactThreads * kCompactUnroll;
+  long long gx = (max_units + per_block - 1) / per_block;
+  if (gx < 1) gx = 1;
+  if (gx > 8192) gx = 8192;  // grid-stride beyond this: 32 workgroups per CU
+  dim3 grid((unsigned)gx, (unsigned)(n_tensors + 1), 1);
+  hipLaunchKernelGGL(compact_kernel, grid, dim3(kCompactThreads), 0, stream, args, cu_seqlens, batch, h, t,
+                     (int)rows_out, idx_out, pos_out, cu_out, n_tensors);
+  return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
+}
+
+}  // namespace earn

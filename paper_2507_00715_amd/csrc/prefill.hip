@@ -1,0 +1,443 @@
+// Causal prefill attention over a packed ragged batch (paper Section 2.2, Eq. 3; used at full length for the first
+// k layers and on the compacted register rows, with their original positions, for the remaining N-k layers —
+// Section 3.2, Inference).
+//
+// Three kernels:
+//   rope_k_kernel        rotates K once per layer into the buffer the KV cache keeps (k_rot_out); every query block
+//                        then reads rotated keys, so the sin/cos work is O(T), not O(T * blocks).
+//   prefill_mfma_kernel  bf16 flash-style attention on the matrix cores (v_mfma_f32_32x32x16_bf16).
+//   prefill_rows_kernel  fp32 (or bf16) attention on the vector ALU: one query row per 4 lanes. Used for the fp32
+//                        configuration, where the 1e-4 tolerance rules out bf16 operands.
+//
+// MFMA kernel layout (all shapes in the 32x32x16 tile of the instruction, 64 lanes, lane = (r32 = lane%32, hf = lane/32)):
+//   The kernel computes the TRANSPOSED score tile S^T = K Q^T (keys x queries).  Its accumulator layout gives every lane
+//   ONE query column (r32) and 16 of the 32 keys of a block, so the softmax row statistics are a private loop plus one
+//   exchange with lane^32, and the rescaling of the output accumulator is lane-private as well.
+//   The accumulator registers of S^T, converted to bf16, are exactly the B operand (keys x queries, 8 keys per lane)
+//   of the second product O^T = V^T P^T, so P never leaves registers.  The 8 key slots of a lane are keys
+//   {4hf..4hf+3, 8+4hf..8+4hf+3} of a 16-key step; the A operand V^T uses the same key order, which is what two
+//   transposing LDS reads (ds_read_b64_tr_b16: 4 consecutive keys of one d column) deliver from a V tile kept in its
+//   natural [key][d] layout.
+//   A workgroup is 4 waves; each wave owns 64 query rows (2 column blocks), so every K/V fragment read from LDS feeds
+//   two MFMAs; the 64-key K/V tile in LDS is shared by the 4 waves (256 query rows per tile load).
+#include "common.h"
+
+namespace earn {
+
+struct PrefillParams {
+  const void* q; const void* k_rot; const void* v; const int32_t* cu; const int32_t* positions;
+  void* out; float* lse;
+  int batch, hq, hkv, max_seqlen;
+  float scale_log2;
+  RopeTable rope;
+};
+
+// ------------------------------------------------------------------------------------------------------------------
+// K rotation: one thread per (token, kv head, group of 8 rotary pairs)
+// ------------------------------------------------------------------------------------------------------------------
+template <typename T> struct Vec8;
+template <> struct Vec8<float> {
+  static __device__ __forceinline__ void load(const float* p, float* x) {
+    f32x4 a = *(const f32x4*)p, b = *(const f32x4*)(p + 4);
+    x[0] = a[0]; x[1] = a[1]; x[2] = a[2]; x[3] = a[3]; x[4] = b[0]; x[5] = b[1]; x[6] = b[2]; x[7] = b[3];
+  }
+  static __device__ __forceinline__ void store(float* p, const float* x) {
+    f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
+    *(f32x4*)p = a; *(f32x4*)(p + 4) = b;
+  }
+};
+template <> struct Vec8<__bf16> {
+  static __device__ __forceinline__ void load(const __bf16* p, float* x) {
+    u32x4 w = *(const u32x4*)p;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { x[2 * i] = bf16_lo(w[i]); x[2 * i + 1] = bf16_hi(w[i]); }
+  }
+  static __device__ __forceinline__ void store(__bf16* p, const float* x) {
+    u32x4 w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = pack_bf16(x[2 * i], x[2 * i + 1]);
+    *(u32x4*)p = w;
+  }
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T* __restrict__ k_rot,
+                                                     const int32_t* __restrict__ cu,
+                                                     const int32_t* __restrict__ positions, int batch, int total,
+                                                     int hkv, RopeTable rope) {
+  constexpr int G = D / 16;  // groups of 8 pairs per head
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (long long)total * hkv * G) return;
+  const int g = (int)(t % G);
+  const long long th = t / G;  // token * hkv + head
+  const int token = (int)(th / hkv);
+  int pos;
+  if (positions) pos = positions[token];
+  else pos = token - cu[find_seq(cu, batch, token)];
+  const T* src = k + th * D + g * 8;
+  T* dst = k_rot + th * D + g * 8;
+  float lo[8], hi[8];
+  Vec8<T>::load(src, lo);
+  Vec8<T>::load(src + D / 2, hi);
+  if (rope.enabled) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float s, c;
+      sincos_turns_precise(rope_turns((float)pos, rope.hi[g * 8 + i], rope.lo[g * 8 + i]), &s, &c);
+      float a = lo[i], b = hi[i];
+      lo[i] = a * c - b * s;
+      hi[i] = b * c + a * s;
+    }
+  }
+  Vec8<T>::store(dst, lo);
+  Vec8<T>::store(dst + D / 2, hi);
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// vector-ALU attention: 64 query rows per workgroup, 4 lanes per row (each holds D/4 elements of q and of the output)
+// ------------------------------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
+  constexpr int E = D / 8;  // elements per contiguous piece; a lane holds pieces [qt*E, +E) and [D/2 + qt*E, +E)
+  const int a = blockIdx.y, s = blockIdx.z;
+  const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
+  const int row0 = blockIdx.x * 64;
+  if (row0 >= n) return;
+  const int qt = threadIdx.x & 3;
+  const int i = row0 + (threadIdx.x >> 2);
+  const bool row_ok = i < n;
+  const int ic = row_ok ? i : n - 1;
+  const int c = a / (p.hq / p.hkv);
+  const T* qrow = (const T*)p.q + ((long long)(b0 + ic) * p.hq + a) * D;
+  float ql[E], qh[E];
+#pragma unroll
+  for (int e = 0; e < E; e += 8) { Vec8<T>::load(qrow + qt * E + e, ql + e); Vec8<T>::load(qrow + D / 2 + qt * E + e, qh + e); }
+  const int pos = p.positions ? p.positions[b0 + ic] : ic;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    float sn = 0.f, cs = 1.f;
+    if (p.rope.enabled) sincos_turns_precise(rope_turns((float)pos, p.rope.hi[qt * E + e], p.rope.lo[qt * E + e]), &sn, &cs);
+    float x = ql[e], y = qh[e];
+    ql[e] = (x * cs - y * sn) * p.scale_log2;
+    qh[e] = (y * cs + x * sn) * p.scale_log2;
+  }
+  float ol[E], oh[E], m = -INFINITY, l = 0.f;
+#pragma unroll
+  for (int e = 0; e < E; ++e) { ol[e] = 0.f; oh[e] = 0.f; }
+  // all rows of a wave walk the keys together up to the wave's last row
+  const int wave_last = min(n - 1, row0 + (int)(threadIdx.x / kWave) * 16 + 15);
+  const T* kbase = (const T*)p.k_rot + ((long long)b0 * p.hkv + c) * D;
+  const T* vbase = (const T*)p.v + ((long long)b0 * p.hkv + c) * D;
+  const long long rs = (long long)p.hkv * D;
+  for (int j = 0; j <= wave_last; ++j) {
+    float kl[E], kh[E], vl[E], vh[E];
+#pragma unroll
+    for (int e = 0; e < E; e += 8) {
+      Vec8<T>::load(kbase + j * rs + qt * E + e, kl + e);
+      Vec8<T>::load(kbase + j * rs + D / 2 + qt * E + e, kh + e);
+      Vec8<T>::load(vbase + j * rs + qt * E + e, vl + e);
+      Vec8<T>::load(vbase + j * rs + D / 2 + qt * E + e, vh + e);
+    }
+    float sc = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) sc = __builtin_fmaf(ql[e], kl[e], __builtin_fmaf(qh[e], kh[e], sc));
+    sc += __shfl_xor(sc, 1, kWave);
+    sc += __shfl_xor(sc, 2, kWave);
+    if (j <= ic) {  // causal: keys 0..i
+      float mn = fmaxf(m, sc);
+      float corr = __builtin_amdgcn_exp2f(m - mn);  // exp2(-inf) = 0 on the first key
+      float pr = __builtin_amdgcn_exp2f(sc - mn);
+      l = l * corr + pr;
+#pragma unroll
+      for (int e = 0; e < E; ++e) { ol[e] = __builtin_fmaf(pr, vl[e], ol[e] * corr); oh[e] = __builtin_fmaf(pr, vh[e], oh[e] * corr); }
+      m = mn;
+    }
+  }
+  if (!row_ok) return;
+  const float inv = 1.f / l;
+#pragma unroll
+  for (int e = 0; e < E; ++e) { ol[e] *= inv; oh[e] *= inv; }
+  T* orow = (T*)p.out + ((long long)(b0 + i) * p.hq + a) * D;
+#pragma unroll
+  for (int e = 0; e < E; e += 8) { Vec8<T>::store(orow + qt * E + e, ol + e); Vec8<T>::store(orow + D / 2 + qt * E + e, oh + e); }
+  if (p.lse && qt == 0) p.lse[(long long)(b0 + i) * p.hq + a] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// bf16 MFMA flash attention
+// ------------------------------------------------------------------------------------------------------------------
+constexpr int kPfThreads = 256;
+constexpr int kPfWaves = 4;
+constexpr int kWaveRows = 64;                     // query rows per wave (2 MFMA column blocks)
+constexpr int kBlockRows = kPfWaves * kWaveRows;  // 256 query rows per workgroup
+constexpr int kTileKeys = 64;                     // keys per K/V tile in LDS
+
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+
+template <int D>
+struct PfSmem {
+  static constexpr int KS = D + 8;    // K row stride (elements): 16-byte reads of 16 consecutive rows hit all banks
+  static constexpr int VS = D + 32;   // V row stride: the 4 rows of a transposing read land 64 bytes apart (mod 256)
+  __bf16 k[kTileKeys * KS];
+  __bf16 v[kTileKeys * VS];
+};
+
+template <int D>
+__global__ __launch_bounds__(kPfThreads, 1) void prefill_mfma_kernel(PrefillParams p) {
+  constexpr int KSTEPS = D / 16;         // MFMA k-steps over head_dim for S^T
+  constexpr int DB = D / 32;             // 32-row blocks of O^T
+  constexpr int UPR = D / 8;             // 16-byte units per K/V row
+  constexpr int UNITS = kTileKeys * UPR / kPfThreads;  // units per thread per tile (4 for d=128, 2 for d=64)
+  using Sm = PfSmem<D>;
+  __shared__ Sm sm;
+
+  const int a = blockIdx.x, s = blockIdx.y;
+  const int qblk = gridDim.z - 1 - blockIdx.z;  // long (late) query blocks are dispatched first
+  const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
+  const int q0 = qblk * kBlockRows;
+  if (q0 >= n) return;
+  const int c = a / (p.hq / p.hkv);
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int r32 = lane & 31, hf = lane >> 5;
+  const int qw = q0 + wave * kWaveRows;          // first query row of this wave
+  const bool wave_active = qw < n;
+  const int t_diag = qw / kTileKeys;             // last (diagonal) tile of this wave
+  const int n_tiles = (min(q0 + kBlockRows, n) + kTileKeys - 1) / kTileKeys;
+
+  const __bf16* Qg = (const __bf16*)p.q;
+  const __bf16* Kg = (const __bf16*)p.k_rot + ((long long)b0 * p.hkv + c) * D;
+  const __bf16* Vg = (const __bf16*)p.v + ((long long)b0 * p.hkv + c) * D;
+  const long long kv_stride = (long long)p.hkv * D;
+
+  // ---- Q fragments: rotate at the original position, fold in scale*log2(e), keep as bf16 B operands ----
+  bf16x8 qf[2][KSTEPS];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int qi = min(qw + 32 * qb + r32, n - 1);
+    const float pos = (float)(p.positions ? p.positions[b0 + qi] : qi);
+    const __bf16* qrow = Qg + ((long long)(b0 + qi) * p.hq + a) * D + 8 * hf;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS / 2; ++ks) {
+      float lo[8], hi[8];
+      Vec8<__bf16>::load(qrow + 16 * ks, lo);
+      Vec8<__bf16>::load(qrow + 16 * ks + D / 2, hi);
+      u32x4 wl, wh;
+#pragma unroll
+      for (int j = 0; j < 8; j += 2) {
+        float x[2], y[2];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          float sn = 0.f, cs = 1.f;
+          const int e = 16 * ks + 8 * hf + j + jj;
+          if (p.rope.enabled) sincos_turns_fast(rope_turns(pos, p.rope.hi[e], p.rope.lo[e]), &sn, &cs);
+          x[jj] = (lo[j + jj] * cs - hi[j + jj] * sn) * p.scale_log2;
+          y[jj] = (hi[j + jj] * cs + lo[j + jj] * sn) * p.scale_log2;
+        }
+        wl[j / 2] = pack_bf16(x[0], x[1]);
+        wh[j / 2] = pack_bf16(y[0], y[1]);
+      }
+      qf[qb][ks] = __builtin_bit_cast(bf16x8, wl);
+      qf[qb][ks + KSTEPS / 2] = __builtin_bit_cast(bf16x8, wh);
+    }
+  }
+
+  f32x16 o[DB][2];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][qb][i] = 0.f;
+  float mrow[2] = {-INFINITY, -INFINITY}, lrow[2] = {0.f, 0.f};
+
+  // ---- tile staging: global -> registers -> LDS ----
+  u32x4 kreg[UNITS], vreg[UNITS];
+  auto load_tile = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < UNITS; ++i) {
+      const int u = i * kPfThreads + threadIdx.x;
+      const int row = u / UPR, cu8 = u % UPR;
+      const int key = min(t * kTileKeys + row, n - 1);  // rows past the sequence end repeat the last row (finite data)
+      kreg[i] = *(const u32x4*)(Kg + key * kv_stride + cu8 * 8);
+      vreg[i] = *(const u32x4*)(Vg + key * kv_stride + cu8 * 8);
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int i = 0; i < UNITS; ++i) {
+      const int u = i * kPfThreads + threadIdx.x;
+      const int row = u / UPR, cu8 = u % UPR;
+      *(u32x4*)(sm.k + row * Sm::KS + cu8 * 8) = kreg[i];
+      *(u32x4*)(sm.v + row * Sm::VS + cu8 * 8) = vreg[i];
+    }
+  };
+
+  // per-lane LDS offsets
+  const int k_off = r32 * Sm::KS + 8 * hf;                                                   // + kb*32*KS + 16*ks
+  const int v_off = (4 * hf + ((lane & 15) >> 2)) * Sm::VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 16*kk*VS + 32*db
+
+  load_tile(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    __syncthreads();  // everyone is done reading the previous tile
+    store_tile();
+    __syncthreads();
+    if (t + 1 < n_tiles) load_tile(t + 1);
+    if (!wave_active || t > t_diag) continue;
+
+    // ---- S^T = K Q^T ----
+    f32x16 sc[2][2];  // [key block][query block]
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sc[kb][qb][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const bf16x8 kf = *(const bf16x8*)(sm.k + k_off + kb * 32 * Sm::KS + 16 * ks);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+          sc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sc[kb][qb], 0, 0, 0);
+      }
+    }
+    // ---- causal mask on the diagonal tile (keys beyond the sequence end are beyond every valid query too) ----
+    if (t == t_diag) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int key = 32 * kb + 8 * (i >> 2) + 4 * hf + (i & 3);
+            if (key > 32 * qb + r32) sc[kb][qb][i] = -INFINITY;
+          }
+    }
+    // ---- online softmax, one query column per lane ----
+    bf16x8 pf[2][4];  // [query block][16-key step]
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      float mloc = sc[0][qb][0];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mloc = fmaxf(mloc, sc[kb][qb][i]);
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
+      const float mnew = fmaxf(mrow[qb], mloc);
+      const float alpha = __builtin_amdgcn_exp2f(mrow[qb] - mnew);
+      mrow[qb] = mnew;
+      float lsum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float e = __builtin_amdgcn_exp2f(sc[kb][qb][i] - mnew);
+          sc[kb][qb][i] = e;
+          lsum += e;
+        }
+      lrow[qb] = lrow[qb] * alpha + lsum;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        u32x4 w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          w[j] = pack_bf16(sc[kk >> 1][qb][8 * (kk & 1) + 2 * j], sc[kk >> 1][qb][8 * (kk & 1) + 2 * j + 1]);
+        pf[qb][kk] = __builtin_bit_cast(bf16x8, w);
+      }
+    }
+    // ---- O^T += V^T P^T ----
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const __bf16* vp = sm.v + v_off + 16 * kk * Sm::VS + 32 * db;
+        s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
+        s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * Sm::VS));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+          o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][kk], o[db][qb], 0, 0, 0);
+      }
+    }
+  }
+
+  if (!wave_active) return;
+  // ---- epilogue: normalise and store; lane holds d = 32db + 8j + 4hf + (0..3) of query r32 ----
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int qi = qw + 32 * qb + r32;
+    const float ltot = lrow[qb] + __shfl_xor(lrow[qb], 32, kWave);
+    if (qi >= n) continue;
+    const float inv = 1.f / ltot;
+    __bf16* orow = (__bf16*)p.out + ((long long)(b0 + qi) * p.hq + a) * D + 4 * hf;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        u32x2 w;
+        w[0] = pack_bf16(o[db][qb][4 * j] * inv, o[db][qb][4 * j + 1] * inv);
+        w[1] = pack_bf16(o[db][qb][4 * j + 2] * inv, o[db][qb][4 * j + 3] * inv);
+        *(u32x2*)(orow + 32 * db + 8 * j) = w;
+      }
+    if (p.lse && hf == 0) p.lse[(long long)(b0 + qi) * p.hq + a] = (mrow[qb] + __builtin_log2f(ltot)) * 0.6931471805599453f;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------------------------
+size_t prefill_workspace_bytes(const earn_attn_desc* desc, int total_tokens, int have_k_rot_out) {
+  if (have_k_rot_out) return 0;
+  const size_t e = desc->dtype == EARN_F32 ? 4 : 2;
+  return ((size_t)total_tokens * desc->n_kv_heads * desc->head_dim * e + 255) / 256 * 256;
+}
+
+template <typename T, int D>
+static void launch_rope_k(const void* k, void* k_rot, const int32_t* cu, const int32_t* positions, int batch, int total,
+                          int hkv, const RopeTable& rope, hipStream_t stream) {
+  long long threads = (long long)total * hkv * (D / 16);
+  hipLaunchKernelGGL((rope_k_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
+                     (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope);
+}
+
+int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                   const int32_t* positions, int batch, int total_tokens, int max_seqlen, void* out, void* k_rot_out,
+                   float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+  const int d = desc->head_dim;
+  const size_t need = prefill_workspace_bytes(desc, total_tokens, k_rot_out != nullptr);
+  if (need > workspace_bytes || (need > 0 && !workspace)) {
+    set_error("earn_prefill_attn: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
+    return EARN_ERR_WORKSPACE_TOO_SMALL;
+  }
+  void* k_rot = k_rot_out ? k_rot_out : workspace;
+  PrefillParams p;
+  p.q = q; p.k_rot = k_rot; p.v = v; p.cu = cu_seqlens; p.positions = positions; p.out = out; p.lse = lse_out;
+  p.batch = batch; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.max_seqlen = max_seqlen;
+  const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
+  p.scale_log2 = scale * 1.4426950408889634f;
+  p.rope = make_rope_table(desc->rope_base, d);
+  const bool f32 = desc->dtype == EARN_F32;
+  if (f32) {
+    if (d == 64) launch_rope_k<float, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
+    else launch_rope_k<float, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
+    dim3 grid((max_seqlen + 63) / 64, p.hq, batch);
+    if (d == 64) hipLaunchKernelGGL((prefill_rows_kernel<float, 64>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((prefill_rows_kernel<float, 128>), grid, dim3(256), 0, stream, p);
+  } else {
+    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
+    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
+    dim3 grid(p.hq, batch, (max_seqlen + kBlockRows - 1) / kBlockRows);
+    if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64>), grid, dim3(kPfThreads), 0, stream, p);
+    else hipLaunchKernelGGL((prefill_mfma_kernel<128>), grid, dim3(kPfThreads), 0, stream, p);
+  }
+  return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
+}
+
+}  // namespace earn

@@ -1,0 +1,121 @@
+"""The EARN attention path on the GPU, expressed as calls into libearn (paper Section 3.2, Inference).
+
+    first k layers   earn_prefill_attn on all tokens; the rotated keys and the values are the layer's cache
+    layer k input    earn_compact_registers gathers the register rows (hidden-state stand-in and the per-layer
+                     Q/K/V of the remaining layers, which in a full model would be projected from the gathered rows)
+    layers k..N-1    earn_prefill_attn on the r = h+t register rows with their original positions
+    decode step g    earn_decode_attn per layer: full cache for layers < k, register cache for layers >= k
+
+All buffers are allocated once in the constructor; the methods only enqueue kernels on the current stream.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import torch
+
+from . import binding as B
+
+
+class EarnPath:
+    def __init__(self, *, n_layers: int, split_k: int, n_head_reg: int, n_tail_reg: int, n_q_heads: int,
+                 n_kv_heads: int, head_dim: int, dtype: torch.dtype, cu_seqlens: Sequence[int],
+                 stream_to_seq: Sequence[int], gen_cap: int, rope_base: float = 10000.0, softmax_scale: float = 0.0,
+                 device="cuda:0", want_lse: bool = False):
+        self.N, self.k, self.h, self.t = n_layers, split_k, n_head_reg, n_tail_reg
+        self.r = n_head_reg + n_tail_reg
+        self.hq, self.hkv, self.d, self.dtype = n_q_heads, n_kv_heads, head_dim, dtype
+        self.device = torch.device(device)
+        self.desc = B.make_desc(dtype, n_q_heads, n_kv_heads, head_dim, softmax_scale, rope_base)
+        lens = [cu_seqlens[i + 1] - cu_seqlens[i] for i in range(len(cu_seqlens) - 1)]
+        self.lens = lens
+        self.batch = len(lens)
+        self.T = int(cu_seqlens[-1])
+        self.max_seqlen = max(lens)
+        self.Tc = self.batch * self.r
+        self.S = len(stream_to_seq)
+        self.gen_cap = gen_cap
+        dev, i32 = self.device, torch.int32
+        self.cu = torch.tensor(list(cu_seqlens), dtype=i32, device=dev)
+        self.stream_to_seq = torch.tensor(list(stream_to_seq), dtype=i32, device=dev)
+        self.seq_len_of_stream = torch.tensor([lens[s] for s in stream_to_seq], dtype=i32, device=dev)
+        self.idx = torch.empty(self.Tc, dtype=i32, device=dev)
+        self.pos = torch.empty(self.Tc, dtype=i32, device=dev)
+        self.cu_c = torch.empty(self.batch + 1, dtype=i32, device=dev)
+        e = lambda *shape: torch.empty(shape, dtype=dtype, device=dev)
+        N, k = self.N, self.k
+        self.prefill_out = [e(self.T if l < k else self.Tc, self.hq, self.d) for l in range(N)]
+        self.k_cache = [e(self.T if l < k else self.Tc, self.hkv, self.d) for l in range(N)]
+        self.v_cache: List[Optional[torch.Tensor]] = [None] * N       # layers < k alias the caller's V
+        self.x_c: Optional[torch.Tensor] = None
+        self.q_c = {l: e(self.Tc, self.hq, self.d) for l in range(k, N)}
+        self.k_c = {l: e(self.Tc, self.hkv, self.d) for l in range(k, N)}
+        self.v_c = {l: e(self.Tc, self.hkv, self.d) for l in range(k, N)}
+        self.lse = ([torch.empty(self.T if l < k else self.Tc, self.hq, dtype=torch.float32, device=dev)
+                     for l in range(N)] if want_lse else [None] * N)
+        self.gen_k = [torch.zeros(self.S, gen_cap, self.hkv, self.d, dtype=dtype, device=dev) for _ in range(N)]
+        self.gen_v = [torch.zeros(self.S, gen_cap, self.hkv, self.d, dtype=dtype, device=dev) for _ in range(N)]
+        self.gen_len = torch.zeros(self.S, dtype=i32, device=dev)
+        self.q_pos = torch.zeros(self.S, dtype=i32, device=dev)
+        self.decode_out = [e(self.S, self.hq, self.d) for _ in range(N)]
+        ws = max(B.earn_decode_workspace_bytes(self.desc, self.S, self.batch, self.max_seqlen, gen_cap),
+                 B.earn_decode_workspace_bytes(self.desc, self.S, self.batch, self.r, gen_cap), 256)
+        self.workspace = torch.empty(ws, dtype=torch.uint8, device=dev)
+
+    # ---- prefill ----
+    def prefill_full_layer(self, l: int, q, k, v) -> None:
+        B.earn_prefill_attn(self.desc, q, k, v, self.cu, None, self.batch, self.T, self.max_seqlen,
+                            self.prefill_out[l], self.k_cache[l], self.lse[l], None)
+        self.v_cache[l] = v
+
+    def compact(self, x: Optional[torch.Tensor], q: Sequence[torch.Tensor], k: Sequence[torch.Tensor],
+                v: Sequence[torch.Tensor]) -> None:
+        """Gather register rows of x and of the per-layer q/k/v for layers k..N-1 (indexable by layer)."""
+        src, dst = [], []
+        if x is not None:
+            if self.x_c is None or self.x_c.shape[1:] != x.shape[1:]:
+                self.x_c = torch.empty((self.Tc,) + tuple(x.shape[1:]), dtype=x.dtype, device=self.device)
+            src.append(x)
+            dst.append(self.x_c)
+        for l in range(self.k, self.N):
+            src += [q[l], k[l], v[l]]
+            dst += [self.q_c[l], self.k_c[l], self.v_c[l]]
+        first = True
+        for i in range(0, max(len(src), 1), B.EARN_MAX_COMPACT_TENSORS):
+            B.earn_compact_registers(src[i:i + B.EARN_MAX_COMPACT_TENSORS], dst[i:i + B.EARN_MAX_COMPACT_TENSORS],
+                                     self.cu, self.batch, self.h, self.t, self.idx if first else None,
+                                     self.pos if first else None, self.cu_c if first else None)
+            first = False
+
+    def prefill_register_layer(self, l: int) -> None:
+        B.earn_prefill_attn(self.desc, self.q_c[l], self.k_c[l], self.v_c[l], self.cu_c, self.pos, self.batch,
+                            self.Tc, self.r, self.prefill_out[l], self.k_cache[l], self.lse[l], None)
+        self.v_cache[l] = self.v_c[l]
+
+    def prefill(self, q: Sequence[torch.Tensor], k: Sequence[torch.Tensor], v: Sequence[torch.Tensor],
+                x: Optional[torch.Tensor]) -> None:
+        for l in range(self.k):
+            self.prefill_full_layer(l, q[l], k[l], v[l])
+        if self.k < self.N:
+            self.compact(x, q, k, v)
+            for l in range(self.k, self.N):
+                self.prefill_register_layer(l)
+
+    # ---- decode ----
+    def set_step(self, g: int) -> None:
+        """gen_len = g and q_pos = n_s + g for every stream (tiny fill kernels, no host sync)."""
+        self.gen_len.fill_(g)
+        torch.add(self.seq_len_of_stream, g, out=self.q_pos)
+
+    def decode_layer(self, l: int, dq, dk, dv) -> None:
+        full = l < self.k
+        B.earn_decode_attn(self.desc, dq, dk, dv, self.q_pos, self.k_cache[l], self.v_cache[l],
+                           self.cu if full else self.cu_c, self.stream_to_seq, self.gen_k[l], self.gen_v[l],
+                           self.gen_len, self.gen_cap, self.S, self.batch, self.max_seqlen if full else self.r,
+                           self.decode_out[l], self.workspace)
+
+    def decode_step(self, g: int, dq: Sequence[torch.Tensor], dk: Sequence[torch.Tensor],
+                    dv: Sequence[torch.Tensor]) -> None:
+        self.set_step(g)
+        for l in range(self.N):
+            self.decode_layer(l, dq[l], dk[l], dv[l])

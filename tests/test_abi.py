@@ -1,0 +1,106 @@
+"""The C-ABI library loads, exports every symbol include/earn.h declares, and rejects bad arguments on the host
+(no kernel is launched by any call in this file, so it runs without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2507_00715_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "earn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(earn_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    lib = B.lib()
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert b"gfx950" in lib.earn_version()
+
+
+def test_cache_entries_closed_form():
+    # Section 3.3 typical values: k L + (N-k) r = 8*512 + 24*2
+    assert B.earn_cache_entries(32, 8, 512, 2, 0) == 4144
+    assert B.earn_cache_entries(4, 2, 100, 4, 4) == 2 * 100 + 2 * 4 + 4 * 4
+
+
+def _desc(dtype=B.EARN_BF16, hq=4, hkv=2, d=64):
+    return B.AttnDesc(dtype, hq, hkv, d, 0.0, 10000.0)
+
+
+def test_prefill_argument_errors():
+    lib = B.lib()
+    fake = ctypes.c_void_p(256)  # never dereferenced: validation fails first
+    call = lambda desc, q=fake, cu=fake, batch=1, total=8, maxlen=8, ws=0: lib.earn_prefill_attn(
+        ctypes.byref(desc), q, fake, fake, cu, None, batch, total, maxlen, fake, fake, None, None, ws, None)
+    assert call(_desc(d=96)) == B.EARN_ERR_UNSUPPORTED and b"head_dim" in lib.earn_last_error()
+    assert call(_desc(dtype=7)) == B.EARN_ERR_UNSUPPORTED
+    assert call(_desc(hq=5, hkv=2)) == B.EARN_ERR_INVALID_ARG and b"multiple" in lib.earn_last_error()
+    assert call(_desc(), batch=0) == B.EARN_ERR_INVALID_ARG
+    assert call(_desc(), q=None) == B.EARN_ERR_INVALID_ARG
+    assert call(_desc(), cu=None) == B.EARN_ERR_INVALID_ARG
+    assert call(_desc(), total=0) == B.EARN_OK          # empty batch is a no-op
+    assert lib.earn_prefill_attn(None, fake, fake, fake, fake, None, 1, 8, 8, fake, None, None, None, 0, None) == B.EARN_ERR_INVALID_ARG
+    # without k_rot_out the rotated keys need workspace
+    rc = lib.earn_prefill_attn(ctypes.byref(_desc()), fake, fake, fake, fake, None, 1, 8, 8, fake, None, None, None, 0, None)
+    assert rc == B.EARN_ERR_WORKSPACE_TOO_SMALL
+    assert B.earn_prefill_workspace_bytes(_desc(), 1, 8, 8, False) >= 8 * 2 * 64 * 2
+    assert B.earn_prefill_workspace_bytes(_desc(), 1, 8, 8, True) == 0
+
+
+def test_compact_argument_errors():
+    lib = B.lib()
+    fake = ctypes.c_void_p(256)
+    vp = ctypes.c_void_p
+
+    def call(n=1, src=256, dst=512, rb=32, cu=fake, batch=2, h=1, t=1):
+        s, d, r = (vp * 1)(src), (vp * 1)(dst), (ctypes.c_int64 * 1)(rb)
+        return lib.earn_compact_registers(n, s, d, r, cu, batch, h, t, None, None, None, None)
+
+    assert call(batch=0) == B.EARN_ERR_INVALID_ARG
+    assert call(h=0, t=0) == B.EARN_ERR_INVALID_ARG
+    assert call(h=-1) == B.EARN_ERR_INVALID_ARG
+    assert call(rb=24) == B.EARN_ERR_INVALID_ARG and b"multiple of 16" in lib.earn_last_error()
+    assert call(rb=0) == B.EARN_ERR_INVALID_ARG
+    assert call(src=264) == B.EARN_ERR_INVALID_ARG and b"aligned" in lib.earn_last_error()
+    assert call(src=None) == B.EARN_ERR_INVALID_ARG
+    assert call(cu=None) == B.EARN_ERR_INVALID_ARG
+    assert call(n=B.EARN_MAX_COMPACT_TENSORS + 1) == B.EARN_ERR_INVALID_ARG
+    assert lib.earn_compact_registers(1, None, None, None, fake, 2, 1, 1, None, None, None, None) == B.EARN_ERR_INVALID_ARG
+
+
+def test_decode_argument_errors():
+    lib = B.lib()
+    fake = ctypes.c_void_p(256)
+
+    def call(desc=None, q=fake, s2s=fake, gen_cap=4, S=2, batch=2, maxlen=8, ws=None, ws_bytes=0):
+        desc = desc or _desc()
+        return lib.earn_decode_attn(ctypes.byref(desc), q, fake, fake, fake, fake, fake, fake, s2s, fake, fake, fake,
+                                    gen_cap, S, batch, maxlen, fake, ws, ws_bytes, None)
+
+    assert call(desc=_desc(d=32)) == B.EARN_ERR_UNSUPPORTED
+    assert call(q=None) == B.EARN_ERR_INVALID_ARG
+    assert call(gen_cap=0) == B.EARN_ERR_INVALID_ARG
+    assert call(S=0) == B.EARN_ERR_INVALID_ARG
+    assert call(maxlen=-1) == B.EARN_ERR_INVALID_ARG
+    assert call(s2s=None, S=4, batch=2) == B.EARN_ERR_INVALID_ARG and b"stream_to_seq" in lib.earn_last_error()
+    # long caches are split over workgroups and need workspace for the partial results
+    need = B.earn_decode_workspace_bytes(_desc(), 2, 2, 100000, 4)
+    assert need > 0
+    assert call(maxlen=100000) == B.EARN_ERR_WORKSPACE_TOO_SMALL
+    assert B.earn_decode_workspace_bytes(_desc(hq=64, hkv=64), 512, 512, 16, 4) == 0
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(AssertionError):
+        B.earn_compact_registers([torch.zeros(4, 16, dtype=torch.uint8)], [torch.zeros(2, 16, dtype=torch.uint8)],
+                                 torch.zeros(2, dtype=torch.int32), 1, 1, 1)
