@@ -1,0 +1,264 @@
+#!/usr/bin/env python3
+"""Benchmark of the EARN attention hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch of a configuration:
+    k full-length prefill layers -> register compaction -> N-k register-only prefill layers -> G decode steps
+    (each decode step runs all N layers: full cache for layers < k, register cache for layers >= k).
+Inputs are generated on the GPU before the timed region (seeded, synthetic, see paper_2507_00715_amd/workloads.py).
+
+Prints ONE JSON line.  `value` is the prefill-attention rate in algorithmic causal TFLOP/s
+(4*d*Hq*sum_s m_s(m_s+1)/2 per layer, summed over all N prefill launches, divided by the time the prefill
+launches took inside the timed steps); decode and compaction figures, a roofline object for the dominant
+kernel and the CPU oracle timed on the host cores are carried in the same line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2507_00715_amd import workloads as W  # noqa: E402
+
+METRIC = "prefill attn TFLOP/s + decode attn µs/step & HBM GB/s vs roofline, 1 MI355X"
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3     # fp32 vector
+PEAK_HBM_GBPS = 8000.0      # HBM3E
+HEADLINE = "long_beam"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class PhaseTimer:
+    """HIP events on torch's current stream (the stream every libearn launch of this script goes to)."""
+
+    def __init__(self):
+        self.pairs = {}
+
+    def start(self, name):
+        ev = torch.cuda.Event(enable_timing=True)
+        ev.record()
+        self.pairs.setdefault(name, []).append([ev, None])
+
+    def stop(self, name):
+        ev = torch.cuda.Event(enable_timing=True)
+        ev.record()
+        self.pairs[name][-1][1] = ev
+
+    def totals_ms(self):
+        return {k: sum(a.elapsed_time(b) for a, b in v) for k, v in self.pairs.items()}
+
+    def counts(self):
+        return {k: len(v) for k, v in self.pairs.items()}
+
+
+def algorithmic_counts(w: W.Workload):
+    """FLOPs and bytes the method itself requires (not what the kernels happen to move)."""
+    c = w.cfg
+    e, d, hq, hkv, B, r, S = c.elem_bytes, c.head_dim, c.n_q_heads, c.n_kv_heads, c.batch, c.r, w.n_streams
+    flops_full = 4.0 * d * hq * w.causal_pairs(False)
+    flops_reg = 4.0 * d * hq * w.causal_pairs(True)
+    # decode bytes per layer per step g: K and V rows (shared rows once per sequence) + q,o + k_new,v_new read+write
+    def dec_bytes(g, full):
+        shared = w.total_tokens if full else B * r
+        return 2 * hkv * d * e * (shared + S * (g + 1)) + 2 * hq * d * e * S + 4 * hkv * d * e * S
+    dec_full = [dec_bytes(g, True) for g in range(c.decode_steps)]
+    dec_reg = [dec_bytes(g, False) for g in range(c.decode_steps)]
+    # compaction: x [T, Hq*d] plus q,k,v of the N-k register layers; read + write of B*r rows each, plus index outputs
+    row_bytes = [hq * d * e] + [hq * d * e, hkv * d * e, hkv * d * e] * (c.n_layers - c.split_k)
+    comp = sum(2 * B * r * rb for rb in row_bytes) + 12 * B * r + 8 * B
+    return dict(flops_full=flops_full, flops_reg=flops_reg, dec_full=dec_full, dec_reg=dec_reg, compaction=comp)
+
+
+def build_inputs(w: W.Workload, dev):
+    c = w.cfg
+    t0 = time.time()
+    seq, pos = w.token_coords(dev)
+    mk = lambda which: [w.prefill_tensor(which, l, coords=(seq, pos)) for l in range(c.n_layers)]
+    q, k, v = mk("q"), mk("k"), mk("v")
+    x = w.prefill_tensor("x", 0, coords=(seq, pos))
+    dmk = lambda which: [[w.decode_tensor(which, l, g, device=dev) for l in range(c.n_layers)]
+                         for g in range(c.decode_steps)]
+    dq, dk, dv = dmk("q"), dmk("k"), dmk("v")
+    torch.cuda.synchronize()
+    log(f"[bench] {c.name}: inputs generated on GPU in {time.time() - t0:.1f}s "
+        f"({torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated)")
+    return q, k, v, x, dq, dk, dv
+
+
+def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
+    from paper_2507_00715_amd.pipeline import EarnPath
+    cfg = W.CONFIGS[name]
+    w = W.Workload(cfg)
+    c = cfg
+    q, k, v, x, dq, dk, dv = build_inputs(w, dev)
+    path = EarnPath(n_layers=c.n_layers, split_k=c.split_k, n_head_reg=c.n_head_reg, n_tail_reg=c.n_tail_reg,
+                    n_q_heads=c.n_q_heads, n_kv_heads=c.n_kv_heads, head_dim=c.head_dim, dtype=c.torch_dtype,
+                    cu_seqlens=w.cu_seqlens, stream_to_seq=w.stream_to_seq, gen_cap=c.decode_steps,
+                    rope_base=c.rope_base, device=dev)
+    N, kk, G = c.n_layers, c.split_k, c.decode_steps
+
+    def one_step(tm: PhaseTimer | None):
+        ph = (lambda n: tm.start(n)) if tm else (lambda n: None)
+        pe = (lambda n: tm.stop(n)) if tm else (lambda n: None)
+        ph("prefill_full")
+        for l in range(kk):
+            path.prefill_full_layer(l, q[l], k[l], v[l])
+        pe("prefill_full")
+        ph("compact")
+        path.compact(x, q, k, v)
+        pe("compact")
+        ph("prefill_reg")
+        for l in range(kk, N):
+            path.prefill_register_layer(l)
+        pe("prefill_reg")
+        for g in range(G):
+            path.set_step(g)
+            ph("decode_full")
+            for l in range(kk):
+                path.decode_layer(l, dq[g][l], dk[g][l], dv[g][l])
+            pe("decode_full")
+            ph("decode_reg")
+            for l in range(kk, N):
+                path.decode_layer(l, dq[g][l], dk[g][l], dv[g][l])
+            pe("decode_reg")
+
+    for _ in range(warmup):
+        one_step(None)
+    torch.cuda.synchronize()
+    tm = PhaseTimer()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_step(tm)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = tm.totals_ms()
+    alg = algorithmic_counts(w)
+
+    full_ms = ms["prefill_full"] / (steps * kk)              # per launch of the dominant kernel (+ its K rotation)
+    reg_ms = ms["prefill_reg"] / (steps * max(N - kk, 1))
+    prefill_flops = kk * alg["flops_full"] + (N - kk) * alg["flops_reg"]
+    prefill_tflops = prefill_flops * steps / ((ms["prefill_full"] + ms["prefill_reg"]) * 1e-3) / 1e12
+    full_tflops = alg["flops_full"] / (full_ms * 1e-3) / 1e12
+    dec_bytes_step = [kk * alg["dec_full"][g] + (N - kk) * alg["dec_reg"][g] for g in range(G)]
+    dec_ms_total = ms["decode_full"] + ms["decode_reg"]
+    dec_us_per_step = dec_ms_total * 1e3 / (steps * G)
+    dec_gbps = sum(dec_bytes_step) * steps / (dec_ms_total * 1e-3) / 1e9
+    dec_full_gbps = kk * sum(alg["dec_full"]) * steps / (ms["decode_full"] * 1e-3) / 1e9
+    dec_reg_gbps = (N - kk) * sum(alg["dec_reg"]) * steps / (ms["decode_reg"] * 1e-3) / 1e9
+    comp_us = ms["compact"] * 1e3 / steps
+    comp_gbps = alg["compaction"] / (comp_us * 1e-6) / 1e9
+    peak = PEAK_BF16_TFLOPS if c.dtype == "bf16" else PEAK_F32_TFLOPS
+    res = {
+        "workload": w.describe(),
+        "ms_per_step": wall * 1e3 / steps,
+        "prefill_tflops": prefill_tflops,
+        "prefill_full_layer": {"ms_per_launch": full_ms, "tflops": full_tflops, "frac_of_peak": full_tflops / peak,
+                               "flops_per_launch": alg["flops_full"]},
+        "prefill_register_layer": {"us_per_launch": reg_ms * 1e3, "flops_per_launch": alg["flops_reg"]},
+        "compaction": {"us": comp_us, "bytes": alg["compaction"], "GBps": comp_gbps,
+                       "frac_of_hbm_peak": comp_gbps / PEAK_HBM_GBPS},
+        "decode": {"us_per_step": dec_us_per_step, "bytes_first_step": dec_bytes_step[0],
+                   "bytes_last_step": dec_bytes_step[-1], "GBps": dec_gbps, "frac_of_hbm_peak": dec_gbps / PEAK_HBM_GBPS,
+                   "full_cache_layers": {"us_per_layer": ms["decode_full"] * 1e3 / (steps * G * kk),
+                                         "GBps": dec_full_gbps, "frac_of_hbm_peak": dec_full_gbps / PEAK_HBM_GBPS},
+                   "register_cache_layers": {"us_per_layer": ms["decode_reg"] * 1e3 / (steps * G * max(N - kk, 1)),
+                                             "GBps": dec_reg_gbps, "frac_of_hbm_peak": dec_reg_gbps / PEAK_HBM_GBPS}},
+        "phase_ms_per_step": {k_: v_ / steps for k_, v_ in ms.items()},
+    }
+    del path, q, k, v, x, dq, dk, dv
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(name: str) -> dict:
+    """The fp64 oracle, untuned, on a bounded sample of the headline workload's first prefill layer."""
+    from oracle import earn_oracle as O
+    cfg = W.CONFIGS[name]
+    w = W.Workload(cfg)
+    seq_id = 0
+    n = w.seq_lengths[seq_id]
+    stride = max(1, n // 512)
+    q = W.to_f64(w.prefill_tensor("q", 0, seqs=[seq_id]))
+    k = W.to_f64(w.prefill_tensor("k", 0, seqs=[seq_id]))
+    v = W.to_f64(w.prefill_tensor("v", 0, seqs=[seq_id]))
+    sel = np.zeros(n, dtype=np.uint8)
+    sel[stride - 1::stride] = 1
+    rows = np.nonzero(sel)[0]
+    pairs = float(np.sum(rows + 1)) * cfg.n_q_heads
+    flops = 4.0 * cfg.head_dim * pairs
+    t0 = time.perf_counter()
+    O.prefill_attn(q, k, v, [0, n], rope_base=cfg.rope_base, row_sel=sel)
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    cores = min(cores, cfg.n_q_heads)  # the oracle parallelises over (sequence, head)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle", "seconds": dt,
+            "sample": f"{name} layer 0, sequence {seq_id} (n={n}), all {cfg.n_q_heads} query heads, every "
+                      f"{stride}th query row ({len(rows)} rows, {pairs:.3g} causal pairs)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default=HEADLINE, choices=W.CONFIG_ORDER)
+    ap.add_argument("--others", default="small_gqa,mid_mha,serving",
+                    help="comma-separated workloads also measured and reported under 'other_workloads' ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is a single-GPU hot path; --gpus N with N > 1 is not supported "
+              "(sequences are independent, so N GPUs would run N independent copies).", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(3)
+    from paper_2507_00715_amd import binding
+    binding.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    head = run_workload(args.workload, args.steps, args.warmup, dev)
+    others = {}
+    for name in [s for s in args.others.split(",") if s and s != args.workload]:
+        r = run_workload(name, args.steps, args.warmup, dev)
+        others[name] = r
+    cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
+
+    cfg = W.CONFIGS[args.workload]
+    pf = head["prefill_full_layer"]
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    line = {
+        "metric": METRIC,
+        "value": head["prefill_tflops"],
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": head["workload"],
+        "roofline": {"kernel": "prefill_mfma_kernel (full-length causal layer)", "bound": "mfma",
+                     "achieved": pf["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": pf["tflops"] / peak,
+                     "traffic": None, "ms_per_launch": pf["ms_per_launch"], "flops_per_launch": pf["flops_per_launch"]},
+        "cpu_baseline": cpu,
+        "decode": head["decode"],
+        "compaction": head["compaction"],
+        "prefill_register_layer": head["prefill_register_layer"],
+        "phase_ms_per_step": head["phase_ms_per_step"],
+        "other_workloads": {n: {kk: vv for kk, vv in r.items()} for n, r in others.items()},
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
