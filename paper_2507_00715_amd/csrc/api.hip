@@ -44,7 +44,8 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
                   const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
                   int n_streams, int batch, int max_shared_len, void* out, void* workspace, size_t workspace_bytes,
                   hipStream_t stream);
-size_t decode_workspace_bytes(int hq, int hkv, int d, int n_streams, int max_total_len);
+size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, int batch, int max_shared_len,
+                              int gen_cap);
 
 static int check_desc(const earn_attn_desc* d, const char* who) {
   if (!d) { set_error("%s: desc is NULL", who); return EARN_ERR_INVALID_ARG; }
@@ -124,9 +125,9 @@ int earn_compact_registers(int32_t n_tensors, const void* const* src, void* cons
 
 size_t earn_decode_workspace_bytes(const earn_attn_desc* desc, int32_t n_streams, int32_t batch,
                                    int32_t max_shared_len, int32_t gen_cap) {
-  (void)batch;
-  if (check_desc(desc, "earn_decode_workspace_bytes") != EARN_OK || n_streams <= 0 || max_shared_len < 0 || gen_cap <= 0) return 0;
-  return decode_workspace_bytes(desc->n_q_heads, desc->n_kv_heads, desc->head_dim, n_streams, max_shared_len + gen_cap);
+  if (check_desc(desc, "earn_decode_workspace_bytes") != EARN_OK || n_streams <= 0 || batch <= 0 || max_shared_len < 0 || gen_cap <= 0) return 0;
+  return decode_workspace_bytes(desc->dtype, desc->n_q_heads, desc->n_kv_heads, desc->head_dim, n_streams, batch,
+                                max_shared_len, gen_cap);
 }
 
 int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,

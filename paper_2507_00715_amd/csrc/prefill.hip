@@ -430,6 +430,14 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
     dim3 grid((max_seqlen + 63) / 64, p.hq, batch);
     if (d == 64) hipLaunchKernelGGL((prefill_rows_kernel<float, 64>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((prefill_rows_kernel<float, 128>), grid, dim3(256), 0, stream, p);
+  } else if (max_seqlen <= 64) {
+    // register-only layers: a handful of rows per sequence, far too little work for a 256-row MFMA tile; the
+    // vector kernel keeps many small workgroups in flight instead
+    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
+    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
+    dim3 grid(1, p.hq, batch);
+    if (d == 64) hipLaunchKernelGGL((prefill_rows_kernel<__bf16, 64>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((prefill_rows_kernel<__bf16, 128>), grid, dim3(256), 0, stream, p);
   } else {
     if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
     else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);

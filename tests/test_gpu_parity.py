@@ -186,6 +186,10 @@ DECODE_CASES = [
     (torch.bfloat16, 32, 32, 128, [32, 2059, 700], 1, [2, 0, 7], 8),
     (torch.bfloat16, 32, 8, 128, [64, 8256], 3, [0, 1, 2, 3, 4, 7], 8),
     (torch.bfloat16, 12, 2, 128, [16, 1038, 81], 1, [3, 0, 1], 4),
+    # beams: 4 heads x 20 beams = 80 query rows per cache (more than one 64-row pass), ragged last tile, empty cache
+    (torch.bfloat16, 32, 8, 128, [64, 2100, 0], 20, [i % 5 for i in range(60)], 5),
+    (torch.bfloat16, 14, 2, 64, [300, 16, 1000], 6, [i % 3 for i in range(18)], 3),
+    (torch.bfloat16, 8, 8, 64, [33, 700], 4, [0, 1, 2, 3, 3, 2, 1, 0], 4),
 ]
 
 
