@@ -20,6 +20,8 @@
 //   natural [key][d] layout.
 //   A workgroup is 4 waves; each wave owns 64 query rows (2 column blocks), so every K/V fragment read from LDS feeds
 //   two MFMAs; the 64-key K/V tile in LDS is shared by the 4 waves (256 query rows per tile load).
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace earn {
@@ -166,11 +168,8 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
 // ------------------------------------------------------------------------------------------------------------------
 // bf16 MFMA flash attention
 // ------------------------------------------------------------------------------------------------------------------
-constexpr int kPfThreads = 256;
-constexpr int kPfWaves = 4;
-constexpr int kWaveRows = 64;                     // query rows per wave (2 MFMA column blocks)
-constexpr int kBlockRows = kPfWaves * kWaveRows;  // 256 query rows per workgroup
-constexpr int kTileKeys = 64;                     // keys per K/V tile in LDS
+constexpr int kBlockRows = 256;  // query rows per workgroup
+constexpr int kTileKeys = 64;    // keys per K/V tile in LDS
 
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
@@ -178,16 +177,39 @@ template <int D>
 struct PfSmem {
   static constexpr int KS = D + 8;    // K row stride (elements): 16-byte reads of 16 consecutive rows hit all banks
   static constexpr int VS = D + 32;   // V row stride: the 4 rows of a transposing read land 64 bytes apart (mod 256)
-  __bf16 k[kTileKeys * KS];
-  __bf16 v[kTileKeys * VS];
+  __bf16 k[2][kTileKeys * KS];   // double buffered: tile t+1 is written while tile t is read
+  __bf16 v[2][kTileKeys * VS];
 };
 
-template <int D>
-__global__ __launch_bounds__(kPfThreads, 1) void prefill_mfma_kernel(PrefillParams p) {
+// Largest rise of a row maximum (log2 units) tolerated before the accumulators are rescaled.  Between rescales the
+// exponentials are taken against a stale maximum, so they can reach 2^8: harmless in fp32 sums and in bf16 operands,
+// and the final normalisation uses the same reference, so the result is the same function.  Rescaling touches all
+// 128 accumulator registers per lane, so doing it only when needed removes most vector-ALU work from the key loop.
+constexpr float kRescaleThreshold = 8.0f;
+
+// max / sum of a value with its partner in the other half of the wave (lane ^ 32), without going through LDS
+__device__ __forceinline__ float half_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// QB = 32-query column blocks per wave; the workgroup has 8/QB waves (256 query rows either way).
+//   QB = 2: 4 waves, one per SIMD, every K/V fragment read from LDS feeds two MFMAs, ~470 registers per lane.
+//   QB = 1: 8 waves, two per SIMD (<= 256 registers per lane): while one wave of a SIMD runs its softmax on the
+//           vector ALU the other keeps the matrix core busy; LDS traffic per MFMA doubles (fits: LDS reads run at
+//           256 B/clk per CU on this part).
+template <int D, int QB>
+__global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams p) {
+  constexpr int kPfThreads = 512 / QB;
+  constexpr int kWaveRows = 32 * QB;
   constexpr int KSTEPS = D / 16;         // MFMA k-steps over head_dim for S^T
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int UPR = D / 8;             // 16-byte units per K/V row
-  constexpr int UNITS = kTileKeys * UPR / kPfThreads;  // units per thread per tile (4 for d=128, 2 for d=64)
+  constexpr int UNITS = kTileKeys * UPR / kPfThreads;  // 16-byte units per thread per tile and tensor
   using Sm = PfSmem<D>;
   __shared__ Sm sm;
 
@@ -202,6 +224,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_mfma_kernel(PrefillPara
   const int qw = q0 + wave * kWaveRows;          // first query row of this wave
   const bool wave_active = qw < n;
   const int t_diag = qw / kTileKeys;             // last (diagonal) tile of this wave
+  const int q_in_tile = qw - t_diag * kTileKeys; // offset of the wave's first query inside that tile
   const int n_tiles = (min(q0 + kBlockRows, n) + kTileKeys - 1) / kTileKeys;
 
   const __bf16* Qg = (const __bf16*)p.q;
@@ -210,9 +233,9 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_mfma_kernel(PrefillPara
   const long long kv_stride = (long long)p.hkv * D;
 
   // ---- Q fragments: rotate at the original position, fold in scale*log2(e), keep as bf16 B operands ----
-  bf16x8 qf[2][KSTEPS];
+  bf16x8 qf[QB][KSTEPS];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
+  for (int qb = 0; qb < QB; ++qb) {
     const int qi = min(qw + 32 * qb + r32, n - 1);
     const float pos = (float)(p.positions ? p.positions[b0 + qi] : qi);
     const __bf16* qrow = Qg + ((long long)(b0 + qi) * p.hq + a) * D + 8 * hf;
@@ -241,14 +264,16 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_mfma_kernel(PrefillPara
     }
   }
 
-  f32x16 o[DB][2];
+  f32x16 o[DB][QB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[db][qb][i] = 0.f;
-  float mrow[2] = {-INFINITY, -INFINITY}, lrow[2] = {0.f, 0.f};
+  float mrow[QB], lrow[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) { mrow[qb] = -INFINITY; lrow[qb] = 0.f; }
 
   // ---- tile staging: global -> registers -> LDS ----
   u32x4 kreg[UNITS], vreg[UNITS];
@@ -262,13 +287,13 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_mfma_kernel(PrefillPara
       vreg[i] = *(const u32x4*)(Vg + key * kv_stride + cu8 * 8);
     }
   };
-  auto store_tile = [&]() {
+  auto store_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < UNITS; ++i) {
       const int u = i * kPfThreads + threadIdx.x;
       const int row = u / UPR, cu8 = u % UPR;
-      *(u32x4*)(sm.k + row * Sm::KS + cu8 * 8) = kreg[i];
-      *(u32x4*)(sm.v + row * Sm::VS + cu8 * 8) = vreg[i];
+      *(u32x4*)(sm.k[buf] + row * Sm::KS + cu8 * 8) = kreg[i];
+      *(u32x4*)(sm.v[buf] + row * Sm::VS + cu8 * 8) = vreg[i];
     }
   };
 
@@ -276,71 +301,68 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_mfma_kernel(PrefillPara
   const int k_off = r32 * Sm::KS + 8 * hf;                                                   // + kb*32*KS + 16*ks
   const int v_off = (4 * hf + ((lane & 15) >> 2)) * Sm::VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 16*kk*VS + 32*db
 
-  load_tile(0);
-  for (int t = 0; t < n_tiles; ++t) {
-    __syncthreads();  // everyone is done reading the previous tile
-    store_tile();
-    __syncthreads();
-    if (t + 1 < n_tiles) load_tile(t + 1);
-    if (!wave_active || t > t_diag) continue;
-
-    // ---- S^T = K Q^T ----
-    f32x16 sc[2][2];  // [key block][query block]
+  // ---- pieces of one key-tile iteration ----
+  auto stage = [&](int t) {
+    // tile t+1 goes to the other buffer (last read in iteration t-1, which every wave has left), tile t+2 into registers
+    if (t + 1 < n_tiles) store_tile((t & 1) ^ 1);
+    if (t + 2 < n_tiles) load_tile(t + 2);
+  };
+  // S^T = K Q^T for tile t, causal mask on the diagonal tile, row maxima of the tile
+  auto scores = [&](int t, f32x16 (&sc)[2][QB], float (&mloc)[QB]) {
+    const __bf16* smk = sm.k[t & 1];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
+      for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) sc[kb][qb][i] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 kf = *(const bf16x8*)(sm.k + k_off + kb * 32 * Sm::KS + 16 * ks);
+        const bf16x8 kf = *(const bf16x8*)(smk + k_off + kb * 32 * Sm::KS + 16 * ks);
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
           sc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sc[kb][qb], 0, 0, 0);
       }
     }
-    // ---- causal mask on the diagonal tile (keys beyond the sequence end are beyond every valid query too) ----
-    if (t == t_diag) {
+    if (t == t_diag) {  // keys beyond the sequence end are beyond every valid query too
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int key = 32 * kb + 8 * (i >> 2) + 4 * hf + (i & 3);
-            if (key > 32 * qb + r32) sc[kb][qb][i] = -INFINITY;
+            if (key > q_in_tile + 32 * qb + r32) sc[kb][qb][i] = -INFINITY;
           }
     }
-    // ---- online softmax, one query column per lane ----
-    bf16x8 pf[2][4];  // [query block][16-key step]
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      float mloc = sc[0][qb][0];
+    for (int qb = 0; qb < QB; ++qb) {
+      float m = sc[0][qb][0];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mloc = fmaxf(mloc, sc[kb][qb][i]);
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
-      const float mnew = fmaxf(mrow[qb], mloc);
-      const float alpha = __builtin_amdgcn_exp2f(mrow[qb] - mnew);
-      mrow[qb] = mnew;
+        for (int i = 0; i < 16; ++i) m = fmaxf(m, sc[kb][qb][i]);
+      mloc[qb] = half_max(m);
+    }
+  };
+  // P = exp2(S - m) against the current reference maxima, row sums, O^T += V^T P^T
+  auto softmax_pv = [&](int t, f32x16 (&sc)[2][QB]) {
+    const __bf16* smv = sm.v[t & 1];
+    bf16x8 pf[QB][4];  // [query block][16-key step]
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
       float lsum = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const float e = __builtin_amdgcn_exp2f(sc[kb][qb][i] - mnew);
+          const float e = __builtin_amdgcn_exp2f(sc[kb][qb][i] - mrow[qb]);
           sc[kb][qb][i] = e;
           lsum += e;
         }
-      lrow[qb] = lrow[qb] * alpha + lsum;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
+      lrow[qb] += lsum;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         u32x4 w;
@@ -350,30 +372,76 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_mfma_kernel(PrefillPara
         pf[qb][kk] = __builtin_bit_cast(bf16x8, w);
       }
     }
-    // ---- O^T += V^T P^T ----
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const __bf16* vp = sm.v + v_off + 16 * kk * Sm::VS + 32 * db;
+        const __bf16* vp = smv + v_off + 16 * kk * Sm::VS + 32 * db;
         s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
         s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * Sm::VS));
         typedef short s16x8 __attribute__((ext_vector_type(8)));
         s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
         const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
           o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][kk], o[db][qb], 0, 0, 0);
       }
+    }
+  };
+
+  load_tile(0);
+  store_tile(0);
+  if (n_tiles > 1) load_tile(1);
+  __syncthreads();
+  // Every tile iteration ends in exactly one barrier, whichever path a wave takes.  The steady-state loop never touches
+  // the output accumulators with the vector ALU; when a row maximum rises by more than the threshold the wave leaves
+  // the loop, rescales (exact), finishes that tile and re-enters.  Keeping the rescale outside the loop keeps the
+  // accumulator <-> vector register moves out of the steady state.
+  int t = 0;
+  while (t < n_tiles) {
+    bool rescale = false;
+    for (; t < n_tiles; ++t) {
+      stage(t);
+      if (wave_active && t <= t_diag) {
+        f32x16 sc[2][QB];
+        float mloc[QB];
+        scores(t, sc, mloc);
+        bool need = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) need |= mloc[qb] > mrow[qb] + kRescaleThreshold;
+        if (__any(need)) { rescale = true; break; }
+        softmax_pv(t, sc);
+      }
+      __syncthreads();  // tile t+1 is visible; nobody reads buffer t&1 any more
+    }
+    if (!rescale) break;
+    {
+      f32x16 sc[2][QB];
+      float mloc[QB];
+      scores(t, sc, mloc);  // recomputed: cheaper than carrying 64 registers out of the loop
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const float mnew = fmaxf(mrow[qb], mloc[qb]);   // finite: tile 0 holds key 0, visible to every query
+        const float alpha = __builtin_amdgcn_exp2f(mrow[qb] - mnew);
+        mrow[qb] = mnew;
+        lrow[qb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
+      }
+      softmax_pv(t, sc);
+      __syncthreads();
+      ++t;
     }
   }
 
   if (!wave_active) return;
   // ---- epilogue: normalise and store; lane holds d = 32db + 8j + 4hf + (0..3) of query r32 ----
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
+  for (int qb = 0; qb < QB; ++qb) {
     const int qi = qw + 32 * qb + r32;
-    const float ltot = lrow[qb] + __shfl_xor(lrow[qb], 32, kWave);
+    const float ltot = half_sum(lrow[qb]);
     if (qi >= n) continue;
     const float inv = 1.f / ltot;
     __bf16* orow = (__bf16*)p.out + ((long long)(b0 + qi) * p.hq + a) * D + 4 * hf;
@@ -442,8 +510,14 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
     if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
     else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
     dim3 grid(p.hq, batch, (max_seqlen + kBlockRows - 1) / kBlockRows);
-    if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64>), grid, dim3(kPfThreads), 0, stream, p);
-    else hipLaunchKernelGGL((prefill_mfma_kernel<128>), grid, dim3(kPfThreads), 0, stream, p);
+    static const int qb_env = getenv("EARN_PREFILL_QB") ? atoi(getenv("EARN_PREFILL_QB")) : 1;
+    if (qb_env == 2) {
+      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 2>), grid, dim3(256), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 2>), grid, dim3(256), 0, stream, p);
+    } else {
+      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1>), grid, dim3(512), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1>), grid, dim3(512), 0, stream, p);
+    }
   }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
 }
