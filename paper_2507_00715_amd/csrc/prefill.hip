@@ -30,12 +30,13 @@ struct PrefillParams {
   const void* q; const void* k_rot; const void* v; const int32_t* cu; const int32_t* positions;
   void* out; float* lse;
   int batch, hq, hkv, max_seqlen;
+  int n_qblk;  // query blocks of the longest sequence
   float scale_log2;
   RopeTable rope;
 };
 
 // ------------------------------------------------------------------------------------------------------------------
-// K rotation: one thread per (token, kv head, group of 8 rotary pairs)
+// K rotation
 // ------------------------------------------------------------------------------------------------------------------
 template <typename T> struct Vec8;
 template <> struct Vec8<float> {
@@ -62,6 +63,8 @@ template <> struct Vec8<__bf16> {
   }
 };
 
+// One thread per (token, group of 8 rotary pairs): the sin/cos of the group are computed once and applied to every kv
+// head of the token.  bf16 rows use the hardware sin/cos (error ~1e-6, far below bf16 resolution).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T* __restrict__ k_rot,
                                                      const int32_t* __restrict__ cu,
@@ -69,30 +72,39 @@ __global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T*
                                                      int hkv, RopeTable rope) {
   constexpr int G = D / 16;  // groups of 8 pairs per head
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (long long)total * hkv * G) return;
+  if (t >= (long long)total * G) return;
   const int g = (int)(t % G);
-  const long long th = t / G;  // token * hkv + head
-  const int token = (int)(th / hkv);
-  int pos;
-  if (positions) pos = positions[token];
-  else pos = token - cu[find_seq(cu, batch, token)];
-  const T* src = k + th * D + g * 8;
-  T* dst = k_rot + th * D + g * 8;
-  float lo[8], hi[8];
-  Vec8<T>::load(src, lo);
-  Vec8<T>::load(src + D / 2, hi);
+  const int token = (int)(t / G);
+  float sn[8], cs[8];
   if (rope.enabled) {
+    int pos;
+    if (positions) pos = positions[token];
+    else pos = token - cu[find_seq(cu, batch, token)];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      float s, c;
-      sincos_turns_precise(rope_turns((float)pos, rope.hi[g * 8 + i], rope.lo[g * 8 + i]), &s, &c);
-      float a = lo[i], b = hi[i];
-      lo[i] = a * c - b * s;
-      hi[i] = b * c + a * s;
+      const float turns = rope_turns((float)pos, rope.hi[g * 8 + i], rope.lo[g * 8 + i]);
+      if (sizeof(T) == 2) sincos_turns_fast(turns, &sn[i], &cs[i]);
+      else sincos_turns_precise(turns, &sn[i], &cs[i]);
     }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { sn[i] = 0.f; cs[i] = 1.f; }
   }
-  Vec8<T>::store(dst, lo);
-  Vec8<T>::store(dst + D / 2, hi);
+  const T* src = k + (long long)token * hkv * D + g * 8;
+  T* dst = k_rot + (long long)token * hkv * D + g * 8;
+  for (int h = 0; h < hkv; ++h) {
+    float lo[8], hi[8];
+    Vec8<T>::load(src + h * D, lo);
+    Vec8<T>::load(src + h * D + D / 2, hi);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float a = lo[i], b = hi[i];
+      lo[i] = a * cs[i] - b * sn[i];
+      hi[i] = b * cs[i] + a * sn[i];
+    }
+    Vec8<T>::store(dst + h * D, lo);
+    Vec8<T>::store(dst + h * D + D / 2, hi);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -169,6 +181,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
 // bf16 MFMA flash attention
 // ------------------------------------------------------------------------------------------------------------------
 constexpr int kBlockRows = 256;  // query rows per workgroup
+constexpr int kXcds = 8;         // accelerator complex dies, each with a private L2
 constexpr int kTileKeys = 64;    // keys per K/V tile in LDS
 
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
@@ -181,11 +194,11 @@ struct PfSmem {
   __bf16 v[2][kTileKeys * VS];
 };
 
-// Largest rise of a row maximum (log2 units) tolerated before the accumulators are rescaled.  Between rescales the
-// exponentials are taken against a stale maximum, so they can reach 2^8: harmless in fp32 sums and in bf16 operands,
-// and the final normalisation uses the same reference, so the result is the same function.  Rescaling touches all
-// 128 accumulator registers per lane, so doing it only when needed removes most vector-ALU work from the key loop.
-constexpr float kRescaleThreshold = 8.0f;
+// Between rescales the exponentials are taken against a stale row maximum, so they can exceed 1; they are allowed to
+// grow until a lane's partial row sum passes this limit.  That is harmless in fp32 sums and in bf16 operands, and the
+// final normalisation uses the same reference, so the result is the same function.  Rescaling touches every
+// accumulator register of a lane, so doing it only when needed removes most vector-ALU work from the key loop.
+constexpr float kSumLimit = 1024.0f;  // per lane: 32 exponentials of one query row
 
 // max / sum of a value with its partner in the other half of the wave (lane ^ 32), without going through LDS
 __device__ __forceinline__ float half_max(float x) {
@@ -213,12 +226,23 @@ __global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams
   using Sm = PfSmem<D>;
   __shared__ Sm sm;
 
-  const int a = blockIdx.x, s = blockIdx.y;
-  const int qblk = gridDim.z - 1 - blockIdx.z;  // long (late) query blocks are dispatched first
+  // ---- workgroup -> (sequence, kv head, query block, head of the group), XCD aware ----
+  // Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  Id (x, k) = the k-th
+  // workgroup of XCD x.  Each XCD walks its own list of (sequence, kv head) pairs (pair % 8 == x) one pair at a time:
+  // all query blocks of the pair (long, late blocks first) and all query heads of the group, so the workgroups that
+  // are resident on an XCD at any moment stream the SAME K/V rows and find them in that XCD's L2.
+  const int gq = p.hq / p.hkv;
+  const int xcd = blockIdx.x % kXcds, k_in_xcd = blockIdx.x / kXcds;
+  const int per_pair = p.n_qblk * gq;
+  const int pair = (k_in_xcd / per_pair) * kXcds + xcd;
+  if (pair >= p.batch * p.hkv) return;
+  const int rem = k_in_xcd % per_pair;
+  const int qblk = p.n_qblk - 1 - rem / gq;
+  const int s = pair / p.hkv, c = pair % p.hkv;
+  const int a = c * gq + rem % gq;
   const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
   const int q0 = qblk * kBlockRows;
   if (q0 >= n) return;
-  const int c = a / (p.hq / p.hkv);
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int r32 = lane & 31, hf = lane >> 5;
   const int qw = q0 + wave * kWaveRows;          // first query row of this wave
@@ -277,14 +301,31 @@ __global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams
 
   // ---- tile staging: global -> registers -> LDS ----
   u32x4 kreg[UNITS], vreg[UNITS];
-  auto load_tile = [&](int t) {
+  // element offset of this thread's units inside tile 0; a tile step adds kTileKeys * kv_stride
+  long long unit_off[UNITS];
 #pragma unroll
-    for (int i = 0; i < UNITS; ++i) {
-      const int u = i * kPfThreads + threadIdx.x;
-      const int row = u / UPR, cu8 = u % UPR;
-      const int key = min(t * kTileKeys + row, n - 1);  // rows past the sequence end repeat the last row (finite data)
-      kreg[i] = *(const u32x4*)(Kg + key * kv_stride + cu8 * 8);
-      vreg[i] = *(const u32x4*)(Vg + key * kv_stride + cu8 * 8);
+  for (int i = 0; i < UNITS; ++i) {
+    const int u = i * kPfThreads + threadIdx.x;
+    unit_off[i] = (u / UPR) * kv_stride + (u % UPR) * 8;
+  }
+  const int full_tiles = n / kTileKeys;  // tiles whose 64 rows all exist
+  auto load_tile = [&](int t) {
+    if (t < full_tiles) {
+      const long long base = (long long)t * kTileKeys * kv_stride;
+#pragma unroll
+      for (int i = 0; i < UNITS; ++i) {
+        kreg[i] = *(const u32x4*)(Kg + base + unit_off[i]);
+        vreg[i] = *(const u32x4*)(Vg + base + unit_off[i]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < UNITS; ++i) {
+        const int u = i * kPfThreads + threadIdx.x;
+        const int row = u / UPR, cu8 = u % UPR;
+        const int key = min(t * kTileKeys + row, n - 1);  // rows past the sequence end repeat the last row (finite data)
+        kreg[i] = *(const u32x4*)(Kg + key * kv_stride + cu8 * 8);
+        vreg[i] = *(const u32x4*)(Vg + key * kv_stride + cu8 * 8);
+      }
     }
   };
   auto store_tile = [&](int buf) {
@@ -303,13 +344,26 @@ __global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams
 
   // ---- pieces of one key-tile iteration ----
   auto stage = [&](int t) {
+#if defined(EARN_DBG_NOSTAGE)
+    return;
+#endif
     // tile t+1 goes to the other buffer (last read in iteration t-1, which every wave has left), tile t+2 into registers
     if (t + 1 < n_tiles) store_tile((t & 1) ^ 1);
     if (t + 2 < n_tiles) load_tile(t + 2);
   };
-  // S^T = K Q^T for tile t, causal mask on the diagonal tile, row maxima of the tile
-  auto scores = [&](int t, f32x16 (&sc)[2][QB], float (&mloc)[QB]) {
+  // S^T = K Q^T for tile t, causal mask on the diagonal tile.  All 2*KSTEPS K fragments are requested from LDS before
+  // the first MFMA (and before `staging`, the global->LDS traffic of later tiles), so the MFMAs wait on a draining
+  // queue instead of paying one LDS round trip each.
+  auto scores = [&](int t, f32x16 (&sc)[2][QB], bool do_stage) {
     const __bf16* smk = sm.k[t & 1];
+    bf16x8 kf[2][KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) kf[kb][ks] = *(const bf16x8*)(smk + k_off + kb * 32 * Sm::KS + 16 * ks);
+    __builtin_amdgcn_sched_barrier(0);
+    if (do_stage) stage(t);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -317,15 +371,12 @@ __global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams
 #pragma unroll
         for (int i = 0; i < 16; ++i) sc[kb][qb][i] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
+    for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8 kf = *(const bf16x8*)(smk + k_off + kb * 32 * Sm::KS + 16 * ks);
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
-          sc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sc[kb][qb], 0, 0, 0);
-      }
-    }
+          sc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qb][ks], sc[kb][qb], 0, 0, 0);
     if (t == t_diag) {  // keys beyond the sequence end are beyond every valid query too
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -337,32 +388,49 @@ __global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams
             if (key > q_in_tile + 32 * qb + r32) sc[kb][qb][i] = -INFINITY;
           }
     }
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      float m = sc[0][qb][0];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) m = fmaxf(m, sc[kb][qb][i]);
-      mloc[qb] = half_max(m);
-    }
   };
-  // P = exp2(S - m) against the current reference maxima, row sums, O^T += V^T P^T
-  auto softmax_pv = [&](int t, f32x16 (&sc)[2][QB]) {
-    const __bf16* smv = sm.v[t & 1];
-    bf16x8 pf[QB][4];  // [query block][16-key step]
+  // P = exp2(S - m) against the current reference maxima (in place) and the lane's share of the row sums
+  auto exponentials = [&](f32x16 (&sc)[2][QB], float (&lsum)[QB]) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      float lsum = 0.f;
+      lsum[qb] = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
+#if defined(EARN_DBG_NOEXP)
+          const float e = sc[kb][qb][i] * 1e-30f;
+#else
           const float e = __builtin_amdgcn_exp2f(sc[kb][qb][i] - mrow[qb]);
+#endif
           sc[kb][qb][i] = e;
-          lsum += e;
+          lsum[qb] += e;
         }
-      lrow[qb] += lsum;
+    }
+  };
+  // V^T fragments of tile t (A operands of the second product): requested before the exponentials so that the LDS
+  // latency hides behind the vector-ALU work
+  auto fetch_v = [&](int t, bf16x8 (&vf)[4][DB]) {
+    const __bf16* smv = sm.v[t & 1];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const __bf16* vp = smv + v_off + 16 * kk * Sm::VS + 32 * db;
+        s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
+        s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * Sm::VS));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+        vf[kk][db] = __builtin_bit_cast(bf16x8, vv);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // row sums, O^T += V^T P^T
+  auto accumulate = [&](f32x16 (&sc)[2][QB], float (&lsum)[QB], bf16x8 (&vf)[4][DB]) {
+    bf16x8 pf[QB][4];  // [query block][16-key step]
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      lrow[qb] += lsum[qb];
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         u32x4 w;
@@ -373,55 +441,61 @@ __global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams
       }
     }
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const __bf16* vp = smv + v_off + 16 * kk * Sm::VS + 32 * db;
-        s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
-        s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * Sm::VS));
-        typedef short s16x8 __attribute__((ext_vector_type(8)));
-        s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
-          o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][kk], o[db][qb], 0, 0, 0);
-      }
-    }
+          o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[qb][kk], o[db][qb], 0, 0, 0);
   };
 
   load_tile(0);
   store_tile(0);
   if (n_tiles > 1) load_tile(1);
   __syncthreads();
-  // Every tile iteration ends in exactly one barrier, whichever path a wave takes.  The steady-state loop never touches
-  // the output accumulators with the vector ALU; when a row maximum rises by more than the threshold the wave leaves
-  // the loop, rescales (exact), finishes that tile and re-enters.  Keeping the rescale outside the loop keeps the
-  // accumulator <-> vector register moves out of the steady state.
+  // Every tile iteration ends in exactly one barrier, whichever path a wave takes.  The steady-state loop takes the
+  // exponentials against the reference maxima it already has and never touches the output accumulators with the
+  // vector ALU.  It does not even compute row maxima: a reference is stale exactly when some exponential is large, so
+  // the (already needed) partial row sums are compared with kSumLimit instead; +inf and NaN (first tile, reference
+  // still -inf) fail the comparison too.  A wave that fails leaves the loop, recomputes the tile's scores, takes the
+  // exact maxima, rescales, finishes the tile and re-enters.
   int t = 0;
   while (t < n_tiles) {
     bool rescale = false;
     for (; t < n_tiles; ++t) {
-      stage(t);
       if (wave_active && t <= t_diag) {
         f32x16 sc[2][QB];
-        float mloc[QB];
-        scores(t, sc, mloc);
-        bool need = false;
+        float lsum[QB];
+        bf16x8 vf[4][DB];
+        scores(t, sc, true);
+        fetch_v(t, vf);
+        exponentials(sc, lsum);
+        bool stale = false;
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) need |= mloc[qb] > mrow[qb] + kRescaleThreshold;
-        if (__any(need)) { rescale = true; break; }
-        softmax_pv(t, sc);
+        for (int qb = 0; qb < QB; ++qb) stale |= !(lsum[qb] <= kSumLimit);
+        if (__any(stale)) { rescale = true; break; }
+        accumulate(sc, lsum, vf);
+      } else {
+        stage(t);
       }
+#if !defined(EARN_DBG_NOBARRIER)
       __syncthreads();  // tile t+1 is visible; nobody reads buffer t&1 any more
+#endif
     }
     if (!rescale) break;
     {
       f32x16 sc[2][QB];
-      float mloc[QB];
-      scores(t, sc, mloc);  // recomputed: cheaper than carrying 64 registers out of the loop
+      float lsum[QB];
+      bf16x8 vf[4][DB];
+      scores(t, sc, false);  // the tile was staged before the wave left the loop
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        const float mnew = fmaxf(mrow[qb], mloc[qb]);   // finite: tile 0 holds key 0, visible to every query
+        float m = sc[0][qb][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) m = fmaxf(m, sc[kb][qb][i]);
+        const float mnew = fmaxf(mrow[qb], half_max(m));  // finite: tile 0 holds key 0, visible to every query
         const float alpha = __builtin_amdgcn_exp2f(mrow[qb] - mnew);
         mrow[qb] = mnew;
         lrow[qb] *= alpha;
@@ -430,7 +504,9 @@ __global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams
 #pragma unroll
           for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
       }
-      softmax_pv(t, sc);
+      fetch_v(t, vf);
+      exponentials(sc, lsum);
+      accumulate(sc, lsum, vf);
       __syncthreads();
       ++t;
     }
@@ -470,7 +546,7 @@ size_t prefill_workspace_bytes(const earn_attn_desc* desc, int total_tokens, int
 template <typename T, int D>
 static void launch_rope_k(const void* k, void* k_rot, const int32_t* cu, const int32_t* positions, int batch, int total,
                           int hkv, const RopeTable& rope, hipStream_t stream) {
-  long long threads = (long long)total * hkv * (D / 16);
+  long long threads = (long long)total * (D / 16);
   hipLaunchKernelGGL((rope_k_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
                      (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope);
 }
@@ -509,7 +585,9 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
   } else {
     if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
     else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
-    dim3 grid(p.hq, batch, (max_seqlen + kBlockRows - 1) / kBlockRows);
+    p.n_qblk = (max_seqlen + kBlockRows - 1) / kBlockRows;
+    const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
+    dim3 grid((unsigned)(pairs8 * p.n_qblk * (p.hq / p.hkv)), 1, 1);
     static const int qb_env = getenv("EARN_PREFILL_QB") ? atoi(getenv("EARN_PREFILL_QB")) : 1;
     if (qb_env == 2) {
       if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 2>), grid, dim3(256), 0, stream, p);
