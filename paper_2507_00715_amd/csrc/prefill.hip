@@ -180,7 +180,6 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
 // ------------------------------------------------------------------------------------------------------------------
 // bf16 MFMA flash attention
 // ------------------------------------------------------------------------------------------------------------------
-constexpr int kBlockRows = 256;  // query rows per workgroup
 constexpr int kXcds = 8;         // accelerator complex dies, each with a private L2
 constexpr int kTileKeys = 64;    // keys per K/V tile in LDS
 
@@ -215,10 +214,14 @@ __device__ __forceinline__ float half_sum(float x) {
 //   QB = 1: 8 waves, two per SIMD (<= 256 registers per lane): while one wave of a SIMD runs its softmax on the
 //           vector ALU the other keeps the matrix core busy; LDS traffic per MFMA doubles (fits: LDS reads run at
 //           256 B/clk per CU on this part).
-template <int D, int QB>
-__global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams p) {
-  constexpr int kPfThreads = 512 / QB;
+// WAVES = waves per workgroup.  8 (or 4 with QB = 2) gives 256 query rows per workgroup; WAVES = 4 with QB = 1 gives
+// 128-row workgroups, two of which share a CU: less idle time on the causal diagonal of short sequences, at the price
+// of staging every K/V tile twice as often.
+template <int D, int QB, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES == 4) ? 2 : 1) void prefill_mfma_kernel(PrefillParams p) {
+  constexpr int kPfThreads = 64 * WAVES;
   constexpr int kWaveRows = 32 * QB;
+  constexpr int kBlockRows = kWaveRows * WAVES;
   constexpr int KSTEPS = D / 16;         // MFMA k-steps over head_dim for S^T
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int UPR = D / 8;             // 16-byte units per K/V row
@@ -255,6 +258,37 @@ __global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams
   const __bf16* Kg = (const __bf16*)p.k_rot + ((long long)b0 * p.hkv + c) * D;
   const __bf16* Vg = (const __bf16*)p.v + ((long long)b0 * p.hkv + c) * D;
   const long long kv_stride = (long long)p.hkv * D;
+
+  // ---- tile staging: global -> registers -> LDS ----
+  u32x4 kreg[UNITS], vreg[UNITS];
+  // element offset of this thread's units inside tile 0; a tile step adds kTileKeys * kv_stride
+  long long unit_off[UNITS];
+#pragma unroll
+  for (int i = 0; i < UNITS; ++i) {
+    const int u = i * kPfThreads + threadIdx.x;
+    unit_off[i] = (u / UPR) * kv_stride + (u % UPR) * 8;
+  }
+  const int full_tiles = n / kTileKeys;  // tiles whose 64 rows all exist
+  auto load_tile = [&](int t) {
+    if (t < full_tiles) {
+      const long long base = (long long)t * kTileKeys * kv_stride;
+#pragma unroll
+      for (int i = 0; i < UNITS; ++i) {
+        kreg[i] = *(const u32x4*)(Kg + base + unit_off[i]);
+        vreg[i] = *(const u32x4*)(Vg + base + unit_off[i]);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < UNITS; ++i) {
+        const int u = i * kPfThreads + threadIdx.x;
+        const int row = u / UPR, cu8 = u % UPR;
+        const int key = min(t * kTileKeys + row, n - 1);  // rows past the sequence end repeat the last row (finite data)
+        kreg[i] = *(const u32x4*)(Kg + key * kv_stride + cu8 * 8);
+        vreg[i] = *(const u32x4*)(Vg + key * kv_stride + cu8 * 8);
+      }
+    }
+  };
+  load_tile(0);  // in flight while the queries are loaded and rotated
 
   // ---- Q fragments: rotate at the original position, fold in scale*log2(e), keep as bf16 B operands ----
   bf16x8 qf[QB][KSTEPS];
@@ -299,35 +333,6 @@ __global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) { mrow[qb] = -INFINITY; lrow[qb] = 0.f; }
 
-  // ---- tile staging: global -> registers -> LDS ----
-  u32x4 kreg[UNITS], vreg[UNITS];
-  // element offset of this thread's units inside tile 0; a tile step adds kTileKeys * kv_stride
-  long long unit_off[UNITS];
-#pragma unroll
-  for (int i = 0; i < UNITS; ++i) {
-    const int u = i * kPfThreads + threadIdx.x;
-    unit_off[i] = (u / UPR) * kv_stride + (u % UPR) * 8;
-  }
-  const int full_tiles = n / kTileKeys;  // tiles whose 64 rows all exist
-  auto load_tile = [&](int t) {
-    if (t < full_tiles) {
-      const long long base = (long long)t * kTileKeys * kv_stride;
-#pragma unroll
-      for (int i = 0; i < UNITS; ++i) {
-        kreg[i] = *(const u32x4*)(Kg + base + unit_off[i]);
-        vreg[i] = *(const u32x4*)(Vg + base + unit_off[i]);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < UNITS; ++i) {
-        const int u = i * kPfThreads + threadIdx.x;
-        const int row = u / UPR, cu8 = u % UPR;
-        const int key = min(t * kTileKeys + row, n - 1);  // rows past the sequence end repeat the last row (finite data)
-        kreg[i] = *(const u32x4*)(Kg + key * kv_stride + cu8 * 8);
-        vreg[i] = *(const u32x4*)(Vg + key * kv_stride + cu8 * 8);
-      }
-    }
-  };
   auto store_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < UNITS; ++i) {
@@ -449,7 +454,6 @@ __global__ __launch_bounds__(512 / QB, 1) void prefill_mfma_kernel(PrefillParams
           o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[qb][kk], o[db][qb], 0, 0, 0);
   };
 
-  load_tile(0);
   store_tile(0);
   if (n_tiles > 1) load_tile(1);
   __syncthreads();
@@ -585,16 +589,17 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
   } else {
     if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
     else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
-    p.n_qblk = (max_seqlen + kBlockRows - 1) / kBlockRows;
+    static const int rows_env = getenv("EARN_PREFILL_ROWS") ? atoi(getenv("EARN_PREFILL_ROWS")) : 0;
+    const int block_rows = rows_env ? rows_env : (max_seqlen <= 1280 ? 128 : 256);
+    p.n_qblk = (max_seqlen + block_rows - 1) / block_rows;
     const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
     dim3 grid((unsigned)(pairs8 * p.n_qblk * (p.hq / p.hkv)), 1, 1);
-    static const int qb_env = getenv("EARN_PREFILL_QB") ? atoi(getenv("EARN_PREFILL_QB")) : 1;
-    if (qb_env == 2) {
-      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 2>), grid, dim3(256), 0, stream, p);
-      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 2>), grid, dim3(256), 0, stream, p);
+    if (block_rows == 128) {
+      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 4>), grid, dim3(256), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 4>), grid, dim3(256), 0, stream, p);
     } else {
-      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1>), grid, dim3(512), 0, stream, p);
-      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1>), grid, dim3(512), 0, stream, p);
+      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 8>), grid, dim3(512), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 8>), grid, dim3(512), 0, stream, p);
     }
   }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
