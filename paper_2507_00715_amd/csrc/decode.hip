@@ -10,6 +10,8 @@
 //     across the 4 waves;
 //   * the key range of a long cache is split over several workgroups (split-K); partial (max, sum, out) triples go to
 //     the workspace and a second kernel merges them.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace earn {
@@ -102,7 +104,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams p) {
     for (int i = 0; i < 8; ++i) {
       if (p.rope.enabled) {
         float t = rope_turns(pos, p.rope.hi[e0 + i], p.rope.lo[e0 + i]);
-        sincos_turns_precise(t, &sn[i], &cs[i]);
+        if (sizeof(T) == 2) sincos_turns_fast(t, &sn[i], &cs[i]);   // hardware sin/cos: error far below bf16 resolution
+        else sincos_turns_precise(t, &sn[i], &cs[i]);
       } else { cs[i] = 1.f; sn[i] = 0.f; }
     }
   }
@@ -273,12 +276,19 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const float* __rest
 // heads of the group times the W beams of the sequence — form the M columns of S^T = K Q^T, so the shared K/V rows are
 // streamed from HBM ONCE per sequence, not once per beam or per query head.  Same register-level scheme as the prefill
 // kernel (S^T accumulators feed V^T P^T directly; V^T fragments come from transposing LDS reads), without a mask.
-// The 4 waves of a workgroup walk disjoint 32-key tiles of the workgroup's key range with private LDS staging and
-// private softmax states, which are merged through LDS at the end; key ranges of long caches are split over
-// workgroups and every (row, split) partial goes to the workspace.  The per-stream generated rows and the new token
-// are handled by decode_kernel in gen_only mode (they differ per beam, so they are not a shared matrix product).
+//
+// A workgroup has C groups of 4 waves; group g serves query rows [32g, 32g+32) of the cache (C = 2 covers the 40 rows of
+// 4 grouped heads x 10 beams) at <= 256 registers per wave, i.e. two waves per SIMD.  The workgroup walks its key range
+// in super-tiles of 128 keys that ALL its threads stage together (global -> registers -> LDS, double buffered, the
+// next-but-one super-tile in flight), so every K/V byte is fetched once; wave `sub` of each group works on the 32-key
+// sub-tile `sub` with a private softmax state, and the 4 states of a group are merged through LDS at the end.
+// Key ranges of long caches are split over workgroups; every (row, split) partial goes to the workspace.  The
+// per-stream generated rows and the new token differ per beam and are handled by decode_kernel in gen_only mode.
 // ------------------------------------------------------------------------------------------------------------------
-constexpr int kDsTile = 32;              // keys per wave tile
+constexpr int kDsTile = 32;              // keys per wave sub-tile
+constexpr int kDsGroupWaves = 4;         // waves per 32-row group = sub-tiles per super-tile
+constexpr int kDsSuper = kDsTile * kDsGroupWaves;  // keys per super-tile
+constexpr float kDecSumLimit = 512.0f;   // per lane: 16 exponentials of one query row
 constexpr int kMaxStreamsPerSeq = 1024;  // beams of one sequence the stream list holds
 
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
@@ -287,30 +297,34 @@ template <int D>
 struct DsSmem {
   static constexpr int KS = D + 8;
   static constexpr int VS = D + 32;
-  struct WaveTile { __bf16 k[kDsTile * KS]; __bf16 v[kDsTile * VS]; };
-  WaveTile tile[kDecWaves];   // reused as the merge buffer once the key loop is done
+  struct SubTile { __bf16 k[kDsTile * KS]; __bf16 v[kDsTile * VS]; };
+  SubTile tile[2][kDsGroupWaves];   // [stage][sub-tile]; reused as the merge buffers once the key loop is done
   int streams[kMaxStreamsPerSeq];
   int n_streams_of_seq;
 };
 
-template <int D, int QB>
-__global__ __launch_bounds__(kDecThreads, 1) void decode_shared_mfma_kernel(DecodeParams p) {
+template <int D, int C>
+__global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodeParams p) {
+  constexpr int THREADS = 256 * C;
   constexpr int KSTEPS = D / 16, DB = D / 32, UPR = D / 8;
-  constexpr int UNITS = kDsTile * UPR / kWave;  // 16-byte units per lane per tile and tensor
-  constexpr int ROWS = 32 * QB;
-  constexpr int STATE = DB * QB * 16 + 2 * QB;  // floats per lane in a merge
+  constexpr int UNITS = kDsSuper * UPR / THREADS;  // 16-byte units per thread per super-tile and tensor
+  constexpr int RPU = THREADS / UPR;               // rows between consecutive units of a thread
+  constexpr int ROWS = 32 * C;
+  constexpr int STATE = DB * 16 + 2;               // floats per lane in a merge
   using Sm = DsSmem<D>;
-  static_assert(sizeof(typename Sm::WaveTile) * kDecWaves >= 2 * STATE * kWave * sizeof(float), "merge buffer");
+  static_assert(sizeof(Sm::tile) >= (size_t)C * 2 * STATE * kWave * sizeof(float), "merge buffers");
   __shared__ Sm sm;
 
   const int c = blockIdx.x, s = blockIdx.y, z = blockIdx.z;
   const int gq = p.hq / p.hkv;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int grp = wave / kDsGroupWaves, sub = wave % kDsGroupWaves;
   const int r32 = lane & 31, hf = lane >> 5;
   const int b0 = p.shared_cu[s], ns = p.shared_cu[s + 1] - b0;
   const int j_begin = z * p.chunk;
   const int j_end = min(ns, j_begin + p.chunk);
-  const int n_tiles = j_end > j_begin ? (j_end - j_begin + kDsTile - 1) / kDsTile : 0;
+  const int n_keys = max(j_end - j_begin, 0);
+  const int n_super = (n_keys + kDsSuper - 1) / kDsSuper;
 
   // ---- streams (beams) of this sequence, ascending ----
   if (wave == 0) {
@@ -337,21 +351,29 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_shared_mfma_kernel(Deco
   const __bf16* Kg = (const __bf16*)p.shared_k + ((long long)b0 * p.hkv + c) * D;
   const __bf16* Vg = (const __bf16*)p.shared_v + ((long long)b0 * p.hkv + c) * D;
   const long long kv_stride = (long long)p.hkv * D;
-  __bf16* my_k = sm.tile[wave].k;
-  __bf16* my_v = sm.tile[wave].v;
   const int k_off = r32 * Sm::KS + 8 * hf;
   const int v_off = (4 * hf + ((lane & 15) >> 2)) * Sm::VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  float* mbuf = (float*)&sm.tile[0];
+  float* mbuf = (float*)&sm.tile[0][0] + (size_t)grp * 2 * STATE * kWave;
+  // staging: unit i of this thread is row (tid / UPR + i * RPU) of the super-tile, 16-byte column tid % UPR.
+  // Loads go through buffer descriptors that cover exactly the rows of this workgroup's key range: one vector register
+  // holds the per-thread byte offset, everything else of the address is scalar, and rows past the end of the range
+  // read as zeros (no clamping code, finite data for the masked tail).
+  const int st_row0 = threadIdx.x / UPR, st_col = threadIdx.x % UPR;
+  const int row_bytes = (int)kv_stride * 2;
+  const int st_voff = st_row0 * row_bytes + st_col * 16;
+  const int range_bytes = n_keys > 0 ? (n_keys - 1) * row_bytes + D * 2 : 0;
+  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(Kg + j_begin * kv_stride), 0, range_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(Vg + j_begin * kv_stride), 0, range_bytes, 0x00020000);
 
   for (int row0 = 0; row0 < M; row0 += ROWS) {
-    // ---- Q fragments of rows row0 .. row0+ROWS-1: row m -> (stream list[m / gq], head c*gq + m % gq) ----
-    bf16x8 qf[QB][KSTEPS];
-    int row_u[QB], row_a[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      const int m = min(row0 + 32 * qb + r32, M - 1);
+    // ---- Q fragments of this group's rows: row m -> (stream list[m / gq], head c*gq + m % gq) ----
+    const bool grp_active = row0 + 32 * grp < M;
+    bf16x8 qf[KSTEPS];
+    int row_u, row_a;
+    {
+      const int m = min(row0 + 32 * grp + r32, M - 1);
       const int u = sm.streams[m / gq], a = c * gq + m % gq;
-      row_u[qb] = u; row_a[qb] = a;
+      row_u = u; row_a = a;
       const float pos = (float)p.q_pos[u];
       const __bf16* qrow = (const __bf16*)p.q + ((long long)u * p.hq + a) * D + 8 * hf;
 #pragma unroll
@@ -367,106 +389,95 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_shared_mfma_kernel(Deco
           for (int jj = 0; jj < 2; ++jj) {
             float sn = 0.f, cs = 1.f;
             const int e = 16 * ks + 8 * hf + j + jj;
-            if (p.rope.enabled) sincos_turns_precise(rope_turns(pos, p.rope.hi[e], p.rope.lo[e]), &sn, &cs);
+            if (p.rope.enabled) sincos_turns_fast(rope_turns(pos, p.rope.hi[e], p.rope.lo[e]), &sn, &cs);
             x[jj] = (lo[j + jj] * cs - hi[j + jj] * sn) * p.scale_log2;
             y[jj] = (hi[j + jj] * cs + lo[j + jj] * sn) * p.scale_log2;
           }
           wl[j / 2] = pack_bf16(x[0], x[1]);
           wh[j / 2] = pack_bf16(y[0], y[1]);
         }
-        qf[qb][ks] = __builtin_bit_cast(bf16x8, wl);
-        qf[qb][ks + KSTEPS / 2] = __builtin_bit_cast(bf16x8, wh);
+        qf[ks] = __builtin_bit_cast(bf16x8, wl);
+        qf[ks + KSTEPS / 2] = __builtin_bit_cast(bf16x8, wh);
       }
     }
 
-    f32x16 o[DB][QB];
+    f32x16 o[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][qb][i] = 0.f;
-    float mrow[QB], lrow[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) { mrow[qb] = -INFINITY; lrow[qb] = 0.f; }
+      for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+    float mrow = -INFINITY, lrow = 0.f;
 
-    u32x4 kreg[UNITS], vreg[UNITS];
-    auto load_tile = [&](int t) {
+    // two register sets: super-tiles it+2 and it+3 are in flight while super-tile it is being used (the stream is
+    // bound by HBM latency times bytes in flight, so the depth matters more than anything else here)
+    u32x4 kreg[2][UNITS], vreg[2][UNITS];
+    auto load_super = [&](int it, u32x4 (&kr)[UNITS], u32x4 (&vr)[UNITS]) {
 #pragma unroll
       for (int i = 0; i < UNITS; ++i) {
-        const int un = i * kWave + lane;
-        const int row = un / UPR, cu8 = un % UPR;
-        const int key = min(j_begin + t * kDsTile + row, j_end - 1);  // tail rows repeat the last valid row
-        kreg[i] = *(const u32x4*)(Kg + key * kv_stride + cu8 * 8);
-        vreg[i] = *(const u32x4*)(Vg + key * kv_stride + cu8 * 8);
+        const int soff = (it * kDsSuper + i * RPU) * row_bytes;  // scalar part of the address
+        kr[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, st_voff, soff, 0);
+        vr[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, st_voff, soff, 0);
       }
     };
-    if (wave < n_tiles) load_tile(wave);
-    for (int t = wave; t < n_tiles; t += kDecWaves) {
-      // wave-private staging: LDS operations of one wave execute in order, the fences only pin the compiler
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    auto store_super = [&](int stage, u32x4 (&kr)[UNITS], u32x4 (&vr)[UNITS]) {
 #pragma unroll
       for (int i = 0; i < UNITS; ++i) {
-        const int un = i * kWave + lane;
-        const int row = un / UPR, cu8 = un % UPR;
-        *(u32x4*)(my_k + row * Sm::KS + cu8 * 8) = kreg[i];
-        *(u32x4*)(my_v + row * Sm::VS + cu8 * 8) = vreg[i];
+        const int row = st_row0 + i * RPU;
+        typename Sm::SubTile& tl = sm.tile[stage][row / kDsTile];
+        *(u32x4*)(tl.k + (row % kDsTile) * Sm::KS + st_col * 8) = kr[i];
+        *(u32x4*)(tl.v + (row % kDsTile) * Sm::VS + st_col * 8) = vr[i];
       }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      if (t + kDecWaves < n_tiles) load_tile(t + kDecWaves);
-
-      f32x16 sc[QB];
+    };
+    // super-tile it+1 (register set (it+1)&1) goes to the other LDS stage (last read in iteration it-1); that
+    // register set is then reloaded with super-tile it+3
+    auto stage_next = [&](int it) {
+      if ((it + 1) & 1) {
+        if (it + 1 < n_super) store_super(1, kreg[1], vreg[1]);
+        if (it + 3 < n_super) load_super(it + 3, kreg[1], vreg[1]);
+      } else {
+        if (it + 1 < n_super) store_super(0, kreg[0], vreg[0]);
+        if (it + 3 < n_super) load_super(it + 3, kreg[0], vreg[0]);
+      }
+    };
+    // S^T = K Q^T of this wave's sub-tile; keys past the range end get zero weight
+    auto scores = [&](int it, f32x16& sc) {
+      const __bf16* my_k = sm.tile[it & 1][sub].k;
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sc[qb][i] = 0.f;
+      for (int i = 0; i < 16; ++i) sc[i] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
         const bf16x8 kf = *(const bf16x8*)(my_k + k_off + 16 * ks);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) sc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][ks], sc[qb], 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sc, 0, 0, 0);
       }
-      const int key0 = j_begin + t * kDsTile;
-      if (key0 + kDsTile > j_end) {  // ragged last tile: keys past the range get zero weight
+      const int key0 = j_begin + it * kDsSuper + sub * kDsTile;
+      if (key0 + kDsTile > j_end) {
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            if (key0 + 8 * (i >> 2) + 4 * hf + (i & 3) >= j_end) sc[qb][i] = -INFINITY;
+        for (int i = 0; i < 16; ++i)
+          if (key0 + 8 * (i >> 2) + 4 * hf + (i & 3) >= j_end) sc[i] = -INFINITY;
       }
-      bf16x8 pf[QB][2];
+    };
+    auto exponentials = [&](f32x16& sc, float& lsum) {
+      lsum = 0.f;
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        float mloc = sc[qb][0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, sc[qb][i]);
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
-        const float mnew = fmaxf(mrow[qb], mloc);   // finite: every tile holds at least one valid key
-        const float alpha = __builtin_amdgcn_exp2f(mrow[qb] - mnew);
-        mrow[qb] = mnew;
-        float lsum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float e = __builtin_amdgcn_exp2f(sc[qb][i] - mnew);
-          sc[qb][i] = e;
-          lsum += e;
-        }
-        lrow[qb] = lrow[qb] * alpha + lsum;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-          u32x4 w;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) w[j] = pack_bf16(sc[qb][8 * kk + 2 * j], sc[qb][8 * kk + 2 * j + 1]);
-          pf[qb][kk] = __builtin_bit_cast(bf16x8, w);
-        }
+      for (int i = 0; i < 16; ++i) {
+        const float e = __builtin_amdgcn_exp2f(sc[i] - mrow);
+        sc[i] = e;
+        lsum += e;
       }
+    };
+    auto accumulate = [&](int it, f32x16& sc, float lsum) {
+      const __bf16* my_v = sm.tile[it & 1][sub].v;
+      bf16x8 pf[2];
+      lrow += lsum;
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
+        u32x4 w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = pack_bf16(sc[8 * kk + 2 * j], sc[8 * kk + 2 * j + 1]);
+        pf[kk] = __builtin_bit_cast(bf16x8, w);
+      }
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
           const __bf16* vp = my_v + v_off + 16 * kk * Sm::VS + 32 * db;
@@ -474,77 +485,116 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_shared_mfma_kernel(Deco
           s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * Sm::VS));
           typedef short s16x8 __attribute__((ext_vector_type(8)));
           s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-            o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][kk], o[db][qb], 0, 0, 0);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf[kk], o[db], 0, 0, 0);
         }
+    };
+    // does this wave have keys in super-tile `it`?
+    auto has_keys = [&](int it) {
+#if defined(EARN_DBG_DEC_NOCOMPUTE)
+      return false;
+#endif
+      return grp_active && it * kDsSuper + sub * kDsTile < n_keys;
+    };
+
+    // Every super-tile iteration ends in exactly one barrier, whichever path a wave takes.  The steady-state loop
+    // takes exponentials against the reference maximum it has and never touches the output accumulators with the
+    // vector ALU; a reference is stale exactly when some exponential is large, which shows in the partial row sums
+    // (+inf / NaN on the first tile, whose reference is -inf).  A wave that sees a stale reference leaves the loop,
+    // takes the exact maxima of the tile, rescales, finishes the tile and re-enters.
+    if (n_super > 0) load_super(0, kreg[0], vreg[0]);
+    if (n_super > 1) load_super(1, kreg[1], vreg[1]);
+    if (n_super > 0) store_super(0, kreg[0], vreg[0]);
+    if (n_super > 2) load_super(2, kreg[0], vreg[0]);
+    __syncthreads();
+    int it = 0;
+    while (it < n_super) {
+      bool rescale = false;
+      for (; it < n_super; ++it) {
+        stage_next(it);
+        if (has_keys(it)) {
+          f32x16 sc;
+          float lsum;
+          scores(it, sc);
+          exponentials(sc, lsum);
+          if (__any(!(lsum <= kDecSumLimit))) { rescale = true; break; }
+          accumulate(it, sc, lsum);
+        }
+        __syncthreads();
       }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
+      if (!rescale) break;
+      {
+        f32x16 sc;
+        float lsum;
+        scores(it, sc);  // the tile is still staged
+        float m = sc[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) m = fmaxf(m, sc[i]);
+        m = fmaxf(m, __shfl_xor(m, 32, kWave));
+        const float mnew = fmaxf(mrow, m);   // finite: a sub-tile with keys holds at least one valid key
+        const float alpha = __builtin_amdgcn_exp2f(mrow - mnew);
+        mrow = mnew;
+        lrow *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+        exponentials(sc, lsum);
+        accumulate(it, sc, lsum);
+        __syncthreads();
+        ++it;
+      }
     }
 
-    // ---- merge the 4 waves: (2,3) -> (0,1), then 1 -> 0; lane-wise, the layouts are identical ----
+    // ---- merge the 4 waves of the group: (2,3) -> (0,1), then 1 -> 0; lane-wise, the layouts are identical ----
     auto put = [&](int slot) {
       float* dst = mbuf + (size_t)slot * STATE * kWave + lane;
       int r = 0;
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) { dst[(r++) * kWave] = mrow[qb]; dst[(r++) * kWave] = lrow[qb]; }
+      dst[(r++) * kWave] = mrow;
+      dst[(r++) * kWave] = lrow;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) dst[(r++) * kWave] = o[db][qb][i];
+        for (int i = 0; i < 16; ++i) dst[(r++) * kWave] = o[db][i];
     };
     auto take = [&](int slot) {
       const float* src = mbuf + (size_t)slot * STATE * kWave + lane;
-      float a[QB], b[QB];
       int r = 0;
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const float m2 = src[(r++) * kWave], l2 = src[(r++) * kWave];
-        const float mn = fmaxf(mrow[qb], m2);
-        a[qb] = mrow[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mrow[qb] - mn);
-        b[qb] = m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - mn);
-        lrow[qb] = lrow[qb] * a[qb] + l2 * b[qb];
-        mrow[qb] = mn;
-      }
+      const float m2 = src[(r++) * kWave], l2 = src[(r++) * kWave];
+      const float mn = fmaxf(mrow, m2);
+      const float a = mrow == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mrow - mn);
+      const float b = m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - mn);
+      lrow = lrow * a + l2 * b;
+      mrow = mn;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o[db][qb][i] = o[db][qb][i] * a[qb] + src[(r++) * kWave] * b[qb];
+        for (int i = 0; i < 16; ++i) o[db][i] = o[db][i] * a + src[(r++) * kWave] * b;
     };
+    if (sub >= 2) put(sub - 2);   // the last loop barrier has passed: nobody reads tile memory any more
     __syncthreads();
-    if (wave >= 2) put(wave - 2);
+    if (sub < 2) take(sub);
     __syncthreads();
-    if (wave < 2) take(wave);
+    if (sub == 1) put(0);
     __syncthreads();
-    if (wave == 1) put(0);
-    __syncthreads();
-    if (wave == 0) {
+    if (sub == 0) {
       take(0);
       // ---- partial results of this key range: unnormalised O, running max and sum (base-2 units) ----
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const float ltot = lrow[qb] + __shfl_xor(lrow[qb], 32, kWave);
-        const int m = row0 + 32 * qb + r32;
-        if (m >= M) continue;
-        const long long slot = ((long long)row_u[qb] * p.hq + row_a[qb]) * p.n_slots + z;
+      const float ltot = lrow + __shfl_xor(lrow, 32, kWave);
+      const int m = row0 + 32 * grp + r32;
+      if (m < M) {
+        const long long slot = ((long long)row_u * p.hq + row_a) * p.n_slots + z;
         float* po = p.part_o + slot * D + 4 * hf;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            f32x4 w = {o[db][qb][4 * j], o[db][qb][4 * j + 1], o[db][qb][4 * j + 2], o[db][qb][4 * j + 3]};
+            f32x4 w = {o[db][4 * j], o[db][4 * j + 1], o[db][4 * j + 2], o[db][4 * j + 3]};
             *(f32x4*)(po + 32 * db + 8 * j) = w;
           }
-        if (hf == 0) { p.part_ml[slot * 2] = mrow[qb]; p.part_ml[slot * 2 + 1] = ltot; }
+        if (hf == 0) { p.part_ml[slot * 2] = mrow; p.part_ml[slot * 2 + 1] = ltot; }
       }
     }
-    __syncthreads();  // the merge buffer is tile memory again in the next row chunk
+    __syncthreads();  // the merge buffers are tile memory again in the next row chunk
   }
 }
 
@@ -566,14 +616,15 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
   pl.mfma = dtype == EARN_BF16 && (gq > 1 || n_streams > batch) && max_shared_len >= 128;
   if (pl.mfma) {
     long long base = (long long)hkv * batch;
-    int want = (int)((512 + base - 1) / base);               // >= 2 workgroups per CU
-    int cap = (max_shared_len + 4 * kDsTile - 1) / (4 * kDsTile);  // at least one tile per wave
+    static const int wg_env = getenv("EARN_DEC_WGS") ? atoi(getenv("EARN_DEC_WGS")) : 512;
+    int want = (int)((wg_env + base - 1) / base);               // >= 2 workgroups per CU
+    int cap = (max_shared_len + kDsSuper - 1) / kDsSuper;  // at least one super-tile per workgroup
     int n = want < cap ? want : cap;
     if (n < 1) n = 1;
     if (n > 64) n = 64;
     pl.n_splits = n;
     pl.n_slots = n + 1;
-    pl.chunk = (((max_shared_len + n - 1) / n) + kDsTile - 1) / kDsTile * kDsTile;
+    pl.chunk = (((max_shared_len + n - 1) / n) + kDsSuper - 1) / kDsSuper * kDsSuper;
   } else {
     const int max_total = max_shared_len + gen_cap;
     // aim at >= 1024 workgroups (4 per CU) while keeping at least 256 keys per split
@@ -623,11 +674,11 @@ static void launch_decode_t(DecodeParams& p, const DecodePlan& pl, int gq, hipSt
     return;
   }
   if constexpr (sizeof(T) == 2) {
-    dim3 grid(p.hkv, p.batch, p.n_splits), block(kDecThreads);
-    // one 32-row block is enough when a cache serves at most 32 query rows; beams need the host's upper bound
-    const bool one_block = (long long)gq * (p.n_streams - p.batch + 1) <= 32;
-    if (one_block) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1>), grid, block, 0, stream, p);
-    else hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 2>), grid, block, 0, stream, p);
+    dim3 grid(p.hkv, p.batch, p.n_splits);
+    // one 32-row group is enough when a cache serves at most 32 query rows; with beams the host only has an upper bound
+    const bool one_group = (long long)gq * (p.n_streams - p.batch + 1) <= 32;
+    if (one_group) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 2>), grid, dim3(512), 0, stream, p);
     DecodeParams pg = p;
     pg.gen_only = 1;
     pg.chunk = (p.gen_cap + 1 + 63) / 64 * 64;
@@ -644,6 +695,10 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
   const int hq = desc->n_q_heads, hkv = desc->n_kv_heads, d = desc->head_dim, gq = hq / hkv;
   if (gq > 8) { set_error("earn_decode_attn: more than 8 query heads per kv head is not supported"); return EARN_ERR_UNSUPPORTED; }
   const DecodePlan pl = plan_decode(desc->dtype, hq, hkv, n_streams, batch, max_shared_len, gen_cap);
+  if (pl.mfma && (long long)(max_shared_len + kDsSuper) * hkv * d * 2 >= (1ll << 31)) {
+    set_error("earn_decode_attn: a shared cache of %d rows exceeds the 2 GiB addressing range of one sequence", max_shared_len);
+    return EARN_ERR_UNSUPPORTED;
+  }
   if (pl.mfma && n_streams - batch + 1 > kMaxStreamsPerSeq) {
     set_error("earn_decode_attn: more than %d streams may share one sequence", kMaxStreamsPerSeq);
     return EARN_ERR_UNSUPPORTED;
