@@ -1,0 +1,193 @@
+"""Parity at the full sizes of the benchmark configurations, through the same entry points and launch
+configurations bench.py times.  The quadratic oracle cannot run a whole layer there, so attention outputs are checked
+on SAMPLED rows that the oracle computes one by one (register rows, rows next to tile boundaries, the last row and
+random rows of a few (sequence, head) pairs); compaction is checked in full (bit-exact).
+
+Inputs are drawn on the GPU and, for the sampled sequences, again on the CPU from the same counter-based generator
+(bit-identical, see test_generator_is_bit_identical_on_cpu_and_gpu), so no oracle input comes from the HIP path.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import earn_oracle as O
+from paper_2507_00715_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+BF16_REL = 2e-2
+BF16_CONFIGS = ["small_gqa", "mid_mha", "long_beam", "serving"]
+
+
+def _B():
+    from paper_2507_00715_amd import binding
+    binding.lib()
+    return binding
+
+
+def rel_fro(got, ref):
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30))
+
+
+def sample_rows(n, h, t, rng, n_random=24):
+    rows = set(range(min(h, n))) | set(range(max(n - t, 0), n))
+    for b in (32, 64, 128, 256):
+        for k in range(b, n, b * 7 if b < 256 else b):
+            rows.update(r for r in (k - 1, k, k + 1) if 0 <= r < n)
+    rows.add(n - 1)
+    rows.update(int(x) for x in rng.integers(0, n, size=n_random))
+    return sorted(rows)
+
+
+@pytest.mark.parametrize("name", BF16_CONFIGS)
+def test_full_layer_prefill_sampled_rows(name):
+    B = _B()
+    cfg = W.CONFIGS[name]
+    w = W.Workload(cfg)
+    layer = 0
+    coords = w.token_coords(DEV)
+    q = w.prefill_tensor("q", layer, coords=coords)
+    k = w.prefill_tensor("k", layer, coords=coords)
+    v = w.prefill_tensor("v", layer, coords=coords)
+    out = torch.full_like(q, float("nan"))
+    krot = torch.empty_like(k)
+    lse = torch.empty(w.total_tokens, cfg.n_q_heads, dtype=torch.float32, device=DEV)
+    cu = torch.tensor(w.cu_seqlens, dtype=torch.int32, device=DEV)
+    desc = B.make_desc(cfg.torch_dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, 0.0, cfg.rope_base)
+    B.earn_prefill_attn(desc, q, k, v, cu, None, cfg.batch, w.total_tokens, w.max_seqlen, out, krot, lse, None)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+
+    rng = np.random.default_rng(cfg.config_id)
+    lens = np.asarray(w.seq_lengths)
+    seqs = sorted({int(np.argmax(lens)), int(np.argmin(lens)), int(rng.integers(0, cfg.batch))})
+    gq = cfg.n_q_heads // cfg.n_kv_heads
+    worst = 0.0
+    for s in seqs:
+        n = w.seq_lengths[s]
+        b0 = w.cu_seqlens[s]
+        heads = sorted({0, cfg.n_q_heads - 1, int(rng.integers(0, cfg.n_q_heads))})
+        kvh = sorted({a // gq for a in heads})
+        qc = W.to_f64(w.prefill_tensor("q", layer, seqs=[s], heads=heads))
+        kc = W.to_f64(w.prefill_tensor("k", layer, seqs=[s], heads=kvh))
+        vc = W.to_f64(w.prefill_tensor("v", layer, seqs=[s], heads=kvh))
+        rows = sample_rows(n, cfg.n_head_reg, cfg.n_tail_reg, rng)
+        sel = np.zeros(n, dtype=np.uint8)
+        sel[rows] = 1
+        ref = O.prefill_attn(qc, kc, vc, [0, n], q_to_kv=[kvh.index(a // gq) for a in heads], rope_base=cfg.rope_base,
+                             row_sel=sel)
+        got = out[b0:b0 + n][rows][:, heads].cpu().double().numpy()
+        err = rel_fro(got, ref["out"][rows])
+        worst = max(worst, err)
+        assert err <= BF16_REL, f"{name} seq {s}: rel-Frobenius {err:.3e} on {len(rows)} sampled rows"
+        got_lse = lse[b0:b0 + n][rows][:, heads].cpu().double().numpy()
+        # log-sum-exp: bf16 operands perturb a score s by about 2^-8 |s|, and the lse follows the largest score
+        assert (np.abs(got_lse - ref["lse"][rows]) <= 5e-2 + 1e-2 * np.abs(ref["lse"][rows])).all()
+        got_k = krot[b0:b0 + n][:, kvh].cpu().double().numpy()
+        assert rel_fro(got_k, ref["k_rot"]) <= BF16_REL
+    print(f"{name}: worst sampled rel-Frobenius error {worst:.2e}")
+
+
+@pytest.mark.parametrize("name", BF16_CONFIGS)
+def test_full_size_compaction_bit_exact(name):
+    """Hidden-state stand-in plus K and V of one later layer, gathered in one launch, against the oracle's indices."""
+    B = _B()
+    cfg = W.CONFIGS[name]
+    w = W.Workload(cfg)
+    coords = w.token_coords(DEV)
+    x = w.prefill_tensor("x", 0, coords=coords)
+    k = w.prefill_tensor("k", cfg.split_k, coords=coords)
+    v = w.prefill_tensor("v", cfg.split_k, coords=coords)
+    rows = cfg.batch * cfg.r
+    dst = [torch.empty((rows,) + tuple(t.shape[1:]), dtype=t.dtype, device=DEV) for t in (x, k, v)]
+    idx = torch.empty(rows, dtype=torch.int32, device=DEV)
+    pos = torch.empty(rows, dtype=torch.int32, device=DEV)
+    cu_c = torch.empty(cfg.batch + 1, dtype=torch.int32, device=DEV)
+    cu = torch.tensor(w.cu_seqlens, dtype=torch.int32, device=DEV)
+    B.earn_compact_registers([x, k, v], dst, cu, cfg.batch, cfg.n_head_reg, cfg.n_tail_reg, idx, pos, cu_c)
+    torch.cuda.synchronize()
+    ref = O.compact_registers(None, np.asarray(w.cu_seqlens, dtype=np.int32), cfg.n_head_reg, cfg.n_tail_reg)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref["idx"])
+    np.testing.assert_array_equal(pos.cpu().numpy(), ref["pos"])
+    np.testing.assert_array_equal(cu_c.cpu().numpy(), ref["cu"])
+    # the gathered rows are the source rows the ORACLE's indices name, drawn independently on the CPU
+    seq = torch.repeat_interleave(torch.arange(cfg.batch), cfg.r)
+    cc = (seq, torch.from_numpy(ref["pos"]).long())
+    assert torch.equal(dst[0].cpu(), w.prefill_tensor("x", 0, coords=cc))
+    assert torch.equal(dst[1].cpu(), w.prefill_tensor("k", cfg.split_k, coords=cc))
+    assert torch.equal(dst[2].cpu(), w.prefill_tensor("v", cfg.split_k, coords=cc))
+
+
+@pytest.mark.parametrize("name,mode", [(n, m) for n in BF16_CONFIGS for m in ("full", "registers")])
+def test_full_size_decode_sampled_streams(name, mode):
+    """One decode step of one layer at full size (full-length cache or register cache), sampled (stream, head) rows."""
+    B = _B()
+    cfg = W.CONFIGS[name]
+    w = W.Workload(cfg)
+    layer = 0 if mode == "full" else cfg.split_k
+    step = cfg.decode_steps // 2
+    G, S = cfg.decode_steps, w.n_streams
+    if mode == "full":
+        lens, coords_dev = w.seq_lengths, w.token_coords(DEV)
+    else:
+        lens = [cfg.r] * cfg.batch
+        ref_c = O.compact_registers(None, np.asarray(w.cu_seqlens, dtype=np.int32), cfg.n_head_reg, cfg.n_tail_reg)
+        seq = torch.repeat_interleave(torch.arange(cfg.batch), cfg.r)
+        coords_dev = (seq.to(DEV), torch.from_numpy(ref_c["pos"]).long().to(DEV))
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    # the cache contents stand in for "already rotated keys": drawn, not computed
+    sk = w.prefill_tensor("k", layer, coords=coords_dev)
+    sv = w.prefill_tensor("v", layer, coords=coords_dev)
+    q = w.decode_tensor("q", layer, step, device=DEV)
+    kn = w.decode_tensor("k", layer, step, device=DEV)
+    vn = w.decode_tensor("v", layer, step, device=DEV)
+    # earlier generated rows: draws of the earlier steps (un-rotated draws serve as cache contents)
+    gk = torch.zeros(S, G, cfg.n_kv_heads, cfg.head_dim, dtype=cfg.torch_dtype, device=DEV)
+    gv = torch.zeros_like(gk)
+    for g in range(step):
+        gk[:, g] = w.decode_tensor("k", layer, g, device=DEV)
+        gv[:, g] = w.decode_tensor("v", layer, g, device=DEV)
+    i32 = lambda a: torch.tensor(list(a), dtype=torch.int32, device=DEV)
+    q_pos = w.decode_positions(step)
+    out = torch.full_like(q, float("nan"))
+    desc = B.make_desc(cfg.torch_dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, 0.0, cfg.rope_base)
+    ws = torch.empty(max(B.earn_decode_workspace_bytes(desc, S, cfg.batch, max(lens), G), 256), dtype=torch.uint8,
+                     device=DEV)
+    B.earn_decode_attn(desc, q, kn, vn, i32(q_pos), sk, sv, i32(cu), i32(w.stream_to_seq), gk, gv, i32([step] * S), G, S,
+                       cfg.batch, max(lens), out, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+
+    rng = np.random.default_rng(100 + cfg.config_id)
+    streams = sorted({0, S - 1, *[int(x) for x in rng.integers(0, S, size=4)]})
+    gq = cfg.n_q_heads // cfg.n_kv_heads
+    for u in streams:
+        s = w.stream_to_seq[u]
+        n = lens[s]
+        heads = sorted({0, cfg.n_q_heads - 1, int(rng.integers(0, cfg.n_q_heads))})
+        kvh = sorted({a // gq for a in heads})
+        sl = slice(int(cu[s]), int(cu[s]) + n)
+        f64 = lambda t: t.cpu().to(torch.float64).numpy()
+        # CPU-side inputs of this stream, drawn from the generator (not read back from device buffers)
+        if mode == "full":
+            cs = w.token_coords("cpu", seqs=[s])
+        else:
+            cs = (torch.full((cfg.r,), s, dtype=torch.int64), torch.from_numpy(ref_c["pos"][s * cfg.r:(s + 1) * cfg.r]).long())
+        skc = W.to_f64(w.prefill_tensor("k", layer, coords=cs, heads=kvh))
+        svc = W.to_f64(w.prefill_tensor("v", layer, coords=cs, heads=kvh))
+        qc = W.to_f64(w.decode_tensor("q", layer, step, streams=[u])[:, heads])
+        knc = W.to_f64(w.decode_tensor("k", layer, step, streams=[u])[:, kvh])
+        vnc = W.to_f64(w.decode_tensor("v", layer, step, streams=[u])[:, kvh])
+        ogk = np.zeros((1, G, len(kvh), cfg.head_dim))
+        ogv = np.zeros_like(ogk)
+        for g in range(step):
+            ogk[0, g] = W.to_f64(w.decode_tensor("k", layer, g, streams=[u])[:, kvh])[0]
+            ogv[0, g] = W.to_f64(w.decode_tensor("v", layer, g, streams=[u])[:, kvh])[0]
+        ref = O.decode_attn(qc, knc, vnc, [q_pos[u]], skc, svc, [0, n], None, ogk, ogv, [step],
+                            q_to_kv=[kvh.index(a // gq) for a in heads], rope_base=cfg.rope_base)
+        err = rel_fro(f64(out[u][heads]), ref["out"][0])
+        assert err <= BF16_REL, f"{name}/{mode} stream {u}: rel-Frobenius {err:.3e}"
+        # cache append
+        assert rel_fro(f64(gk[u, step][kvh]), ogk[0, step]) <= BF16_REL
+        assert torch.equal(gv[u, step].cpu(), w.decode_tensor("v", layer, step, streams=[u])[0])
+        del sl
