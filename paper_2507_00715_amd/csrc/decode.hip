@@ -16,8 +16,6 @@
 
 namespace earn {
 
-constexpr int kDecThreads = 256;
-constexpr int kDecWaves = kDecThreads / kWave;
 
 template <typename T>
 struct Row8;  // 8 consecutive elements of a row as floats
@@ -75,17 +73,20 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* o, float 
   m = mn;
 }
 
-template <typename T, int D, int GQ>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams p) {
+// Attention of one (stream u, kv head c) over the key range `z` of its key list, by WAVES cooperating waves
+// (WAVES = 4: a whole workgroup, states merged through `sm`; WAVES = 1: a single wave, no LDS, no barrier — used for
+// short key lists, where the per-wave prologue dominates, and inside the shared-cache kernel for the generated rows).
+template <typename T, int D, int GQ, int WAVES>
+__device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, const int u, const int z,
+                                            const int wave, const int lane, const bool gen_only, const int chunk,
+                                            float* sm_base) {
   constexpr int LPK = D / 8;         // lanes per key row
   constexpr int KPW = kWave / LPK;   // key rows per wave instruction
-  const int c = blockIdx.x, u = blockIdx.y, z = blockIdx.z;
   const int gq = p.hq / p.hkv;       // query heads per kv head
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int sub = lane % LPK, kk = lane / LPK;
   const int s = p.stream_to_seq ? p.stream_to_seq[u] : u;
   const int b0 = p.shared_cu[s];
-  const int ns = p.gen_only ? 0 : p.shared_cu[s + 1] - b0;  // shared rows this launch walks
+  const int ns = gen_only ? 0 : p.shared_cu[s + 1] - b0;  // shared rows this launch walks
   const int g = p.gen_len[u];
   const int m_total = ns + g + 1;    // shared rows, earlier generated rows, the new token
   const float pos = (float)p.q_pos[u];
@@ -143,8 +144,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams p) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) kn[i] = Row8<T>::round(kn[i]);
 
-  const int j_begin = z * p.chunk;
-  const int j_end = min(m_total, j_begin + p.chunk);
+  const int j_begin = z * chunk;
+  const int j_end = min(m_total, j_begin + chunk);
   // cache append (Eq. 4): done by the one workgroup whose key range holds the new token
   if (m_total - 1 >= j_begin && m_total - 1 < j_end && wave == 0 && kk == 0) {
     Row8<T>::store(Gk + (long long)g * row_stride, kn);
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams p) {
     for (int i = 0; i < 8; ++i) o[a][i] = 0.f;
   }
 
-  for (int j0 = j_begin + wave * KPW; j0 < j_end; j0 += kDecWaves * KPW) {
+  for (int j0 = j_begin + wave * KPW; j0 < j_end; j0 += WAVES * KPW) {
     const int j = j0 + kk;
     const bool valid = j < j_end;
     float kx[8], vx[8];
@@ -207,27 +208,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams p) {
       merge_state<8>(mx[a], ls[a], o[a], m2, l2, o2);
     }
   }
-  // merge the waves through LDS
-  __shared__ float sm[kDecWaves][GQ][LPK][10];
-  if (kk == 0) {
-#pragma unroll
-    for (int a = 0; a < GQ; ++a) {
-      sm[wave][a][sub][0] = mx[a];
-      sm[wave][a][sub][1] = ls[a];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) sm[wave][a][sub][2 + i] = o[a][i];
-    }
-  }
-  __syncthreads();
-  // thread t < gq*LPK finishes head a = t / LPK, element group t % LPK
-  const int t = threadIdx.x;
-  if (t < gq * LPK) {
-    const int a = t / LPK, sb = t % LPK;
-    float m = sm[0][a][sb][0], l = sm[0][a][sb][1], oo[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) oo[i] = sm[0][a][sb][2 + i];
-#pragma unroll
-    for (int w = 1; w < kDecWaves; ++w) merge_state<8>(m, l, oo, sm[w][a][sb][0], sm[w][a][sb][1], &sm[w][a][sb][2]);
+  // write one finished (head, 8-element group) state: final output or a partial slot
+  auto finish = [&](int a, int sb, float m, float l, float* oo) {
     const int head = c * gq + a;
     if (p.n_slots == 1) {
       float inv = 1.f / l;
@@ -235,13 +217,52 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams p) {
       for (int i = 0; i < 8; ++i) oo[i] *= inv;
       Row8<T>::store((T*)p.out + ((long long)u * p.hq + head) * D + sb * 8, oo);
     } else {
-      const long long slot = ((long long)u * p.hq + head) * p.n_slots + (p.gen_only ? p.n_slots - 1 : z);
+      const long long slot = ((long long)u * p.hq + head) * p.n_slots + (gen_only ? p.n_slots - 1 : z);
       float* po = p.part_o + slot * D + sb * 8;
 #pragma unroll
       for (int i = 0; i < 8; ++i) po[i] = oo[i];
       if (sb == 0) { p.part_ml[slot * 2] = m; p.part_ml[slot * 2 + 1] = l; }
     }
+  };
+  if constexpr (WAVES == 1) {
+    if (kk == 0) {
+#pragma unroll
+      for (int a = 0; a < GQ; ++a)
+        if (a < gq) finish(a, sub, mx[a], ls[a], o[a]);
+    }
+  } else {
+    // merge the waves through LDS
+    typedef float MergeBuf[GQ][LPK][10];
+    MergeBuf* sm = (MergeBuf*)sm_base;
+    if (kk == 0) {
+#pragma unroll
+      for (int a = 0; a < GQ; ++a) {
+        sm[wave][a][sub][0] = mx[a];
+        sm[wave][a][sub][1] = ls[a];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sm[wave][a][sub][2 + i] = o[a][i];
+      }
+    }
+    __syncthreads();
+    // thread t < gq*LPK finishes head a = t / LPK, element group t % LPK
+    const int t = wave * kWave + lane;
+    if (t < gq * LPK) {
+      const int a = t / LPK, sb = t % LPK;
+      float m = sm[0][a][sb][0], l = sm[0][a][sb][1], oo[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) oo[i] = sm[0][a][sb][2 + i];
+#pragma unroll
+      for (int w = 1; w < WAVES; ++w) merge_state<8>(m, l, oo, sm[w][a][sb][0], sm[w][a][sb][1], &sm[w][a][sb][2]);
+      finish(a, sb, m, l, oo);
+    }
   }
+}
+
+template <typename T, int D, int GQ, int WAVES>
+__global__ __launch_bounds__(kWave * WAVES) void decode_kernel(DecodeParams p) {
+  __shared__ float sm[WAVES > 1 ? WAVES * GQ * (D / 8) * 10 : 1];
+  decode_rows<T, D, GQ, WAVES>(p, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x / kWave, threadIdx.x % kWave,
+                               p.gen_only != 0, p.chunk, sm);
 }
 
 // merge the partial results of the slots: one thread per (stream, head, 8-element group)
@@ -303,7 +324,7 @@ struct DsSmem {
   int n_streams_of_seq;
 };
 
-template <int D, int C>
+template <int D, int C, int GQ>
 __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodeParams p) {
   constexpr int THREADS = 256 * C;
   constexpr int KSTEPS = D / 16, DB = D / 32, UPR = D / 8;
@@ -325,6 +346,39 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   const int j_end = min(ns, j_begin + p.chunk);
   const int n_keys = max(j_end - j_begin, 0);
   const int n_super = (n_keys + kDsSuper - 1) / kDsSuper;
+
+  const __bf16* Kg = (const __bf16*)p.shared_k + ((long long)b0 * p.hkv + c) * D;
+  const __bf16* Vg = (const __bf16*)p.shared_v + ((long long)b0 * p.hkv + c) * D;
+  const long long kv_stride = (long long)p.hkv * D;
+  const int k_off = r32 * Sm::KS + 8 * hf;
+  const int v_off = (4 * hf + ((lane & 15) >> 2)) * Sm::VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  float* mbuf = (float*)&sm.tile[0][0] + (size_t)grp * 2 * STATE * kWave;
+  // staging: unit i of this thread is row (tid / UPR + i * RPU) of the super-tile, 16-byte column tid % UPR.
+  // Loads go through buffer descriptors that cover exactly the rows of this workgroup's key range: one vector register
+  // holds the per-thread byte offset, everything else of the address is scalar, and rows past the end of the range
+  // read as zeros (no clamping code, finite data for the masked tail).
+  const int st_row0 = threadIdx.x / UPR, st_col = threadIdx.x % UPR;
+  const int row_bytes = (int)kv_stride * 2;
+  const int st_voff = st_row0 * row_bytes + st_col * 16;
+  const int range_bytes = n_keys > 0 ? (n_keys - 1) * row_bytes + D * 2 : 0;
+  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(Kg + j_begin * kv_stride), 0, range_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(Vg + j_begin * kv_stride), 0, range_bytes, 0x00020000);
+
+  // two register sets: super-tiles it+2 and it+3 are in flight while super-tile it is being used (the stream is
+  // bound by HBM latency times bytes in flight, so the depth matters more than anything else here)
+  u32x4 kreg[2][UNITS], vreg[2][UNITS];
+  auto load_super = [&](int it, u32x4 (&kr)[UNITS], u32x4 (&vr)[UNITS]) {
+#pragma unroll
+    for (int i = 0; i < UNITS; ++i) {
+      const int soff = (it * kDsSuper + i * RPU) * row_bytes;  // scalar part of the address
+      kr[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, st_voff, soff, 0);
+      vr[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, st_voff, soff, 0);
+    }
+  };
+  // the first two super-tiles are requested before anything else: they fly while the stream list is built and the
+  // queries are rotated
+  if (n_super > 0) load_super(0, kreg[0], vreg[0]);
+  if (n_super > 1) load_super(1, kreg[1], vreg[1]);
 
   // ---- streams (beams) of this sequence, ascending ----
   if (wave == 0) {
@@ -348,22 +402,11 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   __syncthreads();
   const int M = sm.n_streams_of_seq * gq;  // query rows sharing this cache
 
-  const __bf16* Kg = (const __bf16*)p.shared_k + ((long long)b0 * p.hkv + c) * D;
-  const __bf16* Vg = (const __bf16*)p.shared_v + ((long long)b0 * p.hkv + c) * D;
-  const long long kv_stride = (long long)p.hkv * D;
-  const int k_off = r32 * Sm::KS + 8 * hf;
-  const int v_off = (4 * hf + ((lane & 15) >> 2)) * Sm::VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  float* mbuf = (float*)&sm.tile[0][0] + (size_t)grp * 2 * STATE * kWave;
-  // staging: unit i of this thread is row (tid / UPR + i * RPU) of the super-tile, 16-byte column tid % UPR.
-  // Loads go through buffer descriptors that cover exactly the rows of this workgroup's key range: one vector register
-  // holds the per-thread byte offset, everything else of the address is scalar, and rows past the end of the range
-  // read as zeros (no clamping code, finite data for the masked tail).
-  const int st_row0 = threadIdx.x / UPR, st_col = threadIdx.x % UPR;
-  const int row_bytes = (int)kv_stride * 2;
-  const int st_voff = st_row0 * row_bytes + st_col * 16;
-  const int range_bytes = n_keys > 0 ? (n_keys - 1) * row_bytes + D * 2 : 0;
-  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(Kg + j_begin * kv_stride), 0, range_bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(Vg + j_begin * kv_stride), 0, range_bytes, 0x00020000);
+  // ---- generated rows and the new token of this sequence's streams (they differ per beam: vector ALU, one wave per
+  // stream).  The streams are dealt out over the key splits so every workgroup gets an equal share, and the work runs
+  // while the first super-tiles are still on their way from HBM. ----
+  for (int i = z + p.n_splits * wave; i < sm.n_streams_of_seq; i += p.n_splits * 4 * C)
+    decode_rows<__bf16, D, GQ, 1>(p, c, sm.streams[i], 0, 0, lane, true, 1 << 30, nullptr);
 
   for (int row0 = 0; row0 < M; row0 += ROWS) {
     // ---- Q fragments of this group's rows: row m -> (stream list[m / gq], head c*gq + m % gq) ----
@@ -408,17 +451,6 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
     float mrow = -INFINITY, lrow = 0.f;
 
-    // two register sets: super-tiles it+2 and it+3 are in flight while super-tile it is being used (the stream is
-    // bound by HBM latency times bytes in flight, so the depth matters more than anything else here)
-    u32x4 kreg[2][UNITS], vreg[2][UNITS];
-    auto load_super = [&](int it, u32x4 (&kr)[UNITS], u32x4 (&vr)[UNITS]) {
-#pragma unroll
-      for (int i = 0; i < UNITS; ++i) {
-        const int soff = (it * kDsSuper + i * RPU) * row_bytes;  // scalar part of the address
-        kr[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, st_voff, soff, 0);
-        vr[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, st_voff, soff, 0);
-      }
-    };
     auto store_super = [&](int stage, u32x4 (&kr)[UNITS], u32x4 (&vr)[UNITS]) {
 #pragma unroll
       for (int i = 0; i < UNITS; ++i) {
@@ -501,8 +533,10 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     // vector ALU; a reference is stale exactly when some exponential is large, which shows in the partial row sums
     // (+inf / NaN on the first tile, whose reference is -inf).  A wave that sees a stale reference leaves the loop,
     // takes the exact maxima of the tile, rescales, finishes the tile and re-enters.
-    if (n_super > 0) load_super(0, kreg[0], vreg[0]);
-    if (n_super > 1) load_super(1, kreg[1], vreg[1]);
+    if (row0 > 0) {  // further 64-row passes over the same keys
+      if (n_super > 0) load_super(0, kreg[0], vreg[0]);
+      if (n_super > 1) load_super(1, kreg[1], vreg[1]);
+    }
     if (n_super > 0) store_super(0, kreg[0], vreg[0]);
     if (n_super > 2) load_super(2, kreg[0], vreg[0]);
     __syncthreads();
@@ -613,11 +647,12 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
   const int gq = hq / hkv;
   // several query rows per cache (grouped heads or beams) make the shared part a matrix product
   // (short caches are launch-latency bound: the single-launch vector kernel wins there)
-  pl.mfma = dtype == EARN_BF16 && (gq > 1 || n_streams > batch) && max_shared_len >= 128;
+  static const int mfma_min = getenv("EARN_DEC_MFMA_MIN") ? atoi(getenv("EARN_DEC_MFMA_MIN")) : 128;
+  pl.mfma = dtype == EARN_BF16 && (gq > 1 || n_streams > batch) && max_shared_len >= mfma_min;
   if (pl.mfma) {
     long long base = (long long)hkv * batch;
-    static const int wg_env = getenv("EARN_DEC_WGS") ? atoi(getenv("EARN_DEC_WGS")) : 512;
-    int want = (int)((wg_env + base - 1) / base);               // >= 2 workgroups per CU
+    static const int wg_env = getenv("EARN_DEC_WGS") ? atoi(getenv("EARN_DEC_WGS")) : 256;
+    int want = (int)((wg_env + base - 1) / base);               // one workgroup per CU: it holds 8 waves and most of the LDS
     int cap = (max_shared_len + kDsSuper - 1) / kDsSuper;  // at least one super-tile per workgroup
     int n = want < cap ? want : cap;
     if (n < 1) n = 1;
@@ -649,13 +684,20 @@ size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, 
   return rows * d * sizeof(float) + rows * 2 * sizeof(float);
 }
 
+template <typename T, int D, int WAVES>
+static void launch_vector_w(const DecodeParams& p, int gq, dim3 grid, hipStream_t stream) {
+  dim3 block(kWave * WAVES);
+  if (gq == 1) hipLaunchKernelGGL((decode_kernel<T, D, 1, WAVES>), grid, block, 0, stream, p);
+  else if (gq == 2) hipLaunchKernelGGL((decode_kernel<T, D, 2, WAVES>), grid, block, 0, stream, p);
+  else if (gq <= 4) hipLaunchKernelGGL((decode_kernel<T, D, 4, WAVES>), grid, block, 0, stream, p);
+  else hipLaunchKernelGGL((decode_kernel<T, D, 8, WAVES>), grid, block, 0, stream, p);
+}
 template <typename T, int D>
 static void launch_vector(const DecodeParams& p, int gq, dim3 grid, hipStream_t stream) {
-  dim3 block(kDecThreads);
-  if (gq == 1) hipLaunchKernelGGL((decode_kernel<T, D, 1>), grid, block, 0, stream, p);
-  else if (gq == 2) hipLaunchKernelGGL((decode_kernel<T, D, 2>), grid, block, 0, stream, p);
-  else if (gq <= 4) hipLaunchKernelGGL((decode_kernel<T, D, 4>), grid, block, 0, stream, p);
-  else hipLaunchKernelGGL((decode_kernel<T, D, 8>), grid, block, 0, stream, p);
+  // short key lists of a single query head: one wave per (stream, kv head), so the prologue (query rotation) is not
+  // repeated by 4 waves; with several heads per kv head the serial key loop is the longer pole and 4 waves win
+  if (p.chunk <= 128 && gq == 1) launch_vector_w<T, D, 1>(p, gq, grid, stream);
+  else launch_vector_w<T, D, 4>(p, gq, grid, stream);
 }
 
 template <typename T, int D>
@@ -677,12 +719,13 @@ static void launch_decode_t(DecodeParams& p, const DecodePlan& pl, int gq, hipSt
     dim3 grid(p.hkv, p.batch, p.n_splits);
     // one 32-row group is enough when a cache serves at most 32 query rows; with beams the host only has an upper bound
     const bool one_group = (long long)gq * (p.n_streams - p.batch + 1) <= 32;
-    if (one_group) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1>), grid, dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 2>), grid, dim3(512), 0, stream, p);
-    DecodeParams pg = p;
-    pg.gen_only = 1;
-    pg.chunk = (p.gen_cap + 1 + 63) / 64 * 64;
-    launch_vector<T, D>(pg, gq, dim3(p.hkv, p.n_streams, 1), stream);
+    if (one_group) {
+      if (gq <= 4) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1, 4>), grid, dim3(256), 0, stream, p);
+      else hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1, 8>), grid, dim3(256), 0, stream, p);
+    } else {
+      if (gq <= 4) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 2, 4>), grid, dim3(512), 0, stream, p);
+      else hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 2, 8>), grid, dim3(512), 0, stream, p);
+    }
     launch_combine<T, D>(p, stream);
   }
 }
