@@ -32,6 +32,9 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3     # fp32 vector
 PEAK_HBM_GBPS = 8000.0      # HBM3E
 HEADLINE = "long_beam"
+# HBM bytes per launch of the dominant kernel (full-length prefill layer), from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs summarised in profiles/long_beam_hbm_traffic.txt (counters scaled by a 1 GiB copy: x2.0 and x1.0).
+MEASURED_TRAFFIC = {"long_beam": {"fetch_bytes": 2.570e9, "write_bytes": 1.082e9}}
 
 
 def log(*a):
@@ -77,6 +80,13 @@ def algorithmic_counts(w: W.Workload):
     row_bytes = [hq * d * e] + [hq * d * e, hkv * d * e, hkv * d * e] * (c.n_layers - c.split_k)
     comp = sum(2 * B * r * rb for rb in row_bytes) + 12 * B * r + 8 * B
     return dict(flops_full=flops_full, flops_reg=flops_reg, dec_full=dec_full, dec_reg=dec_reg, compaction=comp)
+
+
+def algorithmic_prefill_bytes(name: str) -> float:
+    """Q, K, V read once and O written once for one full-length layer."""
+    c = W.CONFIGS[name]
+    w = W.Workload(c)
+    return float(w.total_tokens * c.head_dim * c.elem_bytes * (2 * c.n_q_heads + 2 * c.n_kv_heads))
 
 
 def build_inputs(w: W.Workload, dev):
@@ -249,7 +259,11 @@ def main():
         "config": head["workload"],
         "roofline": {"kernel": "prefill_mfma_kernel (full-length causal layer)", "bound": "mfma",
                      "achieved": pf["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": pf["tflops"] / peak,
-                     "traffic": None, "ms_per_launch": pf["ms_per_launch"], "flops_per_launch": pf["flops_per_launch"]},
+                     "traffic": (sum(MEASURED_TRAFFIC[args.workload].values())
+                                 if args.workload in MEASURED_TRAFFIC else None),
+                     "traffic_detail": MEASURED_TRAFFIC.get(args.workload),
+                     "algorithmic_bytes": algorithmic_prefill_bytes(args.workload),
+                     "ms_per_launch": pf["ms_per_launch"], "flops_per_launch": pf["flops_per_launch"]},
         "cpu_baseline": cpu,
         "decode": head["decode"],
         "compaction": head["compaction"],
