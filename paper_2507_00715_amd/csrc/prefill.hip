@@ -185,12 +185,12 @@ constexpr int kTileKeys = 64;    // keys per K/V tile in LDS
 
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
-template <int D>
+template <int D, int STAGES>
 struct PfSmem {
   static constexpr int KS = D + 8;    // K row stride (elements): 16-byte reads of 16 consecutive rows hit all banks
   static constexpr int VS = D + 32;   // V row stride: the 4 rows of a transposing read land 64 bytes apart (mod 256)
-  __bf16 k[2][kTileKeys * KS];   // double buffered: tile t+1 is written while tile t is read
-  __bf16 v[2][kTileKeys * VS];
+  __bf16 k[STAGES][kTileKeys * KS];   // STAGES = 2: tile t+1 is written while tile t is read
+  __bf16 v[STAGES][kTileKeys * VS];
 };
 
 // Between rescales the exponentials are taken against a stale row maximum, so they can exceed 1; they are allowed to
@@ -217,8 +217,11 @@ __device__ __forceinline__ float half_sum(float x) {
 // WAVES = waves per workgroup.  8 (or 4 with QB = 2) gives 256 query rows per workgroup; WAVES = 4 with QB = 1 gives
 // 128-row workgroups, two of which share a CU: less idle time on the causal diagonal of short sequences, at the price
 // of staging every K/V tile twice as often.
-template <int D, int QB, int WAVES>
-__global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES == 4) ? 2 : 1) void prefill_mfma_kernel(PrefillParams p) {
+// STAGES = 1 (with WAVES = 2: 64 rows) is the register-only-layer variant: every sequence fits one K/V tile, so there is
+// nothing to double buffer, and the small footprint (38 KiB LDS, 128 threads) lets 4 workgroups share a CU, which is
+// what hides the load -> rotate -> multiply latency chain of these tiny problems.
+template <int D, int QB, int WAVES, int STAGES>
+__global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void prefill_mfma_kernel(PrefillParams p) {
   constexpr int kPfThreads = 64 * WAVES;
   constexpr int kWaveRows = 32 * QB;
   constexpr int kBlockRows = kWaveRows * WAVES;
@@ -226,7 +229,7 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES == 4) ? 2 : 1) void p
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int UPR = D / 8;             // 16-byte units per K/V row
   constexpr int UNITS = kTileKeys * UPR / kPfThreads;  // 16-byte units per thread per tile and tensor
-  using Sm = PfSmem<D>;
+  using Sm = PfSmem<D, STAGES>;
   __shared__ Sm sm;
 
   // ---- workgroup -> (sequence, kv head, query block, head of the group), XCD aware ----
@@ -353,14 +356,16 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES == 4) ? 2 : 1) void p
     return;
 #endif
     // tile t+1 goes to the other buffer (last read in iteration t-1, which every wave has left), tile t+2 into registers
-    if (t + 1 < n_tiles) store_tile((t & 1) ^ 1);
-    if (t + 2 < n_tiles) load_tile(t + 2);
+    if constexpr (STAGES == 2) {
+      if (t + 1 < n_tiles) store_tile((t & 1) ^ 1);
+      if (t + 2 < n_tiles) load_tile(t + 2);
+    }
   };
   // S^T = K Q^T for tile t, causal mask on the diagonal tile.  All 2*KSTEPS K fragments are requested from LDS before
   // the first MFMA (and before `staging`, the global->LDS traffic of later tiles), so the MFMAs wait on a draining
   // queue instead of paying one LDS round trip each.
   auto scores = [&](int t, f32x16 (&sc)[2][QB], bool do_stage) {
-    const __bf16* smk = sm.k[t & 1];
+    const __bf16* smk = sm.k[t & (STAGES - 1)];
     bf16x8 kf[2][KSTEPS];
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks)
@@ -416,7 +421,7 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES == 4) ? 2 : 1) void p
   // V^T fragments of tile t (A operands of the second product): requested before the exponentials so that the LDS
   // latency hides behind the vector-ALU work
   auto fetch_v = [&](int t, bf16x8 (&vf)[4][DB]) {
-    const __bf16* smv = sm.v[t & 1];
+    const __bf16* smv = sm.v[t & (STAGES - 1)];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
@@ -455,7 +460,7 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES == 4) ? 2 : 1) void p
   };
 
   store_tile(0);
-  if (n_tiles > 1) load_tile(1);
+  if (STAGES == 2 && n_tiles > 1) load_tile(1);
   __syncthreads();
   // Every tile iteration ends in exactly one barrier, whichever path a wave takes.  The steady-state loop takes the
   // exponentials against the reference maxima it already has and never touches the output accumulators with the
@@ -464,8 +469,10 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES == 4) ? 2 : 1) void p
   // still -inf) fail the comparison too.  A wave that fails leaves the loop, recomputes the tile's scores, takes the
   // exact maxima, rescales, finishes the tile and re-enters.
   int t = 0;
+  bool first = wave_active;  // tile 0 always needs the exact maxima (the reference is still -inf): no point trying the fast path
   while (t < n_tiles) {
-    bool rescale = false;
+    bool rescale = first;
+    if (!first)
     for (; t < n_tiles; ++t) {
       if (wave_active && t <= t_diag) {
         f32x16 sc[2][QB];
@@ -491,7 +498,8 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES == 4) ? 2 : 1) void p
       f32x16 sc[2][QB];
       float lsum[QB];
       bf16x8 vf[4][DB];
-      scores(t, sc, false);  // the tile was staged before the wave left the loop
+      scores(t, sc, first);  // the tile was staged before the wave left the loop (tile 0: staged here)
+      first = false;
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         float m = sc[0][qb][0];
@@ -578,14 +586,15 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
     dim3 grid((max_seqlen + 63) / 64, p.hq, batch);
     if (d == 64) hipLaunchKernelGGL((prefill_rows_kernel<float, 64>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((prefill_rows_kernel<float, 128>), grid, dim3(256), 0, stream, p);
-  } else if (max_seqlen <= 64) {
-    // register-only layers: a handful of rows per sequence, far too little work for a 256-row MFMA tile; the
-    // vector kernel keeps many small workgroups in flight instead
+  } else if (max_seqlen <= kTileKeys) {
+    // register-only layers: every sequence is a single K/V tile
     if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
     else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
-    dim3 grid(1, p.hq, batch);
-    if (d == 64) hipLaunchKernelGGL((prefill_rows_kernel<__bf16, 64>), grid, dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL((prefill_rows_kernel<__bf16, 128>), grid, dim3(256), 0, stream, p);
+    p.n_qblk = 1;
+    const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
+    dim3 grid((unsigned)(pairs8 * (p.hq / p.hkv)), 1, 1);
+    if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 2, 1>), grid, dim3(128), 0, stream, p);
+    else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 2, 1>), grid, dim3(128), 0, stream, p);
   } else {
     if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
     else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
@@ -595,11 +604,11 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
     const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
     dim3 grid((unsigned)(pairs8 * p.n_qblk * (p.hq / p.hkv)), 1, 1);
     if (block_rows == 128) {
-      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 4>), grid, dim3(256), 0, stream, p);
-      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 4>), grid, dim3(256), 0, stream, p);
+      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 4, 2>), grid, dim3(256), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 4, 2>), grid, dim3(256), 0, stream, p);
     } else {
-      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 8>), grid, dim3(512), 0, stream, p);
-      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 8>), grid, dim3(512), 0, stream, p);
+      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 8, 2>), grid, dim3(512), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 8, 2>), grid, dim3(512), 0, stream, p);
     }
   }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
