@@ -185,13 +185,51 @@ constexpr int kTileKeys = 64;    // keys per K/V tile in LDS
 
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
+// K/V tiles are written to LDS by the memory pipeline itself (buffer loads with the LDS bit: lane l of a wave
+// instruction deposits its 16 bytes at base + 16 l), so rows cannot be padded.  Bank conflicts are avoided by an XOR
+// swizzle instead: the 16-byte chunk c of row `row` lives at chunk position c ^ swz(row); each lane simply FETCHES the
+// chunk that belongs at its fixed LDS position.  The swizzle makes both read patterns conflict free: the K fragments
+// (16 consecutive rows, same chunk) and the transposing V reads (4 consecutive rows x 4 consecutive chunks).
+template <int D>
+__device__ __forceinline__ int swz(int row) {
+  if constexpr (D == 128) return 4 * (row & 3) + ((row >> 2) & 3);     // 16 chunks per row
+  else return 4 * ((row >> 1) & 1) + ((row >> 2) & 3);                  // 8 chunks per row (two rows per 256 bytes)
+}
 template <int D, int STAGES>
 struct PfSmem {
-  static constexpr int KS = D + 8;    // K row stride (elements): 16-byte reads of 16 consecutive rows hit all banks
-  static constexpr int VS = D + 32;   // V row stride: the 4 rows of a transposing read land 64 bytes apart (mod 256)
-  __bf16 k[STAGES][kTileKeys * KS];   // STAGES = 2: tile t+1 is written while tile t is read
-  __bf16 v[STAGES][kTileKeys * VS];
+  __bf16 k[STAGES][kTileKeys * D];   // ring of STAGES tiles: tiles t+1 .. t+STAGES-1 arrive while tile t is read
+  __bf16 v[STAGES][kTileKeys * D];
 };
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+// One 16-byte-per-lane buffer load that lands directly in LDS: lane l's chunk goes to lds_addr + 16 l (lds_addr, the
+// byte address inside LDS, is wave-uniform and travels in M0); a chunk outside the descriptor's range arrives as zeros.
+// Written as an instruction rather than through the compiler's builtin on purpose: the compiler cannot tell which LDS
+// reads such a load may alias and drains the whole vector-memory queue before every later LDS read, which would allow
+// no more than a fraction of one tile's compute time for a tile to arrive.  Here the kernel keeps the order itself
+// (tile_barrier below): a buffer is read only after a counted wait for its loads plus a workgroup barrier.  The kernel
+// uses M0 for nothing else.  The wait state between the M0 write and the load is the one the compiler also leaves.
+__device__ __forceinline__ void dma16_to_lds(u32x4 rsrc, unsigned lds_addr, int voff, int soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+               : "memory");
+}
+// Raw (unstrided, unswizzled) buffer descriptor over [base, base + bytes): accesses are range checked against `bytes`.
+__device__ __forceinline__ u32x4 raw_buffer(const void* base, int bytes) {
+  const unsigned long long a = (unsigned long long)base;
+  u32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((unsigned)a);
+  r[1] = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32) & 0xffffu);
+  r[2] = __builtin_amdgcn_readfirstlane((unsigned)bytes);
+  r[3] = 0x00020000u;
+  return r;
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {  // wait until at most N vector-memory loads of this wave are in flight
+  static_assert(N >= 0 && N < 64);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 
 // Between rescales the exponentials are taken against a stale row maximum, so they can exceed 1; they are allowed to
 // grow until a lane's partial row sum passes this limit.  That is harmless in fp32 sums and in bf16 operands, and the
@@ -228,7 +266,7 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
   constexpr int KSTEPS = D / 16;         // MFMA k-steps over head_dim for S^T
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int UPR = D / 8;             // 16-byte units per K/V row
-  constexpr int UNITS = kTileKeys * UPR / kPfThreads;  // 16-byte units per thread per tile and tensor
+  constexpr int PF = STAGES - 1;         // prefetch distance in tiles
   using Sm = PfSmem<D, STAGES>;
   __shared__ Sm sm;
 
@@ -249,7 +287,9 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
   const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
   const int q0 = qblk * kBlockRows;
   if (q0 >= n) return;
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  // the wave index is the same in all 64 lanes: say so, and everything derived from it (the wave's query window, its
+  // diagonal tile, the tile loop) lives in scalar registers and branches without touching the execution mask
+  const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int r32 = lane & 31, hf = lane >> 5;
   const int qw = q0 + wave * kWaveRows;          // first query row of this wave
   const bool wave_active = qw < n;
@@ -262,36 +302,48 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
   const __bf16* Vg = (const __bf16*)p.v + ((long long)b0 * p.hkv + c) * D;
   const long long kv_stride = (long long)p.hkv * D;
 
-  // ---- tile staging: global -> registers -> LDS ----
-  u32x4 kreg[UNITS], vreg[UNITS];
-  // element offset of this thread's units inside tile 0; a tile step adds kTileKeys * kv_stride
-  long long unit_off[UNITS];
+  // ---- tile staging: global -> LDS directly ----
+  // A tile is kTileKeys*UPR 16-byte units = UPR wave instructions per tensor; wave w issues instructions w, w+WAVES, ...
+  // Instruction I fills LDS units [64 I, 64 I + 64): rows RPI*I + lane/UPR, chunk position lane%UPR.  Rows past the end of
+  // the sequence are outside the buffer descriptor and read as zeros (finite data for the masked tail, no clamping).
+  constexpr int NI = UPR / WAVES;       // instructions per wave, tile and tensor
+  constexpr int RPI = kWave / UPR;      // rows per instruction
+  const int row_bytes = (int)kv_stride * 2;
+  const int seq_bytes = (n - 1) * row_bytes + D * 2;
+  const u32x4 k_rsrc = raw_buffer(Kg, seq_bytes), v_rsrc = raw_buffer(Vg, seq_bytes);
+  int st_voff[NI];
 #pragma unroll
-  for (int i = 0; i < UNITS; ++i) {
-    const int u = i * kPfThreads + threadIdx.x;
-    unit_off[i] = (u / UPR) * kv_stride + (u % UPR) * 8;
+  for (int i = 0; i < NI; ++i) {
+    const int row = RPI * (wave + WAVES * i) + lane / UPR;
+    st_voff[i] = row * row_bytes + ((lane % UPR) ^ swz<D>(row)) * 16;
   }
-  const int full_tiles = n / kTileKeys;  // tiles whose 64 rows all exist
-  auto load_tile = [&](int t) {
-    if (t < full_tiles) {
-      const long long base = (long long)t * kTileKeys * kv_stride;
+  const unsigned lds_k = (unsigned)(size_t)(lds_void_ptr)&sm.k[0][0], lds_v = (unsigned)(size_t)(lds_void_ptr)&sm.v[0][0];
+  auto issue_tile = [&](int t, int buf) {
+#if defined(EARN_DBG_NOSTAGE)
+    if (t >= STAGES) return;
+#endif
+    const int soff = t * kTileKeys * row_bytes;
 #pragma unroll
-      for (int i = 0; i < UNITS; ++i) {
-        kreg[i] = *(const u32x4*)(Kg + base + unit_off[i]);
-        vreg[i] = *(const u32x4*)(Vg + base + unit_off[i]);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < UNITS; ++i) {
-        const int u = i * kPfThreads + threadIdx.x;
-        const int row = u / UPR, cu8 = u % UPR;
-        const int key = min(t * kTileKeys + row, n - 1);  // rows past the sequence end repeat the last row (finite data)
-        kreg[i] = *(const u32x4*)(Kg + key * kv_stride + cu8 * 8);
-        vreg[i] = *(const u32x4*)(Vg + key * kv_stride + cu8 * 8);
-      }
+    for (int i = 0; i < NI; ++i) {
+      const unsigned at = (unsigned)((buf * kTileKeys * D + (wave + WAVES * i) * 512) * 2);
+      dma16_to_lds(k_rsrc, lds_k + at, st_voff[i], soff);
+      dma16_to_lds(v_rsrc, lds_v + at, st_voff[i], soff);
     }
   };
-  load_tile(0);  // in flight while the queries are loaded and rotated
+  // Ends iteration t (t = -1: the prologue): every wave waits until its own part of tile t+1 has landed, then the
+  // barrier makes all parts visible and tells everybody that buffer t % STAGES is free.  Loads complete in order and
+  // each tile is 2 NI loads per wave, so "tile t+1 has landed" = at most the PF-1 younger tiles are still in flight;
+  // near the end of the sequence, where no younger tile was issued, the wave simply drains its queue.
+  auto tile_barrier = [&](int t) {
+#if !defined(EARN_DBG_NOWAIT)
+    if (PF > 1 && t + PF < n_tiles) wait_vmcnt<(PF > 1 ? PF - 1 : 0) * 2 * NI>();
+    else wait_vmcnt<0>();
+#endif
+    __syncthreads();
+  };
+#pragma unroll
+  for (int i = 0; i < (PF > 0 ? PF : 1); ++i)
+    if (i < n_tiles) issue_tile(i, i);  // in flight while the queries are loaded and rotated
 
   // ---- Q fragments: rotate at the original position, fold in scale*log2(e), keep as bf16 B operands ----
   bf16x8 qf[QB][KSTEPS];
@@ -336,44 +388,38 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) { mrow[qb] = -INFINITY; lrow[qb] = 0.f; }
 
-  auto store_tile = [&](int buf) {
+  // per-lane LDS element offsets of the MFMA fragments (the swizzle does not depend on kb / kk: those add multiples of 16 rows)
+  int k_offs[KSTEPS];      // + kb * 32 * D
 #pragma unroll
-    for (int i = 0; i < UNITS; ++i) {
-      const int u = i * kPfThreads + threadIdx.x;
-      const int row = u / UPR, cu8 = u % UPR;
-      *(u32x4*)(sm.k[buf] + row * Sm::KS + cu8 * 8) = kreg[i];
-      *(u32x4*)(sm.v[buf] + row * Sm::VS + cu8 * 8) = vreg[i];
+  for (int ks = 0; ks < KSTEPS; ++ks) k_offs[ks] = r32 * D + (((2 * ks + hf) ^ swz<D>(r32)) << 3);
+  int v_offs[DB][2];       // + kk * 16 * D ; [..][1] is the second group of 4 keys (8 rows further)
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2) {
+      const int row = 4 * hf + 8 * h2 + ((lane & 15) >> 2);
+      const int chunk = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+      v_offs[db][h2] = row * D + ((chunk ^ swz<D>(row)) << 3) + 4 * (lane & 1);
     }
-  };
-
-  // per-lane LDS offsets
-  const int k_off = r32 * Sm::KS + 8 * hf;                                                   // + kb*32*KS + 16*ks
-  const int v_off = (4 * hf + ((lane & 15) >> 2)) * Sm::VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 16*kk*VS + 32*db
 
   // ---- pieces of one key-tile iteration ----
-  auto stage = [&](int t) {
-#if defined(EARN_DBG_NOSTAGE)
-    return;
-#endif
-    // tile t+1 goes to the other buffer (last read in iteration t-1, which every wave has left), tile t+2 into registers
-    if constexpr (STAGES == 2) {
-      if (t + 1 < n_tiles) store_tile((t & 1) ^ 1);
-      if (t + 2 < n_tiles) load_tile(t + 2);
+  // Called at the top of iteration t (buffer buf = t % STAGES holds tile t): tile t+PF starts streaming into the buffer
+  // that was last read in iteration t-1, which every wave has left through its barrier.
+  auto stage = [&](int t, int buf) {
+    if constexpr (STAGES > 1) {
+      if (t + PF < n_tiles) issue_tile(t + PF, buf == 0 ? STAGES - 1 : buf - 1);
     }
   };
   // S^T = K Q^T for tile t, causal mask on the diagonal tile.  All 2*KSTEPS K fragments are requested from LDS before
   // the first MFMA (and before `staging`, the global->LDS traffic of later tiles), so the MFMAs wait on a draining
   // queue instead of paying one LDS round trip each.
-  auto scores = [&](int t, f32x16 (&sc)[2][QB], bool do_stage) {
-    const __bf16* smk = sm.k[t & (STAGES - 1)];
+  auto scores = [&](int t, int buf, f32x16 (&sc)[2][QB]) {
+    const __bf16* smk = sm.k[buf];
     bf16x8 kf[2][KSTEPS];
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) kf[kb][ks] = *(const bf16x8*)(smk + k_off + kb * 32 * Sm::KS + 16 * ks);
-    __builtin_amdgcn_sched_barrier(0);
-    if (do_stage) stage(t);
-    __builtin_amdgcn_sched_barrier(0);
+      for (int kb = 0; kb < 2; ++kb) kf[kb][ks] = *(const bf16x8*)(smk + k_offs[ks] + kb * 32 * D);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -420,15 +466,14 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
   };
   // V^T fragments of tile t (A operands of the second product): requested before the exponentials so that the LDS
   // latency hides behind the vector-ALU work
-  auto fetch_v = [&](int t, bf16x8 (&vf)[4][DB]) {
-    const __bf16* smv = sm.v[t & (STAGES - 1)];
+  auto fetch_v = [&](int buf, bf16x8 (&vf)[4][DB]) {
+    const __bf16* smv = sm.v[buf];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const __bf16* vp = smv + v_off + 16 * kk * Sm::VS + 32 * db;
-        s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
-        s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * Sm::VS));
+        s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smv + v_offs[db][0] + kk * 16 * D));
+        s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smv + v_offs[db][1] + kk * 16 * D));
         typedef short s16x8 __attribute__((ext_vector_type(8)));
         s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
         vf[kk][db] = __builtin_bit_cast(bf16x8, vv);
@@ -459,69 +504,72 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
           o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[qb][kk], o[db][qb], 0, 0, 0);
   };
 
-  store_tile(0);
-  if (STAGES == 2 && n_tiles > 1) load_tile(1);
-  __syncthreads();
+  tile_barrier(-1);
   // Every tile iteration ends in exactly one barrier, whichever path a wave takes.  The steady-state loop takes the
   // exponentials against the reference maxima it already has and never touches the output accumulators with the
   // vector ALU.  It does not even compute row maxima: a reference is stale exactly when some exponential is large, so
   // the (already needed) partial row sums are compared with kSumLimit instead; +inf and NaN (first tile, reference
   // still -inf) fail the comparison too.  A wave that fails leaves the loop, recomputes the tile's scores, takes the
   // exact maxima, rescales, finishes the tile and re-enters.
-  int t = 0;
+  // One steady-state iteration; returns true when the tile was finished, false when the references are stale.
+  auto fast_tile = [&](int t, int buf) -> bool {
+    stage(t, buf);
+    if (!(wave_active && t <= t_diag)) return true;
+    f32x16 sc[2][QB];
+    float lsum[QB];
+    bf16x8 vf[4][DB];
+    scores(t, buf, sc);
+    fetch_v(buf, vf);
+    exponentials(sc, lsum);
+    bool stale = false;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) stale |= !(lsum[qb] <= kSumLimit);
+    if (__any(stale)) return false;
+    accumulate(sc, lsum, vf);
+    return true;
+  };
+  // The same tile with exact maxima and a rescale of everything accumulated so far.
+  auto exact_tile = [&](int t, int buf, bool do_stage) {
+    if (do_stage) stage(t, buf);  // a tile that fell out of the steady-state loop has staged its successor already
+    f32x16 sc[2][QB];
+    float lsum[QB];
+    bf16x8 vf[4][DB];
+    scores(t, buf, sc);
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float m = sc[0][qb][0];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) m = fmaxf(m, sc[kb][qb][i]);
+      const float mnew = fmaxf(mrow[qb], half_max(m));  // finite: tile 0 holds key 0, visible to every query
+      const float alpha = __builtin_amdgcn_exp2f(mrow[qb] - mnew);
+      mrow[qb] = mnew;
+      lrow[qb] *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
+    }
+    fetch_v(buf, vf);
+    exponentials(sc, lsum);
+    accumulate(sc, lsum, vf);
+  };
+  int t = 0, buf = 0;  // buf = t % STAGES
   bool first = wave_active;  // tile 0 always needs the exact maxima (the reference is still -inf): no point trying the fast path
   while (t < n_tiles) {
     bool rescale = first;
     if (!first)
-    for (; t < n_tiles; ++t) {
-      if (wave_active && t <= t_diag) {
-        f32x16 sc[2][QB];
-        float lsum[QB];
-        bf16x8 vf[4][DB];
-        scores(t, sc, true);
-        fetch_v(t, vf);
-        exponentials(sc, lsum);
-        bool stale = false;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) stale |= !(lsum[qb] <= kSumLimit);
-        if (__any(stale)) { rescale = true; break; }
-        accumulate(sc, lsum, vf);
-      } else {
-        stage(t);
-      }
-#if !defined(EARN_DBG_NOBARRIER)
-      __syncthreads();  // tile t+1 is visible; nobody reads buffer t&1 any more
-#endif
+    for (; t < n_tiles; ++t, buf = (buf + 1 == STAGES ? 0 : buf + 1)) {
+      if (!fast_tile(t, buf)) { rescale = true; break; }
+      tile_barrier(t);
     }
     if (!rescale) break;
-    {
-      f32x16 sc[2][QB];
-      float lsum[QB];
-      bf16x8 vf[4][DB];
-      scores(t, sc, first);  // the tile was staged before the wave left the loop (tile 0: staged here)
-      first = false;
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        float m = sc[0][qb][0];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) m = fmaxf(m, sc[kb][qb][i]);
-        const float mnew = fmaxf(mrow[qb], half_max(m));  // finite: tile 0 holds key 0, visible to every query
-        const float alpha = __builtin_amdgcn_exp2f(mrow[qb] - mnew);
-        mrow[qb] = mnew;
-        lrow[qb] *= alpha;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
-      }
-      fetch_v(t, vf);
-      exponentials(sc, lsum);
-      accumulate(sc, lsum, vf);
-      __syncthreads();
-      ++t;
-    }
+    exact_tile(t, buf, first);
+    first = false;
+    tile_barrier(t);
+    ++t;
+    buf = (buf + 1 == STAGES ? 0 : buf + 1);
   }
 
   if (!wave_active) return;
