@@ -23,6 +23,7 @@
 #include <stdlib.h>
 
 #include "common.h"
+#include <type_traits>
 
 namespace earn {
 
@@ -207,7 +208,7 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 // Written as an instruction rather than through the compiler's builtin on purpose: the compiler cannot tell which LDS
 // reads such a load may alias and drains the whole vector-memory queue before every later LDS read, which would allow
 // no more than a fraction of one tile's compute time for a tile to arrive.  Here the kernel keeps the order itself
-// (tile_barrier below): a buffer is read only after a counted wait for its loads plus a workgroup barrier.  The kernel
+// (sync_and_stage below): a buffer is read only after a counted wait for its loads plus a workgroup barrier.  The kernel
 // uses M0 for nothing else.  The wait state between the M0 write and the load is the one the compiler also leaves.
 __device__ __forceinline__ void dma16_to_lds(u32x4 rsrc, unsigned lds_addr, int voff, int soff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
@@ -260,13 +261,13 @@ __device__ __forceinline__ float half_sum(float x) {
 // what hides the load -> rotate -> multiply latency chain of these tiny problems.
 template <int D, int QB, int WAVES, int STAGES>
 __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void prefill_mfma_kernel(PrefillParams p) {
-  constexpr int kPfThreads = 64 * WAVES;
   constexpr int kWaveRows = 32 * QB;
   constexpr int kBlockRows = kWaveRows * WAVES;
   constexpr int KSTEPS = D / 16;         // MFMA k-steps over head_dim for S^T
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int UPR = D / 8;             // 16-byte units per K/V row
-  constexpr int PF = STAGES - 1;         // prefetch distance in tiles
+  constexpr bool PP = STAGES == 3;       // ping-pong schedule of the two waves of a SIMD
+  static_assert(!PP || WAVES == 8, "ping-pong pairs wave w with wave w + 4 on one SIMD");
   using Sm = PfSmem<D, STAGES>;
   __shared__ Sm sm;
 
@@ -330,20 +331,24 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
       dma16_to_lds(v_rsrc, lds_v + at, st_voff[i], soff);
     }
   };
-  // Ends iteration t (t = -1: the prologue): every wave waits until its own part of tile t+1 has landed, then the
-  // barrier makes all parts visible and tells everybody that buffer t % STAGES is free.  Loads complete in order and
-  // each tile is 2 NI loads per wave, so "tile t+1 has landed" = at most the PF-1 younger tiles are still in flight;
-  // near the end of the sequence, where no younger tile was issued, the wave simply drains its queue.
-  auto tile_barrier = [&](int t) {
+  // Barrier b (b = 0, 1, ..): every wave has waited for its own part of tile b, so behind the barrier tile b is
+  // complete and visible; the wave then starts its part of tile b+1 into the next buffer of the ring.  Waves that run
+  // "on time" pass barrier b at the top of iteration b.  With PP (ping-pong, 3 buffers) the upper half of the waves runs
+  // "late": it passes barrier b+1 in the MIDDLE of iteration b, between its two matrix products.  The barrier then
+  // holds the two waves that share a SIMD half an iteration apart for good, so that one of them is in its matrix
+  // products while the other is in its exponentials, instead of both competing for the same unit and leaving the other
+  // idle.  Buffer (b+1) % STAGES held tile b+1-STAGES: on-time waves are done with that tile before barrier b+2-STAGES,
+  // late waves (STAGES = 3) read its V between barriers b-1 and b; both are behind every wave when barrier b opens.
+  auto sync_and_stage = [&](int b) {
 #if !defined(EARN_DBG_NOWAIT)
-    if (PF > 1 && t + PF < n_tiles) wait_vmcnt<(PF > 1 ? PF - 1 : 0) * 2 * NI>();
-    else wait_vmcnt<0>();
+    wait_vmcnt<0>();
 #endif
     __syncthreads();
+    if constexpr (STAGES > 1) {
+      if (b + 1 < n_tiles) issue_tile(b + 1, (b + 1) % STAGES);
+    }
   };
-#pragma unroll
-  for (int i = 0; i < (PF > 0 ? PF : 1); ++i)
-    if (i < n_tiles) issue_tile(i, i);  // in flight while the queries are loaded and rotated
+  issue_tile(0, 0);  // in flight while the queries are loaded and rotated
 
   // ---- Q fragments: rotate at the original position, fold in scale*log2(e), keep as bf16 B operands ----
   bf16x8 qf[QB][KSTEPS];
@@ -403,65 +408,93 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
     }
 
   // ---- pieces of one key-tile iteration ----
-  // Called at the top of iteration t (buffer buf = t % STAGES holds tile t): tile t+PF starts streaming into the buffer
-  // that was last read in iteration t-1, which every wave has left through its barrier.
-  auto stage = [&](int t, int buf) {
-    if constexpr (STAGES > 1) {
-      if (t + PF < n_tiles) issue_tile(t + PF, buf == 0 ? STAGES - 1 : buf - 1);
-    }
-  };
-  // S^T = K Q^T for tile t, causal mask on the diagonal tile.  All 2*KSTEPS K fragments are requested from LDS before
+  // S^T = K Q^T for tile t.  All 2*KSTEPS K fragments are requested from LDS before
   // the first MFMA (and before `staging`, the global->LDS traffic of later tiles), so the MFMAs wait on a draining
   // queue instead of paying one LDS round trip each.
-  auto scores = [&](int t, int buf, f32x16 (&sc)[2][QB]) {
+  auto scores = [&](int buf, f32x16 (&sc)[2][QB], const f32x16 (&init)[QB]) {
     const __bf16* smk = sm.k[buf];
+#ifndef EARN_PF_KAHEAD
+#define EARN_PF_KAHEAD 2
+#endif
+    constexpr int AHEAD = EARN_PF_KAHEAD < KSTEPS ? EARN_PF_KAHEAD : KSTEPS;  // k-steps of K fragments in flight ahead of the MFMAs
     bf16x8 kf[2][KSTEPS];
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks)
+    auto fetch_k = [&](int ks) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) kf[kb][ks] = *(const bf16x8*)(smk + k_offs[ks] + kb * 32 * D);
+    };
+#pragma unroll
+    for (int ks = 0; ks < AHEAD; ++ks) fetch_k(ks);
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      if (ks + AHEAD < KSTEPS) fetch_k(ks + AHEAD);
+      __builtin_amdgcn_sched_barrier(0);  // the fragment requests stay ahead of the MFMAs that hide their latency
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+          sc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qb][ks], ks == 0 ? init[qb] : sc[kb][qb], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // causal mask, in place; it only bites on the wave's diagonal tile (keys beyond the sequence end are beyond every
+  // valid query too), elsewhere the bound is out of reach
+  auto mask_causal = [&](int t, f32x16 (&sc)[2][QB]) {
+    const int bound = t == t_diag ? q_in_tile + r32 - 4 * hf : kTileKeys;  // lane's last visible key, less its 4 hf share
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sc[kb][qb][i] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          sc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qb][ks], sc[kb][qb], 0, 0, 0);
-    if (t == t_diag) {  // keys beyond the sequence end are beyond every valid query too
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key = 32 * kb + 8 * (i >> 2) + 4 * hf + (i & 3);
-            if (key > q_in_tile + 32 * qb + r32) sc[kb][qb][i] = -INFINITY;
-          }
-    }
+        for (int i = 0; i < 16; ++i)
+          sc[kb][qb][i] = (32 * kb + 8 * (i >> 2) + (i & 3) > bound + 32 * qb) ? -INFINITY : sc[kb][qb][i];
   };
-  // P = exp2(S - m) against the current reference maxima (in place) and the lane's share of the row sums
-  auto exponentials = [&](f32x16 (&sc)[2][QB], float (&lsum)[QB]) {
+  // P = exp2(S - m) in place.  SHIFTED: the scores already carry -m (the steady-state path starts its score
+  // accumulators at -m instead of 0, which takes the subtraction off the vector ALU).
+  auto exponentials = [&](f32x16 (&sc)[2][QB], auto shifted) {
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      lsum[qb] = 0.f;
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
 #if defined(EARN_DBG_NOEXP)
-          const float e = sc[kb][qb][i] * 1e-30f;
+          sc[kb][qb][i] = sc[kb][qb][i] * 1e-30f;
 #else
-          const float e = __builtin_amdgcn_exp2f(sc[kb][qb][i] - mrow[qb]);
+          sc[kb][qb][i] = __builtin_amdgcn_exp2f(decltype(shifted)::value ? sc[kb][qb][i] : sc[kb][qb][i] - mrow[qb]);
 #endif
-          sc[kb][qb][i] = e;
-          lsum[qb] += e;
         }
+  };
+  // P as bf16 B operands of the second product, and the lane's share of the row sums.  The sums are taken over the
+  // ROUNDED probabilities (two per instruction, exact products with 1 accumulated in fp32): they are the weights the
+  // second product really applies, and it halves the additions.
+  auto pack_probs = [&](f32x16 (&sc)[2][QB], bf16x8 (&pf)[QB][4], float (&lsum)[QB]) {
+    const unsigned ones = 0x3f803f80u;  // (1.0, 1.0) in bf16
+    // acc += w.lo + w.hi.  Written as instructions: the compiler's own dot builtin came out wrong in this kernel (half
+    // of the words summed twice, the other half not at all).  What the compiler would otherwise look after is done by
+    // hand: a dot result may feed the next dot's accumulator at once, but any other vector instruction has to keep
+    // three wait states' distance, hence the s_nop in front of the closing addition.
+    auto add_pair = [&](float& acc, unsigned w) {
+      asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(acc) : "s"(ones), "v"(w));
+    };
+    auto add_chains = [&](float s0, float s1) {
+      float r;
+      asm("s_nop 2\n\tv_add_f32 %0, %1, %2" : "=v"(r) : "v"(s0), "v"(s1));
+      return r;
+    };
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float s0 = 0.f, s1 = 0.f;  // two chains
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        u32x4 w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          w[j] = pack_bf16(sc[kk >> 1][qb][8 * (kk & 1) + 2 * j], sc[kk >> 1][qb][8 * (kk & 1) + 2 * j + 1]);
+          add_pair(j & 1 ? s1 : s0, w[j]);
+        }
+        pf[qb][kk] = __builtin_bit_cast(bf16x8, w);
+      }
+      lsum[qb] = add_chains(s0, s1);
     }
   };
   // V^T fragments of tile t (A operands of the second product): requested before the exponentials so that the LDS
@@ -481,20 +514,9 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
     __builtin_amdgcn_sched_barrier(0);
   };
   // row sums, O^T += V^T P^T
-  auto accumulate = [&](f32x16 (&sc)[2][QB], float (&lsum)[QB], bf16x8 (&vf)[4][DB]) {
-    bf16x8 pf[QB][4];  // [query block][16-key step]
+  auto accumulate = [&](bf16x8 (&pf)[QB][4], float (&lsum)[QB], bf16x8 (&vf)[4][DB]) {
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      lrow[qb] += lsum[qb];
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        u32x4 w;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          w[j] = pack_bf16(sc[kk >> 1][qb][8 * (kk & 1) + 2 * j], sc[kk >> 1][qb][8 * (kk & 1) + 2 * j + 1]);
-        pf[qb][kk] = __builtin_bit_cast(bf16x8, w);
-      }
-    }
+    for (int qb = 0; qb < QB; ++qb) lrow[qb] += lsum[qb];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
@@ -504,37 +526,29 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
           o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[qb][kk], o[db][qb], 0, 0, 0);
   };
 
-  tile_barrier(-1);
-  // Every tile iteration ends in exactly one barrier, whichever path a wave takes.  The steady-state loop takes the
+  // Every wave passes exactly one barrier per tile, whichever path it takes.  The steady-state loop takes the
   // exponentials against the reference maxima it already has and never touches the output accumulators with the
   // vector ALU.  It does not even compute row maxima: a reference is stale exactly when some exponential is large, so
-  // the (already needed) partial row sums are compared with kSumLimit instead; +inf and NaN (first tile, reference
-  // still -inf) fail the comparison too.  A wave that fails leaves the loop, recomputes the tile's scores, takes the
-  // exact maxima, rescales, finishes the tile and re-enters.
-  // One steady-state iteration; returns true when the tile was finished, false when the references are stale.
-  auto fast_tile = [&](int t, int buf) -> bool {
-    stage(t, buf);
-    if (!(wave_active && t <= t_diag)) return true;
-    f32x16 sc[2][QB];
-    float lsum[QB];
-    bf16x8 vf[4][DB];
-    scores(t, buf, sc);
-    fetch_v(buf, vf);
-    exponentials(sc, lsum);
-    bool stale = false;
+  // the (already needed) partial row sums are compared with kSumLimit instead.  A wave that fails leaves the loop,
+  // recomputes the tile's scores, takes the exact maxima, rescales, finishes the tile and re-enters.  Tile 0 (reference
+  // still -inf) and the wave's diagonal tile (the only one that needs the causal mask) always take the exact path.
+  f32x16 zero16[QB], neg_m[QB];  // score accumulator starts: 0 (exact path), -m in every register (steady state)
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) stale |= !(lsum[qb] <= kSumLimit);
-    if (__any(stale)) return false;
-    accumulate(sc, lsum, vf);
-    return true;
-  };
-  // The same tile with exact maxima and a rescale of everything accumulated so far.
-  auto exact_tile = [&](int t, int buf, bool do_stage) {
-    if (do_stage) stage(t, buf);  // a tile that fell out of the steady-state loop has staged its successor already
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { zero16[qb][i] = 0.f; neg_m[qb][i] = 0.f; }
+  const bool late = PP && wave >= WAVES / 2;
+  if (late) sync_and_stage(0);
+  // The exact path.  synced = the tile fell out of the steady-state loop, which has passed the tile's barrier already.
+  auto exact_tile = [&](int t, int buf, bool synced) {
+    if (!late && !synced) sync_and_stage(t);
     f32x16 sc[2][QB];
     float lsum[QB];
     bf16x8 vf[4][DB];
-    scores(t, buf, sc);
+    bf16x8 pf[QB][4];
+    scores(buf, sc, zero16);
+    mask_causal(t, sc);
+    if (late && !synced && t + 1 < n_tiles) sync_and_stage(t + 1);
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       float m = sc[0][qb][0];
@@ -545,6 +559,8 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
       const float mnew = fmaxf(mrow[qb], half_max(m));  // finite: tile 0 holds key 0, visible to every query
       const float alpha = __builtin_amdgcn_exp2f(mrow[qb] - mnew);
       mrow[qb] = mnew;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) neg_m[qb][i] = -mnew;
       lrow[qb] *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
@@ -552,24 +568,59 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
         for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
     }
     fetch_v(buf, vf);
-    exponentials(sc, lsum);
-    accumulate(sc, lsum, vf);
+    exponentials(sc, std::false_type{});
+    pack_probs(sc, pf, lsum);
+    accumulate(pf, lsum, vf);
   };
+#if defined(EARN_DBG_PHASES)  // working instrumentation: cycles per phase of the steady-state loop, written in place of lse
+  long long ph[5] = {0, 0, 0, 0, 0};
+  int ph_tiles = 0;
+#define PH_STAMP(x) { __builtin_amdgcn_sched_barrier(0); x = (long long)__builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); }
+#else
+#define PH_STAMP(x)
+#endif
   int t = 0, buf = 0;  // buf = t % STAGES
-  bool first = wave_active;  // tile 0 always needs the exact maxima (the reference is still -inf): no point trying the fast path
+  auto next_tile = [&]() { ++t; buf = (buf + 1 == STAGES ? 0 : buf + 1); };
   while (t < n_tiles) {
-    bool rescale = first;
-    if (!first)
-    for (; t < n_tiles; ++t, buf = (buf + 1 == STAGES ? 0 : buf + 1)) {
-      if (!fast_tile(t, buf)) { rescale = true; break; }
-      tile_barrier(t);
+    bool exact = wave_active && t == 0, synced = false;
+    if (!exact)
+    for (; t < n_tiles; next_tile()) {
+      const bool work = wave_active && t <= t_diag;  // else rows past the sequence end or a tile past the diagonal: only stage
+      if (work && t == t_diag) { exact = true; break; }
+      [[maybe_unused]] long long c0, c1, c2, c2b, c3, c4;
+      PH_STAMP(c0);
+      if (!late) sync_and_stage(t);
+      PH_STAMP(c1);
+      f32x16 sc[2][QB];
+      float lsum[QB];
+      bf16x8 vf[4][DB];
+      bf16x8 pf[QB][4];
+      if (work) scores(buf, sc, neg_m);
+      PH_STAMP(c2);
+      if (late && t + 1 < n_tiles) sync_and_stage(t + 1);
+      PH_STAMP(c2b);
+      if (work) {
+        fetch_v(buf, vf);
+#if defined(EARN_DBG_PHASES) && EARN_DBG_PHASES == 2
+        { long long cv; PH_STAMP(cv); ph[4] += cv - c2b; }
+#endif
+        exponentials(sc, std::true_type{});
+        pack_probs(sc, pf, lsum);
+        PH_STAMP(c3);
+        bool stale = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) stale |= !(lsum[qb] <= kSumLimit);
+        if (__any(stale)) { exact = synced = true; break; }
+        accumulate(pf, lsum, vf);
+        PH_STAMP(c4);
+#if defined(EARN_DBG_PHASES)
+        ph[0] += c1 - c0; ph[1] += c2 - c1; ph[2] += c3 - c2b; ph[3] += c4 - c3; ph[4] += c2b - c2; ++ph_tiles;
+#endif
+      }
     }
-    if (!rescale) break;
-    exact_tile(t, buf, first);
-    first = false;
-    tile_barrier(t);
-    ++t;
-    buf = (buf + 1 == STAGES ? 0 : buf + 1);
+    if (!exact) break;
+    exact_tile(t, buf, synced);
+    next_tile();
   }
 
   if (!wave_active) return;
@@ -590,7 +641,11 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
         w[1] = pack_bf16(o[db][qb][4 * j + 2] * inv, o[db][qb][4 * j + 3] * inv);
         *(u32x2*)(orow + 32 * db + 8 * j) = w;
       }
+#if defined(EARN_DBG_PHASES)
+    if (p.lse && hf == 0) p.lse[(long long)(b0 + qi) * p.hq + a] = r32 < 5 ? (float)ph[r32 < 5 ? r32 : 0] / (float)max(ph_tiles, 1) : (float)ph_tiles;
+#else
     if (p.lse && hf == 0) p.lse[(long long)(b0 + qi) * p.hq + a] = (mrow[qb] + __builtin_log2f(ltot)) * 0.6931471805599453f;
+#endif
   }
 }
 
@@ -611,6 +666,12 @@ static void launch_rope_k(const void* k, void* k_rot, const int32_t* cu, const i
                      (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope);
 }
 
+#ifndef EARN_PF_STAGES4
+#define EARN_PF_STAGES4 2
+#endif
+#ifndef EARN_PF_STAGES8
+#define EARN_PF_STAGES8 2
+#endif
 int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
                    const int32_t* positions, int batch, int total_tokens, int max_seqlen, void* out, void* k_rot_out,
                    float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
@@ -652,11 +713,11 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
     const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
     dim3 grid((unsigned)(pairs8 * p.n_qblk * (p.hq / p.hkv)), 1, 1);
     if (block_rows == 128) {
-      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 4, 2>), grid, dim3(256), 0, stream, p);
-      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 4, 2>), grid, dim3(256), 0, stream, p);
+      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 4, EARN_PF_STAGES4>), grid, dim3(256), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 4, EARN_PF_STAGES4>), grid, dim3(256), 0, stream, p);
     } else {
-      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 8, 2>), grid, dim3(512), 0, stream, p);
-      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 8, 2>), grid, dim3(512), 0, stream, p);
+      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 8, EARN_PF_STAGES8>), grid, dim3(512), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 8, EARN_PF_STAGES8>), grid, dim3(512), 0, stream, p);
     }
   }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
