@@ -100,6 +100,10 @@ def earn_prefill_workspace_bytes(desc: AttnDesc, batch: int, total_tokens: int, 
 
 def earn_prefill_attn(desc: AttnDesc, q, k, v, cu_seqlens, positions, batch: int, total_tokens: int, max_seqlen: int,
                       out, k_rot_out=None, lse_out=None, workspace=None) -> None:
+    if workspace is None:  # convenience for one-off calls; loops pass a buffer sized with earn_prefill_workspace_bytes
+        need = earn_prefill_workspace_bytes(desc, batch, total_tokens, max_seqlen, k_rot_out is not None)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().earn_prefill_attn(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(cu_seqlens), _ptr(positions),
                                    batch, total_tokens, max_seqlen, _ptr(out), _ptr(k_rot_out), _ptr(lse_out),

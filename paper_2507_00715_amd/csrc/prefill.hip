@@ -2,15 +2,18 @@
 // k layers and on the compacted register rows, with their original positions, for the remaining N-k layers —
 // Section 3.2, Inference).
 //
-// Three kernels:
+// Kernels:
 //   rope_k_kernel        rotates K once per layer into the buffer the KV cache keeps (k_rot_out); every query block
 //                        then reads rotated keys, so the sin/cos work is O(T), not O(T * blocks).
-//   prefill_mfma_kernel  bf16 flash-style attention on the matrix cores (v_mfma_f32_32x32x16_bf16).
-//   prefill_rows_kernel  fp32 (or bf16) attention on the vector ALU: one query row per 4 lanes. Used for the fp32
+//   prefill_pipe_kernel  bf16 flash-style attention on the matrix cores (v_mfma_f32_32x32x16_bf16), software pipelined:
+//                        long sequences.
+//   prefill_mfma_kernel  the same arithmetic in a plain per-tile schedule with smaller workgroups: medium sequences and
+//                        the register-only layers.
+//   prefill_rows_kernel  fp32 attention on the vector ALU: one query row per 4 lanes. Used for the fp32
 //                        configuration, where the 1e-4 tolerance rules out bf16 operands.
 //
 // MFMA kernel layout (all shapes in the 32x32x16 tile of the instruction, 64 lanes, lane = (r32 = lane%32, hf = lane/32)):
-//   The kernel computes the TRANSPOSED score tile S^T = K Q^T (keys x queries).  Its accumulator layout gives every lane
+//   The kernels compute the TRANSPOSED score tile S^T = K Q^T (keys x queries).  Its accumulator layout gives every lane
 //   ONE query column (r32) and 16 of the 32 keys of a block, so the softmax row statistics are a private loop plus one
 //   exchange with lane^32, and the rescaling of the output accumulator is lane-private as well.
 //   The accumulator registers of S^T, converted to bf16, are exactly the B operand (keys x queries, 8 keys per lane)
@@ -18,17 +21,16 @@
 //   {4hf..4hf+3, 8+4hf..8+4hf+3} of a 16-key step; the A operand V^T uses the same key order, which is what two
 //   transposing LDS reads (ds_read_b64_tr_b16: 4 consecutive keys of one d column) deliver from a V tile kept in its
 //   natural [key][d] layout.
-//   A workgroup is 4 waves; each wave owns 64 query rows (2 column blocks), so every K/V fragment read from LDS feeds
-//   two MFMAs; the 64-key K/V tile in LDS is shared by the 4 waves (256 query rows per tile load).
+//   Each wave owns 32 query rows; the 64-key K/V tile in LDS is shared by the waves of a workgroup.
 #include <stdlib.h>
 
 #include "common.h"
-#include <type_traits>
 
 namespace earn {
 
 struct PrefillParams {
   const void* q; const void* k_rot; const void* v; const int32_t* cu; const int32_t* positions;
+  const f32x2* cs;  // [tokens][d/2] (cos, sin) of every token's rotary angles, written by rope_k_kernel (bf16 paths)
   void* out; float* lse;
   int batch, hq, hkv, max_seqlen;
   int n_qblk;  // query blocks of the longest sequence
@@ -66,11 +68,14 @@ template <> struct Vec8<__bf16> {
 
 // One thread per (token, group of 8 rotary pairs): the sin/cos of the group are computed once and applied to every kv
 // head of the token.  bf16 rows use the hardware sin/cos (error ~1e-6, far below bf16 resolution).
+// cs_out (optional): the (cos, sin) pairs themselves, [token][d/2].  The attention kernels rotate their query rows with
+// them: a workgroup per query head would otherwise recompute the same angles once per head, and on short sequences
+// that prologue costs as much as the attention itself.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T* __restrict__ k_rot,
                                                      const int32_t* __restrict__ cu,
                                                      const int32_t* __restrict__ positions, int batch, int total,
-                                                     int hkv, RopeTable rope) {
+                                                     int hkv, RopeTable rope, f32x2* __restrict__ cs_out) {
   constexpr int G = D / 16;  // groups of 8 pairs per head
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
   if (t >= (long long)total * G) return;
@@ -90,6 +95,11 @@ __global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T*
   } else {
 #pragma unroll
     for (int i = 0; i < 8; ++i) { sn[i] = 0.f; cs[i] = 1.f; }
+  }
+  if (cs_out) {
+    f32x4* dst4 = (f32x4*)(cs_out + (long long)token * (D / 2) + g * 8);
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) dst4[i / 2] = f32x4{cs[i], sn[i], cs[i + 1], sn[i + 1]};
   }
   const T* src = k + (long long)token * hkv * D + g * 8;
   T* dst = k_rot + (long long)token * hkv * D + g * 8;
@@ -185,6 +195,7 @@ constexpr int kXcds = 8;         // accelerator complex dies, each with a privat
 constexpr int kTileKeys = 64;    // keys per K/V tile in LDS
 
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 // K/V tiles are written to LDS by the memory pipeline itself (buffer loads with the LDS bit: lane l of a wave
 // instruction deposits its 16 bytes at base + 16 l), so rows cannot be padded.  Bank conflicts are avoided by an XOR
@@ -196,20 +207,14 @@ __device__ __forceinline__ int swz(int row) {
   if constexpr (D == 128) return 4 * (row & 3) + ((row >> 2) & 3);     // 16 chunks per row
   else return 4 * ((row >> 1) & 1) + ((row >> 2) & 3);                  // 8 chunks per row (two rows per 256 bytes)
 }
-template <int D, int STAGES>
-struct PfSmem {
-  __bf16 k[STAGES][kTileKeys * D];   // ring of STAGES tiles: tiles t+1 .. t+STAGES-1 arrive while tile t is read
-  __bf16 v[STAGES][kTileKeys * D];
-};
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 // One 16-byte-per-lane buffer load that lands directly in LDS: lane l's chunk goes to lds_addr + 16 l (lds_addr, the
 // byte address inside LDS, is wave-uniform and travels in M0); a chunk outside the descriptor's range arrives as zeros.
 // Written as an instruction rather than through the compiler's builtin on purpose: the compiler cannot tell which LDS
 // reads such a load may alias and drains the whole vector-memory queue before every later LDS read, which would allow
-// no more than a fraction of one tile's compute time for a tile to arrive.  Here the kernel keeps the order itself
-// (sync_and_stage below): a buffer is read only after a counted wait for its loads plus a workgroup barrier.  The kernel
-// uses M0 for nothing else.  The wait state between the M0 write and the load is the one the compiler also leaves.
+// no more than a fraction of one tile's compute time for a tile to arrive.  Here the kernels keep the order themselves:
+// a buffer is read only after a wait for the wave's own loads plus a workgroup barrier.  The kernels use M0 for
+// nothing else.  The wait state between the M0 write and the load is the one the compiler also leaves.
 __device__ __forceinline__ void dma16_to_lds(u32x4 rsrc, unsigned lds_addr, int voff, int soff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
@@ -226,10 +231,10 @@ __device__ __forceinline__ u32x4 raw_buffer(const void* base, int bytes) {
   r[3] = 0x00020000u;
   return r;
 }
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {  // wait until at most N vector-memory loads of this wave are in flight
-  static_assert(N >= 0 && N < 64);
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+// wait until none of this wave's vector-memory loads is in flight, then meet the workgroup
+__device__ __forceinline__ void drain_loads_and_barrier() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  __syncthreads();
 }
 
 // Between rescales the exponentials are taken against a stale row maximum, so they can exceed 1; they are allowed to
@@ -248,282 +253,322 @@ __device__ __forceinline__ float half_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// QB = 32-query column blocks per wave; the workgroup has 8/QB waves (256 query rows either way).
-//   QB = 2: 4 waves, one per SIMD, every K/V fragment read from LDS feeds two MFMAs, ~470 registers per lane.
-//   QB = 1: 8 waves, two per SIMD (<= 256 registers per lane): while one wave of a SIMD runs its softmax on the
-//           vector ALU the other keeps the matrix core busy; LDS traffic per MFMA doubles (fits: LDS reads run at
-//           256 B/clk per CU on this part).
-// WAVES = waves per workgroup.  8 (or 4 with QB = 2) gives 256 query rows per workgroup; WAVES = 4 with QB = 1 gives
-// 128-row workgroups, two of which share a CU: less idle time on the causal diagonal of short sequences, at the price
-// of staging every K/V tile twice as often.
-// STAGES = 1 (with WAVES = 2: 64 rows) is the register-only-layer variant: every sequence fits one K/V tile, so there is
-// nothing to double buffer, and the small footprint (38 KiB LDS, 128 threads) lets 4 workgroups share a CU, which is
-// what hides the load -> rotate -> multiply latency chain of these tiny problems.
-template <int D, int QB, int WAVES, int STAGES>
-__global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void prefill_mfma_kernel(PrefillParams p) {
-  constexpr int kWaveRows = 32 * QB;
-  constexpr int kBlockRows = kWaveRows * WAVES;
-  constexpr int KSTEPS = D / 16;         // MFMA k-steps over head_dim for S^T
-  constexpr int DB = D / 32;             // 32-row blocks of O^T
-  constexpr int UPR = D / 8;             // 16-byte units per K/V row
-  constexpr bool PP = STAGES == 3;       // ping-pong schedule of the two waves of a SIMD
-  static_assert(!PP || WAVES == 8, "ping-pong pairs wave w with wave w + 4 on one SIMD");
-  using Sm = PfSmem<D, STAGES>;
-  __shared__ Sm sm;
+// Row sums over ROUNDED probabilities, two per instruction (exact products with 1, accumulated in fp32): they are the
+// weights the second product really applies, and it halves the additions.  acc += w.lo + w.hi.
+// Written as instructions: the compiler's own dot builtin came out wrong inside these kernels (half of the words summed
+// twice, the other half not at all).  What the compiler would otherwise look after is done by hand: a dot result may
+// feed the next dot's accumulator at once, but any other vector instruction has to keep three wait states' distance,
+// hence the s_nop in front of the addition that closes the two chains.
+__device__ __forceinline__ void add_pair(float& acc, unsigned w) {
+  const unsigned ones = 0x3f803f80u;  // (1.0, 1.0) in bf16
+  asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(acc) : "s"(ones), "v"(w));
+}
+__device__ __forceinline__ float add_chains(float s0, float s1) {
+  float r;
+  asm("s_nop 2\n\tv_add_f32 %0, %1, %2" : "=v"(r) : "v"(s0), "v"(s1));
+  return r;
+}
 
-  // ---- workgroup -> (sequence, kv head, query block, head of the group), XCD aware ----
-  // Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  Id (x, k) = the k-th
-  // workgroup of XCD x.  Each XCD walks its own list of (sequence, kv head) pairs (pair % 8 == x) one pair at a time:
-  // all query blocks of the pair (long, late blocks first) and all query heads of the group, so the workgroups that
-  // are resident on an XCD at any moment stream the SAME K/V rows and find them in that XCD's L2.
+// ---- workgroup -> (sequence, kv head, query block, head of the group), XCD aware ----
+// Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  Id (x, k) = the k-th
+// workgroup of XCD x.  Each XCD walks its own list of (sequence, kv head) pairs (pair % 8 == x) one pair at a time:
+// all query blocks of the pair (long, late blocks first) and all query heads of the group, so the workgroups that
+// are resident on an XCD at any moment stream the SAME K/V rows and find them in that XCD's L2.
+struct PfBlock {
+  int c, a;     // kv head, query head
+  int b0, n;    // first packed row and length of the sequence
+  int q0;       // first query row of the workgroup inside the sequence
+  bool valid;
+};
+__device__ __forceinline__ PfBlock pf_map_block(const PrefillParams& p, int block_rows) {
+  PfBlock b;
+  b.valid = false;
   const int gq = p.hq / p.hkv;
   const int xcd = blockIdx.x % kXcds, k_in_xcd = blockIdx.x / kXcds;
   const int per_pair = p.n_qblk * gq;
   const int pair = (k_in_xcd / per_pair) * kXcds + xcd;
-  if (pair >= p.batch * p.hkv) return;
+  if (pair >= p.batch * p.hkv) return b;
   const int rem = k_in_xcd % per_pair;
   const int qblk = p.n_qblk - 1 - rem / gq;
-  const int s = pair / p.hkv, c = pair % p.hkv;
-  const int a = c * gq + rem % gq;
-  const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
-  const int q0 = qblk * kBlockRows;
-  if (q0 >= n) return;
+  const int s = pair / p.hkv;
+  b.c = pair % p.hkv;
+  b.a = b.c * gq + rem % gq;
+  b.b0 = p.cu[s];
+  b.n = p.cu[s + 1] - b.b0;
+  b.q0 = qblk * block_rows;
+  b.valid = b.q0 < b.n;
+  return b;
+}
+
+// ---- tile staging: global -> LDS directly ----
+// A tile is kTileKeys*UPR 16-byte units = UPR wave instructions per tensor (UPR = units per row); wave w issues
+// instructions w, w+WAVES, ...  Instruction I fills LDS units [64 I, 64 I + 64): rows RPI*I + lane/UPR, chunk position
+// lane%UPR.  Rows past the end of the sequence are outside the buffer descriptor and read as zeros (finite data for
+// the masked tail, no clamping).
+template <int D, int WAVES>
+struct TileStager {
+  static constexpr int UPR = D / 8;
+  static constexpr int NI = UPR / WAVES;   // instructions per wave, tile and tensor
+  static constexpr int RPI = kWave / UPR;  // rows per instruction
+  static_assert(NI >= 1 && NI * WAVES == UPR);
+  u32x4 k_rsrc, v_rsrc;
+  int voff[NI];
+  int row_bytes, wave;
+  __device__ __forceinline__ void init(const __bf16* Kg, const __bf16* Vg, int n, int hkv, int wave_, int lane) {
+    row_bytes = hkv * D * 2;
+    wave = wave_;
+    const int seq_bytes = (n - 1) * row_bytes + D * 2;
+    k_rsrc = raw_buffer(Kg, seq_bytes);
+    v_rsrc = raw_buffer(Vg, seq_bytes);
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int row = RPI * (wave + WAVES * i) + lane / UPR;
+      voff[i] = row * row_bytes + ((lane % UPR) ^ swz<D>(row)) * 16;
+    }
+  }
+  // this wave's share of tile t of one tensor, into the tile buffer at LDS byte address lds_tile
+  __device__ __forceinline__ void issue(const u32x4& rsrc, unsigned lds_tile, int t) const {
+    const int soff = t * kTileKeys * row_bytes;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) dma16_to_lds(rsrc, lds_tile + (unsigned)((wave + WAVES * i) * 1024), voff[i], soff);
+  }
+};
+
+// ---- Q fragments: rotate at the original position (tabulated cos/sin), fold in scale*log2(e), keep as bf16 B operands ----
+// lane (r32, hf) holds, for k-step ks, dims 16 ks + 8 hf + (0..7) of query r32
+template <int D>
+__device__ __forceinline__ void pf_load_q(const PrefillParams& p, const __bf16* qrow /* row + 8 hf */,
+                                          const f32x2* csrow /* token's table row + 8 hf */, bf16x8 (&qf)[D / 16]) {
+  constexpr int KSTEPS = D / 16;
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS / 2; ++ks) {
+    float lo[8], hi[8];
+    Vec8<__bf16>::load(qrow + 16 * ks, lo);
+    Vec8<__bf16>::load(qrow + 16 * ks + D / 2, hi);
+    const f32x4* cs4 = (const f32x4*)(csrow + 16 * ks);  // pairs 16 ks + 8 hf + (0..7)
+    u32x4 wl, wh;
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+      const f32x4 c = cs4[j / 2];  // (cos, sin) of pairs j, j + 1
+      const float x0 = (lo[j] * c[0] - hi[j] * c[1]) * p.scale_log2, y0 = (hi[j] * c[0] + lo[j] * c[1]) * p.scale_log2;
+      const float x1 = (lo[j + 1] * c[2] - hi[j + 1] * c[3]) * p.scale_log2, y1 = (hi[j + 1] * c[2] + lo[j + 1] * c[3]) * p.scale_log2;
+      wl[j / 2] = pack_bf16(x0, x1);
+      wh[j / 2] = pack_bf16(y0, y1);
+    }
+    qf[ks] = __builtin_bit_cast(bf16x8, wl);
+    qf[ks + KSTEPS / 2] = __builtin_bit_cast(bf16x8, wh);
+  }
+}
+
+// Per-lane LDS element offsets of the MFMA fragments inside a tile.  The swizzle is an XOR on the chunk index and the
+// k-step / d-block enter the chunk index in bits the lane's own part leaves free, so every offset is one base XOR a
+// constant: three registers instead of one per fragment.
+template <int D>
+struct FragOffsets {
+  int k_base;     // K fragment of k-step ks: (k_base ^ (ks << 4)) + kb * 32 * D
+  int v_base[2];  // V^T fragment of d block db: (v_base[h2] ^ (db << 5)) + kk * 16 * D ; h2 = second group of 4 keys (8 rows further)
+  __device__ __forceinline__ void init(int lane) {
+    const int r32 = lane & 31, hf = lane >> 5;
+    k_base = r32 * D + ((hf ^ swz<D>(r32)) << 3);
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2) {
+      const int row = 4 * hf + 8 * h2 + ((lane & 15) >> 2);
+      const int chunk = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+      v_base[h2] = row * D + ((chunk ^ swz<D>(row)) << 3) + 4 * (lane & 1);
+    }
+  }
+  __device__ __forceinline__ int k(int ks) const { return k_base ^ (ks << 4); }
+  __device__ __forceinline__ int v(int db, int h2) const { return v_base[h2] ^ (db << 5); }
+};
+// V^T fragment (d block db, 16-key step kk) of the V tile at smv: two transposing reads, 4 keys each
+template <int D>
+__device__ __forceinline__ bf16x8 read_v_fragment(const __bf16* smv, const FragOffsets<D>& fo, int db, int kk) {
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smv + fo.v(db, 0) + kk * 16 * D));
+  s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smv + fo.v(db, 1) + kk * 16 * D));
+  return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// S^T (+)= K Q^T for the K tile at smk: two 32-key blocks, K fragments requested AHEAD k-steps before the MFMAs that use
+// them.  ZERO: start from 0, else from `init` in every register (the steady state starts at -m, which takes the
+// subtraction of the reference maximum off the vector ALU).
+template <int D, bool ZERO>
+__device__ __forceinline__ void score_tile(const __bf16* smk, const FragOffsets<D>& fo, const bf16x8 (&qf)[D / 16],
+                                           const f32x16& init, f32x16 (&sc)[2]) {
+  constexpr int KSTEPS = D / 16;
+  constexpr int AHEAD = ZERO ? 1 : (2 < KSTEPS ? 2 : KSTEPS);  // the exact paths are short of registers, not of time
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x8 kf[2][KSTEPS];
+#pragma unroll
+  for (int ks = 0; ks < AHEAD; ++ks)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) kf[kb][ks] = *(const bf16x8*)(smk + fo.k(ks) + kb * 32 * D);
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) {
+    if (ks + AHEAD < KSTEPS) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) kf[kb][ks + AHEAD] = *(const bf16x8*)(smk + fo.k(ks + AHEAD) + kb * 32 * D);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // the fragment requests stay ahead of the MFMAs that hide their latency
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+      sc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[ks], ks == 0 ? (ZERO ? zero : init) : sc[kb], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+// causal mask of the wave's diagonal tile, in place: lane (r32, hf) holds keys 32 kb + 8 (i/4) + 4 hf + i%4 of query
+// q_in_tile + r32 (keys beyond the sequence end are beyond every valid query too)
+__device__ __forceinline__ void mask_diagonal(f32x16 (&sc)[2], int q_in_tile, int r32, int hf) {
+  const int bound = q_in_tile + r32 - 4 * hf;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if (32 * kb + 8 * (i >> 2) + (i & 3) > bound) sc[kb][i] = -INFINITY;
+}
+// Softmax unit u (0..15) of a score tile: two exponentials (the scores already carry -m), the bf16 word that holds
+// them, and the word's contribution to the lane's row sum.  Word (kk, j) of the B operand P^T packs accumulator
+// registers 8 (kk & 1) + 2 j, + 1 of key block kk >> 1; u = 4 kk + j.
+__device__ __forceinline__ void softmax_unit(const f32x16 (&sc)[2], int u, u32x4 (&w)[4], float& s0, float& s1) {
+  const int kk = u >> 2, j = u & 3, r = 8 * (kk & 1) + 2 * j;
+  w[kk][j] = pack_bf16(__builtin_amdgcn_exp2f(sc[kk >> 1][r]), __builtin_amdgcn_exp2f(sc[kk >> 1][r + 1]));
+  add_pair(j & 1 ? s1 : s0, w[kk][j]);
+}
+// normalise and store one query row's share: lane holds d = 32 db + 8 j + 4 hf + (0..3)
+template <int D>
+__device__ __forceinline__ void pf_store_row(__bf16* orow /* row + 4 hf */, const f32x16 (&o)[D / 32], float inv) {
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      u32x2 w;
+      w[0] = pack_bf16(o[db][4 * j] * inv, o[db][4 * j + 1] * inv);
+      w[1] = pack_bf16(o[db][4 * j + 2] * inv, o[db][4 * j + 3] * inv);
+      *(u32x2*)(orow + 32 * db + 8 * j) = w;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// Plain schedule: per tile  barrier -> S^T -> exponentials -> O^T.  One 32-query column block per wave.
+//   WAVES = 4: 128 query rows per workgroup, two workgroups per CU: less idle time on the causal diagonal of medium
+//              sequences than 256-row workgroups, at the price of staging every K/V tile twice as often.
+//   WAVES = 2, STAGES = 1: the register-only-layer variant: every sequence fits one K/V tile, so there is nothing to
+//              double buffer, and the small footprint lets 4 workgroups share a CU, which is what hides the
+//              load -> rotate -> multiply latency chain of these tiny problems.
+// ------------------------------------------------------------------------------------------------------------------
+template <int D, int WAVES, int STAGES>
+__global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_kernel(PrefillParams p) {
+  constexpr int kBlockRows = 32 * WAVES;
+  constexpr int DB = D / 32;             // 32-row blocks of O^T
+  __shared__ __bf16 smk[STAGES][kTileKeys * D];  // tile t+1 arrives while tile t is read
+  __shared__ __bf16 smv[STAGES][kTileKeys * D];
+
+  const PfBlock blk = pf_map_block(p, kBlockRows);
+  if (!blk.valid) return;
+  const int b0 = blk.b0, n = blk.n;
   // the wave index is the same in all 64 lanes: say so, and everything derived from it (the wave's query window, its
   // diagonal tile, the tile loop) lives in scalar registers and branches without touching the execution mask
   const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int r32 = lane & 31, hf = lane >> 5;
-  const int qw = q0 + wave * kWaveRows;          // first query row of this wave
+  const int qw = blk.q0 + wave * 32;             // first query row of this wave
   const bool wave_active = qw < n;
   const int t_diag = qw / kTileKeys;             // last (diagonal) tile of this wave
   const int q_in_tile = qw - t_diag * kTileKeys; // offset of the wave's first query inside that tile
-  const int n_tiles = (min(q0 + kBlockRows, n) + kTileKeys - 1) / kTileKeys;
+  const int n_tiles = (min(blk.q0 + kBlockRows, n) + kTileKeys - 1) / kTileKeys;
 
-  const __bf16* Qg = (const __bf16*)p.q;
-  const __bf16* Kg = (const __bf16*)p.k_rot + ((long long)b0 * p.hkv + c) * D;
-  const __bf16* Vg = (const __bf16*)p.v + ((long long)b0 * p.hkv + c) * D;
-  const long long kv_stride = (long long)p.hkv * D;
-
-  // ---- tile staging: global -> LDS directly ----
-  // A tile is kTileKeys*UPR 16-byte units = UPR wave instructions per tensor; wave w issues instructions w, w+WAVES, ...
-  // Instruction I fills LDS units [64 I, 64 I + 64): rows RPI*I + lane/UPR, chunk position lane%UPR.  Rows past the end of
-  // the sequence are outside the buffer descriptor and read as zeros (finite data for the masked tail, no clamping).
-  constexpr int NI = UPR / WAVES;       // instructions per wave, tile and tensor
-  constexpr int RPI = kWave / UPR;      // rows per instruction
-  const int row_bytes = (int)kv_stride * 2;
-  const int seq_bytes = (n - 1) * row_bytes + D * 2;
-  const u32x4 k_rsrc = raw_buffer(Kg, seq_bytes), v_rsrc = raw_buffer(Vg, seq_bytes);
-  int st_voff[NI];
-#pragma unroll
-  for (int i = 0; i < NI; ++i) {
-    const int row = RPI * (wave + WAVES * i) + lane / UPR;
-    st_voff[i] = row * row_bytes + ((lane % UPR) ^ swz<D>(row)) * 16;
-  }
-  const unsigned lds_k = (unsigned)(size_t)(lds_void_ptr)&sm.k[0][0], lds_v = (unsigned)(size_t)(lds_void_ptr)&sm.v[0][0];
-  auto issue_tile = [&](int t, int buf) {
-#if defined(EARN_DBG_NOSTAGE)
-    if (t >= STAGES) return;
-#endif
-    const int soff = t * kTileKeys * row_bytes;
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const unsigned at = (unsigned)((buf * kTileKeys * D + (wave + WAVES * i) * 512) * 2);
-      dma16_to_lds(k_rsrc, lds_k + at, st_voff[i], soff);
-      dma16_to_lds(v_rsrc, lds_v + at, st_voff[i], soff);
-    }
+  TileStager<D, WAVES> stager;
+  stager.init((const __bf16*)p.k_rot + ((long long)b0 * p.hkv + blk.c) * D, (const __bf16*)p.v + ((long long)b0 * p.hkv + blk.c) * D,
+              n, p.hkv, wave, lane);
+  const unsigned lds_k = (unsigned)(size_t)(lds_void_ptr)&smk[0][0], lds_v = (unsigned)(size_t)(lds_void_ptr)&smv[0][0];
+  auto issue_tile = [&](int t) {
+    const unsigned at = (unsigned)((t % STAGES) * kTileKeys * D * 2);
+    stager.issue(stager.k_rsrc, lds_k + at, t);
+    stager.issue(stager.v_rsrc, lds_v + at, t);
   };
-  // Barrier b (b = 0, 1, ..): every wave has waited for its own part of tile b, so behind the barrier tile b is
-  // complete and visible; the wave then starts its part of tile b+1 into the next buffer of the ring.  Waves that run
-  // "on time" pass barrier b at the top of iteration b.  With PP (ping-pong, 3 buffers) the upper half of the waves runs
-  // "late": it passes barrier b+1 in the MIDDLE of iteration b, between its two matrix products.  The barrier then
-  // holds the two waves that share a SIMD half an iteration apart for good, so that one of them is in its matrix
-  // products while the other is in its exponentials, instead of both competing for the same unit and leaving the other
-  // idle.  Buffer (b+1) % STAGES held tile b+1-STAGES: on-time waves are done with that tile before barrier b+2-STAGES,
-  // late waves (STAGES = 3) read its V between barriers b-1 and b; both are behind every wave when barrier b opens.
-  auto sync_and_stage = [&](int b) {
-#if !defined(EARN_DBG_NOWAIT)
-    wait_vmcnt<0>();
-#endif
-    __syncthreads();
+  // Barrier t: every wave has waited for its own part of tile t, so behind the barrier tile t is complete and visible;
+  // the wave then starts its part of tile t+1 into the other buffer, which every wave has finished reading (tile t-1).
+  auto sync_and_stage = [&](int t) {
+    drain_loads_and_barrier();
     if constexpr (STAGES > 1) {
-      if (b + 1 < n_tiles) issue_tile(b + 1, (b + 1) % STAGES);
+      if (t + 1 < n_tiles) issue_tile(t + 1);
     }
   };
-  issue_tile(0, 0);  // in flight while the queries are loaded and rotated
+  issue_tile(0);  // in flight while the queries are loaded and rotated
 
-  // ---- Q fragments: rotate at the original position, fold in scale*log2(e), keep as bf16 B operands ----
-  bf16x8 qf[QB][KSTEPS];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int qi = min(qw + 32 * qb + r32, n - 1);
-    const float pos = (float)(p.positions ? p.positions[b0 + qi] : qi);
-    const __bf16* qrow = Qg + ((long long)(b0 + qi) * p.hq + a) * D + 8 * hf;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS / 2; ++ks) {
-      float lo[8], hi[8];
-      Vec8<__bf16>::load(qrow + 16 * ks, lo);
-      Vec8<__bf16>::load(qrow + 16 * ks + D / 2, hi);
-      u32x4 wl, wh;
-#pragma unroll
-      for (int j = 0; j < 8; j += 2) {
-        float x[2], y[2];
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          float sn = 0.f, cs = 1.f;
-          const int e = 16 * ks + 8 * hf + j + jj;
-          if (p.rope.enabled) sincos_turns_fast(rope_turns(pos, p.rope.hi[e], p.rope.lo[e]), &sn, &cs);
-          x[jj] = (lo[j + jj] * cs - hi[j + jj] * sn) * p.scale_log2;
-          y[jj] = (hi[j + jj] * cs + lo[j + jj] * sn) * p.scale_log2;
-        }
-        wl[j / 2] = pack_bf16(x[0], x[1]);
-        wh[j / 2] = pack_bf16(y[0], y[1]);
-      }
-      qf[qb][ks] = __builtin_bit_cast(bf16x8, wl);
-      qf[qb][ks + KSTEPS / 2] = __builtin_bit_cast(bf16x8, wh);
-    }
+  bf16x8 qf[D / 16];
+  {
+    const int qi = min(qw + r32, n - 1);
+    pf_load_q<D>(p, (const __bf16*)p.q + ((long long)(b0 + qi) * p.hq + blk.a) * D + 8 * hf,
+                 p.cs + (long long)(b0 + qi) * (D / 2) + 8 * hf, qf);
   }
+  FragOffsets<D> fo;
+  fo.init(lane);
 
-  f32x16 o[DB][QB];
+  f32x16 o[DB], neg_m;  // neg_m: -m in every register, the start value of the steady-state score accumulators
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) o[db][qb][i] = 0.f;
-  float mrow[QB], lrow[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) { mrow[qb] = -INFINITY; lrow[qb] = 0.f; }
+  for (int i = 0; i < 16; ++i) neg_m[i] = 0.f;
+  float mrow = -INFINITY, lrow = 0.f;
 
-  // per-lane LDS element offsets of the MFMA fragments (the swizzle does not depend on kb / kk: those add multiples of 16 rows)
-  int k_offs[KSTEPS];      // + kb * 32 * D
+  // exponentials of a whole score tile (already shifted by -m), packed, with the lane's row sum
+  auto softmax_tile = [&](const f32x16 (&sc)[2], u32x4 (&w)[4], float& lsum) {
+    float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-  for (int ks = 0; ks < KSTEPS; ++ks) k_offs[ks] = r32 * D + (((2 * ks + hf) ^ swz<D>(r32)) << 3);
-  int v_offs[DB][2];       // + kk * 16 * D ; [..][1] is the second group of 4 keys (8 rows further)
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int h2 = 0; h2 < 2; ++h2) {
-      const int row = 4 * hf + 8 * h2 + ((lane & 15) >> 2);
-      const int chunk = 4 * db + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-      v_offs[db][h2] = row * D + ((chunk ^ swz<D>(row)) << 3) + 4 * (lane & 1);
-    }
-
-  // ---- pieces of one key-tile iteration ----
-  // S^T = K Q^T for tile t.  All 2*KSTEPS K fragments are requested from LDS before
-  // the first MFMA (and before `staging`, the global->LDS traffic of later tiles), so the MFMAs wait on a draining
-  // queue instead of paying one LDS round trip each.
-  auto scores = [&](int buf, f32x16 (&sc)[2][QB], const f32x16 (&init)[QB]) {
-    const __bf16* smk = sm.k[buf];
-#ifndef EARN_PF_KAHEAD
-#define EARN_PF_KAHEAD 2
-#endif
-    constexpr int AHEAD = EARN_PF_KAHEAD < KSTEPS ? EARN_PF_KAHEAD : KSTEPS;  // k-steps of K fragments in flight ahead of the MFMAs
-    bf16x8 kf[2][KSTEPS];
-    auto fetch_k = [&](int ks) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) kf[kb][ks] = *(const bf16x8*)(smk + k_offs[ks] + kb * 32 * D);
-    };
-#pragma unroll
-    for (int ks = 0; ks < AHEAD; ++ks) fetch_k(ks);
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      if (ks + AHEAD < KSTEPS) fetch_k(ks + AHEAD);
-      __builtin_amdgcn_sched_barrier(0);  // the fragment requests stay ahead of the MFMAs that hide their latency
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          sc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[qb][ks], ks == 0 ? init[qb] : sc[kb][qb], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    for (int u = 0; u < 16; ++u) softmax_unit(sc, u, w, s0, s1);
+    lsum = add_chains(s0, s1);
   };
-  // causal mask, in place; it only bites on the wave's diagonal tile (keys beyond the sequence end are beyond every
-  // valid query too), elsewhere the bound is out of reach
-  auto mask_causal = [&](int t, f32x16 (&sc)[2][QB]) {
-    const int bound = t == t_diag ? q_in_tile + r32 - 4 * hf : kTileKeys;  // lane's last visible key, less its 4 hf share
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          sc[kb][qb][i] = (32 * kb + 8 * (i >> 2) + (i & 3) > bound + 32 * qb) ? -INFINITY : sc[kb][qb][i];
-  };
-  // P = exp2(S - m) in place.  SHIFTED: the scores already carry -m (the steady-state path starts its score
-  // accumulators at -m instead of 0, which takes the subtraction off the vector ALU).
-  auto exponentials = [&](f32x16 (&sc)[2][QB], auto shifted) {
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-#if defined(EARN_DBG_NOEXP)
-          sc[kb][qb][i] = sc[kb][qb][i] * 1e-30f;
-#else
-          sc[kb][qb][i] = __builtin_amdgcn_exp2f(decltype(shifted)::value ? sc[kb][qb][i] : sc[kb][qb][i] - mrow[qb]);
-#endif
-        }
-  };
-  // P as bf16 B operands of the second product, and the lane's share of the row sums.  The sums are taken over the
-  // ROUNDED probabilities (two per instruction, exact products with 1 accumulated in fp32): they are the weights the
-  // second product really applies, and it halves the additions.
-  auto pack_probs = [&](f32x16 (&sc)[2][QB], bf16x8 (&pf)[QB][4], float (&lsum)[QB]) {
-    const unsigned ones = 0x3f803f80u;  // (1.0, 1.0) in bf16
-    // acc += w.lo + w.hi.  Written as instructions: the compiler's own dot builtin came out wrong in this kernel (half
-    // of the words summed twice, the other half not at all).  What the compiler would otherwise look after is done by
-    // hand: a dot result may feed the next dot's accumulator at once, but any other vector instruction has to keep
-    // three wait states' distance, hence the s_nop in front of the closing addition.
-    auto add_pair = [&](float& acc, unsigned w) {
-      asm("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(acc) : "s"(ones), "v"(w));
-    };
-    auto add_chains = [&](float s0, float s1) {
-      float r;
-      asm("s_nop 2\n\tv_add_f32 %0, %1, %2" : "=v"(r) : "v"(s0), "v"(s1));
-      return r;
-    };
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      float s0 = 0.f, s1 = 0.f;  // two chains
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        u32x4 w;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          w[j] = pack_bf16(sc[kk >> 1][qb][8 * (kk & 1) + 2 * j], sc[kk >> 1][qb][8 * (kk & 1) + 2 * j + 1]);
-          add_pair(j & 1 ? s1 : s0, w[j]);
-        }
-        pf[qb][kk] = __builtin_bit_cast(bf16x8, w);
-      }
-      lsum[qb] = add_chains(s0, s1);
-    }
-  };
-  // V^T fragments of tile t (A operands of the second product): requested before the exponentials so that the LDS
-  // latency hides behind the vector-ALU work
-  auto fetch_v = [&](int buf, bf16x8 (&vf)[4][DB]) {
-    const __bf16* smv = sm.v[buf];
+  // O^T += V^T P^T; the V^T fragments are requested up front so that their latency hides behind whatever the caller
+  // does between fetch and use
+  auto fetch_v = [&](const __bf16* smv_t, bf16x8 (&vf)[4][DB]) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smv + v_offs[db][0] + kk * 16 * D));
-        s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(smv + v_offs[db][1] + kk * 16 * D));
-        typedef short s16x8 __attribute__((ext_vector_type(8)));
-        s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-        vf[kk][db] = __builtin_bit_cast(bf16x8, vv);
-      }
+      for (int db = 0; db < DB; ++db) vf[kk][db] = read_v_fragment<D>(smv_t, fo, db, kk);
     __builtin_amdgcn_sched_barrier(0);
   };
-  // row sums, O^T += V^T P^T
-  auto accumulate = [&](bf16x8 (&pf)[QB][4], float (&lsum)[QB], bf16x8 (&vf)[4][DB]) {
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) lrow[qb] += lsum[qb];
+  auto accumulate = [&](const u32x4 (&w)[4], float lsum, const bf16x8 (&vf)[4][DB]) {
+    lrow += lsum;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
       for (int db = 0; db < DB; ++db)
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], __builtin_bit_cast(bf16x8, w[kk]), o[db], 0, 0, 0);
+  };
+  // The exact path: raw scores, exact row maxima, rescale of everything accumulated so far.
+  // synced = the tile fell out of the steady-state loop, which has passed the tile's barrier already.
+  auto exact_tile = [&](int t, bool synced) {
+    if (!synced) sync_and_stage(t);
+    f32x16 sc[2];
+    bf16x8 vf[4][DB];
+    u32x4 w[4];
+    float lsum;
+    score_tile<D, true>(smk[t % STAGES], fo, qf, neg_m, sc);
+    if (t == t_diag) mask_diagonal(sc, q_in_tile, r32, hf);
+    float m = sc[0][0];
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[qb][kk], o[db][qb], 0, 0, 0);
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) m = fmaxf(m, sc[kb][i]);
+    const float mnew = fmaxf(mrow, half_max(m));  // finite: tile 0 holds key 0, visible to every query
+    const float alpha = __builtin_amdgcn_exp2f(mrow - mnew);
+    mrow = mnew;
+    lrow *= alpha;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) neg_m[i] = -mnew;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    fetch_v(smv[t % STAGES], vf);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sc[kb][i] -= mnew;
+    softmax_tile(sc, w, lsum);
+    accumulate(w, lsum, vf);
   };
 
   // Every wave passes exactly one barrier per tile, whichever path it takes.  The steady-state loop takes the
@@ -532,146 +577,299 @@ __global__ __launch_bounds__(64 * WAVES, (QB == 1 && WAVES <= 4) ? 2 : 1) void p
   // the (already needed) partial row sums are compared with kSumLimit instead.  A wave that fails leaves the loop,
   // recomputes the tile's scores, takes the exact maxima, rescales, finishes the tile and re-enters.  Tile 0 (reference
   // still -inf) and the wave's diagonal tile (the only one that needs the causal mask) always take the exact path.
-  f32x16 zero16[QB], neg_m[QB];  // score accumulator starts: 0 (exact path), -m in every register (steady state)
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { zero16[qb][i] = 0.f; neg_m[qb][i] = 0.f; }
-  const bool late = PP && wave >= WAVES / 2;
-  if (late) sync_and_stage(0);
-  // The exact path.  synced = the tile fell out of the steady-state loop, which has passed the tile's barrier already.
-  auto exact_tile = [&](int t, int buf, bool synced) {
-    if (!late && !synced) sync_and_stage(t);
-    f32x16 sc[2][QB];
-    float lsum[QB];
-    bf16x8 vf[4][DB];
-    bf16x8 pf[QB][4];
-    scores(buf, sc, zero16);
-    mask_causal(t, sc);
-    if (late && !synced && t + 1 < n_tiles) sync_and_stage(t + 1);
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      float m = sc[0][qb][0];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) m = fmaxf(m, sc[kb][qb][i]);
-      const float mnew = fmaxf(mrow[qb], half_max(m));  // finite: tile 0 holds key 0, visible to every query
-      const float alpha = __builtin_amdgcn_exp2f(mrow[qb] - mnew);
-      mrow[qb] = mnew;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) neg_m[qb][i] = -mnew;
-      lrow[qb] *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
-    }
-    fetch_v(buf, vf);
-    exponentials(sc, std::false_type{});
-    pack_probs(sc, pf, lsum);
-    accumulate(pf, lsum, vf);
-  };
-#if defined(EARN_DBG_PHASES)  // working instrumentation: cycles per phase of the steady-state loop, written in place of lse
-  long long ph[5] = {0, 0, 0, 0, 0};
-  int ph_tiles = 0;
-#define PH_STAMP(x) { __builtin_amdgcn_sched_barrier(0); x = (long long)__builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); }
-#else
-#define PH_STAMP(x)
-#endif
-  int t = 0, buf = 0;  // buf = t % STAGES
-  auto next_tile = [&]() { ++t; buf = (buf + 1 == STAGES ? 0 : buf + 1); };
+  int t = 0;
   while (t < n_tiles) {
     bool exact = wave_active && t == 0, synced = false;
     if (!exact)
-    for (; t < n_tiles; next_tile()) {
+    for (; t < n_tiles; ++t) {
       const bool work = wave_active && t <= t_diag;  // else rows past the sequence end or a tile past the diagonal: only stage
       if (work && t == t_diag) { exact = true; break; }
-      [[maybe_unused]] long long c0, c1, c2, c2b, c3, c4;
-      PH_STAMP(c0);
-      if (!late) sync_and_stage(t);
-      PH_STAMP(c1);
-      f32x16 sc[2][QB];
-      float lsum[QB];
-      bf16x8 vf[4][DB];
-      bf16x8 pf[QB][4];
-      if (work) scores(buf, sc, neg_m);
-      PH_STAMP(c2);
-      if (late && t + 1 < n_tiles) sync_and_stage(t + 1);
-      PH_STAMP(c2b);
+      sync_and_stage(t);
       if (work) {
-        fetch_v(buf, vf);
-#if defined(EARN_DBG_PHASES) && EARN_DBG_PHASES == 2
-        { long long cv; PH_STAMP(cv); ph[4] += cv - c2b; }
-#endif
-        exponentials(sc, std::true_type{});
-        pack_probs(sc, pf, lsum);
-        PH_STAMP(c3);
-        bool stale = false;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) stale |= !(lsum[qb] <= kSumLimit);
-        if (__any(stale)) { exact = synced = true; break; }
-        accumulate(pf, lsum, vf);
-        PH_STAMP(c4);
-#if defined(EARN_DBG_PHASES)
-        ph[0] += c1 - c0; ph[1] += c2 - c1; ph[2] += c3 - c2b; ph[3] += c4 - c3; ph[4] += c2b - c2; ++ph_tiles;
-#endif
+        f32x16 sc[2];
+        bf16x8 vf[4][DB];
+        u32x4 w[4];
+        float lsum;
+        score_tile<D, false>(smk[t % STAGES], fo, qf, neg_m, sc);
+        fetch_v(smv[t % STAGES], vf);
+        softmax_tile(sc, w, lsum);
+        if (__any(!(lsum <= kSumLimit))) { exact = synced = true; break; }
+        accumulate(w, lsum, vf);
       }
     }
     if (!exact) break;
-    exact_tile(t, buf, synced);
-    next_tile();
+    exact_tile(t, synced);
+    ++t;
   }
 
   if (!wave_active) return;
-  // ---- epilogue: normalise and store; lane holds d = 32db + 8j + 4hf + (0..3) of query r32 ----
+  const int qi = qw + r32;
+  const float ltot = half_sum(lrow);
+  if (qi >= n) return;
+  pf_store_row<D>((__bf16*)p.out + ((long long)(b0 + qi) * p.hq + blk.a) * D + 4 * hf, o, 1.f / ltot);
+  if (p.lse && hf == 0) p.lse[(long long)(b0 + qi) * p.hq + blk.a] = (mrow + __builtin_log2f(ltot)) * 0.6931471805599453f;
+}
+
+// ------------------------------------------------------------------------------------------------------------------
+// Software-pipelined schedule for long sequences: 8 waves, 256 query rows per workgroup, two waves per SIMD.
+//
+// A single wave cannot hide its exponentials behind its own matrix products when the two alternate, and two waves of a
+// SIMD that meet at a barrier every tile fall into step, so they do not hide them for each other either.  Here every
+// wave overlaps them itself: while the matrix core accumulates the scores of tile t+1, the vector ALU takes the
+// exponentials of tile t, instruction by instruction in one stream; then O^T += V^T P^T of tile t follows at once.  The
+// matrix core always has the next product queued.
+//
+//   iteration t:  barrier t (K(t+1) and V(t) have landed; start K(t+2), V(t+1))
+//                 S(t+1) = K(t+1) Q^T - m   interleaved with   P(t) = exp2(S(t)), row sums
+//                 [sums too large -> reference stale: recompute S(t) exactly from K(t), which is still in LDS]
+//                 O += V(t) P(t)
+//
+// K tiles live in a ring of 3 (t: kept for the exact path, t+1: being multiplied, t+2: in flight), V tiles in a ring
+// of 2 (t: being multiplied, t+1: in flight).  The two score tiles swap roles every iteration; the loop is unrolled by
+// two so that the swap costs no register moves.
+// ------------------------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(512, 1) void prefill_pipe_kernel(PrefillParams p) {
+  constexpr int WAVES = 8, kBlockRows = 256;
+  constexpr int KSTEPS = D / 16, DB = D / 32;
+  constexpr int UPM = 16 / (2 * KSTEPS);  // softmax units per score MFMA: 1 (D = 128) or 2 (D = 64)
+  __shared__ __bf16 smk[3][kTileKeys * D];
+  __shared__ __bf16 smv[2][kTileKeys * D];
+
+  const PfBlock blk = pf_map_block(p, kBlockRows);
+  if (!blk.valid) return;
+  const int b0 = blk.b0, n = blk.n;
+  const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int r32 = lane & 31, hf = lane >> 5;
+  const int qw = blk.q0 + wave * 32;
+  const bool wave_active = qw < n;
+  const int t_diag = qw / kTileKeys;
+  const int q_in_tile = qw - t_diag * kTileKeys;
+  const int n_tiles = (min(blk.q0 + kBlockRows, n) + kTileKeys - 1) / kTileKeys;
+
+  TileStager<D, WAVES> stager;
+  stager.init((const __bf16*)p.k_rot + ((long long)b0 * p.hkv + blk.c) * D, (const __bf16*)p.v + ((long long)b0 * p.hkv + blk.c) * D,
+              n, p.hkv, wave, lane);
+  const unsigned lds_k = (unsigned)(size_t)(lds_void_ptr)&smk[0][0], lds_v = (unsigned)(size_t)(lds_void_ptr)&smv[0][0];
+  auto issue_k = [&](int t) { stager.issue(stager.k_rsrc, lds_k + (unsigned)((t % 3) * kTileKeys * D * 2), t); };
+  auto issue_v = [&](int t) { stager.issue(stager.v_rsrc, lds_v + (unsigned)((t & 1) * kTileKeys * D * 2), t); };
+  // Barrier t.  Before it every wave has waited for its own loads, i.e. its parts of K(t+1) and V(t), issued behind
+  // barrier t-1.  Behind it nobody reads K(t-1) (last use: the exact path of iteration t-1) or V(t-1) any more, which is
+  // where K(t+2) and V(t+1) go.
+  auto sync_and_stage = [&](int t) {
+#if defined(EARN_DBG_NOBARRIER)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+#else
+    drain_loads_and_barrier();
+#endif
+#if !defined(EARN_DBG_NOSTAGE)
+    if (t + 2 < n_tiles) issue_k(t + 2);
+    if (t + 1 < n_tiles) issue_v(t + 1);
+#endif
+  };
+  issue_k(0);
+  issue_v(0);
+  if (n_tiles > 1) issue_k(1);
+
+  bf16x8 qf[KSTEPS];
+  {
+    const int qi = min(qw + r32, n - 1);
+    pf_load_q<D>(p, (const __bf16*)p.q + ((long long)(b0 + qi) * p.hq + blk.a) * D + 8 * hf,
+                 p.cs + (long long)(b0 + qi) * (D / 2) + 8 * hf, qf);
+  }
+  FragOffsets<D> fo;
+  fo.init(lane);
+
+  f32x16 o[DB], neg_m;
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int qi = qw + 32 * qb + r32;
-    const float ltot = half_sum(lrow[qb]);
-    if (qi >= n) continue;
-    const float inv = 1.f / ltot;
-    __bf16* orow = (__bf16*)p.out + ((long long)(b0 + qi) * p.hq + a) * D + 4 * hf;
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) neg_m[i] = 0.f;
+  float mrow = 0.f, lrow = 0.f;
+  f32x16 sa[2], sb[2];  // score tiles (minus m): one has its exponentials taken while the other is accumulated
+
+  // ---- tile 0: exact maxima, so that the pipeline starts from a finite reference ----
+  drain_loads_and_barrier();  // K(0), V(0), K(1)
+  if (wave_active) {
+    score_tile<D, true>(smk[0], fo, qf, neg_m, sa);
+    if (t_diag == 0) mask_diagonal(sa, q_in_tile, r32, hf);
+    float m = sa[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) m = fmaxf(m, sa[kb][i]);
+    mrow = half_max(m);  // finite: key 0 is visible to every query
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sa[kb][i] -= mrow;
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) neg_m[i] = -mrow;
+
+  // The reference of tile t turned out stale (or its sums overflowed): redo the tile exactly.  K(t) is still in LDS.
+  // The next tile's scores were started from the old reference and move with it.
+  auto exact_redo = [&](int t, f32x16 (&nxt)[2], bool have_next, u32x4 (&w)[4], float& lsum, bf16x8 (&vf0)[DB]) {
+    f32x16 sc[2];
+    score_tile<D, true>(smk[t % 3], fo, qf, neg_m, sc);
+    if (t == t_diag) mask_diagonal(sc, q_in_tile, r32, hf);
+    float m = sc[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) m = fmaxf(m, sc[kb][i]);
+    const float mnew = fmaxf(mrow, half_max(m));
+    const float shift = mrow - mnew;  // <= 0
+    const float alpha = __builtin_amdgcn_exp2f(shift);
+    mrow = mnew;
+    lrow *= alpha;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) neg_m[i] = -mnew;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        u32x2 w;
-        w[0] = pack_bf16(o[db][qb][4 * j] * inv, o[db][qb][4 * j + 1] * inv);
-        w[1] = pack_bf16(o[db][qb][4 * j + 2] * inv, o[db][qb][4 * j + 3] * inv);
-        *(u32x2*)(orow + 32 * db + 8 * j) = w;
+      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    if (have_next) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) nxt[kb][i] += shift;
+    }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sc[kb][i] -= mnew;
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) softmax_unit(sc, u, w, s0, s1);
+    lsum = add_chains(s0, s1);
+    // requested again rather than kept: this path is short of registers, not of time
+#pragma unroll
+    for (int db = 0; db < DB; ++db) vf0[db] = read_v_fragment<D>(smv[t & 1], fo, db, 0);
+  };
+
+  // one iteration; cur = S(t) - m (consumed), nxt = S(t+1) - m (produced)
+  auto iteration = [&](int t, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
+    sync_and_stage(t);
+    if (!(wave_active && t <= t_diag)) return;  // rows past the sequence end, tiles past the diagonal: only stage
+    const bool have_next = t < t_diag;
+    const __bf16* smv_t = smv[t & 1];
+    u32x4 w[4];
+    bf16x8 vf[2][DB];  // V^T fragments of two 16-key steps: one feeding the MFMAs, one arriving
+    float lsum, s0 = 0.f, s1 = 0.f;
+    if (have_next) {
+      // S(t+1) on the matrix core, exponentials of S(t) on the vector ALU, in ONE instruction stream laid out by hand:
+      // slot i = [K fragment requests two k-steps ahead] + MFMA i + exponentials of softmax unit(s) i + packing and row
+      // sum of unit(s) i-1 (whose exponentials have had a slot's time to finish).  The scheduling barriers keep the
+      // compiler from regrouping the slots; the last slots also request the first V^T fragments of the second product.
+      const __bf16* smk_n = smk[(t + 1) % 3];
+      constexpr int AHEAD = 2 < KSTEPS ? 2 : KSTEPS;
+      constexpr int SLOTS = 2 * KSTEPS;
+      bf16x8 kf[2][KSTEPS];
+      float e[2][UPM][2];  // exponentials of the units of slot i (parity i & 1)
+#pragma unroll
+      for (int ks = 0; ks < AHEAD; ++ks)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) kf[kb][ks] = *(const bf16x8*)(smk_n + fo.k(ks) + kb * 32 * D);
+#pragma unroll
+      for (int i = 0; i <= SLOTS; ++i) {
+        const int ks = i >> 1, kb = i & 1;
+        if (i < SLOTS) {
+          if (kb == 0 && ks + AHEAD < KSTEPS) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b) kf[b][ks + AHEAD] = *(const bf16x8*)(smk_n + fo.k(ks + AHEAD) + b * 32 * D);
+          }
+          if (i >= SLOTS - DB) vf[0][i - (SLOTS - DB)] = read_v_fragment<D>(smv_t, fo, i - (SLOTS - DB), 0);
+          nxt[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb][ks], qf[ks], ks == 0 ? neg_m : nxt[kb], 0, 0, 0);
+#pragma unroll
+          for (int x = 0; x < UPM; ++x) {
+            const int u = i * UPM + x, kk = u >> 2, j = u & 3, r = 8 * (kk & 1) + 2 * j;
+            e[i & 1][x][0] = __builtin_amdgcn_exp2f(cur[kk >> 1][r]);
+            e[i & 1][x][1] = __builtin_amdgcn_exp2f(cur[kk >> 1][r + 1]);
+          }
+        }
+        if (i > 0) {
+#pragma unroll
+          for (int x = 0; x < UPM; ++x) {
+            const int u = (i - 1) * UPM + x, kk = u >> 2, j = u & 3;
+            w[kk][j] = pack_bf16(e[(i - 1) & 1][x][0], e[(i - 1) & 1][x][1]);
+            add_pair(j & 1 ? s1 : s0, w[kk][j]);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-#if defined(EARN_DBG_PHASES)
-    if (p.lse && hf == 0) p.lse[(long long)(b0 + qi) * p.hq + a] = r32 < 5 ? (float)ph[r32 < 5 ? r32 : 0] / (float)max(ph_tiles, 1) : (float)ph_tiles;
-#else
-    if (p.lse && hf == 0) p.lse[(long long)(b0 + qi) * p.hq + a] = (mrow[qb] + __builtin_log2f(ltot)) * 0.6931471805599453f;
-#endif
+      if (t + 1 == t_diag) {
+        asm volatile("" ::: "memory");  // keeps this a branch: only one tile per wave needs the mask
+        mask_diagonal(nxt, q_in_tile, r32, hf);
+      }
+    } else {
+      // the wave's last tile: nothing to overlap with
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int kk = u >> 2, j = u & 3, r = 8 * (kk & 1) + 2 * j;
+        float x0 = cur[kk >> 1][r], x1 = cur[kk >> 1][r + 1];
+        asm("" : "+v"(x0), "+v"(x1));  // keeps these exponentials apart from the ones in the other branch, which must stay in their slots
+        w[kk][j] = pack_bf16(__builtin_amdgcn_exp2f(x0), __builtin_amdgcn_exp2f(x1));
+        add_pair(j & 1 ? s1 : s0, w[kk][j]);
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db) vf[0][db] = read_v_fragment<D>(smv_t, fo, db, 0);
+    }
+    lsum = add_chains(s0, s1);
+    if (__any(!(lsum <= kSumLimit))) exact_redo(t, nxt, have_next, w, lsum, vf[0]);
+    lrow += lsum;
+    // O^T += V^T P^T, the fragments of the next 16-key step requested while this step's MFMAs run
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        if (kk + 1 < 4) vf[(kk + 1) & 1][db] = read_v_fragment<D>(smv_t, fo, db, kk + 1);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk & 1][db], __builtin_bit_cast(bf16x8, w[kk]), o[db], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+  };
+  // unrolled by two; an odd tile count ends in an iteration past the last tile, which only meets the barrier
+  for (int t = 0; t < n_tiles; t += 2) {
+    iteration(t, sa, sb);
+    iteration(t + 1, sb, sa);
   }
+
+  if (!wave_active) return;
+  const int qi = qw + r32;
+  const float ltot = half_sum(lrow);
+  if (qi >= n) return;
+  pf_store_row<D>((__bf16*)p.out + ((long long)(b0 + qi) * p.hq + blk.a) * D + 4 * hf, o, 1.f / ltot);
+  if (p.lse && hf == 0) p.lse[(long long)(b0 + qi) * p.hq + blk.a] = (mrow + __builtin_log2f(ltot)) * 0.6931471805599453f;
 }
 
 // ------------------------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------------------------
-size_t prefill_workspace_bytes(const earn_attn_desc* desc, int total_tokens, int have_k_rot_out) {
-  if (have_k_rot_out) return 0;
+// rotated keys when the caller keeps none
+static size_t k_rot_bytes(const earn_attn_desc* desc, int total_tokens) {
   const size_t e = desc->dtype == EARN_F32 ? 4 : 2;
   return ((size_t)total_tokens * desc->n_kv_heads * desc->head_dim * e + 255) / 256 * 256;
+}
+// (cos, sin) table of the bf16 paths: [tokens][d/2] pairs of floats
+static size_t cs_table_bytes(const earn_attn_desc* desc, int total_tokens) {
+  if (desc->dtype == EARN_F32) return 0;
+  return ((size_t)total_tokens * (desc->head_dim / 2) * sizeof(f32x2) + 255) / 256 * 256;
+}
+// workspace layout: [rotated keys, unless the caller passes k_rot_out][cos/sin table]
+size_t prefill_workspace_bytes(const earn_attn_desc* desc, int total_tokens, int have_k_rot_out) {
+  return (have_k_rot_out ? 0 : k_rot_bytes(desc, total_tokens)) + cs_table_bytes(desc, total_tokens);
 }
 
 template <typename T, int D>
 static void launch_rope_k(const void* k, void* k_rot, const int32_t* cu, const int32_t* positions, int batch, int total,
-                          int hkv, const RopeTable& rope, hipStream_t stream) {
+                          int hkv, const RopeTable& rope, f32x2* cs_out, hipStream_t stream) {
   long long threads = (long long)total * (D / 16);
   hipLaunchKernelGGL((rope_k_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
-                     (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope);
+                     (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope, cs_out);
 }
 
-#ifndef EARN_PF_STAGES4
-#define EARN_PF_STAGES4 2
-#endif
-#ifndef EARN_PF_STAGES8
-#define EARN_PF_STAGES8 2
-#endif
 int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
                    const int32_t* positions, int batch, int total_tokens, int max_seqlen, void* out, void* k_rot_out,
                    float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
@@ -682,7 +880,9 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
     return EARN_ERR_WORKSPACE_TOO_SMALL;
   }
   void* k_rot = k_rot_out ? k_rot_out : workspace;
+  f32x2* cs = cs_table_bytes(desc, total_tokens) ? (f32x2*)((char*)workspace + (k_rot_out ? 0 : k_rot_bytes(desc, total_tokens))) : nullptr;
   PrefillParams p;
+  p.cs = cs;
   p.q = q; p.k_rot = k_rot; p.v = v; p.cu = cu_seqlens; p.positions = positions; p.out = out; p.lse = lse_out;
   p.batch = batch; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.max_seqlen = max_seqlen;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
@@ -690,34 +890,39 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
   p.rope = make_rope_table(desc->rope_base, d);
   const bool f32 = desc->dtype == EARN_F32;
   if (f32) {
-    if (d == 64) launch_rope_k<float, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
-    else launch_rope_k<float, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
+    if (d == 64) launch_rope_k<float, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
+    else launch_rope_k<float, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
     dim3 grid((max_seqlen + 63) / 64, p.hq, batch);
     if (d == 64) hipLaunchKernelGGL((prefill_rows_kernel<float, 64>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((prefill_rows_kernel<float, 128>), grid, dim3(256), 0, stream, p);
   } else if (max_seqlen <= kTileKeys) {
     // register-only layers: every sequence is a single K/V tile
-    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
-    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
+    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
+    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
     p.n_qblk = 1;
     const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
     dim3 grid((unsigned)(pairs8 * (p.hq / p.hkv)), 1, 1);
-    if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 2, 1>), grid, dim3(128), 0, stream, p);
-    else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 2, 1>), grid, dim3(128), 0, stream, p);
+    if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 2, 1>), grid, dim3(128), 0, stream, p);
+    else hipLaunchKernelGGL((prefill_mfma_kernel<128, 2, 1>), grid, dim3(128), 0, stream, p);
   } else {
-    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
-    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, stream);
+    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
+    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
+    // 128-row workgroups (two per CU) up to medium lengths, the pipelined 256-row kernel beyond
     static const int rows_env = getenv("EARN_PREFILL_ROWS") ? atoi(getenv("EARN_PREFILL_ROWS")) : 0;
+    static const int pipe_env = getenv("EARN_PREFILL_PIPE") ? atoi(getenv("EARN_PREFILL_PIPE")) : 1;
     const int block_rows = rows_env ? rows_env : (max_seqlen <= 1280 ? 128 : 256);
     p.n_qblk = (max_seqlen + block_rows - 1) / block_rows;
     const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
     dim3 grid((unsigned)(pairs8 * p.n_qblk * (p.hq / p.hkv)), 1, 1);
     if (block_rows == 128) {
-      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 4, EARN_PF_STAGES4>), grid, dim3(256), 0, stream, p);
-      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 4, EARN_PF_STAGES4>), grid, dim3(256), 0, stream, p);
+      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 4, 2>), grid, dim3(256), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 4, 2>), grid, dim3(256), 0, stream, p);
+    } else if (pipe_env) {
+      if (d == 64) hipLaunchKernelGGL((prefill_pipe_kernel<64>), grid, dim3(512), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_pipe_kernel<128>), grid, dim3(512), 0, stream, p);
     } else {
-      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 1, 8, EARN_PF_STAGES8>), grid, dim3(512), 0, stream, p);
-      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 1, 8, EARN_PF_STAGES8>), grid, dim3(512), 0, stream, p);
+      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 8, 2>), grid, dim3(512), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 8, 2>), grid, dim3(512), 0, stream, p);
     }
   }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;

@@ -61,11 +61,14 @@ class EarnPath:
         ws = max(B.earn_decode_workspace_bytes(self.desc, self.S, self.batch, self.max_seqlen, gen_cap),
                  B.earn_decode_workspace_bytes(self.desc, self.S, self.batch, self.r, gen_cap), 256)
         self.workspace = torch.empty(ws, dtype=torch.uint8, device=dev)
+        pws = max(B.earn_prefill_workspace_bytes(self.desc, self.batch, self.T, self.max_seqlen, True),
+                  B.earn_prefill_workspace_bytes(self.desc, self.batch, self.Tc, self.r, True), 256)
+        self.prefill_workspace = torch.empty(pws, dtype=torch.uint8, device=dev)
 
     # ---- prefill ----
     def prefill_full_layer(self, l: int, q, k, v) -> None:
         B.earn_prefill_attn(self.desc, q, k, v, self.cu, None, self.batch, self.T, self.max_seqlen,
-                            self.prefill_out[l], self.k_cache[l], self.lse[l], None)
+                            self.prefill_out[l], self.k_cache[l], self.lse[l], self.prefill_workspace)
         self.v_cache[l] = v
 
     def compact(self, x: Optional[torch.Tensor], q: Sequence[torch.Tensor], k: Sequence[torch.Tensor],
@@ -89,7 +92,7 @@ class EarnPath:
 
     def prefill_register_layer(self, l: int) -> None:
         B.earn_prefill_attn(self.desc, self.q_c[l], self.k_c[l], self.v_c[l], self.cu_c, self.pos, self.batch,
-                            self.Tc, self.r, self.prefill_out[l], self.k_cache[l], self.lse[l], None)
+                            self.Tc, self.r, self.prefill_out[l], self.k_cache[l], self.lse[l], self.prefill_workspace)
         self.v_cache[l] = self.v_c[l]
 
     def prefill(self, q: Sequence[torch.Tensor], k: Sequence[torch.Tensor], v: Sequence[torch.Tensor],
