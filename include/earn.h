@@ -89,7 +89,9 @@ int earn_prefill_attn(const earn_attn_desc* desc, const void* q, const void* k, 
                       int32_t max_seqlen, void* out, void* k_rot_out, float* lse_out, void* workspace,
                       size_t workspace_bytes, void* stream);
 
-/* Workspace earn_prefill_attn needs (bytes); depends on whether k_rot_out is supplied. 0 on invalid desc. */
+/* Workspace earn_prefill_attn needs (bytes): the rotated keys when no k_rot_out is supplied, plus, for bf16, a
+ * [total_tokens, d/2] table of (cos, sin) pairs that the query rotation reads. Scratch only: nothing in it outlives the
+ * call. 0 on invalid desc. */
 size_t earn_prefill_workspace_bytes(const earn_attn_desc* desc, int32_t batch, int32_t total_tokens,
                                     int32_t max_seqlen, int32_t have_k_rot_out);
 

@@ -32,6 +32,13 @@ struct Row8<float> {
   }
   // value as it will be read back from storage
   static __device__ __forceinline__ float round(float x) { return x; }
+  // the 8 elements as loaded, converted on use: lets several rows be in flight without holding their floats
+  struct Raw { f32x4 a, b; };
+  static __device__ __forceinline__ Raw load_raw(const float* p) { return Raw{*(const f32x4*)p, *(const f32x4*)(p + 4)}; }
+  static __device__ __forceinline__ void unpack(const Raw& r, float* x) {
+    x[0] = r.a[0]; x[1] = r.a[1]; x[2] = r.a[2]; x[3] = r.a[3]; x[4] = r.b[0]; x[5] = r.b[1]; x[6] = r.b[2]; x[7] = r.b[3];
+  }
+  static constexpr int kRowsInFlight = 2;
 };
 template <>
 struct Row8<__bf16> {
@@ -47,6 +54,13 @@ struct Row8<__bf16> {
     *(u32x4*)p = w;
   }
   static __device__ __forceinline__ float round(float x) { return bf16_lo(pack_bf16(x, 0.f) & 0xffffu); }
+  typedef u32x4 Raw;
+  static __device__ __forceinline__ Raw load_raw(const __bf16* p) { return *(const u32x4*)p; }
+  static __device__ __forceinline__ void unpack(const Raw& w, float* x) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { x[2 * i] = bf16_lo(w[i]); x[2 * i + 1] = bf16_hi(w[i]); }
+  }
+  static constexpr int kRowsInFlight = 4;
 };
 
 struct DecodeParams {
@@ -60,6 +74,23 @@ struct DecodeParams {
   float scale_log2;
   RopeTable rope;
 };
+
+// Sum over the LPK (8 or 16) adjacent lanes that hold one key row, left in every lane of the group.  Data-parallel
+// primitives instead of shuffles through LDS: pairs, quads, the mirrored half (lane i <-> 7-i: the other quad), the
+// mirrored row (lane i <-> 15-i: the other half).
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+template <int LPK>
+__device__ __forceinline__ float group_sum(float x) {
+  static_assert(LPK == 8 || LPK == 16);
+  x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]
+  x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]
+  x += dpp_move<0x141>(x);  // row_half_mirror
+  if (LPK == 16) x += dpp_move<0x140>(x);  // row_mirror
+  return x;
+}
 
 // merge (m2,l2,o2) into (m,l,o); all in base-2 exponent units
 template <int N>
@@ -82,6 +113,13 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
                                             float* sm_base) {
   constexpr int LPK = D / 8;         // lanes per key row
   constexpr int KPW = kWave / LPK;   // key rows per wave instruction
+#if defined(EARN_DBG_PHASES)
+  long long stamp[6];
+#define DEC_STAMP(i) { __builtin_amdgcn_sched_barrier(0); stamp[i] = (long long)__builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); }
+#else
+#define DEC_STAMP(i)
+#endif
+  DEC_STAMP(0);
   const int gq = p.hq / p.hkv;       // query heads per kv head
   const int sub = lane % LPK, kk = lane / LPK;
   const int s = p.stream_to_seq ? p.stream_to_seq[u] : u;
@@ -96,6 +134,32 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
   T* Gk = (T*)p.gen_k + (((long long)u * p.gen_cap) * p.hkv + c) * D + sub * 8;
   T* Gv = (T*)p.gen_v + (((long long)u * p.gen_cap) * p.hkv + c) * D + sub * 8;
   const long long row_stride = (long long)p.hkv * D;
+
+  // The wave's keys are j_begin + wave*KPW + kk + i*WAVES*KPW.  NP iterations' rows are requested together, then
+  // consumed: a short key list (register-only caches) is one memory round trip instead of one per iteration, and
+  // the first batch is requested here, ahead of the query rotation, which then runs in its shadow.
+  constexpr int NP = GQ >= 8 ? 2 : Row8<T>::kRowsInFlight;  // fewer with many heads: their accumulators need the registers
+  const int j_begin = z * chunk;
+  const int j_end = min(m_total, j_begin + chunk);
+  typename Row8<T>::Raw kr[NP], vr[NP];
+  auto load_batch = [&](int jb) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int j = jb + i * WAVES * KPW + kk;
+      if (j < ns && j < j_end) {
+        kr[i] = Row8<T>::load_raw(Kc + (long long)j * row_stride);
+        vr[i] = Row8<T>::load_raw(Vc + (long long)j * row_stride);
+      } else if (j < m_total - 1 && j < j_end) {
+        kr[i] = Row8<T>::load_raw(Gk + (long long)(j - ns) * row_stride);
+        vr[i] = Row8<T>::load_raw(Gv + (long long)(j - ns) * row_stride);
+      } else {
+        kr[i] = typename Row8<T>::Raw{};
+        vr[i] = typename Row8<T>::Raw{};
+      }
+    }
+  };
+  const int jb_first = j_begin + wave * KPW;
+  if (jb_first < j_end) load_batch(jb_first);
 
   // rotary factors of this lane's 8 elements (pairs (e, e + D/2): this lane holds one side, the partner lane the other)
   float cs[8], sn[8];
@@ -144,8 +208,7 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
 #pragma unroll
   for (int i = 0; i < 8; ++i) kn[i] = Row8<T>::round(kn[i]);
 
-  const int j_begin = z * chunk;
-  const int j_end = min(m_total, j_begin + chunk);
+  DEC_STAMP(1);
   // cache append (Eq. 4): done by the one workgroup whose key range holds the new token
   if (m_total - 1 >= j_begin && m_total - 1 < j_end && wave == 0 && kk == 0) {
     Row8<T>::store(Gk + (long long)g * row_stride, kn);
@@ -160,43 +223,63 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
     for (int i = 0; i < 8; ++i) o[a][i] = 0.f;
   }
 
-  for (int j0 = j_begin + wave * KPW; j0 < j_end; j0 += WAVES * KPW) {
-    const int j = j0 + kk;
-    const bool valid = j < j_end;
-    float kx[8], vx[8];
-    if (valid) {
-      if (j < ns) {
-        Row8<T>::load(Kc + (long long)j * row_stride, kx);
-        Row8<T>::load(Vc + (long long)j * row_stride, vx);
-      } else if (j < m_total - 1) {
-        Row8<T>::load(Gk + (long long)(j - ns) * row_stride, kx);
-        Row8<T>::load(Gv + (long long)(j - ns) * row_stride, vx);
-      } else {
+  for (int jb = jb_first; jb < j_end; jb += NP * WAVES * KPW) {
+    if (jb != jb_first) load_batch(jb);
+    // scores of the batch first, then one reference update per head for the whole batch, then the weighted values:
+    // the running maximum and the rescale of the accumulators are paid once per NP keys instead of once per key
+    float sc[NP][GQ];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { kx[i] = kn[i]; vx[i] = vn[i]; }
+    for (int i = 0; i < NP; ++i) {
+      const int j = jb + i * WAVES * KPW + kk;
+      const bool valid = j < j_end;
+      float kx[8];
+      Row8<T>::unpack(kr[i], kx);
+      if (valid && j == m_total - 1) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) kx[e] = kn[e];
       }
-    } else {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { kx[i] = 0.f; vx[i] = 0.f; }
+      for (int a = 0; a < GQ; ++a) {
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) d = __builtin_fmaf(qv[a][e], kx[e], d);
+        sc[i][a] = valid ? group_sum<LPK>(d) : -INFINITY;
+      }
     }
 #pragma unroll
     for (int a = 0; a < GQ; ++a) {
-      float sc = 0.f;
+      float mn = mx[a];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) sc = __builtin_fmaf(qv[a][i], kx[i], sc);
+      for (int i = 0; i < NP; ++i) mn = fmaxf(mn, sc[i][a]);
+      const float corr = (mx[a] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mx[a] - mn);
+      float sum = 0.f;
 #pragma unroll
-      for (int off = LPK / 2; off >= 1; off >>= 1) sc += __shfl_xor(sc, off, kWave);
-      if (!valid) sc = -INFINITY;
-      float mn = fmaxf(mx[a], sc);
-      float corr = (mx[a] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mx[a] - mn);
-      float pr = valid ? __builtin_amdgcn_exp2f(sc - mn) : 0.f;
-      ls[a] = ls[a] * corr + pr;
+      for (int i = 0; i < NP; ++i) {
+        sc[i][a] = (sc[i][a] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sc[i][a] - mn);  // a finite score makes mn finite
+        sum += sc[i][a];
+      }
+      ls[a] = ls[a] * corr + sum;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) o[a][i] = __builtin_fmaf(pr, vx[i], o[a][i] * corr);
+      for (int e = 0; e < 8; ++e) o[a][e] *= corr;
       mx[a] = mn;
+    }
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int j = jb + i * WAVES * KPW + kk;
+      float vx[8];
+      Row8<T>::unpack(vr[i], vx);
+      if (j == m_total - 1) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vx[e] = vn[e];
+      }
+#pragma unroll
+      for (int a = 0; a < GQ; ++a)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[a][e] = __builtin_fmaf(sc[i][a], vx[e], o[a][e]);
     }
   }
 
+  DEC_STAMP(2);
   // merge the KPW lane groups of the wave (lanes with equal `sub`)
 #pragma unroll
   for (int a = 0; a < GQ; ++a) {
@@ -224,6 +307,7 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
       if (sb == 0) { p.part_ml[slot * 2] = m; p.part_ml[slot * 2 + 1] = l; }
     }
   };
+  DEC_STAMP(3);
   if constexpr (WAVES == 1) {
     if (kk == 0) {
 #pragma unroll
@@ -256,6 +340,15 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
       finish(a, sb, m, l, oo);
     }
   }
+#if defined(EARN_DBG_PHASES)
+  DEC_STAMP(4);
+  if (wave == 0 && lane == 0 && p.part_o) {
+    float* dbg = p.part_o + ((long long)u * p.hkv + c) * 8;
+    for (int i = 0; i < 4; ++i) dbg[i] = (float)(stamp[i + 1] - stamp[i]);
+    dbg[4] = (float)(stamp[0] & 0xffffff);  // start time, low bits
+    dbg[5] = (float)(stamp[4] & 0xffffff);
+  }
+#endif
 }
 
 template <typename T, int D, int GQ, int WAVES>
@@ -694,9 +787,13 @@ static void launch_vector_w(const DecodeParams& p, int gq, dim3 grid, hipStream_
 }
 template <typename T, int D>
 static void launch_vector(const DecodeParams& p, int gq, dim3 grid, hipStream_t stream) {
-  // short key lists of a single query head: one wave per (stream, kv head), so the prologue (query rotation) is not
-  // repeated by 4 waves; with several heads per kv head the serial key loop is the longer pole and 4 waves win
-  if (p.chunk <= 128 && gq == 1) launch_vector_w<T, D, 1>(p, gq, grid, stream);
+  // Short key lists are latency bound: every wave repeats the prologue (query rotation), and what counts is that all
+  // workgroups are resident at once.  One wave per (stream, kv head) for a single query head, two for grouped heads
+  // (more arithmetic per key); long key lists take four.
+  static const int waves_env = getenv("EARN_DEC_VEC_WAVES") ? atoi(getenv("EARN_DEC_VEC_WAVES")) : 0;
+  const int waves = waves_env ? waves_env : (p.chunk > 128 ? 4 : (gq == 1 ? 1 : 2));
+  if (waves == 1) launch_vector_w<T, D, 1>(p, gq, grid, stream);
+  else if (waves == 2) launch_vector_w<T, D, 2>(p, gq, grid, stream);
   else launch_vector_w<T, D, 4>(p, gq, grid, stream);
 }
 

@@ -611,7 +611,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
 }
 
 // ------------------------------------------------------------------------------------------------------------------
-// Software-pipelined schedule for long sequences: 8 waves, 256 query rows per workgroup, two waves per SIMD.
+// Software-pipelined schedule for long sequences (instantiated with 8 waves: 256 query rows per workgroup, one
+// workgroup per CU, two waves per SIMD).
 //
 // A single wave cannot hide its exponentials behind its own matrix products when the two alternate, and two waves of a
 // SIMD that meet at a barrier every tile fall into step, so they do not hide them for each other either.  Here every
@@ -628,9 +629,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
 // of 2 (t: being multiplied, t+1: in flight).  The two score tiles swap roles every iteration; the loop is unrolled by
 // two so that the swap costs no register moves.
 // ------------------------------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(512, 1) void prefill_pipe_kernel(PrefillParams p) {
-  constexpr int WAVES = 8, kBlockRows = 256;
+template <int D, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_pipe_kernel(PrefillParams p) {
+  constexpr int kBlockRows = 32 * WAVES;
   constexpr int KSTEPS = D / 16, DB = D / 32;
   constexpr int UPM = 16 / (2 * KSTEPS);  // softmax units per score MFMA: 1 (D = 128) or 2 (D = 64)
   __shared__ __bf16 smk[3][kTileKeys * D];
@@ -657,15 +658,9 @@ __global__ __launch_bounds__(512, 1) void prefill_pipe_kernel(PrefillParams p) {
   // barrier t-1.  Behind it nobody reads K(t-1) (last use: the exact path of iteration t-1) or V(t-1) any more, which is
   // where K(t+2) and V(t+1) go.
   auto sync_and_stage = [&](int t) {
-#if defined(EARN_DBG_NOBARRIER)
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-#else
     drain_loads_and_barrier();
-#endif
-#if !defined(EARN_DBG_NOSTAGE)
     if (t + 2 < n_tiles) issue_k(t + 2);
     if (t + 1 < n_tiles) issue_v(t + 1);
-#endif
   };
   issue_k(0);
   issue_v(0);
@@ -907,22 +902,19 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
   } else {
     if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
     else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
-    // 128-row workgroups (two per CU) up to medium lengths, the pipelined 256-row kernel beyond
+    // 128-row workgroups (two per CU) in the plain schedule up to medium lengths, where the ends of a workgroup's
+    // life (first tile's latency, output store) and the causal diagonal weigh most; the pipelined 256-row kernel beyond
     static const int rows_env = getenv("EARN_PREFILL_ROWS") ? atoi(getenv("EARN_PREFILL_ROWS")) : 0;
-    static const int pipe_env = getenv("EARN_PREFILL_PIPE") ? atoi(getenv("EARN_PREFILL_PIPE")) : 1;
-    const int block_rows = rows_env ? rows_env : (max_seqlen <= 1280 ? 128 : 256);
+    const int block_rows = rows_env == 128 || rows_env == 256 ? rows_env : (max_seqlen <= 3072 ? 128 : 256);
     p.n_qblk = (max_seqlen + block_rows - 1) / block_rows;
     const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
     dim3 grid((unsigned)(pairs8 * p.n_qblk * (p.hq / p.hkv)), 1, 1);
     if (block_rows == 128) {
       if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 4, 2>), grid, dim3(256), 0, stream, p);
       else hipLaunchKernelGGL((prefill_mfma_kernel<128, 4, 2>), grid, dim3(256), 0, stream, p);
-    } else if (pipe_env) {
-      if (d == 64) hipLaunchKernelGGL((prefill_pipe_kernel<64>), grid, dim3(512), 0, stream, p);
-      else hipLaunchKernelGGL((prefill_pipe_kernel<128>), grid, dim3(512), 0, stream, p);
     } else {
-      if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 8, 2>), grid, dim3(512), 0, stream, p);
-      else hipLaunchKernelGGL((prefill_mfma_kernel<128, 8, 2>), grid, dim3(512), 0, stream, p);
+      if (d == 64) hipLaunchKernelGGL((prefill_pipe_kernel<64, 8>), grid, dim3(512), 0, stream, p);
+      else hipLaunchKernelGGL((prefill_pipe_kernel<128, 8>), grid, dim3(512), 0, stream, p);
     }
   }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;

@@ -52,8 +52,14 @@ def test_prefill_argument_errors():
     # without k_rot_out the rotated keys need workspace
     rc = lib.earn_prefill_attn(ctypes.byref(_desc()), fake, fake, fake, fake, None, 1, 8, 8, fake, None, None, None, 0, None)
     assert rc == B.EARN_ERR_WORKSPACE_TOO_SMALL
-    assert B.earn_prefill_workspace_bytes(_desc(), 1, 8, 8, False) >= 8 * 2 * 64 * 2
-    assert B.earn_prefill_workspace_bytes(_desc(), 1, 8, 8, True) == 0
+    with_k = B.earn_prefill_workspace_bytes(_desc(), 1, 8, 8, True)      # bf16: the cos/sin table of the 8 tokens
+    without_k = B.earn_prefill_workspace_bytes(_desc(), 1, 8, 8, False)  # plus the rotated keys
+    assert with_k >= 8 * 32 * 8 and with_k % 256 == 0
+    assert without_k - with_k >= 8 * 2 * 64 * 2 and without_k % 256 == 0
+    # with k_rot_out but no workspace the bf16 path still lacks room for its table; the fp32 path needs none
+    rc = lib.earn_prefill_attn(ctypes.byref(_desc()), fake, fake, fake, fake, None, 1, 8, 8, fake, fake, None, None, 0, None)
+    assert rc == B.EARN_ERR_WORKSPACE_TOO_SMALL
+    assert B.earn_prefill_workspace_bytes(_desc(dtype=B.EARN_F32), 1, 8, 8, True) == 0
 
 
 def test_compact_argument_errors():
