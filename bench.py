@@ -35,6 +35,7 @@ HEADLINE = "long_beam"
 # HBM bytes per launch of the dominant kernel (full-length prefill layer), from the rocprofv3 FETCH_SIZE / WRITE_SIZE
 # runs summarised in profiles/long_beam_hbm_traffic.txt (counters scaled by a 1 GiB copy: x2.0 and x1.0).
 MEASURED_TRAFFIC = {"long_beam": {"fetch_bytes": 2.570e9, "write_bytes": 1.082e9}}
+DOMINANT_KERNEL = "prefill_pipe_kernel + rope_k_kernel (one full-length causal layer)"
 
 
 def log(*a):
@@ -190,6 +191,41 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
     return res
 
 
+def run_single(name: str, kind: str, dev) -> dict:
+    """One kernel of the path on its own, launched twice, with as few other dispatches as possible: the form in which
+    the hardware-counter passes (rocprofv3 --pmc), which serialise and slow every dispatch, are taken."""
+    from paper_2507_00715_amd.pipeline import EarnPath
+    c = W.CONFIGS[name]
+    w = W.Workload(c)
+    seq, pos = w.token_coords(dev)
+    path = EarnPath(n_layers=c.n_layers, split_k=c.split_k, n_head_reg=c.n_head_reg, n_tail_reg=c.n_tail_reg,
+                    n_q_heads=c.n_q_heads, n_kv_heads=c.n_kv_heads, head_dim=c.head_dim, dtype=c.torch_dtype,
+                    cu_seqlens=w.cu_seqlens, stream_to_seq=w.stream_to_seq, gen_cap=c.decode_steps,
+                    rope_base=c.rope_base, device=dev)
+    q0, k0, v0 = (w.prefill_tensor(t, 0, coords=(seq, pos)) for t in "qkv")
+    if kind == "prefill_full":
+        launch = lambda: path.prefill_full_layer(0, q0, k0, v0)
+    elif kind == "decode_full":
+        path.prefill_full_layer(0, q0, k0, v0)
+        path.set_step(0)
+        dq, dk, dv = (w.decode_tensor(t, 0, 0, device=dev) for t in "qkv")
+        launch = lambda: path.decode_layer(0, dq, dk, dv)
+    elif kind == "compact":
+        N, kk = c.n_layers, c.split_k
+        mk = lambda which: [w.prefill_tensor(which, l, coords=(seq, pos)) if l >= kk else None for l in range(N)]
+        x, q, k, v = w.prefill_tensor("x", 0, coords=(seq, pos)), mk("q"), mk("k"), mk("v")
+        launch = lambda: path.compact(x, q, k, v)
+    else:
+        raise SystemExit(f"bench.py: unknown --single kind {kind!r}")
+    torch.cuda.synchronize()
+    launch()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    launch()
+    torch.cuda.synchronize()
+    return {"workload": name, "single": kind, "launches": 2, "second_launch_ms": (time.perf_counter() - t0) * 1e3}
+
+
 def cpu_baseline(name: str) -> dict:
     """The fp64 oracle, untuned, on a bounded sample of the headline workload's first prefill layer."""
     from oracle import earn_oracle as O
@@ -197,7 +233,7 @@ def cpu_baseline(name: str) -> dict:
     w = W.Workload(cfg)
     seq_id = 0
     n = w.seq_lengths[seq_id]
-    stride = max(1, n // 512)
+    stride = max(1, n // 4096)  # about 10-20 s of oracle time on 16 host cores
     q = W.to_f64(w.prefill_tensor("q", 0, seqs=[seq_id]))
     k = W.to_f64(w.prefill_tensor("k", 0, seqs=[seq_id]))
     v = W.to_f64(w.prefill_tensor("v", 0, seqs=[seq_id]))
@@ -225,6 +261,8 @@ def main():
     ap.add_argument("--others", default="small_gqa,mid_mha,serving",
                     help="comma-separated workloads also measured and reported under 'other_workloads' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--single", default="", choices=["", "prefill_full", "decode_full", "compact"],
+                    help="launch just this kernel of the workload twice and exit (for hardware-counter passes)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU hot path; --gpus N with N > 1 is not supported "
@@ -238,6 +276,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.single:
+        print(json.dumps(run_single(args.workload, args.single, dev)))
+        return
     head = run_workload(args.workload, args.steps, args.warmup, dev)
     others = {}
     for name in [s for s in args.others.split(",") if s and s != args.workload]:
@@ -257,7 +298,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": head["workload"],
-        "roofline": {"kernel": "prefill_mfma_kernel (full-length causal layer)", "bound": "mfma",
+        "roofline": {"kernel": DOMINANT_KERNEL, "bound": "mfma",
                      "achieved": pf["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": pf["tflops"] / peak,
                      "traffic": (sum(MEASURED_TRAFFIC[args.workload].values())
                                  if args.workload in MEASURED_TRAFFIC else None),

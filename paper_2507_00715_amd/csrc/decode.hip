@@ -13,6 +13,7 @@
 #include <stdlib.h>
 
 #include "common.h"
+#include "mfma_tiles.h"
 
 namespace earn {
 
@@ -405,24 +406,29 @@ constexpr int kDsSuper = kDsTile * kDsGroupWaves;  // keys per super-tile
 constexpr float kDecSumLimit = 512.0f;   // per lane: 16 exponentials of one query row
 constexpr int kMaxStreamsPerSeq = 1024;  // beams of one sequence the stream list holds
 
-typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+// Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS traffic, not for its global loads.
+// (__syncthreads() also drains the vector-memory queue, which would cut the depth of the K/V stream below to the one
+// super-tile a single iteration can cover.)  The empty asm statements keep the compiler from moving memory accesses
+// across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
 
 template <int D>
 struct DsSmem {
-  static constexpr int KS = D + 8;
-  static constexpr int VS = D + 32;
-  struct SubTile { __bf16 k[kDsTile * KS]; __bf16 v[kDsTile * VS]; };
-  SubTile tile[2][kDsGroupWaves];   // [stage][sub-tile]; reused as the merge buffers once the key loop is done
+  // [stage][K, V][128 keys x D], rows unpadded, 16-byte chunks swizzled as in the prefill kernels (the loads deposit
+  // them directly); reused as the merge buffers once the key loop is done
+  __bf16 tile[2][2][kDsSuper * D];
   int streams[kMaxStreamsPerSeq];
   int n_streams_of_seq;
 };
 
 template <int D, int C, int GQ>
 __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodeParams p) {
-  constexpr int THREADS = 256 * C;
-  constexpr int KSTEPS = D / 16, DB = D / 32, UPR = D / 8;
-  constexpr int UNITS = kDsSuper * UPR / THREADS;  // 16-byte units per thread per super-tile and tensor
-  constexpr int RPU = THREADS / UPR;               // rows between consecutive units of a thread
+  constexpr int KSTEPS = D / 16, DB = D / 32;
   constexpr int ROWS = 32 * C;
   constexpr int STATE = DB * 16 + 2;               // floats per lane in a merge
   using Sm = DsSmem<D>;
@@ -431,7 +437,9 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 
   const int c = blockIdx.x, s = blockIdx.y, z = blockIdx.z;
   const int gq = p.hq / p.hkv;
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  // the wave index is the same in all 64 lanes: saying so keeps the key loop and everything derived from the wave's
+  // place in the workgroup in scalar registers
+  const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int grp = wave / kDsGroupWaves, sub = wave % kDsGroupWaves;
   const int r32 = lane & 31, hf = lane >> 5;
   const int b0 = p.shared_cu[s], ns = p.shared_cu[s + 1] - b0;
@@ -443,35 +451,23 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   const __bf16* Kg = (const __bf16*)p.shared_k + ((long long)b0 * p.hkv + c) * D;
   const __bf16* Vg = (const __bf16*)p.shared_v + ((long long)b0 * p.hkv + c) * D;
   const long long kv_stride = (long long)p.hkv * D;
-  const int k_off = r32 * Sm::KS + 8 * hf;
-  const int v_off = (4 * hf + ((lane & 15) >> 2)) * Sm::VS + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  float* mbuf = (float*)&sm.tile[0][0] + (size_t)grp * 2 * STATE * kWave;
-  // staging: unit i of this thread is row (tid / UPR + i * RPU) of the super-tile, 16-byte column tid % UPR.
-  // Loads go through buffer descriptors that cover exactly the rows of this workgroup's key range: one vector register
-  // holds the per-thread byte offset, everything else of the address is scalar, and rows past the end of the range
-  // read as zeros (no clamping code, finite data for the masked tail).
-  const int st_row0 = threadIdx.x / UPR, st_col = threadIdx.x % UPR;
-  const int row_bytes = (int)kv_stride * 2;
-  const int st_voff = st_row0 * row_bytes + st_col * 16;
-  const int range_bytes = n_keys > 0 ? (n_keys - 1) * row_bytes + D * 2 : 0;
-  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(Kg + j_begin * kv_stride), 0, range_bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(Vg + j_begin * kv_stride), 0, range_bytes, 0x00020000);
-
-  // two register sets: super-tiles it+2 and it+3 are in flight while super-tile it is being used (the stream is
-  // bound by HBM latency times bytes in flight, so the depth matters more than anything else here)
-  u32x4 kreg[2][UNITS], vreg[2][UNITS];
-  auto load_super = [&](int it, u32x4 (&kr)[UNITS], u32x4 (&vr)[UNITS]) {
-#pragma unroll
-    for (int i = 0; i < UNITS; ++i) {
-      const int soff = (it * kDsSuper + i * RPU) * row_bytes;  // scalar part of the address
-      kr[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, st_voff, soff, 0);
-      vr[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, st_voff, soff, 0);
-    }
+  FragOffsets<D> fo;
+  fo.init(lane);
+  float* mbuf = (float*)&sm.tile[0][0][0] + (size_t)grp * 2 * STATE * kWave;
+  // Staging: the super-tiles of this workgroup's key range stream from global memory straight into LDS, all waves
+  // sharing the instructions; the buffer descriptors cover exactly the rows of the range, so rows past its end read as
+  // zeros (no clamping code, finite data for the masked tail).  Super-tile it+1 is in flight while super-tile it is used.
+  TileStager<D, 4 * C, kDsSuper> stager;
+  stager.init(Kg + j_begin * kv_stride, Vg + j_begin * kv_stride, n_keys, p.hkv, wave, lane);
+  const unsigned lds_tiles = (unsigned)(size_t)(lds_void_ptr)&sm.tile[0][0][0];
+  auto issue_super = [&](int it) {
+    const unsigned at = lds_tiles + (unsigned)((it & 1) * 2 * kDsSuper * D * 2);
+    stager.issue(stager.k_rsrc, at, it);
+    stager.issue(stager.v_rsrc, at + (unsigned)(kDsSuper * D * 2), it);
   };
-  // the first two super-tiles are requested before anything else: they fly while the stream list is built and the
-  // queries are rotated
-  if (n_super > 0) load_super(0, kreg[0], vreg[0]);
-  if (n_super > 1) load_super(1, kreg[1], vreg[1]);
+  // the first super-tile is requested before anything else: it flies while the stream list is built, the generated
+  // rows are handled and the queries are rotated
+  if (n_super > 0) issue_super(0);
 
   // ---- streams (beams) of this sequence, ascending ----
   if (wave == 0) {
@@ -544,34 +540,14 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
     float mrow = -INFINITY, lrow = 0.f;
 
-    auto store_super = [&](int stage, u32x4 (&kr)[UNITS], u32x4 (&vr)[UNITS]) {
-#pragma unroll
-      for (int i = 0; i < UNITS; ++i) {
-        const int row = st_row0 + i * RPU;
-        typename Sm::SubTile& tl = sm.tile[stage][row / kDsTile];
-        *(u32x4*)(tl.k + (row % kDsTile) * Sm::KS + st_col * 8) = kr[i];
-        *(u32x4*)(tl.v + (row % kDsTile) * Sm::VS + st_col * 8) = vr[i];
-      }
-    };
-    // super-tile it+1 (register set (it+1)&1) goes to the other LDS stage (last read in iteration it-1); that
-    // register set is then reloaded with super-tile it+3
-    auto stage_next = [&](int it) {
-      if ((it + 1) & 1) {
-        if (it + 1 < n_super) store_super(1, kreg[1], vreg[1]);
-        if (it + 3 < n_super) load_super(it + 3, kreg[1], vreg[1]);
-      } else {
-        if (it + 1 < n_super) store_super(0, kreg[0], vreg[0]);
-        if (it + 3 < n_super) load_super(it + 3, kreg[0], vreg[0]);
-      }
-    };
     // S^T = K Q^T of this wave's sub-tile; keys past the range end get zero weight
     auto scores = [&](int it, f32x16& sc) {
-      const __bf16* my_k = sm.tile[it & 1][sub].k;
+      const __bf16* my_k = sm.tile[it & 1][0] + sub * kDsTile * D;
 #pragma unroll
       for (int i = 0; i < 16; ++i) sc[i] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
-        const bf16x8 kf = *(const bf16x8*)(my_k + k_off + 16 * ks);
+        const bf16x8 kf = *(const bf16x8*)(my_k + fo.k(ks));
         sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sc, 0, 0, 0);
       }
       const int key0 = j_begin + it * kDsSuper + sub * kDsTile;
@@ -591,7 +567,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       }
     };
     auto accumulate = [&](int it, f32x16& sc, float lsum) {
-      const __bf16* my_v = sm.tile[it & 1][sub].v;
+      const __bf16* my_v = sm.tile[it & 1][1] + sub * kDsTile * D;
       bf16x8 pf[2];
       lrow += lsum;
 #pragma unroll
@@ -605,12 +581,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const __bf16* vp = my_v + v_off + 16 * kk * Sm::VS + 32 * db;
-          s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp));
-          s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(vp + 8 * Sm::VS));
-          typedef short s16x8 __attribute__((ext_vector_type(8)));
-          s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf[kk], o[db], 0, 0, 0);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_fragment<D>(my_v, fo, db, kk), pf[kk], o[db], 0, 0, 0);
         }
     };
     // does this wave have keys in super-tile `it`?
@@ -626,18 +597,18 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     // vector ALU; a reference is stale exactly when some exponential is large, which shows in the partial row sums
     // (+inf / NaN on the first tile, whose reference is -inf).  A wave that sees a stale reference leaves the loop,
     // takes the exact maxima of the tile, rescales, finishes the tile and re-enters.
-    if (row0 > 0) {  // further 64-row passes over the same keys
-      if (n_super > 0) load_super(0, kreg[0], vreg[0]);
-      if (n_super > 1) load_super(1, kreg[1], vreg[1]);
-    }
-    if (n_super > 0) store_super(0, kreg[0], vreg[0]);
-    if (n_super > 2) load_super(2, kreg[0], vreg[0]);
-    __syncthreads();
+    if (row0 > 0 && n_super > 0) issue_super(0);  // further passes over the same keys for more query rows
+    // Iteration `it` opens with the barrier behind which super-tile `it` is complete (every wave has waited for its own
+    // loads) and nobody reads super-tile it-1 any more, whose buffer the loads of super-tile it+1 then start to fill.
+    auto sync_and_stage = [&](int it) {
+      drain_loads_and_barrier();
+      if (it + 1 < n_super) issue_super(it + 1);
+    };
     int it = 0;
     while (it < n_super) {
       bool rescale = false;
       for (; it < n_super; ++it) {
-        stage_next(it);
+        sync_and_stage(it);
         if (has_keys(it)) {
           f32x16 sc;
           float lsum;
@@ -646,7 +617,6 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
           if (__any(!(lsum <= kDecSumLimit))) { rescale = true; break; }
           accumulate(it, sc, lsum);
         }
-        __syncthreads();
       }
       if (!rescale) break;
       {
@@ -667,10 +637,10 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
           for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
         exponentials(sc, lsum);
         accumulate(it, sc, lsum);
-        __syncthreads();
         ++it;
       }
     }
+    __syncthreads();  // every wave is done with the tiles: their memory becomes the merge buffers
 
     // ---- merge the 4 waves of the group: (2,3) -> (0,1), then 1 -> 0; lane-wise, the layouts are identical ----
     auto put = [&](int slot) {
@@ -697,7 +667,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[db][i] = o[db][i] * a + src[(r++) * kWave] * b;
     };
-    if (sub >= 2) put(sub - 2);   // the last loop barrier has passed: nobody reads tile memory any more
+    if (sub >= 2) put(sub - 2);
     __syncthreads();
     if (sub < 2) take(sub);
     __syncthreads();
