@@ -401,8 +401,9 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const float* __rest
 // per-stream generated rows and the new token differ per beam and are handled by decode_kernel in gen_only mode.
 // ------------------------------------------------------------------------------------------------------------------
 constexpr int kDsTile = 32;              // keys per wave sub-tile
-constexpr int kDsGroupWaves = 4;         // waves per 32-row group = sub-tiles per super-tile
-constexpr int kDsSuper = kDsTile * kDsGroupWaves;  // keys per super-tile
+constexpr int kDsGroupWaves = 4;         // waves per 32-row group: 2 key sub-tiles x 2 halves of the head dimension
+constexpr int kDsRing = 4;               // K/V tiles (kTileKeys = 64 keys each) in LDS: one in use, three on their way
+constexpr int kDsSuper = 128;            // key ranges of the splits are multiples of this
 constexpr float kDecSumLimit = 512.0f;   // per lane: 16 exponentials of one query row
 constexpr int kMaxStreamsPerSeq = 1024;  // beams of one sequence the stream list holds
 
@@ -419,34 +420,59 @@ __device__ __forceinline__ void lds_barrier() {
 
 template <int D>
 struct DsSmem {
-  // [stage][K, V][128 keys x D], rows unpadded, 16-byte chunks swizzled as in the prefill kernels (the loads deposit
-  // them directly); reused as the merge buffers once the key loop is done
-  __bf16 tile[2][2][kDsSuper * D];
+  // [ring slot][K, V][64 keys x D], rows unpadded, 16-byte chunks swizzled as in the prefill kernels (the loads
+  // deposit them directly); reused as the merge buffers once the key loop is done
+  __bf16 tile[kDsRing][2][kTileKeys * D];
   int streams[kMaxStreamsPerSeq];
   int n_streams_of_seq;
 };
 
+#if defined(EARN_DBG_PHASES)
+__device__ float g_dec_dbg[256 * 8 * 16];
+#define DS_STAMP(x) { __builtin_amdgcn_sched_barrier(0); x = (long long)__builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); }
+#else
+#define DS_STAMP(x)
+#endif
 template <int D, int C, int GQ>
 __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodeParams p) {
+  [[maybe_unused]] long long ds_t0, ds_t1, ds_t2, ds_t3, ds_t4, ds_a, ds_b, ds_c, ds_wait = 0, ds_bar = 0, ds_comp = 0;
+  DS_STAMP(ds_t0);
   constexpr int KSTEPS = D / 16, DB = D / 32;
   constexpr int ROWS = 32 * C;
-  constexpr int STATE = DB * 16 + 2;               // floats per lane in a merge
+  constexpr int DBH = DB / 2;                      // d blocks per wave: each wave accumulates half of the head dimension
+  constexpr int STATE = DBH * 16 + 2;              // floats per lane in a merge
   using Sm = DsSmem<D>;
   static_assert(sizeof(Sm::tile) >= (size_t)C * 2 * STATE * kWave * sizeof(float), "merge buffers");
   __shared__ Sm sm;
 
-  const int c = blockIdx.x, s = blockIdx.y, z = blockIdx.z;
+  // Workgroup -> (kv head c, sequence s, key split z).  Linear ids go to the 8 XCDs round-robin; the hkv workgroups that
+  // read the interleaved head slices of the SAME cache rows (one (s, z), all c) get ids 8 apart, i.e. the same XCD and
+  // neighbouring dispatch slots, so that their requests for one DRAM row arrive together.
+  int c, s, z;
+  {
+    const int n_sz = p.batch * p.n_splits, n_sz8 = (n_sz + 7) / 8 * 8;
+    const int L = blockIdx.x;
+#if defined(EARN_DBG_DEC_OLDMAP)
+    c = L % p.hkv; const int sz = L / p.hkv;
+#else
+    const int sz = (L / (8 * p.hkv)) * 8 + L % 8;
+    c = (L / 8) % p.hkv;
+#endif
+    if (sz >= n_sz || L >= n_sz8 * p.hkv) return;
+    s = sz % p.batch; z = sz / p.batch;
+  }
   const int gq = p.hq / p.hkv;
   // the wave index is the same in all 64 lanes: saying so keeps the key loop and everything derived from the wave's
   // place in the workgroup in scalar registers
   const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int grp = wave / kDsGroupWaves, sub = wave % kDsGroupWaves;
+  const int ksub = sub & 1, dh = sub >> 1;   // key sub-tile of the tile, half of the head dimension
   const int r32 = lane & 31, hf = lane >> 5;
   const int b0 = p.shared_cu[s], ns = p.shared_cu[s + 1] - b0;
   const int j_begin = z * p.chunk;
   const int j_end = min(ns, j_begin + p.chunk);
   const int n_keys = max(j_end - j_begin, 0);
-  const int n_super = (n_keys + kDsSuper - 1) / kDsSuper;
+  const int n_tiles = (n_keys + kTileKeys - 1) / kTileKeys;
 
   const __bf16* Kg = (const __bf16*)p.shared_k + ((long long)b0 * p.hkv + c) * D;
   const __bf16* Vg = (const __bf16*)p.shared_v + ((long long)b0 * p.hkv + c) * D;
@@ -454,20 +480,29 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   FragOffsets<D> fo;
   fo.init(lane);
   float* mbuf = (float*)&sm.tile[0][0][0] + (size_t)grp * 2 * STATE * kWave;
-  // Staging: the super-tiles of this workgroup's key range stream from global memory straight into LDS, all waves
-  // sharing the instructions; the buffer descriptors cover exactly the rows of the range, so rows past its end read as
-  // zeros (no clamping code, finite data for the masked tail).  Super-tile it+1 is in flight while super-tile it is used.
-  TileStager<D, 4 * C, kDsSuper> stager;
+  // Staging: the 64-key tiles of this workgroup's key range stream from global memory straight into a ring of LDS
+  // buffers, all waves sharing the instructions; the buffer descriptors cover exactly the rows of the range, so rows
+  // past its end read as zeros (no clamping code, finite data for the masked tail).  Three tiles are on their way while
+  // one is used: the stream is bound by memory latency times bytes in flight, so the kernel keeps as much of its LDS
+  // in flight as it can and consumes in small pieces.
+  using Stager = TileStager<D, 4 * C, kTileKeys>;
+  constexpr int LPT = 2 * Stager::NI;  // loads per wave and tile (K and V)
+  Stager stager;
   stager.init(Kg + j_begin * kv_stride, Vg + j_begin * kv_stride, n_keys, p.hkv, wave, lane);
   const unsigned lds_tiles = (unsigned)(size_t)(lds_void_ptr)&sm.tile[0][0][0];
-  auto issue_super = [&](int it) {
-    const unsigned at = lds_tiles + (unsigned)((it & 1) * 2 * kDsSuper * D * 2);
-    stager.issue(stager.k_rsrc, at, it);
-    stager.issue(stager.v_rsrc, at + (unsigned)(kDsSuper * D * 2), it);
+  auto issue_tile = [&](int t) {
+    const unsigned at = lds_tiles + (unsigned)((t % kDsRing) * 2 * kTileKeys * D * 2);
+    stager.issue(stager.k_rsrc, at, t);
+    stager.issue(stager.v_rsrc, at + (unsigned)(kTileKeys * D * 2), t);
   };
-  // the first super-tile is requested before anything else: it flies while the stream list is built, the generated
-  // rows are handled and the queries are rotated
-  if (n_super > 0) issue_super(0);
+  auto issue_first_tiles = [&]() {
+#pragma unroll
+    for (int t = 0; t < kDsRing - 1; ++t)
+      if (t < n_tiles) issue_tile(t);
+  };
+  // the first tiles are requested before anything else: they fly while the stream list is built, the generated rows
+  // are handled and the queries are rotated
+  issue_first_tiles();
 
   // ---- streams (beams) of this sequence, ascending ----
   if (wave == 0) {
@@ -476,13 +511,21 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       if (lane == 0) sm.streams[0] = s;
       count = 1;
     } else {
-      for (int base = 0; base < p.n_streams; base += kWave) {
-        const int u = base + lane;
-        const bool hit = u < p.n_streams && p.stream_to_seq[u] == s;
-        const unsigned long long mask = __ballot(hit);
-        const int idx = count + __popcll(mask & ((1ull << lane) - 1ull));
-        if (hit && idx < kMaxStreamsPerSeq) sm.streams[idx] = u;
-        count += __popcll(mask);
+      for (int base = 0; base < p.n_streams; base += 4 * kWave) {
+        int seq_of[4];  // four chunks of the list are requested together: one memory round trip, not four
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4) {
+          const int u = base + k4 * kWave + lane;
+          seq_of[k4] = u < p.n_streams ? p.stream_to_seq[u] : -1;
+        }
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4) {
+          const bool hit = seq_of[k4] == s;
+          const unsigned long long mask = __ballot(hit);
+          const int idx = count + __popcll(mask & ((1ull << lane) - 1ull));
+          if (hit && idx < kMaxStreamsPerSeq) sm.streams[idx] = base + k4 * kWave + lane;
+          count += __popcll(mask);
+        }
       }
       if (count > kMaxStreamsPerSeq) count = kMaxStreamsPerSeq;
     }
@@ -490,6 +533,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   }
   __syncthreads();
   const int M = sm.n_streams_of_seq * gq;  // query rows sharing this cache
+  DS_STAMP(ds_t1);
 
   // ---- generated rows and the new token of this sequence's streams (they differ per beam: vector ALU, one wave per
   // stream).  The streams are dealt out over the key splits so every workgroup gets an equal share, and the work runs
@@ -497,6 +541,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   for (int i = z + p.n_splits * wave; i < sm.n_streams_of_seq; i += p.n_splits * 4 * C)
     decode_rows<__bf16, D, GQ, 1>(p, c, sm.streams[i], 0, 0, lane, true, 1 << 30, nullptr);
 
+  DS_STAMP(ds_t2);
   for (int row0 = 0; row0 < M; row0 += ROWS) {
     // ---- Q fragments of this group's rows: row m -> (stream list[m / gq], head c*gq + m % gq) ----
     const bool grp_active = row0 + 32 * grp < M;
@@ -533,24 +578,28 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       }
     }
 
-    f32x16 o[DB];
+    f32x16 o[DBH];  // d blocks dh * DBH + (0 .. DBH-1)
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DBH; ++db)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
     float mrow = -INFINITY, lrow = 0.f;
 
-    // S^T = K Q^T of this wave's sub-tile; keys past the range end get zero weight
+    // S^T = K Q^T of this wave's sub-tile (the two waves that share a sub-tile both compute it: the matrix core has
+    // time to spare here, LDS space has not); keys past the range end get zero weight
     auto scores = [&](int it, f32x16& sc) {
-      const __bf16* my_k = sm.tile[it & 1][0] + sub * kDsTile * D;
+      const __bf16* my_k = sm.tile[it % kDsRing][0] + ksub * kDsTile * D;
 #pragma unroll
       for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+      // all K fragments of the sub-tile are requested before the first MFMA: the products form one dependent chain, and
+      // a read per step would put the LDS latency into every link
+      bf16x8 kf[KSTEPS];
 #pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) {
-        const bf16x8 kf = *(const bf16x8*)(my_k + fo.k(ks));
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sc, 0, 0, 0);
-      }
-      const int key0 = j_begin + it * kDsSuper + sub * kDsTile;
+      for (int ks = 0; ks < KSTEPS; ++ks) kf[ks] = *(const bf16x8*)(my_k + fo.k(ks));
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sc, 0, 0, 0);
+      const int key0 = j_begin + it * kTileKeys + ksub * kDsTile;
       if (key0 + kDsTile > j_end) {
 #pragma unroll
         for (int i = 0; i < 16; ++i)
@@ -566,8 +615,16 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         lsum += e;
       }
     };
-    auto accumulate = [&](int it, f32x16& sc, float lsum) {
-      const __bf16* my_v = sm.tile[it & 1][1] + sub * kDsTile * D;
+    // V^T fragments of this wave's sub-tile and half of the head dimension, requested ahead of the exponentials
+    auto fetch_v = [&](int it, bf16x8 (&vf)[2][DBH]) {
+      const __bf16* my_v = sm.tile[it % kDsRing][1] + ksub * kDsTile * D;
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int db = 0; db < DBH; ++db) vf[kk][db] = read_v_fragment<D>(my_v, fo, dh * DBH + db, kk);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    auto accumulate = [&](f32x16& sc, float lsum, const bf16x8 (&vf)[2][DBH]) {
       bf16x8 pf[2];
       lrow += lsum;
 #pragma unroll
@@ -580,49 +637,64 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_v_fragment<D>(my_v, fo, db, kk), pf[kk], o[db], 0, 0, 0);
-        }
+        for (int db = 0; db < DBH; ++db)
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[kk], o[db], 0, 0, 0);
     };
     // does this wave have keys in super-tile `it`?
     auto has_keys = [&](int it) {
 #if defined(EARN_DBG_DEC_NOCOMPUTE)
       return false;
 #endif
-      return grp_active && it * kDsSuper + sub * kDsTile < n_keys;
+      return grp_active && it * kTileKeys + ksub * kDsTile < n_keys;
     };
 
-    // Every super-tile iteration ends in exactly one barrier, whichever path a wave takes.  The steady-state loop
-    // takes exponentials against the reference maximum it has and never touches the output accumulators with the
-    // vector ALU; a reference is stale exactly when some exponential is large, which shows in the partial row sums
+    // Every tile iteration opens with exactly one barrier, whichever path a wave takes.  The steady-state loop takes
+    // exponentials against the reference maximum it has and never touches the output accumulators with the vector
+    // ALU; a reference is stale exactly when some exponential is large, which shows in the partial row sums
     // (+inf / NaN on the first tile, whose reference is -inf).  A wave that sees a stale reference leaves the loop,
     // takes the exact maxima of the tile, rescales, finishes the tile and re-enters.
-    if (row0 > 0 && n_super > 0) issue_super(0);  // further passes over the same keys for more query rows
-    // Iteration `it` opens with the barrier behind which super-tile `it` is complete (every wave has waited for its own
-    // loads) and nobody reads super-tile it-1 any more, whose buffer the loads of super-tile it+1 then start to fill.
+    if (row0 > 0) issue_first_tiles();  // further passes over the same keys for more query rows
+    // Iteration `it` opens with the barrier behind which tile `it` is complete (every wave has waited for its own part:
+    // loads complete in order, so that means at most the younger tiles' loads are still in flight) and nobody reads
+    // tile it-1 any more, whose ring slot the loads of tile it+3 then start to fill.
     auto sync_and_stage = [&](int it) {
-      drain_loads_and_barrier();
-      if (it + 1 < n_super) issue_super(it + 1);
+      DS_STAMP(ds_a);
+      const int younger = min(n_tiles - 1 - it, kDsRing - 2);  // tiles issued after tile `it`
+      if (younger >= 2) wait_vmcnt<2 * LPT>();
+      else if (younger == 1) wait_vmcnt<LPT>();
+      else wait_vmcnt<0>();
+      DS_STAMP(ds_b);
+      lds_barrier();
+      DS_STAMP(ds_c);
+#if defined(EARN_DBG_PHASES)
+      ds_wait += ds_b - ds_a; ds_bar += ds_c - ds_b;
+#endif
+      if (it + kDsRing - 1 < n_tiles) issue_tile(it + kDsRing - 1);
     };
+    DS_STAMP(ds_t3);
     int it = 0;
-    while (it < n_super) {
+    while (it < n_tiles) {
       bool rescale = false;
-      for (; it < n_super; ++it) {
+      for (; it < n_tiles; ++it) {
         sync_and_stage(it);
         if (has_keys(it)) {
           f32x16 sc;
           float lsum;
+          bf16x8 vf[2][DBH];
           scores(it, sc);
+          fetch_v(it, vf);
           exponentials(sc, lsum);
           if (__any(!(lsum <= kDecSumLimit))) { rescale = true; break; }
-          accumulate(it, sc, lsum);
+          accumulate(sc, lsum, vf);
         }
       }
       if (!rescale) break;
       {
         f32x16 sc;
         float lsum;
+        bf16x8 vf[2][DBH];
         scores(it, sc);  // the tile is still staged
+        fetch_v(it, vf);
         float m = sc[0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) m = fmaxf(m, sc[i]);
@@ -632,24 +704,26 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         mrow = mnew;
         lrow *= alpha;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DBH; ++db)
 #pragma unroll
           for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
         exponentials(sc, lsum);
-        accumulate(it, sc, lsum);
+        accumulate(sc, lsum, vf);
         ++it;
       }
     }
+    DS_STAMP(ds_t4);
     __syncthreads();  // every wave is done with the tiles: their memory becomes the merge buffers
 
-    // ---- merge the 4 waves of the group: (2,3) -> (0,1), then 1 -> 0; lane-wise, the layouts are identical ----
+    // ---- merge the two key sub-tiles of each half of the head dimension: wave (ksub 1, dh) -> wave (ksub 0, dh);
+    // lane-wise, the layouts are identical ----
     auto put = [&](int slot) {
       float* dst = mbuf + (size_t)slot * STATE * kWave + lane;
       int r = 0;
       dst[(r++) * kWave] = mrow;
       dst[(r++) * kWave] = lrow;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DBH; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) dst[(r++) * kWave] = o[db][i];
     };
@@ -663,37 +737,49 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       lrow = lrow * a + l2 * b;
       mrow = mn;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DBH; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[db][i] = o[db][i] * a + src[(r++) * kWave] * b;
     };
-    if (sub >= 2) put(sub - 2);
+    if (ksub == 1) put(dh);
     __syncthreads();
-    if (sub < 2) take(sub);
-    __syncthreads();
-    if (sub == 1) put(0);
-    __syncthreads();
-    if (sub == 0) {
-      take(0);
-      // ---- partial results of this key range: unnormalised O, running max and sum (base-2 units) ----
+    if (ksub == 0) {
+      take(dh);
+      // ---- partial results of this key range: unnormalised O (this wave's half of the head dimension), running max
+      // and sum (base-2 units; both halves hold the same ones) ----
       const float ltot = lrow + __shfl_xor(lrow, 32, kWave);
       const int m = row0 + 32 * grp + r32;
       if (m < M) {
         const long long slot = ((long long)row_u * p.hq + row_a) * p.n_slots + z;
-        float* po = p.part_o + slot * D + 4 * hf;
+        float* po = p.part_o + slot * D + dh * (D / 2) + 4 * hf;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DBH; ++db)
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             f32x4 w = {o[db][4 * j], o[db][4 * j + 1], o[db][4 * j + 2], o[db][4 * j + 3]};
             *(f32x4*)(po + 32 * db + 8 * j) = w;
           }
-        if (hf == 0) { p.part_ml[slot * 2] = mrow; p.part_ml[slot * 2 + 1] = ltot; }
+        if (hf == 0 && dh == 0) { p.part_ml[slot * 2] = mrow; p.part_ml[slot * 2 + 1] = ltot; }
       }
     }
     __syncthreads();  // the merge buffers are tile memory again in the next row chunk
   }
+#if defined(EARN_DBG_PHASES)
+  {
+    long long ds_t5; DS_STAMP(ds_t5);
+    if (lane == 0 && blockIdx.x < 256) {
+      float* d = g_dec_dbg + (blockIdx.x * 8 + (wave & 7)) * 16;
+      d[0] = (float)(ds_t1 - ds_t0); d[1] = (float)(ds_t2 - ds_t1); d[2] = (float)(ds_t3 - ds_t2); d[3] = (float)(ds_t4 - ds_t3);
+      d[4] = (float)(ds_t5 - ds_t4); d[5] = (float)ds_wait; d[6] = (float)ds_bar; d[7] = (float)n_tiles; d[8] = (float)(ds_t5 - ds_t0);
+    }
+  }
+#endif
 }
+#if defined(EARN_DBG_PHASES)
+extern "C" int earn_debug_read(float* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dec_dbg), n * sizeof(float));
+}
+#endif
 
 // ------------------------------------------------------------------------------------------------------------------
 // host side
@@ -783,7 +869,7 @@ static void launch_decode_t(DecodeParams& p, const DecodePlan& pl, int gq, hipSt
     return;
   }
   if constexpr (sizeof(T) == 2) {
-    dim3 grid(p.hkv, p.batch, p.n_splits);
+    dim3 grid((unsigned)(((long long)p.batch * p.n_splits + 7) / 8 * 8 * p.hkv), 1, 1);
     // one 32-row group is enough when a cache serves at most 32 query rows; with beams the host only has an upper bound
     const bool one_group = (long long)gq * (p.n_streams - p.batch + 1) <= 32;
     if (one_group) {

@@ -44,6 +44,12 @@ __device__ __forceinline__ u32x4 raw_buffer(const void* base, int bytes) {
   r[3] = 0x00020000u;
   return r;
 }
+// wait until at most N of this wave's vector-memory loads are in flight (they complete in order)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 // wait until none of this wave's vector-memory loads is in flight, then meet the workgroup
 __device__ __forceinline__ void drain_loads_and_barrier() {
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
