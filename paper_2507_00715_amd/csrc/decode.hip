@@ -114,13 +114,6 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
                                             float* sm_base) {
   constexpr int LPK = D / 8;         // lanes per key row
   constexpr int KPW = kWave / LPK;   // key rows per wave instruction
-#if defined(EARN_DBG_PHASES)
-  long long stamp[6];
-#define DEC_STAMP(i) { __builtin_amdgcn_sched_barrier(0); stamp[i] = (long long)__builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); }
-#else
-#define DEC_STAMP(i)
-#endif
-  DEC_STAMP(0);
   const int gq = p.hq / p.hkv;       // query heads per kv head
   const int sub = lane % LPK, kk = lane / LPK;
   const int s = p.stream_to_seq ? p.stream_to_seq[u] : u;
@@ -209,7 +202,6 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
 #pragma unroll
   for (int i = 0; i < 8; ++i) kn[i] = Row8<T>::round(kn[i]);
 
-  DEC_STAMP(1);
   // cache append (Eq. 4): done by the one workgroup whose key range holds the new token
   if (m_total - 1 >= j_begin && m_total - 1 < j_end && wave == 0 && kk == 0) {
     Row8<T>::store(Gk + (long long)g * row_stride, kn);
@@ -280,7 +272,6 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
     }
   }
 
-  DEC_STAMP(2);
   // merge the KPW lane groups of the wave (lanes with equal `sub`)
 #pragma unroll
   for (int a = 0; a < GQ; ++a) {
@@ -308,7 +299,6 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
       if (sb == 0) { p.part_ml[slot * 2] = m; p.part_ml[slot * 2 + 1] = l; }
     }
   };
-  DEC_STAMP(3);
   if constexpr (WAVES == 1) {
     if (kk == 0) {
 #pragma unroll
@@ -341,15 +331,6 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
       finish(a, sb, m, l, oo);
     }
   }
-#if defined(EARN_DBG_PHASES)
-  DEC_STAMP(4);
-  if (wave == 0 && lane == 0 && p.part_o) {
-    float* dbg = p.part_o + ((long long)u * p.hkv + c) * 8;
-    for (int i = 0; i < 4; ++i) dbg[i] = (float)(stamp[i + 1] - stamp[i]);
-    dbg[4] = (float)(stamp[0] & 0xffffff);  // start time, low bits
-    dbg[5] = (float)(stamp[4] & 0xffffff);
-  }
-#endif
 }
 
 template <typename T, int D, int GQ, int WAVES>
@@ -394,11 +375,14 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const float* __rest
 //
 // A workgroup has C groups of 4 waves; group g serves query rows [32g, 32g+32) of the cache (C = 2 covers the 40 rows of
 // 4 grouped heads x 10 beams) at <= 256 registers per wave, i.e. two waves per SIMD.  The workgroup walks its key range
-// in super-tiles of 128 keys that ALL its threads stage together (global -> registers -> LDS, double buffered, the
-// next-but-one super-tile in flight), so every K/V byte is fetched once; wave `sub` of each group works on the 32-key
-// sub-tile `sub` with a private softmax state, and the 4 states of a group are merged through LDS at the end.
-// Key ranges of long caches are split over workgroups; every (row, split) partial goes to the workspace.  The
-// per-stream generated rows and the new token differ per beam and are handled by decode_kernel in gen_only mode.
+// in tiles of 64 keys that stream from global memory straight into a ring of four LDS buffers (three tiles on their
+// way while one is used), so every K/V byte is fetched once.  Wave (ksub, dh) of a group works on the 32-key sub-tile
+// ksub of the tile and accumulates half dh of the head dimension (both waves of a sub-tile compute its scores: the
+// matrix core has time to spare here, LDS space has not) with a private softmax state; the states of the two
+// sub-tiles are merged through LDS at the end.
+// Key ranges of long caches are split over workgroups; every (row, split) partial goes to the workspace and
+// decode_combine_kernel merges them.  The per-stream generated rows and the new token differ per beam: the waves handle
+// them with the vector code above while the first tiles are on their way.
 // ------------------------------------------------------------------------------------------------------------------
 constexpr int kDsTile = 32;              // keys per wave sub-tile
 constexpr int kDsGroupWaves = 4;         // waves per 32-row group: 2 key sub-tiles x 2 halves of the head dimension
@@ -406,6 +390,7 @@ constexpr int kDsRing = 4;               // K/V tiles (kTileKeys = 64 keys each)
 constexpr int kDsSuper = 128;            // key ranges of the splits are multiples of this
 constexpr float kDecSumLimit = 512.0f;   // per lane: 16 exponentials of one query row
 constexpr int kMaxStreamsPerSeq = 1024;  // beams of one sequence the stream list holds
+constexpr int kDsTabStreams = 16;        // streams whose rotary factors are tabulated in LDS
 
 // Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS traffic, not for its global loads.
 // (__syncthreads() also drains the vector-memory queue, which would cut the depth of the K/V stream below to the one
@@ -425,18 +410,13 @@ struct DsSmem {
   __bf16 tile[kDsRing][2][kTileKeys * D];
   int streams[kMaxStreamsPerSeq];
   int n_streams_of_seq;
+  // (cos, sin) of the rotary angles of the first kDsTabStreams streams of the list, [stream][d/2]: computed once by
+  // the workgroup instead of once per query row (the gq heads of a stream share them)
+  f32x2 cs[kDsTabStreams][D / 2];
 };
 
-#if defined(EARN_DBG_PHASES)
-__device__ float g_dec_dbg[256 * 8 * 16];
-#define DS_STAMP(x) { __builtin_amdgcn_sched_barrier(0); x = (long long)__builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); }
-#else
-#define DS_STAMP(x)
-#endif
 template <int D, int C, int GQ>
 __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodeParams p) {
-  [[maybe_unused]] long long ds_t0, ds_t1, ds_t2, ds_t3, ds_t4, ds_a, ds_b, ds_c, ds_wait = 0, ds_bar = 0, ds_comp = 0;
-  DS_STAMP(ds_t0);
   constexpr int KSTEPS = D / 16, DB = D / 32;
   constexpr int ROWS = 32 * C;
   constexpr int DBH = DB / 2;                      // d blocks per wave: each wave accumulates half of the head dimension
@@ -452,12 +432,8 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   {
     const int n_sz = p.batch * p.n_splits, n_sz8 = (n_sz + 7) / 8 * 8;
     const int L = blockIdx.x;
-#if defined(EARN_DBG_DEC_OLDMAP)
-    c = L % p.hkv; const int sz = L / p.hkv;
-#else
     const int sz = (L / (8 * p.hkv)) * 8 + L % 8;
     c = (L / 8) % p.hkv;
-#endif
     if (sz >= n_sz || L >= n_sz8 * p.hkv) return;
     s = sz % p.batch; z = sz / p.batch;
   }
@@ -533,7 +509,17 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   }
   __syncthreads();
   const int M = sm.n_streams_of_seq * gq;  // query rows sharing this cache
-  DS_STAMP(ds_t1);
+  // rotary factors of the tabulated streams, one (stream, pair) per thread and pass; read after the barrier that
+  // follows the generated rows' part
+  if (p.rope.enabled) {
+    const int n_tab = min(sm.n_streams_of_seq, kDsTabStreams);
+    for (int i = threadIdx.x; i < n_tab * (D / 2); i += 256 * C) {
+      const int e = i % (D / 2);
+      float sn, cs;
+      sincos_turns_fast(rope_turns((float)p.q_pos[sm.streams[i / (D / 2)]], p.rope.hi[e], p.rope.lo[e]), &sn, &cs);
+      sm.cs[i / (D / 2)][e] = f32x2{cs, sn};
+    }
+  }
 
   // ---- generated rows and the new token of this sequence's streams (they differ per beam: vector ALU, one wave per
   // stream).  The streams are dealt out over the key splits so every workgroup gets an equal share, and the work runs
@@ -541,7 +527,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   for (int i = z + p.n_splits * wave; i < sm.n_streams_of_seq; i += p.n_splits * 4 * C)
     decode_rows<__bf16, D, GQ, 1>(p, c, sm.streams[i], 0, 0, lane, true, 1 << 30, nullptr);
 
-  DS_STAMP(ds_t2);
+  __syncthreads();  // the table of rotary factors is complete
   for (int row0 = 0; row0 < M; row0 += ROWS) {
     // ---- Q fragments of this group's rows: row m -> (stream list[m / gq], head c*gq + m % gq) ----
     const bool grp_active = row0 + 32 * grp < M;
@@ -566,7 +552,10 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
           for (int jj = 0; jj < 2; ++jj) {
             float sn = 0.f, cs = 1.f;
             const int e = 16 * ks + 8 * hf + j + jj;
-            if (p.rope.enabled) sincos_turns_fast(rope_turns(pos, p.rope.hi[e], p.rope.lo[e]), &sn, &cs);
+            if (p.rope.enabled) {
+              if (m / gq < kDsTabStreams) { const f32x2 t = sm.cs[m / gq][e]; cs = t[0]; sn = t[1]; }
+              else sincos_turns_fast(rope_turns(pos, p.rope.hi[e], p.rope.lo[e]), &sn, &cs);
+            }
             x[jj] = (lo[j + jj] * cs - hi[j + jj] * sn) * p.scale_log2;
             y[jj] = (hi[j + jj] * cs + lo[j + jj] * sn) * p.scale_log2;
           }
@@ -642,9 +631,6 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     };
     // does this wave have keys in super-tile `it`?
     auto has_keys = [&](int it) {
-#if defined(EARN_DBG_DEC_NOCOMPUTE)
-      return false;
-#endif
       return grp_active && it * kTileKeys + ksub * kDsTile < n_keys;
     };
 
@@ -658,20 +644,13 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     // loads complete in order, so that means at most the younger tiles' loads are still in flight) and nobody reads
     // tile it-1 any more, whose ring slot the loads of tile it+3 then start to fill.
     auto sync_and_stage = [&](int it) {
-      DS_STAMP(ds_a);
       const int younger = min(n_tiles - 1 - it, kDsRing - 2);  // tiles issued after tile `it`
       if (younger >= 2) wait_vmcnt<2 * LPT>();
       else if (younger == 1) wait_vmcnt<LPT>();
       else wait_vmcnt<0>();
-      DS_STAMP(ds_b);
       lds_barrier();
-      DS_STAMP(ds_c);
-#if defined(EARN_DBG_PHASES)
-      ds_wait += ds_b - ds_a; ds_bar += ds_c - ds_b;
-#endif
       if (it + kDsRing - 1 < n_tiles) issue_tile(it + kDsRing - 1);
     };
-    DS_STAMP(ds_t3);
     int it = 0;
     while (it < n_tiles) {
       bool rescale = false;
@@ -712,7 +691,6 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         ++it;
       }
     }
-    DS_STAMP(ds_t4);
     __syncthreads();  // every wave is done with the tiles: their memory becomes the merge buffers
 
     // ---- merge the two key sub-tiles of each half of the head dimension: wave (ksub 1, dh) -> wave (ksub 0, dh);
@@ -764,22 +742,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     }
     __syncthreads();  // the merge buffers are tile memory again in the next row chunk
   }
-#if defined(EARN_DBG_PHASES)
-  {
-    long long ds_t5; DS_STAMP(ds_t5);
-    if (lane == 0 && blockIdx.x < 256) {
-      float* d = g_dec_dbg + (blockIdx.x * 8 + (wave & 7)) * 16;
-      d[0] = (float)(ds_t1 - ds_t0); d[1] = (float)(ds_t2 - ds_t1); d[2] = (float)(ds_t3 - ds_t2); d[3] = (float)(ds_t4 - ds_t3);
-      d[4] = (float)(ds_t5 - ds_t4); d[5] = (float)ds_wait; d[6] = (float)ds_bar; d[7] = (float)n_tiles; d[8] = (float)(ds_t5 - ds_t0);
-    }
-  }
-#endif
 }
-#if defined(EARN_DBG_PHASES)
-extern "C" int earn_debug_read(float* host, int n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dec_dbg), n * sizeof(float));
-}
-#endif
 
 // ------------------------------------------------------------------------------------------------------------------
 // host side
