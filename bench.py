@@ -32,9 +32,9 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3     # fp32 vector
 PEAK_HBM_GBPS = 8000.0      # HBM3E
 HEADLINE = "long_beam"
-# HBM bytes per launch of the dominant kernel (full-length prefill layer), from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+# HBM bytes per full-length prefill layer (K rotation + attention kernel), from the rocprofv3 FETCH_SIZE / WRITE_SIZE
 # runs summarised in profiles/long_beam_hbm_traffic.txt (counters scaled by a 1 GiB copy: x2.0 and x1.0).
-MEASURED_TRAFFIC = {"long_beam": {"fetch_bytes": 2.570e9, "write_bytes": 1.082e9}}
+MEASURED_TRAFFIC = {"long_beam": {"fetch_bytes": 3.537e9, "write_bytes": 1.422e9}}
 DOMINANT_KERNEL = "prefill_pipe_kernel + rope_k_kernel (one full-length causal layer)"
 
 
@@ -84,10 +84,10 @@ def algorithmic_counts(w: W.Workload):
 
 
 def algorithmic_prefill_bytes(name: str) -> float:
-    """Q, K, V read once and O written once for one full-length layer."""
+    """Q, K, V read once, O and the rotated K (the layer's key cache) written once, for one full-length layer."""
     c = W.CONFIGS[name]
     w = W.Workload(c)
-    return float(w.total_tokens * c.head_dim * c.elem_bytes * (2 * c.n_q_heads + 2 * c.n_kv_heads))
+    return float(w.total_tokens * c.head_dim * c.elem_bytes * (2 * c.n_q_heads + 3 * c.n_kv_heads))
 
 
 def build_inputs(w: W.Workload, dev):
