@@ -1,0 +1,80 @@
+"""Parity of the long-sequence (software-pipelined) prefill kernel on a RAGGED batch: the longest sequence is past the
+length at which earn_prefill_attn switches to 256-row workgroups, the others end inside a workgroup, inside a wave's
+32 rows, inside a 64-key tile, or are shorter than one tile.  A few key rows are scaled up (outliers), so the running
+softmax reference jumps and the exact-recompute path of the kernel runs too.
+
+Attention outputs are checked against the fp64 oracle on sampled rows (every row of the short sequences); inputs are
+drawn on the GPU and again on the CPU from the same counter-based generator.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import earn_oracle as O
+from paper_2507_00715_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+BF16_REL = 2e-2
+# n_s = r + L_s with r = 16: 17, 64, 65, 300, 3100, 4100 tokens
+HISTORY = (1, 48, 49, 284, 3084, 4084)
+
+
+def _B():
+    from paper_2507_00715_amd import binding
+    binding.lib()
+    return binding
+
+
+def rel_fro(got, ref):
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30))
+
+
+@pytest.mark.parametrize("head_dim", [128, 64])
+def test_pipelined_prefill_ragged_batch_with_outliers(head_dim):
+    B = _B()
+    cfg = W.CONFIGS["mid_mha"].replace(name="ragged_long", config_id=41, batch=len(HISTORY), len_dist=("list", HISTORY),
+                                       n_head_reg=8, n_tail_reg=8, n_q_heads=4, n_kv_heads=2, head_dim=head_dim,
+                                       outlier_prob=0.05, outlier_scale=8.0)
+    w = W.Workload(cfg)
+    assert w.max_seqlen > 3072  # the pipelined kernel's range
+    coords = w.token_coords(DEV)
+    q, k, v = (w.prefill_tensor(t, 0, coords=coords) for t in "qkv")
+    out = torch.full_like(q, float("nan"))
+    krot = torch.empty_like(k)
+    lse = torch.empty(w.total_tokens, cfg.n_q_heads, dtype=torch.float32, device=DEV)
+    cu = torch.tensor(w.cu_seqlens, dtype=torch.int32, device=DEV)
+    desc = B.make_desc(cfg.torch_dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, 0.0, cfg.rope_base)
+    B.earn_prefill_attn(desc, q, k, v, cu, None, cfg.batch, w.total_tokens, w.max_seqlen, out, krot, lse, None)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+
+    rng = np.random.default_rng(7)
+    gq = cfg.n_q_heads // cfg.n_kv_heads
+    heads = list(range(cfg.n_q_heads))
+    for s, n in enumerate(w.seq_lengths):
+        b0 = w.cu_seqlens[s]
+        qc = W.to_f64(w.prefill_tensor("q", 0, seqs=[s]))
+        kc = W.to_f64(w.prefill_tensor("k", 0, seqs=[s]))
+        vc = W.to_f64(w.prefill_tensor("v", 0, seqs=[s]))
+        if n <= 300:
+            rows = list(range(n))
+        else:  # rows around wave (32), tile (64) and workgroup (256) boundaries, the ends, and random rows
+            rows = set(range(16)) | set(range(n - 16, n))
+            for b in (32, 64, 256):
+                for edge in range(b, n, b * 5):
+                    rows.update(r for r in (edge - 1, edge, edge + 1) if r < n)
+            rows.update(int(x) for x in rng.integers(0, n, size=48))
+            rows = sorted(rows)
+        sel = np.zeros(n, dtype=np.uint8)
+        sel[rows] = 1
+        ref = O.prefill_attn(qc, kc, vc, [0, n], q_to_kv=[a // gq for a in heads], rope_base=cfg.rope_base, row_sel=sel)
+        got = out[b0:b0 + n][rows].cpu().double().numpy()
+        err = rel_fro(got, ref["out"][rows])
+        assert err <= BF16_REL, f"d={head_dim} seq {s} (n={n}): rel-Frobenius {err:.3e} on {len(rows)} rows"
+        # row by row as well: a wrong tile shows in single rows long before it moves the norm of the whole sample
+        row_err = np.linalg.norm(got - ref["out"][rows], axis=(1, 2)) / np.maximum(np.linalg.norm(ref["out"][rows], axis=(1, 2)), 1e-30)
+        assert row_err.max() <= 3 * BF16_REL, f"d={head_dim} seq {s}: row {rows[int(row_err.argmax())]} off by {row_err.max():.3e}"
+        got_lse = lse[b0:b0 + n][rows].cpu().double().numpy()
+        assert (np.abs(got_lse - ref["lse"][rows]) <= 5e-2 + 1e-2 * np.abs(ref["lse"][rows])).all()
+        assert rel_fro(krot[b0:b0 + n].cpu().double().numpy(), ref["k_rot"]) <= BF16_REL
