@@ -11,6 +11,9 @@ struct CompactArgs {
   const u32x4* src[EARN_MAX_COMPACT_TENSORS];
   u32x4* dst[EARN_MAX_COMPACT_TENSORS];
   unsigned int units_per_row[EARN_MAX_COMPACT_TENSORS];  // row_bytes / 16
+  // first workgroup of every tensor in the one-dimensional grid (tensors differ in size: a grid row per tensor would
+  // launch, for the small ones, mostly workgroups with nothing to do); [n_tensors] = first workgroup of the index part
+  unsigned int first_block[EARN_MAX_COMPACT_TENSORS + 1];
 };
 
 constexpr int kCompactThreads = 256;
@@ -31,16 +34,27 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactArgs ar
                                                                   int32_t* __restrict__ pos_out,
                                                                   int32_t* __restrict__ cu_out, int n_tensors) {
   const int r = h + t;
-  const int tensor = blockIdx.y;
-  if (tensor == n_tensors) {  // the extra grid row writes the index outputs
-    for (int m = blockIdx.x * kCompactThreads + threadIdx.x; m < rows_out; m += gridDim.x * kCompactThreads) {
+  // tensor of this workgroup: the last one whose first workgroup is not beyond it (uniform binary search)
+  int tensor = 0;
+  {
+    int lo = 0, hi = n_tensors + 1;  // answer in [lo, hi)
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (args.first_block[mid] <= blockIdx.x) lo = mid; else hi = mid;
+    }
+    tensor = lo;
+  }
+  const unsigned int block_in_tensor = blockIdx.x - args.first_block[tensor];
+  if (tensor == n_tensors) {  // the workgroups behind the last tensor write the index outputs
+    const unsigned int n_blocks = gridDim.x - args.first_block[n_tensors];
+    for (int m = block_in_tensor * kCompactThreads + threadIdx.x; m < rows_out; m += n_blocks * kCompactThreads) {
       int pos;
       int idx = source_row(cu, m, r, h, t, &pos);
       if (idx_out) idx_out[m] = idx;
       if (pos_out) pos_out[m] = pos;
     }
     if (cu_out)
-      for (int s = blockIdx.x * kCompactThreads + threadIdx.x; s <= batch; s += gridDim.x * kCompactThreads)
+      for (int s = block_in_tensor * kCompactThreads + threadIdx.x; s <= batch; s += n_blocks * kCompactThreads)
         cu_out[s] = s * r;
     return;
   }
@@ -48,8 +62,8 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactArgs ar
   u32x4* __restrict__ dst = args.dst[tensor];
   const unsigned int upr = args.units_per_row[tensor];
   const long long total_units = (long long)rows_out * upr;
-  const long long stride = (long long)gridDim.x * kCompactThreads * kCompactUnroll;
-  for (long long base = (long long)blockIdx.x * kCompactThreads * kCompactUnroll; base < total_units; base += stride) {
+  const long long stride = (long long)(args.first_block[tensor + 1] - args.first_block[tensor]) * kCompactThreads * kCompactUnroll;
+  for (long long base = (long long)block_in_tensor * kCompactThreads * kCompactUnroll; base < total_units; base += stride) {
     u32x4 v[kCompactUnroll];
     long long u[kCompactUnroll];
 #pragma unroll
@@ -74,19 +88,24 @@ int launch_compact(int n_tensors, const void* const* src, void* const* dst, cons
                    int32_t* cu_out, hipStream_t stream) {
   CompactArgs args;
   const long long rows_out = (long long)batch * (h + t);
-  long long max_units = 0;
+  const long long per_block = (long long)kCompactThreads * kCompactUnroll;
+  unsigned int blocks = 0;
   for (int i = 0; i < n_tensors; ++i) {
     args.src[i] = (const u32x4*)src[i];
     args.dst[i] = (u32x4*)dst[i];
     args.units_per_row[i] = (unsigned int)(row_bytes[i] / 16);
-    long long units = rows_out * (row_bytes[i] / 16);
-    if (units > max_units) max_units = units;
+    const long long units = rows_out * (row_bytes[i] / 16);
+    long long gx = (units + per_block - 1) / per_block;
+    if (gx < 1) gx = 1;
+    if (gx > 8192) gx = 8192;  // grid-stride beyond this: 32 workgroups per CU
+    args.first_block[i] = blocks;
+    blocks += (unsigned int)gx;
   }
-  const long long per_block = (long long)kCompactThreads * kCompactUnroll;
-  long long gx = (max_units + per_block - 1) / per_block;
-  if (gx < 1) gx = 1;
-  if (gx > 8192) gx = 8192;  // grid-stride beyond this: 32 workgroups per CU
-  dim3 grid((unsigned)gx, (unsigned)(n_tensors + 1), 1);
+  args.first_block[n_tensors] = blocks;
+  long long gi = (rows_out + kCompactThreads - 1) / kCompactThreads;  // index outputs
+  if (gi < 1) gi = 1;
+  if (gi > 256) gi = 256;
+  dim3 grid(blocks + (unsigned)gi, 1, 1);
   hipLaunchKernelGGL(compact_kernel, grid, dim3(kCompactThreads), 0, stream, args, cu_seqlens, batch, h, t,
                      (int)rows_out, idx_out, pos_out, cu_out, n_tensors);
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
