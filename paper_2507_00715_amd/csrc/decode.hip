@@ -12,6 +12,8 @@
 //     the workspace and a second kernel merges them.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "common.h"
 #include "mfma_tiles.h"
 
@@ -523,7 +525,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 
   // ---- generated rows and the new token of this sequence's streams (they differ per beam: vector ALU, one wave per
   // stream).  The streams are dealt out over the key splits so every workgroup gets an equal share, and the work runs
-  // while the first super-tiles are still on their way from HBM. ----
+  // while the first tiles are still on their way from HBM. ----
   for (int i = z + p.n_splits * wave; i < sm.n_streams_of_seq; i += p.n_splits * 4 * C)
     decode_rows<__bf16, D, GQ, 1>(p, c, sm.streams[i], 0, 0, lane, true, 1 << 30, nullptr);
 
@@ -573,13 +575,22 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
     float mrow = -INFINITY, lrow = 0.f;
+    f32x16 neg_m;  // -m in every register; +inf while there is no reference yet, which sends the first tile down the exact path
+#pragma unroll
+    for (int i = 0; i < 16; ++i) neg_m[i] = INFINITY;
 
     // S^T = K Q^T of this wave's sub-tile (the two waves that share a sub-tile both compute it: the matrix core has
     // time to spare here, LDS space has not); keys past the range end get zero weight
-    auto scores = [&](int it, f32x16& sc) {
+    // SHIFTED: the accumulator starts at -m in every register (the steady state: no subtraction on the vector ALU),
+    // else at 0 (the exact path, which needs the raw scores)
+    auto scores = [&](int it, f32x16& sc, auto shifted) {
       const __bf16* my_k = sm.tile[it % kDsRing][0] + ksub * kDsTile * D;
+      if constexpr (decltype(shifted)::value) {
+        sc = neg_m;
+      } else {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+        for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+      }
       // all K fragments of the sub-tile are requested before the first MFMA: the products form one dependent chain, and
       // a read per step would put the LDS latency into every link
       bf16x8 kf[KSTEPS];
@@ -595,14 +606,21 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
           if (key0 + 8 * (i >> 2) + 4 * hf + (i & 3) >= j_end) sc[i] = -INFINITY;
       }
     };
-    auto exponentials = [&](f32x16& sc, float& lsum) {
-      lsum = 0.f;
+    // P = exp2(S - m) of scores that already carry -m, as the bf16 B operands of the second product, and the lane's
+    // share of the row sum (over the rounded probabilities, two per instruction)
+    auto softmax_tile = [&](const f32x16& sc, bf16x8 (&pf)[2], float& lsum) {
+      float s0 = 0.f, s1 = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float e = __builtin_amdgcn_exp2f(sc[i] - mrow);
-        sc[i] = e;
-        lsum += e;
+      for (int kk = 0; kk < 2; ++kk) {
+        u32x4 w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          w[j] = pack_bf16(__builtin_amdgcn_exp2f(sc[8 * kk + 2 * j]), __builtin_amdgcn_exp2f(sc[8 * kk + 2 * j + 1]));
+          add_pair(j & 1 ? s1 : s0, w[j]);
+        }
+        pf[kk] = __builtin_bit_cast(bf16x8, w);
       }
+      lsum = add_chains(s0, s1);
     };
     // V^T fragments of this wave's sub-tile and half of the head dimension, requested ahead of the exponentials
     auto fetch_v = [&](int it, bf16x8 (&vf)[2][DBH]) {
@@ -613,16 +631,8 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         for (int db = 0; db < DBH; ++db) vf[kk][db] = read_v_fragment<D>(my_v, fo, dh * DBH + db, kk);
       __builtin_amdgcn_sched_barrier(0);
     };
-    auto accumulate = [&](f32x16& sc, float lsum, const bf16x8 (&vf)[2][DBH]) {
-      bf16x8 pf[2];
+    auto accumulate = [&](const bf16x8 (&pf)[2], float lsum, const bf16x8 (&vf)[2][DBH]) {
       lrow += lsum;
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        u32x4 w;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w[j] = pack_bf16(sc[8 * kk + 2 * j], sc[8 * kk + 2 * j + 1]);
-        pf[kk] = __builtin_bit_cast(bf16x8, w);
-      }
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
@@ -659,20 +669,20 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         if (has_keys(it)) {
           f32x16 sc;
           float lsum;
-          bf16x8 vf[2][DBH];
-          scores(it, sc);
+          bf16x8 vf[2][DBH], pf[2];
+          scores(it, sc, std::true_type{});
           fetch_v(it, vf);
-          exponentials(sc, lsum);
+          softmax_tile(sc, pf, lsum);
           if (__any(!(lsum <= kDecSumLimit))) { rescale = true; break; }
-          accumulate(sc, lsum, vf);
+          accumulate(pf, lsum, vf);
         }
       }
       if (!rescale) break;
       {
         f32x16 sc;
         float lsum;
-        bf16x8 vf[2][DBH];
-        scores(it, sc);  // the tile is still staged
+        bf16x8 vf[2][DBH], pf[2];
+        scores(it, sc, std::false_type{});  // the tile is still staged
         fetch_v(it, vf);
         float m = sc[0];
 #pragma unroll
@@ -686,8 +696,10 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         for (int db = 0; db < DBH; ++db)
 #pragma unroll
           for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-        exponentials(sc, lsum);
-        accumulate(sc, lsum, vf);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { neg_m[i] = -mnew; sc[i] -= mnew; }
+        softmax_tile(sc, pf, lsum);
+        accumulate(pf, lsum, vf);
         ++it;
       }
     }
