@@ -83,6 +83,17 @@ def algorithmic_counts(w: W.Workload):
     return dict(flops_full=flops_full, flops_reg=flops_reg, dec_full=dec_full, dec_reg=dec_reg, compaction=comp)
 
 
+def executed_tile_flops(w: W.Workload, tile_keys: int = 64, wave_rows: int = 32) -> float:
+    """FLOPs the matrix cores are actually asked for in one full-length layer: every wave of 32 query rows multiplies
+    whole 64-key tiles up to and including the tile of its diagonal (masked entries included)."""
+    c = w.cfg
+    pairs = 0
+    for n in w.seq_lengths:
+        for q0 in range(0, n, wave_rows):
+            pairs += wave_rows * tile_keys * (q0 // tile_keys + 1)
+    return 4.0 * c.head_dim * c.n_q_heads * pairs
+
+
 def algorithmic_prefill_bytes(name: str) -> float:
     """Q, K, V read once, O and the rotated K (the layer's key cache) written once, for one full-length layer."""
     c = W.CONFIGS[name]
@@ -174,7 +185,8 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
         "ms_per_step": wall * 1e3 / steps,
         "prefill_tflops": prefill_tflops,
         "prefill_full_layer": {"ms_per_launch": full_ms, "tflops": full_tflops, "frac_of_peak": full_tflops / peak,
-                               "flops_per_launch": alg["flops_full"]},
+                               "flops_per_launch": alg["flops_full"],
+                               "executed_tile_flops_per_launch": executed_tile_flops(w) if c.dtype == "bf16" else None},
         "prefill_register_layer": {"us_per_launch": reg_ms * 1e3, "flops_per_launch": alg["flops_reg"]},
         "compaction": {"us": comp_us, "bytes": alg["compaction"], "GBps": comp_gbps,
                        "frac_of_hbm_peak": comp_gbps / PEAK_HBM_GBPS},
@@ -185,6 +197,15 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
                    "register_cache_layers": {"us_per_layer": ms["decode_reg"] * 1e3 / (steps * G * max(N - kk, 1)),
                                              "GBps": dec_reg_gbps, "frac_of_hbm_peak": dec_reg_gbps / PEAK_HBM_GBPS}},
         "phase_ms_per_step": {k_: v_ / steps for k_, v_ in ms.items()},
+        # Context, attention only (not comparable with the paper's end-to-end figures): the same N layers run the
+        # vanilla way (every layer full length) would cost N full-layer launches; next to it the closed forms of
+        # Section 3.3 (k/N for attention work, (k n + (N-k) r)/(N n) for cache entries).
+        "attention_only_vs_vanilla": {
+            "prefill_speedup": N * full_ms / (kk * full_ms + (N - kk) * reg_ms),
+            "decode_speedup": (N * ms["decode_full"] / max(kk, 1)) / (ms["decode_full"] + ms["decode_reg"]),
+            "closed_form_attention_ratio": kk / N,
+            "closed_form_cache_ratio": sum(kk * n + (N - kk) * c.r for n in w.seq_lengths) / float(N * sum(w.seq_lengths)),
+        },
     }
     del path, q, k, v, x, dq, dk, dv
     torch.cuda.empty_cache()
@@ -304,12 +325,14 @@ def main():
                                  if args.workload in MEASURED_TRAFFIC else None),
                      "traffic_detail": MEASURED_TRAFFIC.get(args.workload),
                      "algorithmic_bytes": algorithmic_prefill_bytes(args.workload),
-                     "ms_per_launch": pf["ms_per_launch"], "flops_per_launch": pf["flops_per_launch"]},
+                     "ms_per_launch": pf["ms_per_launch"], "flops_per_launch": pf["flops_per_launch"],
+                     "executed_tile_flops_per_launch": pf["executed_tile_flops_per_launch"]},
         "cpu_baseline": cpu,
         "decode": head["decode"],
         "compaction": head["compaction"],
         "prefill_register_layer": head["prefill_register_layer"],
         "phase_ms_per_step": head["phase_ms_per_step"],
+        "attention_only_vs_vanilla": head["attention_only_vs_vanilla"],
         "other_workloads": {n: {kk: vv for kk, vv in r.items()} for n, r in others.items()},
     }
     print(json.dumps(line))
