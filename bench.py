@@ -247,14 +247,44 @@ def run_single(name: str, kind: str, dev) -> dict:
     return {"workload": name, "single": kind, "launches": 2, "second_launch_ms": (time.perf_counter() - t0) * 1e3}
 
 
-def cpu_baseline(name: str) -> dict:
-    """The fp64 oracle, untuned, on a bounded sample of the headline workload's first prefill layer."""
+def launch_floor_us(dev, launches: int = 200) -> float:
+    """Cost of one launch through the library with next to no work in it (compaction of one 16-byte row): what every
+    per-launch figure of the latency-bound phases contains."""
+    from paper_2507_00715_amd import binding as B
+    src = torch.zeros(4, 16, dtype=torch.uint8, device=dev)
+    dst = torch.zeros(2, 16, dtype=torch.uint8, device=dev)
+    cu = torch.tensor([0, 4], dtype=torch.int32, device=dev)
+    idx, pos = (torch.zeros(2, dtype=torch.int32, device=dev) for _ in range(2))
+    cu_out = torch.zeros(2, dtype=torch.int32, device=dev)
+    call = lambda: B.earn_compact_registers([src], [dst], cu, 1, 1, 1, idx, pos, cu_out)
+    for _ in range(20):
+        call()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(launches):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / launches
+
+
+def cpu_baseline(name: str, threads: int = 0, rows_target: int = 4096) -> dict:
+    """The fp64 oracle, untuned, on a bounded sample of the headline workload's first prefill layer (threads = 0: all
+    the threads OpenMP gives it; otherwise that many, set through the OpenMP runtime the oracle is linked with)."""
     from oracle import earn_oracle as O
     cfg = W.CONFIGS[name]
     w = W.Workload(cfg)
     seq_id = 0
     n = w.seq_lengths[seq_id]
-    stride = max(1, n // 4096)  # about 10-20 s of oracle time on 16 host cores
+    stride = max(1, n // rows_target)  # 4096 rows: about 10-20 s of oracle time on 16 host cores
+    omp = None
+    if threads > 0:
+        import ctypes
+        O.lib()
+        omp = ctypes.CDLL("libgomp.so.1")
+        before = omp.omp_get_max_threads()
+        omp.omp_set_num_threads(threads)
     q = W.to_f64(w.prefill_tensor("q", 0, seqs=[seq_id]))
     k = W.to_f64(w.prefill_tensor("k", 0, seqs=[seq_id]))
     v = W.to_f64(w.prefill_tensor("v", 0, seqs=[seq_id]))
@@ -267,6 +297,9 @@ def cpu_baseline(name: str) -> dict:
     O.prefill_attn(q, k, v, [0, n], rope_base=cfg.rope_base, row_sel=sel)
     dt = time.perf_counter() - t0
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    if omp is not None:
+        omp.omp_set_num_threads(before)
+        cores = threads
     cores = min(cores, cfg.n_q_heads)  # the oracle parallelises over (sequence, head)
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle", "seconds": dt,
             "sample": f"{name} layer 0, sequence {seq_id} (n={n}), all {cfg.n_q_heads} query heads, every "
@@ -306,6 +339,10 @@ def main():
         r = run_workload(name, args.steps, args.warmup, dev)
         others[name] = r
     cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload)
+    if cpu is not None:  # the same oracle on one thread, on a sixteenth of the rows
+        one = cpu_baseline(args.workload, threads=1, rows_target=256)
+        cpu["single_thread"] = {k_: one[k_] for k_ in ("value", "unit", "cores", "seconds", "sample")}
+    floor_us = launch_floor_us(dev)
 
     cfg = W.CONFIGS[args.workload]
     pf = head["prefill_full_layer"]
@@ -332,6 +369,7 @@ def main():
         "compaction": head["compaction"],
         "prefill_register_layer": head["prefill_register_layer"],
         "phase_ms_per_step": head["phase_ms_per_step"],
+        "launch_floor_us": floor_us,
         "attention_only_vs_vanilla": head["attention_only_vs_vanilla"],
         "other_workloads": {n: {kk: vv for kk, vv in r.items()} for n, r in others.items()},
     }
