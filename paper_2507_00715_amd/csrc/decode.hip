@@ -72,8 +72,7 @@ struct DecodeParams {
   void* gen_k; void* gen_v; const int32_t* gen_len;
   void* out; float* part_o; float* part_ml;
   int gen_cap, n_streams, batch, hq, hkv, n_splits, chunk;  // chunk: keys per split (multiple of 64)
-  int n_slots;    // partial-result slots per (stream, head) in the workspace: n_splits (+1 for the generated rows)
-  int gen_only;   // 1: this launch covers only the stream's generated rows and the new token (slot n_slots-1)
+  int n_slots;    // partial-result slots per (stream, head) in the workspace (one per key split)
   float scale_log2;
   RopeTable rope;
 };
@@ -108,19 +107,18 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* o, float 
 }
 
 // Attention of one (stream u, kv head c) over the key range `z` of its key list, by WAVES cooperating waves
-// (WAVES = 4: a whole workgroup, states merged through `sm`; WAVES = 1: a single wave, no LDS, no barrier — used for
-// short key lists, where the per-wave prologue dominates, and inside the shared-cache kernel for the generated rows).
+// (WAVES > 1: states merged through `sm`; WAVES = 1: a single wave, no LDS, no barrier — used for short key lists,
+// where the per-wave prologue dominates).
 template <typename T, int D, int GQ, int WAVES>
 __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, const int u, const int z,
-                                            const int wave, const int lane, const bool gen_only, const int chunk,
-                                            float* sm_base) {
+                                            const int wave, const int lane, const int chunk, float* sm_base) {
   constexpr int LPK = D / 8;         // lanes per key row
   constexpr int KPW = kWave / LPK;   // key rows per wave instruction
   const int gq = p.hq / p.hkv;       // query heads per kv head
   const int sub = lane % LPK, kk = lane / LPK;
   const int s = p.stream_to_seq ? p.stream_to_seq[u] : u;
   const int b0 = p.shared_cu[s];
-  const int ns = gen_only ? 0 : p.shared_cu[s + 1] - b0;  // shared rows this launch walks
+  const int ns = p.shared_cu[s + 1] - b0;
   const int g = p.gen_len[u];
   const int m_total = ns + g + 1;    // shared rows, earlier generated rows, the new token
   const float pos = (float)p.q_pos[u];
@@ -294,7 +292,7 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
       for (int i = 0; i < 8; ++i) oo[i] *= inv;
       Row8<T>::store((T*)p.out + ((long long)u * p.hq + head) * D + sb * 8, oo);
     } else {
-      const long long slot = ((long long)u * p.hq + head) * p.n_slots + (gen_only ? p.n_slots - 1 : z);
+      const long long slot = ((long long)u * p.hq + head) * p.n_slots + z;
       float* po = p.part_o + slot * D + sb * 8;
 #pragma unroll
       for (int i = 0; i < 8; ++i) po[i] = oo[i];
@@ -339,7 +337,7 @@ template <typename T, int D, int GQ, int WAVES>
 __global__ __launch_bounds__(kWave * WAVES) void decode_kernel(DecodeParams p) {
   __shared__ float sm[WAVES > 1 ? WAVES * GQ * (D / 8) * 10 : 1];
   decode_rows<T, D, GQ, WAVES>(p, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x / kWave, threadIdx.x % kWave,
-                               p.gen_only != 0, p.chunk, sm);
+                               p.chunk, sm);
 }
 
 // merge the partial results of the slots: one thread per (stream, head, 8-element group)
@@ -383,8 +381,11 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const float* __rest
 // matrix core has time to spare here, LDS space has not) with a private softmax state; the states of the two
 // sub-tiles are merged through LDS at the end.
 // Key ranges of long caches are split over workgroups; every (row, split) partial goes to the workspace and
-// decode_combine_kernel merges them.  The per-stream generated rows and the new token differ per beam: the waves handle
-// them with the vector code above while the first tiles are on their way.
+// decode_combine_kernel merges them.  The per-stream generated rows and the new token differ per beam.  They are laid
+// out as one more key list, stream after stream at a common pitch, cut into the same 64-key tiles and multiplied
+// against ALL query rows with a mask that lets a query row see only its own stream's rows: a few tiles more for a
+// workgroup that walks dozens, instead of a second, latency-bound pass in vector code.  The workgroup that owns such a
+// tile also rotates the new token's key and appends key and value to the stream's cache (Eq. 4).
 // ------------------------------------------------------------------------------------------------------------------
 constexpr int kDsTile = 32;              // keys per wave sub-tile
 constexpr int kDsGroupWaves = 4;         // waves per 32-row group: 2 key sub-tiles x 2 halves of the head dimension
@@ -411,13 +412,15 @@ struct DsSmem {
   // deposit them directly); reused as the merge buffers once the key loop is done
   __bf16 tile[kDsRing][2][kTileKeys * D];
   int streams[kMaxStreamsPerSeq];
+  int glen[kMaxStreamsPerSeq];  // rows already in the generated cache of each listed stream
   int n_streams_of_seq;
+  int gen_pitch;                // 1 + the largest of them: generated key e is row e % gen_pitch of listed stream e / gen_pitch
   // (cos, sin) of the rotary angles of the first kDsTabStreams streams of the list, [stream][d/2]: computed once by
   // the workgroup instead of once per query row (the gq heads of a stream share them)
   f32x2 cs[kDsTabStreams][D / 2];
 };
 
-template <int D, int C, int GQ>
+template <int D, int C>
 __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodeParams p) {
   constexpr int KSTEPS = D / 16, DB = D / 32;
   constexpr int ROWS = 32 * C;
@@ -484,33 +487,48 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 
   // ---- streams (beams) of this sequence, ascending ----
   if (wave == 0) {
-    int count = 0;
+    int count = 0, gmax = 0;
     if (!p.stream_to_seq) {
-      if (lane == 0) sm.streams[0] = s;
+      gmax = p.gen_len[s];
+      if (lane == 0) { sm.streams[0] = s; sm.glen[0] = gmax; }
       count = 1;
     } else {
       for (int base = 0; base < p.n_streams; base += 4 * kWave) {
-        int seq_of[4];  // four chunks of the list are requested together: one memory round trip, not four
+        int seq_of[4], gl[4];  // four chunks of both lists are requested together: one memory round trip, not eight
 #pragma unroll
         for (int k4 = 0; k4 < 4; ++k4) {
           const int u = base + k4 * kWave + lane;
           seq_of[k4] = u < p.n_streams ? p.stream_to_seq[u] : -1;
+          gl[k4] = u < p.n_streams ? p.gen_len[u] : 0;
         }
 #pragma unroll
         for (int k4 = 0; k4 < 4; ++k4) {
           const bool hit = seq_of[k4] == s;
           const unsigned long long mask = __ballot(hit);
           const int idx = count + __popcll(mask & ((1ull << lane) - 1ull));
-          if (hit && idx < kMaxStreamsPerSeq) sm.streams[idx] = base + k4 * kWave + lane;
+          if (hit && idx < kMaxStreamsPerSeq) {
+            sm.streams[idx] = base + k4 * kWave + lane;
+            sm.glen[idx] = gl[k4];
+            gmax = max(gmax, gl[k4]);
+          }
           count += __popcll(mask);
         }
       }
       if (count > kMaxStreamsPerSeq) count = kMaxStreamsPerSeq;
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) gmax = max(gmax, __shfl_xor(gmax, off, kWave));
     }
-    if (lane == 0) sm.n_streams_of_seq = count;
+    if (lane == 0) { sm.n_streams_of_seq = count; sm.gen_pitch = gmax + 1; }
   }
   __syncthreads();
-  const int M = sm.n_streams_of_seq * gq;  // query rows sharing this cache
+  const int n_st = sm.n_streams_of_seq;
+  const int M = n_st * gq;  // query rows sharing this cache
+  // the generated part as a key list of its own: n_st streams x gp rows (rows past a stream's own length are masked)
+  const int gp = sm.gen_pitch;
+  const int n_gen_keys = n_st * gp;
+  const int n_gen_tiles = (n_gen_keys + kTileKeys - 1) / kTileKeys;
+  const int tg0 = p.n_splits - 1 - z;  // this workgroup takes generated tiles tg0, tg0 + n_splits, ...: the last split,
+                                       // whose key range is the shortest, takes the first
   // rotary factors of the tabulated streams, one (stream, pair) per thread and pass; read after the barrier that
   // follows the generated rows' part
   if (p.rope.enabled) {
@@ -523,13 +541,73 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     }
   }
 
-  // ---- generated rows and the new token of this sequence's streams (they differ per beam: vector ALU, one wave per
-  // stream).  The streams are dealt out over the key splits so every workgroup gets an equal share, and the work runs
-  // while the first tiles are still on their way from HBM. ----
-  for (int i = z + p.n_splits * wave; i < sm.n_streams_of_seq; i += p.n_splits * 4 * C)
-    decode_rows<__bf16, D, GQ, 1>(p, c, sm.streams[i], 0, 0, lane, true, 1 << 30, nullptr);
+  lds_barrier();  // the table of rotary factors is complete
 
-  __syncthreads();  // the table of rotary factors is complete
+  // ---- a tile of the generated key list, fetched into registers (one 16-byte unit of K and of V per thread and pass):
+  // rows of the streams' generated caches as stored; the row after a stream's last one is its new token, whose key is
+  // rotated and rounded here and, with `append`, written to its cache slot together with the value ----
+  constexpr int UPR = D / 8, NCH = kTileKeys * UPR / (256 * C);
+  static_assert(NCH >= 1 && NCH * 256 * C == kTileKeys * UPR);
+  u32x4 gk[NCH], gv[NCH];
+  auto load_gen_tile = [&](int tg, bool append) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int unit = threadIdx.x + i * 256 * C;
+      const int row = unit / UPR, ch = unit % UPR;
+      const int e = tg * kTileKeys + row;
+      const int si = e / gp, ri = e - si * gp;
+      u32x4 kx = {0u, 0u, 0u, 0u}, vx = {0u, 0u, 0u, 0u};
+      if (si < n_st) {
+        const int u = sm.streams[si], g = sm.glen[si];
+        const long long row0_of_u = (((long long)u * p.gen_cap) * p.hkv + c) * D + ch * 8;
+        if (ri < g) {
+          kx = *(const u32x4*)((const __bf16*)p.gen_k + row0_of_u + ri * kv_stride);
+          vx = *(const u32x4*)((const __bf16*)p.gen_v + row0_of_u + ri * kv_stride);
+        } else if (ri == g) {
+          const long long tok = ((long long)u * p.hkv + c) * D;
+          float x[8], y[8];  // this unit's elements and their rotary partners (the unit half a row away)
+          Row8<__bf16>::load((const __bf16*)p.k_new + tok + ch * 8, x);
+          Row8<__bf16>::load((const __bf16*)p.k_new + tok + (ch ^ (UPR / 2)) * 8, y);
+          vx = *(const u32x4*)((const __bf16*)p.v_new + tok + ch * 8);
+          const bool upper = ch >= UPR / 2;
+          const float pos = (float)p.q_pos[u];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int pe = (ch % (UPR / 2)) * 8 + j;
+            float sn = 0.f, cs = 1.f;
+            if (p.rope.enabled) {
+              if (si < kDsTabStreams) { const f32x2 t = sm.cs[si][pe]; cs = t[0]; sn = t[1]; }
+              else sincos_turns_fast(rope_turns(pos, p.rope.hi[pe], p.rope.lo[pe]), &sn, &cs);
+            }
+            x[j] = upper ? x[j] * cs + y[j] * sn : x[j] * cs - y[j] * sn;
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) kx[j] = pack_bf16(x[2 * j], x[2 * j + 1]);
+          if (append) {
+            *(u32x4*)((__bf16*)p.gen_k + row0_of_u + g * kv_stride) = kx;
+            *(u32x4*)((__bf16*)p.gen_v + row0_of_u + g * kv_stride) = vx;
+          }
+        }
+      }
+      gk[i] = kx;
+      gv[i] = vx;
+    }
+  };
+  auto store_gen_tile = [&](int slot) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int unit = threadIdx.x + i * 256 * C;
+      const int row = unit / UPR, ch = unit % UPR;
+      const int off = row * D + ((ch ^ swz<D>(row)) << 3);
+      *(u32x4*)(sm.tile[slot][0] + off) = gk[i];
+      *(u32x4*)(sm.tile[slot][1] + off) = gv[i];
+    }
+  };
+  // the first generated tile of this workgroup is requested now, in the shadow of the first K/V tiles, and waits in
+  // registers until the key loop is through
+  bool gen_tile_in_regs = tg0 < n_gen_tiles;
+  if (gen_tile_in_regs) load_gen_tile(tg0, true);
+
   for (int row0 = 0; row0 < M; row0 += ROWS) {
     // ---- Q fragments of this group's rows: row m -> (stream list[m / gq], head c*gq + m % gq) ----
     const bool grp_active = row0 + 32 * grp < M;
@@ -583,8 +661,9 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     // time to spare here, LDS space has not); keys past the range end get zero weight
     // SHIFTED: the accumulator starts at -m in every register (the steady state: no subtraction on the vector ALU),
     // else at 0 (the exact path, which needs the raw scores)
-    auto scores = [&](int it, f32x16& sc, auto shifted) {
-      const __bf16* my_k = sm.tile[it % kDsRing][0] + ksub * kDsTile * D;
+    // `mask` sets the scores of keys this lane's query row must not see to -inf
+    auto scores = [&](int slot, f32x16& sc, auto shifted, auto mask) {
+      const __bf16* my_k = sm.tile[slot][0] + ksub * kDsTile * D;
       if constexpr (decltype(shifted)::value) {
         sc = neg_m;
       } else {
@@ -599,12 +678,33 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sc, 0, 0, 0);
-      const int key0 = j_begin + it * kTileKeys + ksub * kDsTile;
-      if (key0 + kDsTile > j_end) {
+      mask(sc);
+    };
+    // register i of a score tile is key 8 (i / 4) + 4 hf + i % 4 of the wave's 32-key sub-tile
+    // shared rows: keys past the end of the workgroup's key range
+    auto range_mask = [&](int it) {
+      return [&, it](f32x16& sc) {
+        const int key0 = j_begin + it * kTileKeys + ksub * kDsTile;
+        if (key0 + kDsTile > j_end) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (key0 + 8 * (i >> 2) + 4 * hf + (i & 3) >= j_end) sc[i] = -INFINITY;
-      }
+          for (int i = 0; i < 16; ++i)
+            if (key0 + 8 * (i >> 2) + 4 * hf + (i & 3) >= j_end) sc[i] = -INFINITY;
+        }
+      };
+    };
+    // generated rows: a query row sees keys [gen_lo, gen_hi] of the generated key list, its own stream's rows
+    // including the new token
+    const int q_si = min(row0 + 32 * grp + r32, M - 1) / gq;
+    const int gen_lo = q_si * gp, gen_hi = gen_lo + sm.glen[q_si];
+    auto gen_mask = [&](int tg) {
+      return [&, tg](f32x16& sc) {
+        const int e0 = tg * kTileKeys + ksub * kDsTile + 4 * hf;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int e = e0 + 8 * (i >> 2) + (i & 3);
+          if (e < gen_lo || e > gen_hi) sc[i] = -INFINITY;
+        }
+      };
     };
     // P = exp2(S - m) of scores that already carry -m, as the bf16 B operands of the second product, and the lane's
     // share of the row sum (over the rounded probabilities, two per instruction)
@@ -623,8 +723,8 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       lsum = add_chains(s0, s1);
     };
     // V^T fragments of this wave's sub-tile and half of the head dimension, requested ahead of the exponentials
-    auto fetch_v = [&](int it, bf16x8 (&vf)[2][DBH]) {
-      const __bf16* my_v = sm.tile[it % kDsRing][1] + ksub * kDsTile * D;
+    auto fetch_v = [&](int slot, bf16x8 (&vf)[2][DBH]) {
+      const __bf16* my_v = sm.tile[slot][1] + ksub * kDsTile * D;
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
@@ -638,6 +738,27 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 #pragma unroll
         for (int db = 0; db < DBH; ++db)
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[kk][db], pf[kk], o[db], 0, 0, 0);
+    };
+    // A new reference for the rows of a tile whose raw scores are in `sc` (the exact path): the exact row maxima enter
+    // the running ones, sums and outputs are rescaled, and the scores leave relative to the new reference.  A row that
+    // has not met a visible key yet (every score so far masked) keeps "no reference".
+    auto rebase = [&](f32x16& sc) {
+      float m = sc[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) m = fmaxf(m, sc[i]);
+      m = fmaxf(m, __shfl_xor(m, 32, kWave));
+      const float mnew = fmaxf(mrow, m);
+      const float ref = mnew == -INFINITY ? 0.f : mnew;
+      const float alpha = __builtin_amdgcn_exp2f(mrow - ref);  // 0 for a row without a reference: its sums are 0
+      mrow = mnew;
+      lrow *= alpha;
+#pragma unroll
+      for (int db = 0; db < DBH; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+      const float nm = mnew == -INFINITY ? INFINITY : -mnew;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { neg_m[i] = nm; sc[i] -= ref; }
     };
     // does this wave have keys in super-tile `it`?
     auto has_keys = [&](int it) {
@@ -670,8 +791,8 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
           f32x16 sc;
           float lsum;
           bf16x8 vf[2][DBH], pf[2];
-          scores(it, sc, std::true_type{});
-          fetch_v(it, vf);
+          scores(it % kDsRing, sc, std::true_type{}, range_mask(it));
+          fetch_v(it % kDsRing, vf);
           softmax_tile(sc, pf, lsum);
           if (__any(!(lsum <= kDecSumLimit))) { rescale = true; break; }
           accumulate(pf, lsum, vf);
@@ -682,25 +803,35 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         f32x16 sc;
         float lsum;
         bf16x8 vf[2][DBH], pf[2];
-        scores(it, sc, std::false_type{});  // the tile is still staged
-        fetch_v(it, vf);
-        float m = sc[0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) m = fmaxf(m, sc[i]);
-        m = fmaxf(m, __shfl_xor(m, 32, kWave));
-        const float mnew = fmaxf(mrow, m);   // finite: a sub-tile with keys holds at least one valid key
-        const float alpha = __builtin_amdgcn_exp2f(mrow - mnew);
-        mrow = mnew;
-        lrow *= alpha;
-#pragma unroll
-        for (int db = 0; db < DBH; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { neg_m[i] = -mnew; sc[i] -= mnew; }
+        scores(it % kDsRing, sc, std::false_type{}, range_mask(it));  // the tile is still staged
+        fetch_v(it % kDsRing, vf);
+        rebase(sc);
         softmax_tile(sc, pf, lsum);
         accumulate(pf, lsum, vf);
         ++it;
+      }
+    }
+
+    // ---- the generated key list: this workgroup's tiles of it, one at a time through ring slot 0 ----
+    for (int tg = tg0; tg < n_gen_tiles; tg += p.n_splits) {
+      if (!gen_tile_in_regs) load_gen_tile(tg, row0 == 0);
+      gen_tile_in_regs = false;
+      __syncthreads();  // nobody reads the slot any more (all of the workgroup's loads into LDS have landed long ago)
+      store_gen_tile(0);
+      __syncthreads();
+      if (grp_active && tg * kTileKeys + ksub * kDsTile < n_gen_keys) {
+        f32x16 sc;
+        float lsum;
+        bf16x8 vf[2][DBH], pf[2];
+        scores(0, sc, std::true_type{}, gen_mask(tg));
+        fetch_v(0, vf);
+        softmax_tile(sc, pf, lsum);
+        if (__any(!(lsum <= kDecSumLimit))) {
+          scores(0, sc, std::false_type{}, gen_mask(tg));
+          rebase(sc);
+          softmax_tile(sc, pf, lsum);
+        }
+        accumulate(pf, lsum, vf);
       }
     }
     __syncthreads();  // every wave is done with the tiles: their memory becomes the merge buffers
@@ -760,7 +891,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 // host side
 // ------------------------------------------------------------------------------------------------------------------
 struct DecodePlan {
-  bool mfma;      // shared rows on the matrix cores + generated rows on the vector ALU + combine
+  bool mfma;      // shared and generated rows on the matrix cores + combine
   int n_splits;   // key-range splits of the shared (mfma) or whole (vector) key list
   int n_slots;    // partial slots per (stream, head)
   int chunk;      // keys per split
@@ -782,7 +913,7 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
     if (n < 1) n = 1;
     if (n > 64) n = 64;
     pl.n_splits = n;
-    pl.n_slots = n + 1;
+    pl.n_slots = n;
     pl.chunk = (((max_shared_len + n - 1) / n) + kDsSuper - 1) / kDsSuper * kDsSuper;
   } else {
     const int max_total = max_shared_len + gen_cap;
@@ -803,7 +934,7 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
 size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, int batch, int max_shared_len,
                               int gen_cap) {
   DecodePlan pl = plan_decode(dtype, hq, hkv, n_streams, batch, max_shared_len, gen_cap);
-  if (pl.n_slots == 1) return 0;
+  if (!pl.mfma && pl.n_slots == 1) return 0;  // the vector kernel writes final outputs itself when nothing is split
   size_t rows = (size_t)n_streams * hq * pl.n_slots;
   return rows * d * sizeof(float) + rows * 2 * sizeof(float);
 }
@@ -847,13 +978,8 @@ static void launch_decode_t(DecodeParams& p, const DecodePlan& pl, int gq, hipSt
     dim3 grid((unsigned)(((long long)p.batch * p.n_splits + 7) / 8 * 8 * p.hkv), 1, 1);
     // one 32-row group is enough when a cache serves at most 32 query rows; with beams the host only has an upper bound
     const bool one_group = (long long)gq * (p.n_streams - p.batch + 1) <= 32;
-    if (one_group) {
-      if (gq <= 4) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1, 4>), grid, dim3(256), 0, stream, p);
-      else hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1, 8>), grid, dim3(256), 0, stream, p);
-    } else {
-      if (gq <= 4) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 2, 4>), grid, dim3(512), 0, stream, p);
-      else hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 2, 8>), grid, dim3(512), 0, stream, p);
-    }
+    if (one_group) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 2>), grid, dim3(512), 0, stream, p);
     launch_combine<T, D>(p, stream);
   }
 }
@@ -879,7 +1005,7 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
   p.shared_k = shared_k; p.shared_v = shared_v; p.shared_cu = shared_cu; p.stream_to_seq = stream_to_seq;
   p.gen_k = gen_k; p.gen_v = gen_v; p.gen_len = gen_len; p.out = out;
   p.gen_cap = gen_cap; p.n_streams = n_streams; p.batch = batch; p.hq = hq; p.hkv = hkv;
-  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.gen_only = 0;
+  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk;
   const size_t need = decode_workspace_bytes(desc->dtype, hq, hkv, d, n_streams, batch, max_shared_len, gen_cap);
   if (need > workspace_bytes || (need > 0 && !workspace)) {
     set_error("earn_decode_attn: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);

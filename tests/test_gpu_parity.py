@@ -190,6 +190,9 @@ DECODE_CASES = [
     (torch.bfloat16, 32, 8, 128, [64, 2100, 0], 20, [i % 5 for i in range(60)], 5),
     (torch.bfloat16, 14, 2, 64, [300, 16, 1000], 6, [i % 3 for i in range(18)], 3),
     (torch.bfloat16, 8, 8, 64, [33, 700], 4, [0, 1, 2, 3, 3, 2, 1, 0], 4),
+    # long generated caches of very different lengths: the generated rows span several key tiles
+    (torch.bfloat16, 8, 2, 128, [500, 129], 2, [199, 70, 0, 130], 200),
+    (torch.bfloat16, 4, 2, 64, [256], 3, [64, 63, 0], 65),
 ]
 
 
