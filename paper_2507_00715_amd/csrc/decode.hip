@@ -413,6 +413,7 @@ struct DsSmem {
   __bf16 tile[kDsRing][2][kTileKeys * D];
   int streams[kMaxStreamsPerSeq];
   int glen[kMaxStreamsPerSeq];  // rows already in the generated cache of each listed stream
+  float qpos[kMaxStreamsPerSeq];  // position of each listed stream's new token
   int n_streams_of_seq;
   int gen_pitch;                // 1 + the largest of them: generated key e is row e % gen_pitch of listed stream e / gen_pitch
   // (cos, sin) of the rotary angles of the first kDsTabStreams streams of the list, [stream][d/2]: computed once by
@@ -449,6 +450,21 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   const int grp = wave / kDsGroupWaves, sub = wave % kDsGroupWaves;
   const int ksub = sub & 1, dh = sub >> 1;   // key sub-tile of the tile, half of the head dimension
   const int r32 = lane & 31, hf = lane >> 5;
+  // Wave 0 builds the list of this sequence's streams below.  Its first look at the per-stream arrays is requested
+  // here, ahead of everything else that goes to memory, so the lists, the sequence bounds and the first K/V tiles share
+  // one round trip instead of queueing behind each other.
+  int seq_of[4], gl[4], qp[4];
+  auto fetch_lists = [&](int base) {
+#pragma unroll
+    for (int k4 = 0; k4 < 4; ++k4) {
+      const int u = base + k4 * kWave + lane;
+      const bool in = u < p.n_streams;
+      seq_of[k4] = in ? p.stream_to_seq[u] : -1;
+      gl[k4] = in ? p.gen_len[u] : 0;
+      qp[k4] = in ? p.q_pos[u] : 0;
+    }
+  };
+  if (wave == 0 && p.stream_to_seq) fetch_lists(0);
   const int b0 = p.shared_cu[s], ns = p.shared_cu[s + 1] - b0;
   const int j_begin = z * p.chunk;
   const int j_end = min(ns, j_begin + p.chunk);
@@ -490,17 +506,11 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     int count = 0, gmax = 0;
     if (!p.stream_to_seq) {
       gmax = p.gen_len[s];
-      if (lane == 0) { sm.streams[0] = s; sm.glen[0] = gmax; }
+      if (lane == 0) { sm.streams[0] = s; sm.glen[0] = gmax; sm.qpos[0] = (float)p.q_pos[s]; }
       count = 1;
     } else {
       for (int base = 0; base < p.n_streams; base += 4 * kWave) {
-        int seq_of[4], gl[4];  // four chunks of both lists are requested together: one memory round trip, not eight
-#pragma unroll
-        for (int k4 = 0; k4 < 4; ++k4) {
-          const int u = base + k4 * kWave + lane;
-          seq_of[k4] = u < p.n_streams ? p.stream_to_seq[u] : -1;
-          gl[k4] = u < p.n_streams ? p.gen_len[u] : 0;
-        }
+        if (base > 0) fetch_lists(base);  // four chunks of the three lists per memory round trip
 #pragma unroll
         for (int k4 = 0; k4 < 4; ++k4) {
           const bool hit = seq_of[k4] == s;
@@ -509,6 +519,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
           if (hit && idx < kMaxStreamsPerSeq) {
             sm.streams[idx] = base + k4 * kWave + lane;
             sm.glen[idx] = gl[k4];
+            sm.qpos[idx] = (float)qp[k4];
             gmax = max(gmax, gl[k4]);
           }
           count += __popcll(mask);
@@ -529,14 +540,27 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   const int n_gen_tiles = (n_gen_keys + kTileKeys - 1) / kTileKeys;
   const int tg0 = p.n_splits - 1 - z;  // this workgroup takes generated tiles tg0, tg0 + n_splits, ...: the last split,
                                        // whose key range is the shortest, takes the first
-  // rotary factors of the tabulated streams, one (stream, pair) per thread and pass; read after the barrier that
-  // follows the generated rows' part
+  // ---- the queries of the first 32 * C rows are requested before the rotary table is worked out, and rotated after ----
+  // row m of the cache's query rows is head c*gq + m % gq of listed stream m / gq; a group's lane holds row r32 and,
+  // per k-step, elements [16 ks + 8 hf, + 8) of both rotary halves
+  u32x4 q_lo[KSTEPS / 2], q_hi[KSTEPS / 2];
+  auto load_q_raw = [&](int row0) {
+    const int m = min(row0 + 32 * grp + r32, M - 1);
+    const __bf16* qrow = (const __bf16*)p.q + ((long long)sm.streams[m / gq] * p.hq + c * gq + m % gq) * D + 8 * hf;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS / 2; ++ks) {
+      q_lo[ks] = *(const u32x4*)(qrow + 16 * ks);
+      q_hi[ks] = *(const u32x4*)(qrow + 16 * ks + D / 2);
+    }
+  };
+  if (M > 0) load_q_raw(0);
+  // rotary factors of the tabulated streams, one (stream, pair) per thread and pass
   if (p.rope.enabled) {
     const int n_tab = min(sm.n_streams_of_seq, kDsTabStreams);
     for (int i = threadIdx.x; i < n_tab * (D / 2); i += 256 * C) {
       const int e = i % (D / 2);
       float sn, cs;
-      sincos_turns_fast(rope_turns((float)p.q_pos[sm.streams[i / (D / 2)]], p.rope.hi[e], p.rope.lo[e]), &sn, &cs);
+      sincos_turns_fast(rope_turns(sm.qpos[i / (D / 2)], p.rope.hi[e], p.rope.lo[e]), &sn, &cs);
       sm.cs[i / (D / 2)][e] = f32x2{cs, sn};
     }
   }
@@ -570,7 +594,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
           Row8<__bf16>::load((const __bf16*)p.k_new + tok + (ch ^ (UPR / 2)) * 8, y);
           vx = *(const u32x4*)((const __bf16*)p.v_new + tok + ch * 8);
           const bool upper = ch >= UPR / 2;
-          const float pos = (float)p.q_pos[u];
+          const float pos = sm.qpos[si];
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const int pe = (ch % (UPR / 2)) * 8 + j;
@@ -609,21 +633,20 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   if (gen_tile_in_regs) load_gen_tile(tg0, true);
 
   for (int row0 = 0; row0 < M; row0 += ROWS) {
-    // ---- Q fragments of this group's rows: row m -> (stream list[m / gq], head c*gq + m % gq) ----
+    // ---- Q fragments of this group's rows, rotated and pre-scaled ----
     const bool grp_active = row0 + 32 * grp < M;
     bf16x8 qf[KSTEPS];
     int row_u, row_a;
+    if (row0 > 0) load_q_raw(row0);
     {
       const int m = min(row0 + 32 * grp + r32, M - 1);
-      const int u = sm.streams[m / gq], a = c * gq + m % gq;
-      row_u = u; row_a = a;
-      const float pos = (float)p.q_pos[u];
-      const __bf16* qrow = (const __bf16*)p.q + ((long long)u * p.hq + a) * D + 8 * hf;
+      row_u = sm.streams[m / gq]; row_a = c * gq + m % gq;
+      const float pos = sm.qpos[m / gq];
 #pragma unroll
       for (int ks = 0; ks < KSTEPS / 2; ++ks) {
         float lo[8], hi[8];
-        Row8<__bf16>::load(qrow + 16 * ks, lo);
-        Row8<__bf16>::load(qrow + 16 * ks + D / 2, hi);
+        Row8<__bf16>::unpack(q_lo[ks], lo);
+        Row8<__bf16>::unpack(q_hi[ks], hi);
         u32x4 wl, wh;
 #pragma unroll
         for (int j = 0; j < 8; j += 2) {
@@ -870,7 +893,20 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       // and sum (base-2 units; both halves hold the same ones) ----
       const float ltot = lrow + __shfl_xor(lrow, 32, kWave);
       const int m = row0 + 32 * grp + r32;
-      if (m < M) {
+      if (m < M && p.n_slots == 1) {
+        // nothing was split: this is the whole key list of the row (the new token is always among the keys, so the
+        // sum is positive); normalise and store the final output
+        const float inv = 1.f / ltot;
+        __bf16* po = (__bf16*)p.out + ((long long)row_u * p.hq + row_a) * D + dh * (D / 2) + 4 * hf;
+#pragma unroll
+        for (int db = 0; db < DBH; ++db)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            u32x2 w = {pack_bf16(o[db][4 * j] * inv, o[db][4 * j + 1] * inv),
+                       pack_bf16(o[db][4 * j + 2] * inv, o[db][4 * j + 3] * inv)};
+            *(u32x2*)(po + 32 * db + 8 * j) = w;
+          }
+      } else if (m < M) {
         const long long slot = ((long long)row_u * p.hq + row_a) * p.n_slots + z;
         float* po = p.part_o + slot * D + dh * (D / 2) + 4 * hf;
 #pragma unroll
@@ -934,7 +970,7 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
 size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, int batch, int max_shared_len,
                               int gen_cap) {
   DecodePlan pl = plan_decode(dtype, hq, hkv, n_streams, batch, max_shared_len, gen_cap);
-  if (!pl.mfma && pl.n_slots == 1) return 0;  // the vector kernel writes final outputs itself when nothing is split
+  if (pl.n_slots == 1) return 0;  // nothing is split: the kernels write the final outputs themselves
   size_t rows = (size_t)n_streams * hq * pl.n_slots;
   return rows * d * sizeof(float) + rows * 2 * sizeof(float);
 }
@@ -980,7 +1016,7 @@ static void launch_decode_t(DecodeParams& p, const DecodePlan& pl, int gq, hipSt
     const bool one_group = (long long)gq * (p.n_streams - p.batch + 1) <= 32;
     if (one_group) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 2>), grid, dim3(512), 0, stream, p);
-    launch_combine<T, D>(p, stream);
+    if (p.n_slots > 1) launch_combine<T, D>(p, stream);
   }
 }
 

@@ -103,12 +103,10 @@ def test_decode_argument_errors():
     assert need > 0
     assert call(maxlen=100000) == B.EARN_ERR_WORKSPACE_TOO_SMALL
     assert B.earn_decode_workspace_bytes(_desc(hq=64, hkv=64), 512, 512, 16, 4) == 0
-    # grouped heads on a cache of >= 128 rows go through the matrix-core kernel, which always leaves partial results
-    # in the workspace, also when the key range is not split (many sequences): (d + 2) floats per (stream, head)
-    need = B.earn_decode_workspace_bytes(_desc(hq=12, hkv=2, d=128), 256, 256, 1038, 4)
-    assert need >= 256 * 12 * (128 + 2) * 4
-    assert call(desc=_desc(hq=12, hkv=2, d=128), S=256, batch=256, maxlen=1038, ws=fake, ws_bytes=256) == \
-        B.EARN_ERR_WORKSPACE_TOO_SMALL
+    # many sequences: the key range of the matrix-core kernel is not split either, no partial results
+    assert B.earn_decode_workspace_bytes(_desc(hq=12, hkv=2, d=128), 256, 256, 1038, 4) == 0
+    # few sequences with long caches: one partial (d + 2 floats) per (stream, head, split), at least two splits
+    assert B.earn_decode_workspace_bytes(_desc(hq=32, hkv=8, d=128), 160, 16, 8256, 8) >= 2 * 160 * 32 * (128 + 2) * 4
 
 
 def test_binding_refuses_host_tensors():

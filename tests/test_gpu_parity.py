@@ -193,6 +193,8 @@ DECODE_CASES = [
     # long generated caches of very different lengths: the generated rows span several key tiles
     (torch.bfloat16, 8, 2, 128, [500, 129], 2, [199, 70, 0, 130], 200),
     (torch.bfloat16, 4, 2, 64, [256], 3, [64, 63, 0], 65),
+    # enough (sequence, kv head) pairs to fill the GPU without splitting key ranges: final outputs without a merge pass
+    (torch.bfloat16, 16, 8, 64, [130 + 7 * (i % 5) for i in range(32)], 1, [i % 3 for i in range(32)], 3),
 ]
 
 
