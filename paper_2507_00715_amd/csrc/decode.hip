@@ -939,7 +939,10 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
   // several query rows per cache (grouped heads or beams) make the shared part a matrix product
   // (short caches are launch-latency bound: the single-launch vector kernel wins there)
   static const int mfma_min = getenv("EARN_DEC_MFMA_MIN") ? atoi(getenv("EARN_DEC_MFMA_MIN")) : 128;
-  pl.mfma = dtype == EARN_BF16 && (gq > 1 || n_streams > batch) && max_shared_len >= mfma_min;
+  // ... unless all its workgroups (one per CU: they hold most of the LDS) fit on the GPU at once
+  static const int mfma_wgs = getenv("EARN_DEC_MFMA_SHORT_WGS") ? atoi(getenv("EARN_DEC_MFMA_SHORT_WGS")) : 256;
+  pl.mfma = dtype == EARN_BF16 && (gq > 1 || n_streams > batch) &&
+            (max_shared_len >= mfma_min || (long long)hkv * batch <= mfma_wgs);
   if (pl.mfma) {
     long long base = (long long)hkv * batch;
     static const int wg_env = getenv("EARN_DEC_WGS") ? atoi(getenv("EARN_DEC_WGS")) : 256;
