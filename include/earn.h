@@ -158,6 +158,39 @@ size_t earn_decode_workspace_bytes(const earn_attn_desc* desc, int32_t n_streams
                                    int32_t max_shared_len, int32_t gen_cap);
 
 /*
+ * Prefill attention of the LAST full-length layer (layer k-1) at the register rows only.
+ *
+ * Section 3.2 (inference): the input of layer k keeps only the register tokens, so of layer k-1's attention outputs
+ * only the rows of the h prefix and t suffix registers are ever used; the layer's keys and values are still needed at
+ * full length (they are the layer's cache, which decoding reads: Section 3.2, decoding; Section 3.3, N_KV's k L term).
+ * This entry point computes exactly those rows of Eq. 3 — row m of sequence s is the causal attention of token
+ * row_pos[s*r + m] over keys 0 .. row_pos[s*r + m] of the sequence — and rotates K into the cache, skipping the
+ * other n_s - r query rows: an exact saving of about 1/k of the prefill attention work that the efficiency analysis
+ * of Section 3.3 (Gamma_attn) does not count.
+ *
+ *   q_rows        device, [batch*r, Hq, d]: the query rows of the register tokens in compacted order, un-rotated
+ *                 (what earn_compact_registers gathers from the layer's [total, Hq, d] queries)
+ *   k, v          device, [total_tokens, Hkv, d], K un-rotated; rotary positions of K are the token indices in the
+ *                 sequence (this entry point takes no explicit position list for K)
+ *   cu_seqlens    device, [batch+1]
+ *   row_pos       device, [batch*r]: token index inside its sequence (= rotary position) of every row, ascending per
+ *                 sequence, each < the sequence's length (earn_compact_registers' pos_out); precondition, unchecked
+ *   rows_per_seq  r = h + t, the same for every sequence, <= 1024
+ *   out_rows      device, [batch*r, Hq, d]
+ *   k_rot_out     device, [total_tokens, Hkv, d], required: the rotated keys = the layer's cache
+ *   workspace     at least earn_prefill_register_rows_workspace_bytes(...) bytes, 256-byte aligned; may be NULL when 0
+ * bf16 only (EARN_ERR_UNSUPPORTED otherwise).  Enqueues on `stream`, allocates nothing, does not synchronise.
+ */
+int earn_prefill_register_rows(const earn_attn_desc* desc, const void* q_rows, const void* k, const void* v,
+                               const int32_t* cu_seqlens, const int32_t* row_pos, int32_t batch, int32_t total_tokens,
+                               int32_t max_seqlen, int32_t rows_per_seq, void* out_rows, void* k_rot_out,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace earn_prefill_register_rows needs (bytes) for split-key partial results. 0 on invalid arguments. */
+size_t earn_prefill_register_rows_workspace_bytes(const earn_attn_desc* desc, int32_t batch, int32_t max_seqlen,
+                                                  int32_t rows_per_seq);
+
+/*
  * KV-cache entries per attention head one sequence holds under EARN (paper Section 3.3, "KV Cache Size":
  * N_KV = n_h (k L + (N-k) r), here per head and with L = the length the first k layers see, plus `gen`
  * generated tokens kept by every layer).  Used for allocation and as an invariant.

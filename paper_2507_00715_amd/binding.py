@@ -24,7 +24,8 @@ EARN_F32, EARN_BF16 = 0, 1
 EARN_MAX_COMPACT_TENSORS = 112
 
 EXPORTS = ["earn_last_error", "earn_version", "earn_prefill_attn", "earn_prefill_workspace_bytes",
-           "earn_compact_registers", "earn_decode_attn", "earn_decode_workspace_bytes", "earn_cache_entries"]
+           "earn_compact_registers", "earn_decode_attn", "earn_decode_workspace_bytes", "earn_cache_entries",
+           "earn_prefill_register_rows", "earn_prefill_register_rows_workspace_bytes"]
 
 
 class EarnError(RuntimeError):
@@ -58,6 +59,11 @@ def lib():
         L.earn_decode_attn.restype = ctypes.c_int
         L.earn_decode_attn.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
                                        i32, i32, vp, vp, sz, vp]
+        L.earn_prefill_register_rows.restype = ctypes.c_int
+        L.earn_prefill_register_rows.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp,
+                                                 vp, sz, vp]
+        L.earn_prefill_register_rows_workspace_bytes.restype = sz
+        L.earn_prefill_register_rows_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), i32, i32, i32]
         L.earn_decode_workspace_bytes.restype = sz
         L.earn_decode_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), i32, i32, i32, i32]
         L.earn_cache_entries.restype = ctypes.c_int64
@@ -125,6 +131,18 @@ def earn_compact_registers(src: Sequence[torch.Tensor], dst: Sequence[torch.Tens
         assert t.is_cuda and t.is_contiguous()
     _check(lib().earn_compact_registers(n, src_arr, dst_arr, rb_arr, _ptr(cu_seqlens), batch, n_head_reg, n_tail_reg,
                                         _ptr(idx_out), _ptr(pos_out), _ptr(cu_out), _stream()))
+
+
+def earn_prefill_register_rows_workspace_bytes(desc: AttnDesc, batch: int, max_seqlen: int, rows_per_seq: int) -> int:
+    return int(lib().earn_prefill_register_rows_workspace_bytes(ctypes.byref(desc), batch, max_seqlen, rows_per_seq))
+
+
+def earn_prefill_register_rows(desc: AttnDesc, q_rows, k, v, cu_seqlens, row_pos, batch: int, total_tokens: int,
+                               max_seqlen: int, rows_per_seq: int, out_rows, k_rot_out, workspace=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().earn_prefill_register_rows(ctypes.byref(desc), _ptr(q_rows), _ptr(k), _ptr(v), _ptr(cu_seqlens),
+                                            _ptr(row_pos), batch, total_tokens, max_seqlen, rows_per_seq,
+                                            _ptr(out_rows), _ptr(k_rot_out), _ptr(workspace), ws_bytes, _stream()))
 
 
 def earn_decode_workspace_bytes(desc: AttnDesc, n_streams: int, batch: int, max_shared_len: int, gen_cap: int) -> int:

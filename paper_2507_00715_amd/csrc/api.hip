@@ -46,6 +46,12 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
                   hipStream_t stream);
 size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, int batch, int max_shared_len,
                               int gen_cap);
+int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, const int32_t* cu_seqlens,
+                     const int32_t* positions, int batch, int total_tokens, hipStream_t stream);
+size_t prefill_rows_workspace_bytes(int hq, int hkv, int d, int batch, int max_seqlen, int rows_per_seq);
+int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
+                        const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen, int rows_per_seq,
+                        void* out_rows, void* workspace, size_t workspace_bytes, hipStream_t stream);
 
 static int check_desc(const earn_attn_desc* d, const char* who) {
   if (!d) { set_error("%s: desc is NULL", who); return EARN_ERR_INVALID_ARG; }
@@ -150,6 +156,45 @@ int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_ne
   if (!stream_to_seq && n_streams != batch) { set_error("earn_decode_attn: stream_to_seq is NULL but n_streams (%d) != batch (%d)", n_streams, batch); return EARN_ERR_INVALID_ARG; }
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
                        gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+size_t earn_prefill_register_rows_workspace_bytes(const earn_attn_desc* desc, int32_t batch, int32_t max_seqlen,
+                                                  int32_t rows_per_seq) {
+  if (check_desc(desc, "earn_prefill_register_rows_workspace_bytes") != EARN_OK || batch <= 0 || max_seqlen < 0 ||
+      rows_per_seq <= 0)
+    return 0;
+  return prefill_rows_workspace_bytes(desc->n_q_heads, desc->n_kv_heads, desc->head_dim, batch, max_seqlen, rows_per_seq);
+}
+
+int earn_prefill_register_rows(const earn_attn_desc* desc, const void* q_rows, const void* k, const void* v,
+                               const int32_t* cu_seqlens, const int32_t* row_pos, int32_t batch, int32_t total_tokens,
+                               int32_t max_seqlen, int32_t rows_per_seq, void* out_rows, void* k_rot_out,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  int rc = check_desc(desc, "earn_prefill_register_rows");
+  if (rc != EARN_OK) return rc;
+  if (batch <= 0 || total_tokens <= 0 || max_seqlen <= 0 || rows_per_seq <= 0) {
+    set_error("earn_prefill_register_rows: batch (%d), total_tokens (%d), max_seqlen (%d) and rows_per_seq (%d) must be positive", batch, total_tokens, max_seqlen, rows_per_seq);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (rows_per_seq > max_seqlen) {
+    set_error("earn_prefill_register_rows: rows_per_seq (%d) exceeds max_seqlen (%d)", rows_per_seq, max_seqlen);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (!q_rows || !k || !v || !cu_seqlens || !row_pos || !out_rows || !k_rot_out) {
+    set_error("earn_prefill_register_rows: a required pointer is NULL");
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (desc->dtype != EARN_BF16) { set_error("earn_prefill_register_rows: bf16 only"); return EARN_ERR_UNSUPPORTED; }
+  const size_t need = prefill_rows_workspace_bytes(desc->n_q_heads, desc->n_kv_heads, desc->head_dim, batch, max_seqlen, rows_per_seq);
+  if (need > workspace_bytes || (need > 0 && !workspace)) {
+    set_error("earn_prefill_register_rows: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
+    return EARN_ERR_WORKSPACE_TOO_SMALL;
+  }
+  rc = launch_rope_keys(desc, k, k_rot_out, cu_seqlens, nullptr, batch, total_tokens, (hipStream_t)stream);
+  if (rc != EARN_OK) return rc;
+  return launch_prefill_rows(desc, q_rows, k_rot_out, v, cu_seqlens, row_pos, batch, max_seqlen, rows_per_seq, out_rows,
+                             workspace, workspace_bytes, (hipStream_t)stream);
 }
 
 int64_t earn_cache_entries(int32_t n_layers, int32_t split_k, int64_t seq_len, int32_t n_registers, int64_t gen) {

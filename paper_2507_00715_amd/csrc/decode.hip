@@ -73,6 +73,10 @@ struct DecodeParams {
   void* out; float* part_o; float* part_ml;
   int gen_cap, n_streams, batch, hq, hkv, n_splits, chunk;  // chunk: keys per split (multiple of 64)
   int n_slots;    // partial-result slots per (stream, head) in the workspace (one per key split)
+  // Prefill of chosen rows with the decode machinery (0 = decode).  r > 0: the "streams" are r query rows per sequence
+  // (stream s*r + i belongs to sequence s), q_pos[u] is the row's token index in its sequence, a row sees shared keys
+  // 0 .. q_pos[u] (causal), and there is no generated part and no new token.
+  int causal_rows;
   float scale_log2;
   RopeTable rope;
 };
@@ -464,7 +468,8 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       qp[k4] = in ? p.q_pos[u] : 0;
     }
   };
-  if (wave == 0 && p.stream_to_seq) fetch_lists(0);
+  const bool causal = p.causal_rows > 0;
+  if (wave == 0 && p.stream_to_seq && !causal) fetch_lists(0);
   const int b0 = p.shared_cu[s], ns = p.shared_cu[s + 1] - b0;
   const int j_begin = z * p.chunk;
   const int j_end = min(ns, j_begin + p.chunk);
@@ -492,19 +497,26 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     stager.issue(stager.k_rsrc, at, t);
     stager.issue(stager.v_rsrc, at + (unsigned)(kTileKeys * D * 2), t);
   };
-  auto issue_first_tiles = [&]() {
+  auto issue_first_tiles = [&](int nt) {
 #pragma unroll
     for (int t = 0; t < kDsRing - 1; ++t)
-      if (t < n_tiles) issue_tile(t);
+      if (t < nt) issue_tile(t);
   };
-  // the first tiles are requested before anything else: they fly while the stream list is built, the generated rows
-  // are handled and the queries are rotated
-  issue_first_tiles();
+  // the first tiles are requested before anything else: they fly while the stream list is built and the queries are
+  // rotated
+  issue_first_tiles(n_tiles);
 
   // ---- streams (beams) of this sequence, ascending ----
   if (wave == 0) {
     int count = 0, gmax = 0;
-    if (!p.stream_to_seq) {
+    if (causal) {
+      count = p.causal_rows;
+      for (int i = lane; i < count; i += kWave) {
+        sm.streams[i] = s * count + i;
+        sm.glen[i] = 0;
+        sm.qpos[i] = (float)p.q_pos[s * count + i];
+      }
+    } else if (!p.stream_to_seq) {
       gmax = p.gen_len[s];
       if (lane == 0) { sm.streams[0] = s; sm.glen[0] = gmax; sm.qpos[0] = (float)p.q_pos[s]; }
       count = 1;
@@ -536,7 +548,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   const int M = n_st * gq;  // query rows sharing this cache
   // the generated part as a key list of its own: n_st streams x gp rows (rows past a stream's own length are masked)
   const int gp = sm.gen_pitch;
-  const int n_gen_keys = n_st * gp;
+  const int n_gen_keys = causal ? 0 : n_st * gp;
   const int n_gen_tiles = (n_gen_keys + kTileKeys - 1) / kTileKeys;
   const int tg0 = p.n_splits - 1 - z;  // this workgroup takes generated tiles tg0, tg0 + n_splits, ...: the last split,
                                        // whose key range is the shortest, takes the first
@@ -684,6 +696,25 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     // time to spare here, LDS space has not); keys past the range end get zero weight
     // SHIFTED: the accumulator starts at -m in every register (the steady state: no subtraction on the vector ALU),
     // else at 0 (the exact path, which needs the raw scores)
+    const int q_si = min(row0 + 32 * grp + r32, M - 1) / gq;
+    // causal rows: this lane's row sees keys 0 .. my_pos, the wave's rows at least 0 .. wave_min_pos
+    int my_pos = 0, wave_min_pos = 0, wave_max_pos = 0;
+    int nt = n_tiles;  // tiles of the key range this pass walks: with causal rows, those holding a key some row sees
+    if (causal) {
+      my_pos = (int)sm.qpos[q_si];
+      wave_min_pos = wave_max_pos = my_pos;
+#pragma unroll
+      for (int off = 1; off < 32; off <<= 1) {
+        wave_min_pos = min(wave_min_pos, __shfl_xor(wave_min_pos, off, kWave));
+        wave_max_pos = max(wave_max_pos, __shfl_xor(wave_max_pos, off, kWave));
+      }
+      wave_min_pos = __builtin_amdgcn_readfirstlane(wave_min_pos);
+      wave_max_pos = __builtin_amdgcn_readfirstlane(wave_max_pos);
+      int pass_max_pos = 0;
+      for (int i = row0 / gq; i <= min(M - 1, row0 + ROWS - 1) / gq; ++i) pass_max_pos = max(pass_max_pos, (int)sm.qpos[i]);
+      pass_max_pos = __builtin_amdgcn_readfirstlane(pass_max_pos);
+      nt = min(n_tiles, (max(pass_max_pos + 1 - j_begin, 0) + kTileKeys - 1) / kTileKeys);
+    }
     // `mask` sets the scores of keys this lane's query row must not see to -inf
     auto scores = [&](int slot, f32x16& sc, auto shifted, auto mask) {
       const __bf16* my_k = sm.tile[slot][0] + ksub * kDsTile * D;
@@ -713,11 +744,15 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
           for (int i = 0; i < 16; ++i)
             if (key0 + 8 * (i >> 2) + 4 * hf + (i & 3) >= j_end) sc[i] = -INFINITY;
         }
+        if (causal && key0 + kDsTile - 1 > wave_min_pos) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (key0 + 8 * (i >> 2) + 4 * hf + (i & 3) > my_pos) sc[i] = -INFINITY;
+        }
       };
     };
     // generated rows: a query row sees keys [gen_lo, gen_hi] of the generated key list, its own stream's rows
     // including the new token
-    const int q_si = min(row0 + 32 * grp + r32, M - 1) / gq;
     const int gen_lo = q_si * gp, gen_hi = gen_lo + sm.glen[q_si];
     auto gen_mask = [&](int tg) {
       return [&, tg](f32x16& sc) {
@@ -785,7 +820,8 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     };
     // does this wave have keys in super-tile `it`?
     auto has_keys = [&](int it) {
-      return grp_active && it * kTileKeys + ksub * kDsTile < n_keys;
+      const int k0 = it * kTileKeys + ksub * kDsTile;
+      return grp_active && k0 < n_keys && (!causal || j_begin + k0 <= wave_max_pos);
     };
 
     // Every tile iteration opens with exactly one barrier, whichever path a wave takes.  The steady-state loop takes
@@ -793,22 +829,22 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     // ALU; a reference is stale exactly when some exponential is large, which shows in the partial row sums
     // (+inf / NaN on the first tile, whose reference is -inf).  A wave that sees a stale reference leaves the loop,
     // takes the exact maxima of the tile, rescales, finishes the tile and re-enters.
-    if (row0 > 0) issue_first_tiles();  // further passes over the same keys for more query rows
+    if (row0 > 0) issue_first_tiles(nt);  // further passes over the same keys for more query rows
     // Iteration `it` opens with the barrier behind which tile `it` is complete (every wave has waited for its own part:
     // loads complete in order, so that means at most the younger tiles' loads are still in flight) and nobody reads
     // tile it-1 any more, whose ring slot the loads of tile it+3 then start to fill.
     auto sync_and_stage = [&](int it) {
-      const int younger = min(n_tiles - 1 - it, kDsRing - 2);  // tiles issued after tile `it`
+      const int younger = min(nt - 1 - it, kDsRing - 2);  // tiles issued after tile `it` (at least)
       if (younger >= 2) wait_vmcnt<2 * LPT>();
       else if (younger == 1) wait_vmcnt<LPT>();
       else wait_vmcnt<0>();
       lds_barrier();
-      if (it + kDsRing - 1 < n_tiles) issue_tile(it + kDsRing - 1);
+      if (it + kDsRing - 1 < nt) issue_tile(it + kDsRing - 1);
     };
     int it = 0;
-    while (it < n_tiles) {
+    while (it < nt) {
       bool rescale = false;
-      for (; it < n_tiles; ++it) {
+      for (; it < nt; ++it) {
         sync_and_stage(it);
         if (has_keys(it)) {
           f32x16 sc;
@@ -834,6 +870,10 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         ++it;
       }
     }
+
+    // Tiles requested before the pass knew how few it needs (causal rows) may still be on their way into the ring;
+    // nothing may be, past this point: the ring's memory is about to be written by the workgroup itself.
+    wait_vmcnt<0>();
 
     // ---- the generated key list: this workgroup's tiles of it, one at a time through ring slot 0 ----
     for (int tg = tg0; tg < n_gen_tiles; tg += p.n_splits) {
@@ -1044,7 +1084,7 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
   p.shared_k = shared_k; p.shared_v = shared_v; p.shared_cu = shared_cu; p.stream_to_seq = stream_to_seq;
   p.gen_k = gen_k; p.gen_v = gen_v; p.gen_len = gen_len; p.out = out;
   p.gen_cap = gen_cap; p.n_streams = n_streams; p.batch = batch; p.hq = hq; p.hkv = hkv;
-  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk;
+  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = 0;
   const size_t need = decode_workspace_bytes(desc->dtype, hq, hkv, d, n_streams, batch, max_shared_len, gen_cap);
   if (need > workspace_bytes || (need > 0 && !workspace)) {
     set_error("earn_decode_attn: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
@@ -1059,6 +1099,73 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
     if (d == 64) launch_decode_t<float, 64>(p, pl, gq, stream); else launch_decode_t<float, 128>(p, pl, gq, stream);
   } else {
     if (d == 64) launch_decode_t<__bf16, 64>(p, pl, gq, stream); else launch_decode_t<__bf16, 128>(p, pl, gq, stream);
+  }
+  return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
+}
+
+// ---- causal attention of r chosen rows per sequence over the sequence's full-length keys, on the shared-cache kernel:
+// the rows of a (sequence, kv head) are its "beams" ----
+static DecodePlan plan_rows(int hkv, int batch, int max_seqlen) {
+  DecodePlan pl;
+  pl.mfma = true;
+  const long long base = (long long)hkv * batch;
+  int n = (int)((256 + base - 1) / base);
+  const int cap = (max_seqlen + kDsSuper - 1) / kDsSuper;
+  if (n > cap) n = cap;
+  if (n < 1) n = 1;
+  if (n > 64) n = 64;
+  pl.n_splits = pl.n_slots = n;
+  pl.chunk = (((max_seqlen + n - 1) / n) + kDsSuper - 1) / kDsSuper * kDsSuper;
+  return pl;
+}
+
+size_t prefill_rows_workspace_bytes(int hq, int hkv, int d, int batch, int max_seqlen, int rows_per_seq) {
+  const DecodePlan pl = plan_rows(hkv, batch, max_seqlen);
+  if (pl.n_slots == 1) return 0;
+  const size_t rows = (size_t)batch * rows_per_seq * hq * pl.n_slots;
+  return rows * d * sizeof(float) + rows * 2 * sizeof(float);
+}
+
+int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
+                        const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen, int rows_per_seq,
+                        void* out_rows, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+  const int hq = desc->n_q_heads, hkv = desc->n_kv_heads, d = desc->head_dim, gq = hq / hkv;
+  if (desc->dtype != EARN_BF16) { set_error("earn_prefill_register_rows: bf16 only"); return EARN_ERR_UNSUPPORTED; }
+  if (rows_per_seq > kMaxStreamsPerSeq) {
+    set_error("earn_prefill_register_rows: more than %d rows per sequence", kMaxStreamsPerSeq);
+    return EARN_ERR_UNSUPPORTED;
+  }
+  if ((long long)(max_seqlen + kDsSuper) * hkv * d * 2 >= (1ll << 31)) {
+    set_error("earn_prefill_register_rows: a sequence of %d rows exceeds the 2 GiB addressing range of one sequence", max_seqlen);
+    return EARN_ERR_UNSUPPORTED;
+  }
+  const DecodePlan pl = plan_rows(hkv, batch, max_seqlen);
+  const size_t need = prefill_rows_workspace_bytes(hq, hkv, d, batch, max_seqlen, rows_per_seq);
+  if (need > workspace_bytes || (need > 0 && !workspace)) {
+    set_error("earn_prefill_register_rows: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
+    return EARN_ERR_WORKSPACE_TOO_SMALL;
+  }
+  DecodeParams p;
+  p.q = q_rows; p.k_new = nullptr; p.v_new = nullptr; p.q_pos = row_pos;
+  p.shared_k = k_rot; p.shared_v = v; p.shared_cu = cu_seqlens; p.stream_to_seq = nullptr;
+  p.gen_k = nullptr; p.gen_v = nullptr; p.gen_len = nullptr; p.out = out_rows;
+  p.gen_cap = 0; p.n_streams = batch * rows_per_seq; p.batch = batch; p.hq = hq; p.hkv = hkv;
+  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = rows_per_seq;
+  p.part_o = (float*)workspace;
+  p.part_ml = p.part_o + (size_t)p.n_streams * hq * p.n_slots * d;
+  const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
+  p.scale_log2 = scale * 1.4426950408889634f;
+  p.rope = make_rope_table(desc->rope_base, d);
+  const dim3 grid((unsigned)(((long long)batch * p.n_splits + 7) / 8 * 8 * hkv), 1, 1);
+  const bool one_group = rows_per_seq * gq <= 32;
+  if (d == 64) {
+    if (one_group) hipLaunchKernelGGL((decode_shared_mfma_kernel<64, 1>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((decode_shared_mfma_kernel<64, 2>), grid, dim3(512), 0, stream, p);
+    if (p.n_slots > 1) launch_combine<__bf16, 64>(p, stream);
+  } else {
+    if (one_group) hipLaunchKernelGGL((decode_shared_mfma_kernel<128, 1>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((decode_shared_mfma_kernel<128, 2>), grid, dim3(512), 0, stream, p);
+    if (p.n_slots > 1) launch_combine<__bf16, 128>(p, stream);
   }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
 }

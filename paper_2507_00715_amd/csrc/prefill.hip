@@ -727,6 +727,21 @@ static void launch_rope_k(const void* k, void* k_rot, const int32_t* cu, const i
                      (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope, cs_out);
 }
 
+// K rotation on its own (for callers that run the attention with another kernel)
+int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, const int32_t* cu_seqlens,
+                     const int32_t* positions, int batch, int total_tokens, hipStream_t stream) {
+  const RopeTable rope = make_rope_table(desc->rope_base, desc->head_dim);
+  const int hkv = desc->n_kv_heads;
+  if (desc->dtype == EARN_F32) {
+    if (desc->head_dim == 64) launch_rope_k<float, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, hkv, rope, nullptr, stream);
+    else launch_rope_k<float, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, hkv, rope, nullptr, stream);
+  } else {
+    if (desc->head_dim == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, hkv, rope, nullptr, stream);
+    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, hkv, rope, nullptr, stream);
+  }
+  return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
+}
+
 int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
                    const int32_t* positions, int batch, int total_tokens, int max_seqlen, void* out, void* k_rot_out,
                    float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {

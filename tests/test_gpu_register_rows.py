@@ -1,0 +1,84 @@
+"""Parity of earn_prefill_register_rows — the last full-length layer evaluated at the register rows only — with the
+fp64 oracle: the oracle runs the plain causal attention of Eq. 3 over the whole sequences and is read at the register
+rows (its row_sel only spares it the other rows' work).  The query rows and their positions come from
+earn_compact_registers, as in the path itself.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import earn_oracle as O
+from paper_2507_00715_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+BF16_REL = 2e-2
+
+
+def _B():
+    from paper_2507_00715_amd import binding
+    binding.lib()
+    return binding
+
+
+def rel_fro(got, ref):
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30))
+
+
+CASES = [
+    # hq, hkv, d, h, t, sequence lengths (registers included)
+    (8, 2, 128, 4, 4, [300, 64, 1000, 9]),          # 32 query rows per cache: one pass; one sequence barely longer than r
+    (14, 2, 64, 8, 8, [17, 530, 2100]),             # 7 heads per kv head: 112 rows per cache, two passes
+    (4, 4, 64, 2, 0, [50, 700]),                    # no suffix registers, one query head per kv head
+    (4, 2, 128, 0, 3, [129, 3, 640]),               # no prefix registers; a sequence that is all registers
+    (32, 8, 128, 32, 32, [4200, 64, 1500]),         # 256 rows per cache: four passes, prefix-only passes stop early
+]
+
+
+@pytest.mark.parametrize("hq,hkv,d,h,t,lens", CASES)
+def test_register_rows_of_last_full_layer(hq, hkv, d, h, t, lens):
+    B = _B()
+    r, batch, T = h + t, len(lens), sum(lens)
+    gtor = torch.Generator().manual_seed(1000 * hq + T)
+    rnd = lambda *shape: torch.randn(*shape, generator=gtor).to(torch.bfloat16)
+    q, k, v = rnd(T, hq, d), rnd(T, hkv, d), rnd(T, hkv, d)
+    k[::7] *= 6.0  # a few large keys: the running softmax reference has to move
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    d_cu = torch.from_numpy(cu).to(DEV)
+    d_q, d_k, d_v = q.to(DEV), k.to(DEV), v.to(DEV)
+
+    # the register rows of Q and their positions, as the path gets them
+    q_rows = torch.empty(batch * r, hq, d, dtype=torch.bfloat16, device=DEV)
+    idx, pos = (torch.empty(batch * r, dtype=torch.int32, device=DEV) for _ in range(2))
+    cu_c = torch.empty(batch + 1, dtype=torch.int32, device=DEV)
+    B.earn_compact_registers([d_q], [q_rows], d_cu, batch, h, t, idx, pos, cu_c)
+
+    desc = B.make_desc(torch.bfloat16, hq, hkv, d)
+    out = torch.full((batch * r, hq, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    k_rot = torch.empty_like(d_k)
+    ws = torch.empty(max(B.earn_prefill_register_rows_workspace_bytes(desc, batch, max(lens), r), 256),
+                     dtype=torch.uint8, device=DEV)
+    B.earn_prefill_register_rows(desc, q_rows, d_k, d_v, d_cu, pos, batch, T, max(lens), r, out, k_rot, ws)
+    torch.cuda.synchronize()
+
+    ref_c = O.compact_registers(None, cu, h, t)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref_c["idx"])
+    sel = np.zeros(T, dtype=np.uint8)
+    sel[ref_c["idx"]] = 1
+    ref = O.prefill_attn(W.to_f64(q), W.to_f64(k), W.to_f64(v), cu, row_sel=sel)
+    got = out.cpu().double().numpy()
+    assert np.isfinite(got).all()
+    want = ref["out"][ref_c["idx"]]
+    for s in range(batch):
+        rows = slice(s * r, (s + 1) * r)
+        err = rel_fro(got[rows], want[rows])
+        assert err <= BF16_REL, f"sequence {s} (n={lens[s]}): rel-Frobenius {err:.3e}"
+    row_err = np.linalg.norm(got - want, axis=(1, 2)) / np.maximum(np.linalg.norm(want, axis=(1, 2)), 1e-30)
+    assert row_err.max() <= 3 * BF16_REL, f"row {int(row_err.argmax())} off by {row_err.max():.3e}"
+    assert rel_fro(k_rot.cpu().double().numpy(), ref["k_rot"]) <= BF16_REL
+
+    # the same rows from the full-length entry point (it computes every row): the two HIP paths agree as well
+    full = torch.empty(T, hq, d, dtype=torch.bfloat16, device=DEV)
+    B.earn_prefill_attn(desc, d_q, d_k, d_v, d_cu, None, batch, T, max(lens), full, torch.empty_like(d_k), None, None)
+    torch.cuda.synchronize()
+    assert rel_fro(got, full[idx.long()].cpu().double().numpy()) <= BF16_REL
