@@ -166,6 +166,33 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
     ms = tm.totals_ms()
     alg = algorithmic_counts(w)
 
+    # Beyond the paper's method, exact: layer k-1 evaluated at the register rows only (its other outputs are dropped by
+    # the compaction).  Timed on its own, gather of the query rows included; the timed steps above do not use it.
+    rows_only = None
+    if c.dtype == "bf16" and 0 < kk < N:
+        from paper_2507_00715_amd import binding as B
+        l = kk - 1
+        q_rows = torch.empty(path.Tc, c.n_q_heads, c.head_dim, dtype=c.torch_dtype, device=dev)
+        out_rows = torch.empty_like(q_rows)
+        ws = torch.empty(max(B.earn_prefill_register_rows_workspace_bytes(path.desc, path.batch, path.max_seqlen, path.r),
+                             256), dtype=torch.uint8, device=dev)
+
+        def rows_layer():
+            B.earn_compact_registers([q[l]], [q_rows], path.cu, path.batch, path.h, path.t, path.idx, path.pos, path.cu_c)
+            B.earn_prefill_register_rows(path.desc, q_rows, k[l], v[l], path.cu, path.pos, path.batch, path.T,
+                                         path.max_seqlen, path.r, out_rows, path.k_cache[l], ws)
+        rows_layer()
+        reps = 10
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            rows_layer()
+        e1.record()
+        torch.cuda.synchronize()
+        rows_only = e0.elapsed_time(e1) / reps
+        del q_rows, out_rows, ws
+
     full_ms = ms["prefill_full"] / (steps * kk)              # per launch of the dominant kernel (+ its K rotation)
     reg_ms = ms["prefill_reg"] / (steps * max(N - kk, 1))
     prefill_flops = kk * alg["flops_full"] + (N - kk) * alg["flops_reg"]
@@ -197,6 +224,11 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
                    "register_cache_layers": {"us_per_layer": ms["decode_reg"] * 1e3 / (steps * G * max(N - kk, 1)),
                                              "GBps": dec_reg_gbps, "frac_of_hbm_peak": dec_reg_gbps / PEAK_HBM_GBPS}},
         "phase_ms_per_step": {k_: v_ / steps for k_, v_ in ms.items()},
+        "last_full_layer_register_rows_only": None if rows_only is None else {
+            "ms_per_launch": rows_only, "full_layer_ms_per_launch": ms["prefill_full"] / (steps * kk),
+            "ms_per_step_with_it": (wall * 1e3 - ms["prefill_full"] / kk) / steps + rows_only,
+            "note": "layer k-1 at the B*r register rows only (gather of the query rows + K rotation + attention); "
+                    "exact, beyond the paper's method; not used inside the timed steps"},
         # Context, attention only (not comparable with the paper's end-to-end figures): the same N layers run the
         # vanilla way (every layer full length) would cost N full-layer launches; next to it the closed forms of
         # Section 3.3 (k/N for attention work, (k n + (N-k) r)/(N n) for cache entries).
@@ -370,6 +402,7 @@ def main():
         "prefill_register_layer": head["prefill_register_layer"],
         "phase_ms_per_step": head["phase_ms_per_step"],
         "launch_floor_us": floor_us,
+        "last_full_layer_register_rows_only": head["last_full_layer_register_rows_only"],
         "attention_only_vs_vanilla": head["attention_only_vs_vanilla"],
         "other_workloads": {n: {kk: vv for kk, vv in r.items()} for n, r in others.items()},
     }

@@ -6,6 +6,11 @@
     layers k..N-1    earn_prefill_attn on the r = h+t register rows with their original positions
     decode step g    earn_decode_attn per layer: full cache for layers < k, register cache for layers >= k
 
+With rows_only_last_full_layer=True, layer k-1 — whose outputs at prompt tokens nothing downstream reads, since the
+input of layer k keeps the register rows only — is evaluated at the register rows alone (earn_prefill_register_rows on
+the gathered query rows); its keys and values stay full length, they are the layer's cache.  prefill_out[k-1] then
+holds the B*r register rows in compacted order.
+
 All buffers are allocated once in the constructor; the methods only enqueue kernels on the current stream.
 """
 from __future__ import annotations
@@ -21,7 +26,7 @@ class EarnPath:
     def __init__(self, *, n_layers: int, split_k: int, n_head_reg: int, n_tail_reg: int, n_q_heads: int,
                  n_kv_heads: int, head_dim: int, dtype: torch.dtype, cu_seqlens: Sequence[int],
                  stream_to_seq: Sequence[int], gen_cap: int, rope_base: float = 10000.0, softmax_scale: float = 0.0,
-                 device="cuda:0", want_lse: bool = False):
+                 device="cuda:0", want_lse: bool = False, rows_only_last_full_layer: bool = False):
         self.N, self.k, self.h, self.t = n_layers, split_k, n_head_reg, n_tail_reg
         self.r = n_head_reg + n_tail_reg
         self.hq, self.hkv, self.d, self.dtype = n_q_heads, n_kv_heads, head_dim, dtype
@@ -35,6 +40,9 @@ class EarnPath:
         self.Tc = self.batch * self.r
         self.S = len(stream_to_seq)
         self.gen_cap = gen_cap
+        self.rows_only = bool(rows_only_last_full_layer) and 0 < split_k < n_layers
+        if self.rows_only and dtype != torch.bfloat16:
+            raise ValueError("rows_only_last_full_layer needs bf16 (earn_prefill_register_rows)")
         dev, i32 = self.device, torch.int32
         self.cu = torch.tensor(list(cu_seqlens), dtype=i32, device=dev)
         self.stream_to_seq = torch.tensor(list(stream_to_seq), dtype=i32, device=dev)
@@ -44,7 +52,9 @@ class EarnPath:
         self.cu_c = torch.empty(self.batch + 1, dtype=i32, device=dev)
         e = lambda *shape: torch.empty(shape, dtype=dtype, device=dev)
         N, k = self.N, self.k
-        self.prefill_out = [e(self.T if l < k else self.Tc, self.hq, self.d) for l in range(N)]
+        rows_layer = k - 1 if self.rows_only else -1
+        self.prefill_out = [e(self.T if l < k and l != rows_layer else self.Tc, self.hq, self.d) for l in range(N)]
+        self.q_rows = e(self.Tc, self.hq, self.d) if self.rows_only else None
         self.k_cache = [e(self.T if l < k else self.Tc, self.hkv, self.d) for l in range(N)]
         self.v_cache: List[Optional[torch.Tensor]] = [None] * N       # layers < k alias the caller's V
         self.x_c: Optional[torch.Tensor] = None
@@ -63,12 +73,23 @@ class EarnPath:
         self.workspace = torch.empty(ws, dtype=torch.uint8, device=dev)
         pws = max(B.earn_prefill_workspace_bytes(self.desc, self.batch, self.T, self.max_seqlen, True),
                   B.earn_prefill_workspace_bytes(self.desc, self.batch, self.Tc, self.r, True), 256)
+        if self.rows_only:
+            pws = max(pws, B.earn_prefill_register_rows_workspace_bytes(self.desc, self.batch, self.max_seqlen, self.r))
         self.prefill_workspace = torch.empty(pws, dtype=torch.uint8, device=dev)
 
     # ---- prefill ----
     def prefill_full_layer(self, l: int, q, k, v) -> None:
         B.earn_prefill_attn(self.desc, q, k, v, self.cu, None, self.batch, self.T, self.max_seqlen,
                             self.prefill_out[l], self.k_cache[l], self.lse[l], self.prefill_workspace)
+        self.v_cache[l] = v
+
+    def prefill_last_full_layer_rows(self, q, k, v) -> None:
+        """Layer k-1 at the register rows only: gather its query rows (which also yields idx/pos/cu_c), then attend."""
+        l = self.k - 1
+        B.earn_compact_registers([q], [self.q_rows], self.cu, self.batch, self.h, self.t, self.idx, self.pos, self.cu_c)
+        B.earn_prefill_register_rows(self.desc, self.q_rows, k, v, self.cu, self.pos, self.batch, self.T,
+                                     self.max_seqlen, self.r, self.prefill_out[l], self.k_cache[l],
+                                     self.prefill_workspace)
         self.v_cache[l] = v
 
     def compact(self, x: Optional[torch.Tensor], q: Sequence[torch.Tensor], k: Sequence[torch.Tensor],
@@ -98,7 +119,10 @@ class EarnPath:
     def prefill(self, q: Sequence[torch.Tensor], k: Sequence[torch.Tensor], v: Sequence[torch.Tensor],
                 x: Optional[torch.Tensor]) -> None:
         for l in range(self.k):
-            self.prefill_full_layer(l, q[l], k[l], v[l])
+            if self.rows_only and l == self.k - 1:
+                self.prefill_last_full_layer_rows(q[l], k[l], v[l])
+            else:
+                self.prefill_full_layer(l, q[l], k[l], v[l])
         if self.k < self.N:
             self.compact(x, q, k, v)
             for l in range(self.k, self.N):

@@ -8,6 +8,7 @@ import pytest
 import torch
 
 from oracle import earn_oracle as O
+from oracle import pipeline as OP
 from paper_2507_00715_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -82,3 +83,38 @@ def test_register_rows_of_last_full_layer(hq, hkv, d, h, t, lens):
     B.earn_prefill_attn(desc, d_q, d_k, d_v, d_cu, None, batch, T, max(lens), full, torch.empty_like(d_k), None, None)
     torch.cuda.synchronize()
     assert rel_fro(got, full[idx.long()].cpu().double().numpy()) <= BF16_REL
+
+
+def test_whole_path_with_register_rows_only_in_the_last_full_layer():
+    """The path with layer k-1 evaluated at the register rows only: that layer's outputs are the oracle's full-length
+    outputs read at the register rows, and everything downstream (caches, later layers, decode steps) is unchanged."""
+    from paper_2507_00715_amd.pipeline import EarnPath
+    _B()
+    cfg = W.CONFIGS["small_gqa"].replace(n_layers=4, split_k=2, decode_steps=2, batch=5)
+    w = W.Workload(cfg, history_lengths=[256, 300, 512, 0, 64])
+    N, G, kk = cfg.n_layers, cfg.decode_steps, cfg.split_k
+    mk = lambda which, dev: [w.prefill_tensor(which, l, device=dev) for l in range(N)]
+    dmk = lambda which, dev: [[w.decode_tensor(which, l, g, device=dev) for l in range(N)] for g in range(G)]
+    inputs = lambda dev: dict(q=mk("q", dev), k=mk("k", dev), v=mk("v", dev), x=w.prefill_tensor("x", 0, device=dev),
+                              dq=dmk("q", dev), dk=dmk("k", dev), dv=dmk("v", dev))
+    cpu, gpu = inputs("cpu"), inputs(DEV)
+    ref = OP.run(n_layers=N, split_k=kk, n_head_reg=cfg.n_head_reg, n_tail_reg=cfg.n_tail_reg, cu_seqlens=w.cu_seqlens,
+                 stream_to_seq=w.stream_to_seq, rope_base=cfg.rope_base, **cpu)
+    path = EarnPath(n_layers=N, split_k=kk, n_head_reg=cfg.n_head_reg, n_tail_reg=cfg.n_tail_reg,
+                    n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, dtype=cfg.torch_dtype,
+                    cu_seqlens=w.cu_seqlens, stream_to_seq=w.stream_to_seq, gen_cap=G, rope_base=cfg.rope_base,
+                    device=DEV, rows_only_last_full_layer=True)
+    path.prefill(gpu["q"], gpu["k"], gpu["v"], gpu["x"])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(path.idx.cpu().numpy(), ref["idx"])
+    f64 = lambda t: t.detach().cpu().double().numpy()
+    for l in range(N):
+        want = ref["prefill_out"][l][ref["idx"]] if l == kk - 1 else ref["prefill_out"][l]
+        assert path.prefill_out[l].shape[0] == want.shape[0]
+        assert rel_fro(f64(path.prefill_out[l]), want) <= BF16_REL, f"prefill layer {l}"
+        assert rel_fro(f64(path.k_cache[l]), ref["k_cache"][l]) <= BF16_REL, f"k cache layer {l}"
+    for g in range(G):
+        path.decode_step(g, gpu["dq"][g], gpu["dk"][g], gpu["dv"][g])
+        torch.cuda.synchronize()
+        for l in range(N):
+            assert rel_fro(f64(path.decode_out[l]), ref["decode_out"][g][l]) <= BF16_REL, f"decode step {g} layer {l}"
