@@ -109,6 +109,32 @@ def test_decode_argument_errors():
     assert B.earn_decode_workspace_bytes(_desc(hq=32, hkv=8, d=128), 160, 16, 8256, 8) >= 2 * 160 * 32 * (128 + 2) * 4
 
 
+def test_register_rows_argument_errors():
+    lib = B.lib()
+    fake = ctypes.c_void_p(256)
+
+    def call(desc=None, q=fake, pos=fake, batch=2, total=600, maxlen=400, r=8, krot=fake, ws=None, ws_bytes=0):
+        desc = desc or _desc(hq=8, hkv=2, d=128)
+        return lib.earn_prefill_register_rows(ctypes.byref(desc), q, fake, fake, fake, pos, batch, total, maxlen, r,
+                                              fake, krot, ws, ws_bytes, None)
+
+    assert call(q=None) == B.EARN_ERR_INVALID_ARG
+    assert call(pos=None) == B.EARN_ERR_INVALID_ARG
+    assert call(krot=None) == B.EARN_ERR_INVALID_ARG          # the rotated keys are the layer's cache: required
+    assert call(batch=0) == B.EARN_ERR_INVALID_ARG
+    assert call(r=0) == B.EARN_ERR_INVALID_ARG
+    assert call(r=500) == B.EARN_ERR_INVALID_ARG and b"rows_per_seq" in lib.earn_last_error()
+    assert call(desc=_desc(dtype=B.EARN_F32, hq=8, hkv=2, d=128)) == B.EARN_ERR_UNSUPPORTED
+    assert call(desc=_desc(hq=8, hkv=2, d=32)) == B.EARN_ERR_UNSUPPORTED
+    # two sequences x two kv heads leave room for key splits: partial results need workspace
+    need = B.earn_prefill_register_rows_workspace_bytes(_desc(hq=8, hkv=2, d=128), 2, 400, 8)
+    assert need >= 2 * (2 * 8) * 8 * (128 + 2) * 4 and need % 4 == 0
+    assert call() == B.EARN_ERR_WORKSPACE_TOO_SMALL
+    # enough (sequence, kv head) pairs: nothing is split, no workspace
+    assert B.earn_prefill_register_rows_workspace_bytes(_desc(hq=8, hkv=8, d=128), 64, 400, 8) == 0
+    assert B.earn_prefill_register_rows_workspace_bytes(_desc(hq=8, hkv=3, d=128), 2, 400, 8) == 0  # invalid desc
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(AssertionError):
