@@ -390,6 +390,11 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const float* __rest
 // against ALL query rows with a mask that lets a query row see only its own stream's rows: a few tiles more for a
 // workgroup that walks dozens, instead of a second, latency-bound pass in vector code.  The workgroup that owns such a
 // tile also rotates the new token's key and appends key and value to the stream's cache (Eq. 4).
+// Without key splits (enough (sequence, kv head) pairs to fill the GPU) the kernel normalises and stores the outputs.
+//
+// The same kernel computes prefill attention at chosen rows (DecodeParams::causal_rows): the r register rows of a
+// sequence against the sequence's full-length keys (Section 3.2: the input of layer k keeps only those rows of layer
+// k-1's output) are r "beams" with a causal limit each and without a generated part.
 // ------------------------------------------------------------------------------------------------------------------
 constexpr int kDsTile = 32;              // keys per wave sub-tile
 constexpr int kDsGroupWaves = 4;         // waves per 32-row group: 2 key sub-tiles x 2 halves of the head dimension
