@@ -340,7 +340,16 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
 template <typename T, int D, int GQ, int WAVES>
 __global__ __launch_bounds__(kWave * WAVES) void decode_kernel(DecodeParams p) {
   __shared__ float sm[WAVES > 1 ? WAVES * GQ * (D / 8) * 10 : 1];
-  decode_rows<T, D, GQ, WAVES>(p, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x / kWave, threadIdx.x % kWave,
+  // Workgroup -> (kv head c, stream u, key split z).  Linear ids go to the 8 XCDs round-robin.  The hkv workgroups that
+  // read the interleaved head slices of the same cache rows (one (u, z), all c) get ids 8 apart: one XCD then sees
+  // whole rows, i.e. all address residues, instead of the same few head slices of every row (which would load only
+  // a few of its L2 channels).
+  const int n_uz = p.n_streams * p.n_splits, n_uz8 = (n_uz + 7) / 8 * 8;
+  const int L = blockIdx.x;
+  const int uz = (L / (8 * p.hkv)) * 8 + L % 8;
+  const int c = (L / 8) % p.hkv;
+  if (uz >= n_uz || L >= n_uz8 * p.hkv) return;
+  decode_rows<T, D, GQ, WAVES>(p, c, uz % p.n_streams, uz / p.n_streams, threadIdx.x / kWave, threadIdx.x % kWave,
                                p.chunk, sm);
 }
 
@@ -1003,7 +1012,8 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
     const int max_total = max_shared_len + gen_cap;
     // aim at >= 1024 workgroups (4 per CU) while keeping at least 256 keys per split
     long long base = (long long)hkv * n_streams;
-    int want = (int)((1024 + base - 1) / base);
+    static const int wgs_env = getenv("EARN_DEC_VEC_WGS") ? atoi(getenv("EARN_DEC_VEC_WGS")) : 1024;
+    int want = (int)((wgs_env + base - 1) / base);
     int cap = (max_total + 255) / 256;
     int n = want < cap ? want : cap;
     if (n < 1) n = 1;
@@ -1054,7 +1064,7 @@ static void launch_combine(const DecodeParams& p, hipStream_t stream) {
 template <typename T, int D>
 static void launch_decode_t(DecodeParams& p, const DecodePlan& pl, int gq, hipStream_t stream) {
   if (!pl.mfma) {
-    launch_vector<T, D>(p, gq, dim3(p.hkv, p.n_streams, p.n_splits), stream);
+    launch_vector<T, D>(p, gq, dim3((unsigned)(((long long)p.n_streams * p.n_splits + 7) / 8 * 8 * p.hkv), 1, 1), stream);
     if (p.n_slots > 1) launch_combine<T, D>(p, stream);
     return;
   }
