@@ -234,6 +234,39 @@ def test_decode_matches_oracle(dtype, hq, hkv, d, slens, beams, glens, gen_cap):
         assert torch.equal(got_gk[u, keep], gk[u, keep]) and torch.equal(got_gv[u, keep], gv[u, keep])
 
 
+@pytest.mark.parametrize("dtype,hq,hkv,d,slens", [(torch.bfloat16, 8, 2, 128, [300, 129, 1000]),   # matrix-core kernel
+                                                   (torch.bfloat16, 4, 4, 64, [300, 16, 70]),        # vector kernel
+                                                   (torch.float32, 4, 2, 64, [40, 9])])
+def test_decode_without_stream_map(dtype, hq, hkv, d, slens):
+    """stream_to_seq = NULL means one stream per sequence, stream u reading sequence u's cache."""
+    B = _B()
+    gtor = torch.Generator().manual_seed(7 * sum(slens) + hq)
+    rnd = lambda *shape: torch.randn(*shape, generator=gtor).to(dtype)
+    S = len(slens)
+    glens, gen_cap = [u % 3 for u in range(S)], 3
+    cu = np.concatenate([[0], np.cumsum(slens)]).astype(np.int32)
+    sk, sv = rnd(int(cu[-1]), hkv, d), rnd(int(cu[-1]), hkv, d)
+    q, kn, vn = rnd(S, hq, d), rnd(S, hkv, d), rnd(S, hkv, d)
+    gk, gv = rnd(S, gen_cap, hkv, d), rnd(S, gen_cap, hkv, d)
+    q_pos = [slens[u] + glens[u] for u in range(S)]
+    desc = B.make_desc(dtype, hq, hkv, d)
+    dev = lambda x: x.to(DEV)
+    i32 = lambda x: torch.tensor(list(x), dtype=torch.int32, device=DEV)
+    d_gk, d_gv = dev(gk), dev(gv)
+    out = torch.full((S, hq, d), float("nan"), dtype=dtype, device=DEV)
+    ws = torch.empty(max(B.earn_decode_workspace_bytes(desc, S, S, max(slens), gen_cap), 1), dtype=torch.uint8, device=DEV)
+    B.earn_decode_attn(desc, dev(q), dev(kn), dev(vn), i32(q_pos), dev(sk), dev(sv), i32(cu), None, d_gk, d_gv,
+                       i32(glens), gen_cap, S, S, max(slens), out, ws)
+    torch.cuda.synchronize()
+    o_gk, o_gv = W.to_f64(gk), W.to_f64(gv)
+    ref = O.decode_attn(W.to_f64(q), W.to_f64(kn), W.to_f64(vn), q_pos, W.to_f64(sk), W.to_f64(sv), cu, list(range(S)),
+                        o_gk, o_gv, glens)
+    check_attn(out, ref["out"], dtype, "out")
+    for u in range(S):
+        check_attn(d_gk[u, glens[u]], o_gk[u, glens[u]], dtype, "gen_k slot")
+        assert torch.equal(d_gv[u, glens[u]].cpu(), vn[u])
+
+
 # --------------------------------------------------------------------------------------------------
 def _pipeline_inputs(w, device):
     cfg = w.cfg
