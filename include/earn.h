@@ -179,7 +179,7 @@ size_t earn_decode_workspace_bytes(const earn_attn_desc* desc, int32_t n_streams
  *   out_rows      device, [batch*r, Hq, d]
  *   k_rot_out     device, [total_tokens, Hkv, d], required: the rotated keys = the layer's cache
  *   workspace     at least earn_prefill_register_rows_workspace_bytes(...) bytes, 256-byte aligned; may be NULL when 0
- * bf16 only (EARN_ERR_UNSUPPORTED otherwise).  Enqueues on `stream`, allocates nothing, does not synchronise.
+ * Both dtypes (fp32 needs no workspace).  Enqueues on `stream`, allocates nothing, does not synchronise.
  */
 int earn_prefill_register_rows(const earn_attn_desc* desc, const void* q_rows, const void* k, const void* v,
                                const int32_t* cu_seqlens, const int32_t* row_pos, int32_t batch, int32_t total_tokens,

@@ -48,6 +48,9 @@ size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, 
                               int gen_cap);
 int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, const int32_t* cu_seqlens,
                      const int32_t* positions, int batch, int total_tokens, hipStream_t stream);
+int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
+                            const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen,
+                            int rows_per_seq, void* out_rows, hipStream_t stream);
 size_t prefill_rows_workspace_bytes(int hq, int hkv, int d, int batch, int max_seqlen, int rows_per_seq);
 int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
                         const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen, int rows_per_seq,
@@ -163,6 +166,7 @@ size_t earn_prefill_register_rows_workspace_bytes(const earn_attn_desc* desc, in
   if (check_desc(desc, "earn_prefill_register_rows_workspace_bytes") != EARN_OK || batch <= 0 || max_seqlen < 0 ||
       rows_per_seq <= 0)
     return 0;
+  if (desc->dtype == EARN_F32) return 0;
   return prefill_rows_workspace_bytes(desc->n_q_heads, desc->n_kv_heads, desc->head_dim, batch, max_seqlen, rows_per_seq);
 }
 
@@ -185,7 +189,12 @@ int earn_prefill_register_rows(const earn_attn_desc* desc, const void* q_rows, c
     set_error("earn_prefill_register_rows: a required pointer is NULL");
     return EARN_ERR_INVALID_ARG;
   }
-  if (desc->dtype != EARN_BF16) { set_error("earn_prefill_register_rows: bf16 only"); return EARN_ERR_UNSUPPORTED; }
+  if (desc->dtype == EARN_F32) {
+    rc = launch_rope_keys(desc, k, k_rot_out, cu_seqlens, nullptr, batch, total_tokens, (hipStream_t)stream);
+    if (rc != EARN_OK) return rc;
+    return launch_prefill_rows_f32(desc, q_rows, k_rot_out, v, cu_seqlens, row_pos, batch, max_seqlen, rows_per_seq,
+                                   out_rows, (hipStream_t)stream);
+  }
   const size_t need = prefill_rows_workspace_bytes(desc->n_q_heads, desc->n_kv_heads, desc->head_dim, batch, max_seqlen, rows_per_seq);
   if (need > workspace_bytes || (need > 0 && !workspace)) {
     set_error("earn_prefill_register_rows: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);

@@ -35,6 +35,10 @@ struct PrefillParams {
   void* out; float* lse;
   int batch, hq, hkv, max_seqlen;
   int n_qblk;  // query blocks of the longest sequence
+  // chosen-rows mode of the vector kernel (rows_per_seq > 0): q and out hold rows_per_seq rows per sequence in
+  // compacted order, row m of sequence s being token row_pos[s * rows_per_seq + m] (ascending) of the sequence
+  const int32_t* row_pos;
+  int rows_per_seq;
   float scale_log2;
   RopeTable rope;
 };
@@ -128,17 +132,21 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   const int a = blockIdx.y, s = blockIdx.z;
   const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
   const int row0 = blockIdx.x * 64;
-  if (row0 >= n) return;
+  const int r = p.rows_per_seq;           // 0: every row of the sequence
+  const int n_rows = r > 0 ? r : n;
+  if (row0 >= n_rows) return;
   const int qt = threadIdx.x & 3;
-  const int i = row0 + (threadIdx.x >> 2);
-  const bool row_ok = i < n;
-  const int ic = row_ok ? i : n - 1;
+  const int mrow = row0 + (threadIdx.x >> 2);                  // row of the sequence's row list
+  const bool row_ok = mrow < n_rows;
+  const int mc = row_ok ? mrow : n_rows - 1;
+  const int ic = r > 0 ? p.row_pos[s * r + mc] : mc;           // its token index: it sees keys 0 .. ic
+  const long long io = r > 0 ? (long long)s * r + mc : (long long)b0 + mc;  // its row in q / out / lse
   const int c = a / (p.hq / p.hkv);
-  const T* qrow = (const T*)p.q + ((long long)(b0 + ic) * p.hq + a) * D;
+  const T* qrow = (const T*)p.q + (io * p.hq + a) * D;
   float ql[E], qh[E];
 #pragma unroll
   for (int e = 0; e < E; e += 8) { Vec8<T>::load(qrow + qt * E + e, ql + e); Vec8<T>::load(qrow + D / 2 + qt * E + e, qh + e); }
-  const int pos = p.positions ? p.positions[b0 + ic] : ic;
+  const int pos = (p.positions && r == 0) ? p.positions[b0 + ic] : ic;
 #pragma unroll
   for (int e = 0; e < E; ++e) {
     float sn = 0.f, cs = 1.f;
@@ -151,7 +159,8 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
 #pragma unroll
   for (int e = 0; e < E; ++e) { ol[e] = 0.f; oh[e] = 0.f; }
   // all rows of a wave walk the keys together up to the wave's last row
-  const int wave_last = min(n - 1, row0 + (int)(threadIdx.x / kWave) * 16 + 15);
+  const int wave_last_row = min(n_rows - 1, row0 + (int)(threadIdx.x / kWave) * 16 + 15);
+  const int wave_last = r > 0 ? p.row_pos[s * r + wave_last_row] : wave_last_row;
   const T* kbase = (const T*)p.k_rot + ((long long)b0 * p.hkv + c) * D;
   const T* vbase = (const T*)p.v + ((long long)b0 * p.hkv + c) * D;
   const long long rs = (long long)p.hkv * D;
@@ -183,10 +192,10 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   const float inv = 1.f / l;
 #pragma unroll
   for (int e = 0; e < E; ++e) { ol[e] *= inv; oh[e] *= inv; }
-  T* orow = (T*)p.out + ((long long)(b0 + i) * p.hq + a) * D;
+  T* orow = (T*)p.out + (io * p.hq + a) * D;
 #pragma unroll
   for (int e = 0; e < E; e += 8) { Vec8<T>::store(orow + qt * E + e, ol + e); Vec8<T>::store(orow + D / 2 + qt * E + e, oh + e); }
-  if (p.lse && qt == 0) p.lse[(long long)(b0 + i) * p.hq + a] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
+  if (p.lse && qt == 0) p.lse[io * p.hq + a] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -727,6 +736,24 @@ static void launch_rope_k(const void* k, void* k_rot, const int32_t* cu, const i
                      (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope, cs_out);
 }
 
+// fp32: the chosen rows of every sequence (q_rows, out_rows: [batch * r, Hq, d]) against the rotated keys, vector kernel
+int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
+                            const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen,
+                            int rows_per_seq, void* out_rows, hipStream_t stream) {
+  const int d = desc->head_dim;
+  PrefillParams p;
+  p.cs = nullptr; p.row_pos = row_pos; p.rows_per_seq = rows_per_seq;
+  p.q = q_rows; p.k_rot = k_rot; p.v = v; p.cu = cu_seqlens; p.positions = nullptr; p.out = out_rows; p.lse = nullptr;
+  p.batch = batch; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.max_seqlen = max_seqlen; p.n_qblk = 1;
+  const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
+  p.scale_log2 = scale * 1.4426950408889634f;
+  p.rope = make_rope_table(desc->rope_base, d);
+  dim3 grid((rows_per_seq + 63) / 64, p.hq, batch);
+  if (d == 64) hipLaunchKernelGGL((prefill_rows_kernel<float, 64>), grid, dim3(256), 0, stream, p);
+  else hipLaunchKernelGGL((prefill_rows_kernel<float, 128>), grid, dim3(256), 0, stream, p);
+  return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
+}
+
 // K rotation on its own (for callers that run the attention with another kernel)
 int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, const int32_t* cu_seqlens,
                      const int32_t* positions, int batch, int total_tokens, hipStream_t stream) {
@@ -754,7 +781,7 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
   void* k_rot = k_rot_out ? k_rot_out : workspace;
   f32x2* cs = cs_table_bytes(desc, total_tokens) ? (f32x2*)((char*)workspace + (k_rot_out ? 0 : k_rot_bytes(desc, total_tokens))) : nullptr;
   PrefillParams p;
-  p.cs = cs;
+  p.cs = cs; p.row_pos = nullptr; p.rows_per_seq = 0;
   p.q = q; p.k_rot = k_rot; p.v = v; p.cu = cu_seqlens; p.positions = positions; p.out = out; p.lse = lse_out;
   p.batch = batch; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.max_seqlen = max_seqlen;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);

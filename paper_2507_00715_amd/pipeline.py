@@ -41,8 +41,6 @@ class EarnPath:
         self.S = len(stream_to_seq)
         self.gen_cap = gen_cap
         self.rows_only = bool(rows_only_last_full_layer) and 0 < split_k < n_layers
-        if self.rows_only and dtype != torch.bfloat16:
-            raise ValueError("rows_only_last_full_layer needs bf16 (earn_prefill_register_rows)")
         dev, i32 = self.device, torch.int32
         self.cu = torch.tensor(list(cu_seqlens), dtype=i32, device=dev)
         self.stream_to_seq = torch.tensor(list(stream_to_seq), dtype=i32, device=dev)

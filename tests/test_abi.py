@@ -124,7 +124,7 @@ def test_register_rows_argument_errors():
     assert call(batch=0) == B.EARN_ERR_INVALID_ARG
     assert call(r=0) == B.EARN_ERR_INVALID_ARG
     assert call(r=500) == B.EARN_ERR_INVALID_ARG and b"rows_per_seq" in lib.earn_last_error()
-    assert call(desc=_desc(dtype=B.EARN_F32, hq=8, hkv=2, d=128)) == B.EARN_ERR_UNSUPPORTED
+    assert B.earn_prefill_register_rows_workspace_bytes(_desc(dtype=B.EARN_F32, hq=8, hkv=2, d=128), 2, 400, 8) == 0
     assert call(desc=_desc(hq=8, hkv=2, d=32)) == B.EARN_ERR_UNSUPPORTED
     # two sequences x two kv heads leave room for key splits: partial results need workspace
     need = B.earn_prefill_register_rows_workspace_bytes(_desc(hq=8, hkv=2, d=128), 2, 400, 8)
