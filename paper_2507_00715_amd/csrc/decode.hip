@@ -77,6 +77,11 @@ struct DecodeParams {
   // (stream s*r + i belongs to sequence s), q_pos[u] is the row's token index in its sequence, a row sees shared keys
   // 0 .. q_pos[u] (causal), and there is no generated part and no new token.
   int causal_rows;
+  // Query rows beyond one pass (32 rows per wave group) are normally taken in further passes of the same workgroup over
+  // its keys.  n_pass > 1 gives every pass a workgroup of its own instead (pass index in the grid, last pass first):
+  // used with causal rows, where passes differ widely in length and the long ones of a (sequence, kv head) then run
+  // side by side on one XCD, sharing the keys in its L2.
+  int n_pass;
   float scale_log2;
   RopeTable rope;
 };
@@ -452,14 +457,14 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   // Workgroup -> (kv head c, sequence s, key split z).  Linear ids go to the 8 XCDs round-robin; the hkv workgroups that
   // read the interleaved head slices of the SAME cache rows (one (s, z), all c) get ids 8 apart, i.e. the same XCD and
   // neighbouring dispatch slots, so that their requests for one DRAM row arrive together.
-  int c, s, z;
+  int c, s, z, own_pass;
   {
-    const int n_sz = p.batch * p.n_splits, n_sz8 = (n_sz + 7) / 8 * 8;
+    const int n_sz = p.batch * p.n_splits * p.n_pass, n_sz8 = (n_sz + 7) / 8 * 8;
     const int L = blockIdx.x;
     const int sz = (L / (8 * p.hkv)) * 8 + L % 8;
     c = (L / 8) % p.hkv;
     if (sz >= n_sz || L >= n_sz8 * p.hkv) return;
-    s = sz % p.batch; z = sz / p.batch;
+    s = sz % p.batch; z = (sz / p.batch) % p.n_splits; own_pass = p.n_pass - 1 - sz / (p.batch * p.n_splits);
   }
   const int gq = p.hq / p.hkv;
   // the wave index is the same in all 64 lanes: saying so keeps the key loop and everything derived from the wave's
@@ -579,7 +584,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       q_hi[ks] = *(const u32x4*)(qrow + 16 * ks + D / 2);
     }
   };
-  if (M > 0) load_q_raw(0);
+  if (M > 0) load_q_raw(p.n_pass > 1 ? min(own_pass * ROWS, M - 1) : 0);
   // rotary factors of the tabulated streams, one (stream, pair) per thread and pass
   if (p.rope.enabled) {
     const int n_tab = min(sm.n_streams_of_seq, kDsTabStreams);
@@ -658,12 +663,13 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   bool gen_tile_in_regs = tg0 < n_gen_tiles;
   if (gen_tile_in_regs) load_gen_tile(tg0, true);
 
-  for (int row0 = 0; row0 < M; row0 += ROWS) {
+  const int row_begin = p.n_pass > 1 ? own_pass * ROWS : 0, row_end = p.n_pass > 1 ? min(M, row_begin + ROWS) : M;
+  for (int row0 = row_begin; row0 < row_end; row0 += ROWS) {
     // ---- Q fragments of this group's rows, rotated and pre-scaled ----
     const bool grp_active = row0 + 32 * grp < M;
     bf16x8 qf[KSTEPS];
     int row_u, row_a;
-    if (row0 > 0) load_q_raw(row0);
+    if (row0 > row_begin) load_q_raw(row0);
     {
       const int m = min(row0 + 32 * grp + r32, M - 1);
       row_u = sm.streams[m / gq]; row_a = c * gq + m % gq;
@@ -843,7 +849,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     // ALU; a reference is stale exactly when some exponential is large, which shows in the partial row sums
     // (+inf / NaN on the first tile, whose reference is -inf).  A wave that sees a stale reference leaves the loop,
     // takes the exact maxima of the tile, rescales, finishes the tile and re-enters.
-    if (row0 > 0) issue_first_tiles(nt);  // further passes over the same keys for more query rows
+    if (row0 > row_begin) issue_first_tiles(nt);  // further passes over the same keys for more query rows
     // Iteration `it` opens with the barrier behind which tile `it` is complete (every wave has waited for its own part:
     // loads complete in order, so that means at most the younger tiles' loads are still in flight) and nobody reads
     // tile it-1 any more, whose ring slot the loads of tile it+3 then start to fill.
@@ -891,7 +897,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 
     // ---- the generated key list: this workgroup's tiles of it, one at a time through ring slot 0 ----
     for (int tg = tg0; tg < n_gen_tiles; tg += p.n_splits) {
-      if (!gen_tile_in_regs) load_gen_tile(tg, row0 == 0);
+      if (!gen_tile_in_regs) load_gen_tile(tg, row0 == row_begin);
       gen_tile_in_regs = false;
       __syncthreads();  // nobody reads the slot any more (all of the workgroup's loads into LDS have landed long ago)
       store_gen_tile(0);
@@ -1099,7 +1105,7 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
   p.shared_k = shared_k; p.shared_v = shared_v; p.shared_cu = shared_cu; p.stream_to_seq = stream_to_seq;
   p.gen_k = gen_k; p.gen_v = gen_v; p.gen_len = gen_len; p.out = out;
   p.gen_cap = gen_cap; p.n_streams = n_streams; p.batch = batch; p.hq = hq; p.hkv = hkv;
-  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = 0;
+  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = 0; p.n_pass = 1;
   const size_t need = decode_workspace_bytes(desc->dtype, hq, hkv, d, n_streams, batch, max_shared_len, gen_cap);
   if (need > workspace_bytes || (need > 0 && !workspace)) {
     set_error("earn_decode_attn: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
@@ -1120,10 +1126,15 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
 
 // ---- causal attention of r chosen rows per sequence over the sequence's full-length keys, on the shared-cache kernel:
 // the rows of a (sequence, kv head) are its "beams" ----
-static DecodePlan plan_rows(int hkv, int batch, int max_seqlen) {
+// Every pass of 32 * C query rows gets workgroups of its own.  About half of the passes (the suffix registers' rows)
+// walk the whole sequence, the others (prefix registers) a tile or two: the key range is split so that the long ones
+// make about one workgroup per CU.
+static DecodePlan plan_rows(int hkv, int batch, int max_seqlen, int rows_per_seq, int gq, int* n_pass) {
   DecodePlan pl;
   pl.mfma = true;
-  const long long base = (long long)hkv * batch;
+  const int m = rows_per_seq * gq, rows = m <= 32 ? 32 : 64;
+  *n_pass = (m + rows - 1) / rows;
+  const long long base = (long long)hkv * batch * ((*n_pass + 1) / 2);
   int n = (int)((256 + base - 1) / base);
   const int cap = (max_seqlen + kDsSuper - 1) / kDsSuper;
   if (n > cap) n = cap;
@@ -1135,7 +1146,8 @@ static DecodePlan plan_rows(int hkv, int batch, int max_seqlen) {
 }
 
 size_t prefill_rows_workspace_bytes(int hq, int hkv, int d, int batch, int max_seqlen, int rows_per_seq) {
-  const DecodePlan pl = plan_rows(hkv, batch, max_seqlen);
+  int n_pass;
+  const DecodePlan pl = plan_rows(hkv, batch, max_seqlen, rows_per_seq, hq / hkv, &n_pass);
   if (pl.n_slots == 1) return 0;
   const size_t rows = (size_t)batch * rows_per_seq * hq * pl.n_slots;
   return rows * d * sizeof(float) + rows * 2 * sizeof(float);
@@ -1154,7 +1166,8 @@ int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const vo
     set_error("earn_prefill_register_rows: a sequence of %d rows exceeds the 2 GiB addressing range of one sequence", max_seqlen);
     return EARN_ERR_UNSUPPORTED;
   }
-  const DecodePlan pl = plan_rows(hkv, batch, max_seqlen);
+  int n_pass;
+  const DecodePlan pl = plan_rows(hkv, batch, max_seqlen, rows_per_seq, gq, &n_pass);
   const size_t need = prefill_rows_workspace_bytes(hq, hkv, d, batch, max_seqlen, rows_per_seq);
   if (need > workspace_bytes || (need > 0 && !workspace)) {
     set_error("earn_prefill_register_rows: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
@@ -1165,13 +1178,13 @@ int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const vo
   p.shared_k = k_rot; p.shared_v = v; p.shared_cu = cu_seqlens; p.stream_to_seq = nullptr;
   p.gen_k = nullptr; p.gen_v = nullptr; p.gen_len = nullptr; p.out = out_rows;
   p.gen_cap = 0; p.n_streams = batch * rows_per_seq; p.batch = batch; p.hq = hq; p.hkv = hkv;
-  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = rows_per_seq;
+  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = rows_per_seq; p.n_pass = n_pass;
   p.part_o = (float*)workspace;
   p.part_ml = p.part_o + (size_t)p.n_streams * hq * p.n_slots * d;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
   p.rope = make_rope_table(desc->rope_base, d);
-  const dim3 grid((unsigned)(((long long)batch * p.n_splits + 7) / 8 * 8 * hkv), 1, 1);
+  const dim3 grid((unsigned)(((long long)batch * p.n_splits * n_pass + 7) / 8 * 8 * hkv), 1, 1);
   const bool one_group = rows_per_seq * gq <= 32;
   if (d == 64) {
     if (one_group) hipLaunchKernelGGL((decode_shared_mfma_kernel<64, 1>), grid, dim3(256), 0, stream, p);
