@@ -103,6 +103,9 @@ def test_decode_argument_errors():
     assert need > 0
     assert call(maxlen=100000) == B.EARN_ERR_WORKSPACE_TOO_SMALL
     assert B.earn_decode_workspace_bytes(_desc(hq=64, hkv=64), 512, 512, 16, 4) == 0
+    # limits of the matrix-core kernel: beams per sequence, query heads per kv head
+    assert call(S=1500, batch=1, maxlen=500) == B.EARN_ERR_UNSUPPORTED and b"streams" in lib.earn_last_error()
+    assert call(desc=_desc(hq=32, hkv=2, d=64)) == B.EARN_ERR_UNSUPPORTED and b"query heads" in lib.earn_last_error()
     # many sequences: the key range of the matrix-core kernel is not split either, no partial results
     assert B.earn_decode_workspace_bytes(_desc(hq=12, hkv=2, d=128), 256, 256, 1038, 4) == 0
     # few sequences with long caches: one partial (d + 2 floats) per (stream, head, split), at least two splits
