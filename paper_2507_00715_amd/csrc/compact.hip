@@ -3,6 +3,8 @@
 // OUTPUT, which is contiguous: every lane owns 16-byte units of the compacted tensor, a wave stores 1 KiB of
 // consecutive bytes per instruction, and the source of a unit is found with integer arithmetic only.  Source rows
 // of one register group (h head rows, t tail rows) are consecutive in memory as well, so loads coalesce too.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace earn {
@@ -18,6 +20,7 @@ struct CompactArgs {
 
 constexpr int kCompactThreads = 256;
 constexpr int kCompactUnroll = 4;  // 16-byte units per lane: 4 loads in flight before the first store
+constexpr int kCompactBlocksPerWg = 4;  // blocks (kCompactThreads * kCompactUnroll units) a workgroup copies at most
 
 // source row of compacted row m
 __device__ __forceinline__ int source_row(const int32_t* __restrict__ cu, int m, int r, int h, int t, int* pos) {
@@ -89,13 +92,25 @@ int launch_compact(int n_tensors, const void* const* src, void* const* dst, cons
   CompactArgs args;
   const long long rows_out = (long long)batch * (h + t);
   const long long per_block = (long long)kCompactThreads * kCompactUnroll;
+  // Blocks a workgroup copies one behind the other (grid stride apart).  More than one pays when few, long rows are
+  // gathered (a workgroup's start — finding its tensor, the sequence bounds of its rows — then weighs as much as a
+  // block's copy) and costs when many short ones are; the rule is fitted to measurements (1024 rows of 2-8 KB: 4 blocks
+  // -14 %; 2048 rows of 8 KB: 2 blocks -2 %; 4096 rows of 0.5-3 KB: 4 blocks +10 %) and never leaves the GPU fewer than
+  // a dozen workgroups per CU.
+  long long total_blocks = 0;
+  for (int i = 0; i < n_tensors; ++i) total_blocks += (rows_out * (row_bytes[i] / 16) + per_block - 1) / per_block;
+  static const int iters_env = getenv("EARN_COMPACT_ITERS") ? atoi(getenv("EARN_COMPACT_ITERS")) : 0;
+  long long iters = iters_env > 0 ? iters_env : 4096 / (rows_out > 0 ? rows_out : 1);
+  if (iters_env <= 0 && iters > total_blocks / 4096) iters = total_blocks / 4096;
+  if (iters_env <= 0 && iters > kCompactBlocksPerWg) iters = kCompactBlocksPerWg;
+  if (iters < 1) iters = 1;
   unsigned int blocks = 0;
   for (int i = 0; i < n_tensors; ++i) {
     args.src[i] = (const u32x4*)src[i];
     args.dst[i] = (u32x4*)dst[i];
     args.units_per_row[i] = (unsigned int)(row_bytes[i] / 16);
     const long long units = rows_out * (row_bytes[i] / 16);
-    long long gx = (units + per_block - 1) / per_block;
+    long long gx = (units + per_block * iters - 1) / (per_block * iters);
     if (gx < 1) gx = 1;
     if (gx > 8192) gx = 8192;  // grid-stride beyond this: 32 workgroups per CU
     args.first_block[i] = blocks;
