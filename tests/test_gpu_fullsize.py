@@ -89,6 +89,58 @@ def test_full_layer_prefill_sampled_rows(name):
 
 
 @pytest.mark.parametrize("name", BF16_CONFIGS)
+def test_full_size_register_rows_of_last_full_layer(name):
+    """earn_prefill_register_rows at full size, as bench.py launches it (query rows gathered by earn_compact_registers):
+    the register rows of sampled (sequence, head) pairs against the oracle's plain causal attention read at those rows."""
+    B = _B()
+    cfg = W.CONFIGS[name]
+    w = W.Workload(cfg)
+    layer, r = cfg.split_k - 1, cfg.r
+    coords = w.token_coords(DEV)
+    q = w.prefill_tensor("q", layer, coords=coords)
+    k = w.prefill_tensor("k", layer, coords=coords)
+    v = w.prefill_tensor("v", layer, coords=coords)
+    cu = torch.tensor(w.cu_seqlens, dtype=torch.int32, device=DEV)
+    q_rows = torch.empty(cfg.batch * r, cfg.n_q_heads, cfg.head_dim, dtype=cfg.torch_dtype, device=DEV)
+    idx, pos = (torch.empty(cfg.batch * r, dtype=torch.int32, device=DEV) for _ in range(2))
+    cu_c = torch.empty(cfg.batch + 1, dtype=torch.int32, device=DEV)
+    B.earn_compact_registers([q], [q_rows], cu, cfg.batch, cfg.n_head_reg, cfg.n_tail_reg, idx, pos, cu_c)
+    desc = B.make_desc(cfg.torch_dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, 0.0, cfg.rope_base)
+    out = torch.full_like(q_rows, float("nan"))
+    krot = torch.empty_like(k)
+    ws = torch.empty(max(B.earn_prefill_register_rows_workspace_bytes(desc, cfg.batch, w.max_seqlen, r), 256),
+                     dtype=torch.uint8, device=DEV)
+    B.earn_prefill_register_rows(desc, q_rows, k, v, cu, pos, cfg.batch, w.total_tokens, w.max_seqlen, r, out, krot, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+
+    rng = np.random.default_rng(300 + cfg.config_id)
+    lens = np.asarray(w.seq_lengths)
+    seqs = sorted({int(np.argmax(lens)), int(np.argmin(lens)), int(rng.integers(0, cfg.batch))})
+    gq = cfg.n_q_heads // cfg.n_kv_heads
+    for s in seqs:
+        n = w.seq_lengths[s]
+        heads = sorted({0, cfg.n_q_heads - 1, int(rng.integers(0, cfg.n_q_heads))})
+        kvh = sorted({a // gq for a in heads})
+        qc = W.to_f64(w.prefill_tensor("q", layer, seqs=[s], heads=heads))
+        kc = W.to_f64(w.prefill_tensor("k", layer, seqs=[s], heads=kvh))
+        vc = W.to_f64(w.prefill_tensor("v", layer, seqs=[s], heads=kvh))
+        rows = list(range(cfg.n_head_reg)) + list(range(n - cfg.n_tail_reg, n))
+        sel = np.zeros(n, dtype=np.uint8)
+        sel[rows] = 1
+        ref = O.prefill_attn(qc, kc, vc, [0, n], q_to_kv=[kvh.index(a // gq) for a in heads], rope_base=cfg.rope_base,
+                             row_sel=sel)
+        got = out[s * r:(s + 1) * r][:, heads].cpu().double().numpy()
+        want = ref["out"][rows]
+        err = rel_fro(got, want)
+        assert err <= BF16_REL, f"{name} seq {s}: rel-Frobenius {err:.3e}"
+        row_err = np.linalg.norm(got - want, axis=(1, 2)) / np.maximum(np.linalg.norm(want, axis=(1, 2)), 1e-30)
+        assert row_err.max() <= 3 * BF16_REL, f"{name} seq {s}: register row {int(row_err.argmax())} off by {row_err.max():.3e}"
+        b0 = w.cu_seqlens[s]
+        assert rel_fro(krot[b0:b0 + n][:, kvh].cpu().double().numpy(), ref["k_rot"]) <= BF16_REL
+
+
+@pytest.mark.parametrize("name", BF16_CONFIGS)
 def test_full_size_compaction_bit_exact(name):
     """Hidden-state stand-in plus K and V of one later layer, gathered in one launch, against the oracle's indices."""
     B = _B()
