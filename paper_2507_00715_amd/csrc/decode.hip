@@ -661,9 +661,10 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   // the first generated tile of this workgroup is requested now, in the shadow of the first K/V tiles, and waits in
   // registers until the key loop is through
   bool gen_tile_in_regs = tg0 < n_gen_tiles;
-  if (gen_tile_in_regs) load_gen_tile(tg0, true);
+  if (gen_tile_in_regs) load_gen_tile(tg0, own_pass == 0);  // one pass appends the new tokens
 
-  const int row_begin = p.n_pass > 1 ? own_pass * ROWS : 0, row_end = p.n_pass > 1 ? min(M, row_begin + ROWS) : M;
+  const int row_begin = p.n_pass > 1 ? own_pass * ROWS : 0;
+  const int row_end = p.n_pass > 1 && own_pass < p.n_pass - 1 ? min(M, row_begin + ROWS) : M;
   for (int row0 = row_begin; row0 < row_end; row0 += ROWS) {
     // ---- Q fragments of this group's rows, rotated and pre-scaled ----
     const bool grp_active = row0 + 32 * grp < M;
@@ -897,7 +898,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 
     // ---- the generated key list: this workgroup's tiles of it, one at a time through ring slot 0 ----
     for (int tg = tg0; tg < n_gen_tiles; tg += p.n_splits) {
-      if (!gen_tile_in_regs) load_gen_tile(tg, row0 == row_begin);
+      if (!gen_tile_in_regs) load_gen_tile(tg, row0 == row_begin && own_pass == 0);
       gen_tile_in_regs = false;
       __syncthreads();  // nobody reads the slot any more (all of the workgroup's loads into LDS have landed long ago)
       store_gen_tile(0);
@@ -981,6 +982,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     }
     __syncthreads();  // the merge buffers are tile memory again in the next row chunk
   }
+  wait_vmcnt<0>();  // a workgroup without query rows still has its first tiles on their way into LDS
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -991,6 +993,8 @@ struct DecodePlan {
   int n_splits;   // key-range splits of the shared (mfma) or whole (vector) key list
   int n_slots;    // partial slots per (stream, head)
   int chunk;      // keys per split
+  int n_pass;     // matrix-core kernel: passes of 64 query rows that get workgroups of their own (1: the rows of a cache
+                  // beyond the first 64, if any, are taken in further passes of the same workgroup)
 };
 
 static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int batch, int max_shared_len, int gen_cap) {
@@ -1003,8 +1007,16 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
   static const int mfma_wgs = getenv("EARN_DEC_MFMA_SHORT_WGS") ? atoi(getenv("EARN_DEC_MFMA_SHORT_WGS")) : 256;
   pl.mfma = dtype == EARN_BF16 && (gq > 1 || n_streams > batch) &&
             (max_shared_len >= mfma_min || (long long)hkv * batch <= mfma_wgs);
+  pl.n_pass = 1;
   if (pl.mfma) {
-    long long base = (long long)hkv * batch;
+    // Beams beyond 64 query rows per cache (say 20 beams of 7 grouped heads) would make a workgroup walk its keys once
+    // per 64 rows.  Planned from the average beam count, every such pass gets workgroups of its own, with fewer key
+    // splits: the passes of a (sequence, kv head) then run side by side on one XCD and share the keys in its L2.  (The
+    // last pass takes whatever rows a sequence has beyond the plan.)
+    const long long rows_bound = (long long)gq * (n_streams - batch + 1), rows_avg = (long long)gq * ((n_streams + batch - 1) / batch);
+    static const int pass_grid = getenv("EARN_DEC_PASS_GRID") ? atoi(getenv("EARN_DEC_PASS_GRID")) : 1;
+    if (pass_grid && rows_bound > 32 && rows_avg > 64) pl.n_pass = (int)((rows_avg + 63) / 64);
+    long long base = (long long)hkv * batch * pl.n_pass;
     static const int wg_env = getenv("EARN_DEC_WGS") ? atoi(getenv("EARN_DEC_WGS")) : 256;
     int want = (int)((wg_env + base - 1) / base);               // one workgroup per CU: it holds 8 waves and most of the LDS
     int cap = (max_shared_len + kDsSuper - 1) / kDsSuper;  // at least one super-tile per workgroup
@@ -1075,7 +1087,7 @@ static void launch_decode_t(DecodeParams& p, const DecodePlan& pl, int gq, hipSt
     return;
   }
   if constexpr (sizeof(T) == 2) {
-    dim3 grid((unsigned)(((long long)p.batch * p.n_splits + 7) / 8 * 8 * p.hkv), 1, 1);
+    dim3 grid((unsigned)(((long long)p.batch * p.n_splits * p.n_pass + 7) / 8 * 8 * p.hkv), 1, 1);
     // one 32-row group is enough when a cache serves at most 32 query rows; with beams the host only has an upper bound
     const bool one_group = (long long)gq * (p.n_streams - p.batch + 1) <= 32;
     if (one_group) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1>), grid, dim3(256), 0, stream, p);
@@ -1105,7 +1117,7 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
   p.shared_k = shared_k; p.shared_v = shared_v; p.shared_cu = shared_cu; p.stream_to_seq = stream_to_seq;
   p.gen_k = gen_k; p.gen_v = gen_v; p.gen_len = gen_len; p.out = out;
   p.gen_cap = gen_cap; p.n_streams = n_streams; p.batch = batch; p.hq = hq; p.hkv = hkv;
-  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = 0; p.n_pass = 1;
+  p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = 0; p.n_pass = pl.n_pass;
   const size_t need = decode_workspace_bytes(desc->dtype, hq, hkv, d, n_streams, batch, max_shared_len, gen_cap);
   if (need > workspace_bytes || (need > 0 && !workspace)) {
     set_error("earn_decode_attn: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);

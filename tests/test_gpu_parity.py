@@ -234,6 +234,44 @@ def test_decode_matches_oracle(dtype, hq, hkv, d, slens, beams, glens, gen_cap):
         assert torch.equal(got_gk[u, keep], gk[u, keep]) and torch.equal(got_gv[u, keep], gv[u, keep])
 
 
+def test_decode_with_many_and_unevenly_spread_beams():
+    """More query rows per cache than one pass of the matrix-core kernel takes (the passes get workgroups of their own,
+    planned from the average beam count), with one sequence holding most of the streams and one holding none."""
+    B = _B()
+    dtype, hq, hkv, d, gen_cap = torch.bfloat16, 8, 2, 128, 4
+    slens = [700, 260, 300]
+    s2s = [0] * 45 + [1] * 5          # 180 query rows on sequence 0, 20 on sequence 1, none on sequence 2
+    S, batch = len(s2s), len(slens)
+    glens = [u % 4 for u in range(S)]
+    gtor = torch.Generator().manual_seed(99)
+    rnd = lambda *shape: torch.randn(*shape, generator=gtor).to(dtype)
+    cu = np.concatenate([[0], np.cumsum(slens)]).astype(np.int32)
+    sk, sv = rnd(int(cu[-1]), hkv, d), rnd(int(cu[-1]), hkv, d)
+    q, kn, vn = rnd(S, hq, d), rnd(S, hkv, d), rnd(S, hkv, d)
+    gk, gv = rnd(S, gen_cap, hkv, d), rnd(S, gen_cap, hkv, d)
+    q_pos = [slens[s2s[u]] + glens[u] for u in range(S)]
+    desc = B.make_desc(dtype, hq, hkv, d)
+    dev = lambda x: x.to(DEV)
+    i32 = lambda x: torch.tensor(list(x), dtype=torch.int32, device=DEV)
+    d_gk, d_gv = dev(gk), dev(gv)
+    out = torch.full((S, hq, d), float("nan"), dtype=dtype, device=DEV)
+    ws = torch.empty(max(B.earn_decode_workspace_bytes(desc, S, batch, max(slens), gen_cap), 1), dtype=torch.uint8, device=DEV)
+    B.earn_decode_attn(desc, dev(q), dev(kn), dev(vn), i32(q_pos), dev(sk), dev(sv), i32(cu), i32(s2s), d_gk, d_gv,
+                       i32(glens), gen_cap, S, batch, max(slens), out, ws)
+    torch.cuda.synchronize()
+    o_gk, o_gv = W.to_f64(gk), W.to_f64(gv)
+    ref = O.decode_attn(W.to_f64(q), W.to_f64(kn), W.to_f64(vn), q_pos, W.to_f64(sk), W.to_f64(sv), cu, s2s, o_gk, o_gv,
+                        glens)
+    got = out.cpu().double().numpy()
+    assert np.isfinite(got).all()
+    for u in range(S):
+        assert rel_fro(got[u], ref["out"][u]) <= BF16_REL, f"stream {u}"
+        check_attn(d_gk[u, glens[u]], o_gk[u, glens[u]], dtype, "gen_k slot")
+        assert torch.equal(d_gv[u, glens[u]].cpu(), vn[u])
+        keep = [j for j in range(gen_cap) if j != glens[u]]
+        assert torch.equal(d_gk[u, keep].cpu(), gk[u, keep]) and torch.equal(d_gv[u, keep].cpu(), gv[u, keep])
+
+
 @pytest.mark.parametrize("dtype,hq,hkv,d,slens", [(torch.bfloat16, 8, 2, 128, [300, 129, 1000]),   # matrix-core kernel
                                                    (torch.bfloat16, 4, 4, 64, [300, 16, 70]),        # vector kernel
                                                    (torch.float32, 4, 2, 64, [40, 9])])
