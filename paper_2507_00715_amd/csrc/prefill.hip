@@ -778,6 +778,11 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
     set_error("earn_prefill_attn: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
     return EARN_ERR_WORKSPACE_TOO_SMALL;
   }
+  // the matrix-core kernels address the K/V rows of ONE sequence with 32-bit byte offsets
+  if (desc->dtype == EARN_BF16 && (long long)(max_seqlen + 256) * desc->n_kv_heads * d * 2 >= (1ll << 31)) {
+    set_error("earn_prefill_attn: a sequence of %d rows exceeds the 2 GiB addressing range of one sequence", max_seqlen);
+    return EARN_ERR_UNSUPPORTED;
+  }
   void* k_rot = k_rot_out ? k_rot_out : workspace;
   f32x2* cs = cs_table_bytes(desc, total_tokens) ? (f32x2*)((char*)workspace + (k_rot_out ? 0 : k_rot_bytes(desc, total_tokens))) : nullptr;
   PrefillParams p;

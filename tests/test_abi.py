@@ -59,6 +59,11 @@ def test_prefill_argument_errors():
     # with k_rot_out but no workspace the bf16 path still lacks room for its table; the fp32 path needs none
     rc = lib.earn_prefill_attn(ctypes.byref(_desc()), fake, fake, fake, fake, None, 1, 8, 8, fake, fake, None, None, 0, None)
     assert rc == B.EARN_ERR_WORKSPACE_TOO_SMALL
+    # one sequence's K/V rows are addressed with 32-bit byte offsets in the bf16 kernels
+    big = 1 << 23  # 8 Mi tokens x 2 kv heads x 64 x 2 bytes = 2 GiB
+    rc = lib.earn_prefill_attn(ctypes.byref(_desc()), fake, fake, fake, fake, None, 1, big, big, fake, fake, None, fake,
+                               1 << 40, None)
+    assert rc == B.EARN_ERR_UNSUPPORTED and b"2 GiB" in lib.earn_last_error()
     assert B.earn_prefill_workspace_bytes(_desc(dtype=B.EARN_F32), 1, 8, 8, True) == 0
 
 
