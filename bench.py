@@ -341,8 +341,8 @@ def cpu_baseline(name: str, threads: int = 0, rows_target: int = 4096) -> dict:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default=HEADLINE, choices=W.CONFIG_ORDER)
     ap.add_argument("--others", default="small_gqa,mid_mha,serving",
                     help="comma-separated workloads also measured and reported under 'other_workloads' ('' = none)")
