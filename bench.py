@@ -169,7 +169,7 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
     # Beyond the paper's method, exact: layer k-1 evaluated at the register rows only (its other outputs are dropped by
     # the compaction).  Timed on its own, gather of the query rows included; the timed steps above do not use it.
     rows_only = None
-    if c.dtype == "bf16" and 0 < kk < N:
+    if 0 < kk < N:
         from paper_2507_00715_amd import binding as B
         l = kk - 1
         q_rows = torch.empty(path.Tc, c.n_q_heads, c.head_dim, dtype=c.torch_dtype, device=dev)
@@ -344,7 +344,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default=HEADLINE, choices=W.CONFIG_ORDER)
-    ap.add_argument("--others", default="small_gqa,mid_mha,serving",
+    ap.add_argument("--others", default="tiny_f32,small_gqa,mid_mha,serving",
                     help="comma-separated workloads also measured and reported under 'other_workloads' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--single", default="", choices=["", "prefill_full", "decode_full", "compact"],

@@ -164,28 +164,42 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   const T* kbase = (const T*)p.k_rot + ((long long)b0 * p.hkv + c) * D;
   const T* vbase = (const T*)p.v + ((long long)b0 * p.hkv + c) * D;
   const long long rs = (long long)p.hkv * D;
-  for (int j = 0; j <= wave_last; ++j) {
-    float kl[E], kh[E], vl[E], vh[E];
+  // NB keys per step: their rows are requested together and their scores formed side by side (the walk is otherwise a
+  // chain of memory round trips); the softmax state still takes them one after the other, in key order
+  constexpr int NB = D == 64 ? 4 : 2;
+  for (int j0 = 0; j0 <= wave_last; j0 += NB) {
+    float kl[NB][E], kh[NB][E], vl[NB][E], vh[NB][E], sc[NB];
 #pragma unroll
-    for (int e = 0; e < E; e += 8) {
-      Vec8<T>::load(kbase + j * rs + qt * E + e, kl + e);
-      Vec8<T>::load(kbase + j * rs + D / 2 + qt * E + e, kh + e);
-      Vec8<T>::load(vbase + j * rs + qt * E + e, vl + e);
-      Vec8<T>::load(vbase + j * rs + D / 2 + qt * E + e, vh + e);
+    for (int b = 0; b < NB; ++b) {
+      const int j = min(j0 + b, wave_last);
+#pragma unroll
+      for (int e = 0; e < E; e += 8) {
+        Vec8<T>::load(kbase + j * rs + qt * E + e, kl[b] + e);
+        Vec8<T>::load(kbase + j * rs + D / 2 + qt * E + e, kh[b] + e);
+        Vec8<T>::load(vbase + j * rs + qt * E + e, vl[b] + e);
+        Vec8<T>::load(vbase + j * rs + D / 2 + qt * E + e, vh[b] + e);
+      }
     }
-    float sc = 0.f;
 #pragma unroll
-    for (int e = 0; e < E; ++e) sc = __builtin_fmaf(ql[e], kl[e], __builtin_fmaf(qh[e], kh[e], sc));
-    sc += __shfl_xor(sc, 1, kWave);
-    sc += __shfl_xor(sc, 2, kWave);
-    if (j <= ic) {  // causal: keys 0..i
-      float mn = fmaxf(m, sc);
-      float corr = __builtin_amdgcn_exp2f(m - mn);  // exp2(-inf) = 0 on the first key
-      float pr = __builtin_amdgcn_exp2f(sc - mn);
-      l = l * corr + pr;
+    for (int b = 0; b < NB; ++b) {
+      float d = 0.f;
 #pragma unroll
-      for (int e = 0; e < E; ++e) { ol[e] = __builtin_fmaf(pr, vl[e], ol[e] * corr); oh[e] = __builtin_fmaf(pr, vh[e], oh[e] * corr); }
-      m = mn;
+      for (int e = 0; e < E; ++e) d = __builtin_fmaf(ql[e], kl[b][e], __builtin_fmaf(qh[e], kh[b][e], d));
+      d += __shfl_xor(d, 1, kWave);
+      d += __shfl_xor(d, 2, kWave);
+      sc[b] = d;
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      if (j0 + b <= ic && j0 + b <= wave_last) {  // causal: keys 0..i
+        float mn = fmaxf(m, sc[b]);
+        float corr = __builtin_amdgcn_exp2f(m - mn);  // exp2(-inf) = 0 on the first key
+        float pr = __builtin_amdgcn_exp2f(sc[b] - mn);
+        l = l * corr + pr;
+#pragma unroll
+        for (int e = 0; e < E; ++e) { ol[e] = __builtin_fmaf(pr, vl[b][e], ol[e] * corr); oh[e] = __builtin_fmaf(pr, vh[b][e], oh[e] * corr); }
+        m = mn;
+      }
     }
   }
   if (!row_ok) return;
