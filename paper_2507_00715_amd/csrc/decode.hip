@@ -414,7 +414,7 @@ constexpr int kDsTile = 32;              // keys per wave sub-tile
 constexpr int kDsGroupWaves = 4;         // waves per 32-row group: 2 key sub-tiles x 2 halves of the head dimension
 constexpr int kDsRing = 4;               // K/V tiles (kTileKeys = 64 keys each) in LDS: one in use, three on their way
 constexpr int kDsSuper = 128;            // key ranges of the splits are multiples of this
-constexpr float kDecSumLimit = 512.0f;   // per lane: 16 exponentials of one query row
+constexpr float kDecSumLimit = kSumLimit;  // per lane: 16 exponentials of one query row and tile
 constexpr int kMaxStreamsPerSeq = 1024;  // beams of one sequence the stream list holds
 constexpr int kDsTabStreams = 16;        // streams whose rotary factors are tabulated in LDS
 

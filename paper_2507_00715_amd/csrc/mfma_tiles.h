@@ -57,10 +57,14 @@ __device__ __forceinline__ void drain_loads_and_barrier() {
 }
 
 // Between rescales the exponentials are taken against a stale row maximum, so they can exceed 1; they are allowed to
-// grow until a lane's partial row sum passes this limit.  That is harmless in fp32 sums and in bf16 operands, and the
-// final normalisation uses the same reference, so the result is the same function.  Rescaling touches every
-// accumulator register of a lane, so doing it only when needed removes most vector-ALU work from the key loop.
-constexpr float kSumLimit = 1024.0f;  // per lane: 32 exponentials of one query row
+// grow until a lane's partial row sum of one tile passes this limit.  A reference that is too low by D scales every
+// weight, every sum and every output accumulator of the row by the same 2^D, a power of two: exact in fp32 and in the
+// bf16 operands alike, and gone again in the final normalisation, so the result is the same function as long as
+// nothing overflows.  2^40 per tile leaves fp32 eighty-odd binary orders for the sums over tiles and the products with
+// V.  Rescaling touches every accumulator register of a lane and recomputes the tile, so doing it only when it is
+// needed takes most vector-ALU work out of the key loop; with keys of very uneven scale (outlier rows) a tight limit
+// would send tile after tile down the exact path.
+constexpr float kSumLimit = 0x1p40f;
 
 // max / sum of a value with its partner in the other half of the wave (lane ^ 32), without going through LDS
 __device__ __forceinline__ float half_max(float x) {

@@ -234,6 +234,44 @@ def test_decode_matches_oracle(dtype, hq, hkv, d, slens, beams, glens, gen_cap):
         assert torch.equal(got_gk[u, keep], gk[u, keep]) and torch.equal(got_gv[u, keep], gv[u, keep])
 
 
+@pytest.mark.parametrize("hq,hkv,d,beams", [(8, 2, 128, 3), (4, 4, 64, 1)])
+def test_decode_with_late_outlier_keys(hq, hkv, d, beams):
+    """Keys far larger than everything before them, late in the cache and among the generated rows: the running softmax
+    reference has to be replaced in the middle of the key list (matrix-core kernel: exact path; vector kernel: rescale)."""
+    B = _B()
+    dtype, gen_cap = torch.bfloat16, 6
+    slens = [900, 200]
+    batch, S = len(slens), len(slens) * beams
+    s2s = [u // beams for u in range(S)]
+    glens = [(u * 2) % gen_cap for u in range(S)]
+    gtor = torch.Generator().manual_seed(5 + hq)
+    rnd = lambda *shape: torch.randn(*shape, generator=gtor).to(dtype)
+    cu = np.concatenate([[0], np.cumsum(slens)]).astype(np.int32)
+    sk, sv = rnd(int(cu[-1]), hkv, d), rnd(int(cu[-1]), hkv, d)
+    sk[700:720] *= 30.0          # late in sequence 0
+    sk[cu[1] + 150] *= 40.0      # one key near the end of sequence 1
+    q, kn, vn = rnd(S, hq, d), rnd(S, hkv, d), rnd(S, hkv, d)
+    gk, gv = rnd(S, gen_cap, hkv, d), rnd(S, gen_cap, hkv, d)
+    gk[0, 0] *= 50.0             # and a generated row
+    q_pos = [slens[s2s[u]] + glens[u] for u in range(S)]
+    desc = B.make_desc(dtype, hq, hkv, d)
+    dev = lambda x: x.to(DEV)
+    i32 = lambda x: torch.tensor(list(x), dtype=torch.int32, device=DEV)
+    d_gk, d_gv = dev(gk), dev(gv)
+    out = torch.full((S, hq, d), float("nan"), dtype=dtype, device=DEV)
+    ws = torch.empty(max(B.earn_decode_workspace_bytes(desc, S, batch, max(slens), gen_cap), 1), dtype=torch.uint8, device=DEV)
+    B.earn_decode_attn(desc, dev(q), dev(kn), dev(vn), i32(q_pos), dev(sk), dev(sv), i32(cu), i32(s2s), d_gk, d_gv,
+                       i32(glens), gen_cap, S, batch, max(slens), out, ws)
+    torch.cuda.synchronize()
+    o_gk, o_gv = W.to_f64(gk), W.to_f64(gv)
+    ref = O.decode_attn(W.to_f64(q), W.to_f64(kn), W.to_f64(vn), q_pos, W.to_f64(sk), W.to_f64(sv), cu, s2s, o_gk, o_gv,
+                        glens)
+    got = out.cpu().double().numpy()
+    assert np.isfinite(got).all()
+    for u in range(S):
+        assert rel_fro(got[u], ref["out"][u]) <= BF16_REL, f"stream {u}"
+
+
 def test_decode_with_many_and_unevenly_spread_beams():
     """More query rows per cache than one pass of the matrix-core kernel takes (the passes get workgroups of their own,
     planned from the average beam count), with one sequence holding most of the streams and one holding none."""
