@@ -461,14 +461,13 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
   // vector ALU.  It does not even compute row maxima: a reference is stale exactly when some exponential is large, so
   // the (already needed) partial row sums are compared with kSumLimit instead.  A wave that fails leaves the loop,
   // recomputes the tile's scores, takes the exact maxima, rescales, finishes the tile and re-enters.  Tile 0 (reference
-  // still -inf) and the wave's diagonal tile (the only one that needs the causal mask) always take the exact path.
+  // still -inf) always takes the exact path; the wave's diagonal tile is the only one that needs the causal mask.
   int t = 0;
   while (t < n_tiles) {
     bool exact = wave_active && t == 0, synced = false;
     if (!exact)
     for (; t < n_tiles; ++t) {
       const bool work = wave_active && t <= t_diag;  // else rows past the sequence end or a tile past the diagonal: only stage
-      if (work && t == t_diag) { exact = true; break; }
       sync_and_stage(t);
       if (work) {
         f32x16 sc[2];
@@ -476,6 +475,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
         u32x4 w[4];
         float lsum;
         score_tile<D, false>(smk[t % STAGES], fo, qf, neg_m, sc);
+        if (t == t_diag) mask_diagonal(sc, q_in_tile, r32, hf);  // masked scores give weight 0 on this path as well
         fetch_v(smv[t % STAGES], vf);
         softmax_tile(sc, w, lsum);
         if (__any(!(lsum <= kSumLimit))) { exact = synced = true; break; }
