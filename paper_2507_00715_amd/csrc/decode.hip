@@ -345,10 +345,8 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
 template <typename T, int D, int GQ, int WAVES>
 __global__ __launch_bounds__(kWave * WAVES) void decode_kernel(DecodeParams p) {
   __shared__ float sm[WAVES > 1 ? WAVES * GQ * (D / 8) * 10 : 1];
-  // Workgroup -> (kv head c, stream u, key split z).  Linear ids go to the 8 XCDs round-robin.  The hkv workgroups that
-  // read the interleaved head slices of the same cache rows (one (u, z), all c) get ids 8 apart: one XCD then sees
-  // whole rows, i.e. all address residues, instead of the same few head slices of every row (which would load only
-  // a few of its L2 channels).
+  // Work item -> (kv head c, stream u, key split z).  Linear ids go to the 8 XCDs round-robin.  The hkv items that read
+  // the interleaved head slices of the same cache rows (one (u, z), all c) get ids 8 apart, i.e. the same XCD.
   const int n_uz = p.n_streams * p.n_splits, n_uz8 = (n_uz + 7) / 8 * 8;
   const int L = blockIdx.x;
   const int uz = (L / (8 * p.hkv)) * 8 + L % 8;
