@@ -80,7 +80,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T* __restrict__ k_rot,
                                                      const int32_t* __restrict__ cu,
                                                      const int32_t* __restrict__ positions, int batch, int total,
-                                                     int hkv, RopeTable rope, f32x2* __restrict__ cs_out) {
+                                                     int hkv, RopeTable rope, f32x2* __restrict__ cs_out,
+                                                     int heads_per_thread) {
   constexpr int G = D / 16;  // groups of 8 pairs per head
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
   if (t >= (long long)total * G) return;
@@ -101,14 +102,17 @@ __global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T*
 #pragma unroll
     for (int i = 0; i < 8; ++i) { sn[i] = 0.f; cs[i] = 1.f; }
   }
-  if (cs_out) {
+  if (cs_out && blockIdx.y == 0) {
     f32x4* dst4 = (f32x4*)(cs_out + (long long)token * (D / 2) + g * 8);
 #pragma unroll
     for (int i = 0; i < 8; i += 2) dst4[i / 2] = f32x4{cs[i], sn[i], cs[i + 1], sn[i + 1]};
   }
   const T* src = k + (long long)token * hkv * D + g * 8;
   T* dst = k_rot + (long long)token * hkv * D + g * 8;
-  for (int h = 0; h < hkv; ++h) {
+  // grid row y takes kv heads [y * heads_per_thread, + heads_per_thread): all of them when there are tokens enough to
+  // fill the GPU, a few when there are not (the loop over heads is a chain of memory round trips)
+  const int h_begin = blockIdx.y * heads_per_thread, h_end = min(hkv, h_begin + heads_per_thread);
+  for (int h = h_begin; h < h_end; ++h) {
     float lo[8], hi[8];
     Vec8<T>::load(src + h * D, lo);
     Vec8<T>::load(src + h * D + D / 2, hi);
@@ -746,8 +750,11 @@ template <typename T, int D>
 static void launch_rope_k(const void* k, void* k_rot, const int32_t* cu, const int32_t* positions, int batch, int total,
                           int hkv, const RopeTable& rope, f32x2* cs_out, hipStream_t stream) {
   long long threads = (long long)total * (D / 16);
-  hipLaunchKernelGGL((rope_k_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
-                     (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope, cs_out);
+  const unsigned gx = (unsigned)((threads + 255) / 256);
+  // fewer than about two workgroups per CU: split the heads over grid rows as well
+  const int hpt = gx >= 512 ? hkv : (hkv + 7) / 8;
+  hipLaunchKernelGGL((rope_k_kernel<T, D>), dim3(gx, (unsigned)((hkv + hpt - 1) / hpt)), dim3(256), 0, stream,
+                     (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope, cs_out, hpt);
 }
 
 // fp32: the chosen rows of every sequence (q_rows, out_rows: [batch * r, Hq, d]) against the rotated keys, vector kernel
