@@ -43,7 +43,9 @@ class EarnPath:
         self.rows_only = bool(rows_only_last_full_layer) and 0 < split_k < n_layers
         dev, i32 = self.device, torch.int32
         self.cu = torch.tensor(list(cu_seqlens), dtype=i32, device=dev)
-        self.stream_to_seq = torch.tensor(list(stream_to_seq), dtype=i32, device=dev)
+        # one stream per sequence in order: the library takes "no map" and saves every decode workgroup a dependent load
+        identity = list(stream_to_seq) == list(range(self.batch))
+        self.stream_to_seq = None if identity else torch.tensor(list(stream_to_seq), dtype=i32, device=dev)
         self.seq_len_of_stream = torch.tensor([lens[s] for s in stream_to_seq], dtype=i32, device=dev)
         self.idx = torch.empty(self.Tc, dtype=i32, device=dev)
         self.pos = torch.empty(self.Tc, dtype=i32, device=dev)
