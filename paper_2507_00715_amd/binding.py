@@ -159,5 +159,42 @@ def earn_decode_attn(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, shared_v,
                                   _ptr(workspace), ws_bytes, _stream()))
 
 
+class BoundCall:
+    """An entry-point call with its arguments marshalled ONCE: calling the object enqueues the launch on the stream
+    that is current at that moment.  For loops that repeat a call on the same buffers (a decode step per layer on
+    pre-allocated caches), where converting a dozen tensors to pointers costs more host time than the launch itself.
+    The object keeps the tensors alive."""
+    __slots__ = ("_fn", "_args", "_keep")
+
+    def __init__(self, fn, args, keep):
+        self._fn, self._args, self._keep = fn, args, keep
+
+    def __call__(self) -> None:
+        rc = self._fn(*self._args, torch.cuda.current_stream().cuda_stream)
+        if rc != EARN_OK:
+            raise EarnError(rc, last_error())
+
+
+def bind_decode_attn(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v,
+                     gen_len, gen_cap: int, n_streams: int, batch: int, max_shared_len: int, out,
+                     workspace=None) -> BoundCall:
+    """earn_decode_attn with the same arguments, marshalled once (see BoundCall)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    tensors = (q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len)
+    args = (ctypes.byref(desc), *[_ptr(t) for t in tensors], gen_cap, n_streams, batch, max_shared_len, _ptr(out),
+            _ptr(workspace), ws_bytes)
+    return BoundCall(lib().earn_decode_attn, args, (desc, tensors, out, workspace))
+
+
+def bind_prefill_attn(desc: AttnDesc, q, k, v, cu_seqlens, positions, batch: int, total_tokens: int, max_seqlen: int,
+                      out, k_rot_out, lse_out, workspace) -> BoundCall:
+    """earn_prefill_attn with the same arguments (workspace required if the call needs one), marshalled once."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    tensors = (q, k, v, cu_seqlens, positions)
+    args = (ctypes.byref(desc), *[_ptr(t) for t in tensors], batch, total_tokens, max_seqlen, _ptr(out),
+            _ptr(k_rot_out), _ptr(lse_out), _ptr(workspace), ws_bytes)
+    return BoundCall(lib().earn_prefill_attn, args, (desc, tensors, out, k_rot_out, lse_out, workspace))
+
+
 def earn_cache_entries(n_layers: int, split_k: int, seq_len: int, n_registers: int, gen: int = 0) -> int:
     return int(lib().earn_cache_entries(n_layers, split_k, seq_len, n_registers, gen))

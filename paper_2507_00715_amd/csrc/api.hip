@@ -18,6 +18,12 @@ void set_error(const char* fmt, ...) {
 }
 
 RopeTable make_rope_table(float base, int head_dim) {
+  // every entry point asks for the table on every call, nearly always for the same model: keep the last one per thread
+  // (64 calls of pow() cost about as much host time as a kernel launch)
+  static thread_local RopeTable cached;
+  static thread_local float cached_base = 0.f;
+  static thread_local int cached_dim = 0;
+  if (base > 0.f && base == cached_base && head_dim == cached_dim) return cached;
   RopeTable t;
   memset(&t, 0, sizeof(t));
   t.enabled = base > 0.f ? 1 : 0;
@@ -29,6 +35,7 @@ RopeTable make_rope_table(float base, int head_dim) {
     t.hi[e] = hi;
     t.lo[e] = (float)(turns - (double)hi);
   }
+  cached = t; cached_base = base; cached_dim = head_dim;
   return t;
 }
 

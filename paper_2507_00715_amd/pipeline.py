@@ -141,6 +141,21 @@ class EarnPath:
                            self.gen_len, self.gen_cap, self.S, self.batch, self.max_seqlen if full else self.r,
                            self.decode_out[l], self.workspace)
 
+    def bind_decode_layer(self, l: int, dq, dk, dv) -> "B.BoundCall":
+        """decode_layer(l, dq, dk, dv) with its arguments marshalled once: for loops that replay the same buffers."""
+        full = l < self.k
+        return B.bind_decode_attn(self.desc, dq, dk, dv, self.q_pos, self.k_cache[l], self.v_cache[l],
+                                  self.cu if full else self.cu_c, self.stream_to_seq, self.gen_k[l], self.gen_v[l],
+                                  self.gen_len, self.gen_cap, self.S, self.batch, self.max_seqlen if full else self.r,
+                                  self.decode_out[l], self.workspace)
+
+    def bind_prefill_register_layer(self, l: int) -> "B.BoundCall":
+        """prefill_register_layer(l), marshalled once (valid after compact() has run once: v_cache[l] is set here)."""
+        self.v_cache[l] = self.v_c[l]
+        return B.bind_prefill_attn(self.desc, self.q_c[l], self.k_c[l], self.v_c[l], self.cu_c, self.pos, self.batch,
+                                   self.Tc, self.r, self.prefill_out[l], self.k_cache[l], self.lse[l],
+                                   self.prefill_workspace)
+
     def decode_step(self, g: int, dq: Sequence[torch.Tensor], dk: Sequence[torch.Tensor],
                     dv: Sequence[torch.Tensor]) -> None:
         self.set_step(g)

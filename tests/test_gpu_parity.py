@@ -343,6 +343,41 @@ def test_decode_without_stream_map(dtype, hq, hkv, d, slens):
         assert torch.equal(d_gv[u, glens[u]].cpu(), vn[u])
 
 
+def test_bound_calls_equal_direct_calls():
+    """A call marshalled once (binding.BoundCall) enqueues exactly what the direct call does, every time it is called."""
+    B = _B()
+    dtype, hq, hkv, d, gen_cap = torch.bfloat16, 8, 2, 64, 3
+    slens = [200, 40]
+    S = batch = len(slens)
+    gtor = torch.Generator().manual_seed(11)
+    rnd = lambda *shape: torch.randn(*shape, generator=gtor).to(dtype).to(DEV)
+    cu = torch.tensor([0, 200, 240], dtype=torch.int32, device=DEV)
+    sk, sv, q, kn, vn = rnd(240, hkv, d), rnd(240, hkv, d), rnd(S, hq, d), rnd(S, hkv, d), rnd(S, hkv, d)
+    gk0, gv0 = rnd(S, gen_cap, hkv, d), rnd(S, gen_cap, hkv, d)
+    glen = torch.tensor([1, 2], dtype=torch.int32, device=DEV)
+    qpos = torch.tensor([201, 42], dtype=torch.int32, device=DEV)
+    desc = B.make_desc(dtype, hq, hkv, d)
+    ws = torch.empty(max(B.earn_decode_workspace_bytes(desc, S, batch, 200, gen_cap), 1), dtype=torch.uint8, device=DEV)
+    gk1, gv1, out1 = gk0.clone(), gv0.clone(), torch.empty_like(q)
+    B.earn_decode_attn(desc, q, kn, vn, qpos, sk, sv, cu, None, gk1, gv1, glen, gen_cap, S, batch, 200, out1, ws)
+    gk2, gv2, out2 = gk0.clone(), gv0.clone(), torch.full_like(q, float("nan"))
+    call = B.bind_decode_attn(desc, q, kn, vn, qpos, sk, sv, cu, None, gk2, gv2, glen, gen_cap, S, batch, 200, out2, ws)
+    for _ in range(3):
+        out2.fill_(float("nan"))
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(out1, out2) and torch.equal(gk1, gk2) and torch.equal(gv1, gv2)
+    # prefill
+    T = 240
+    qf, out_a, out_b = rnd(T, hq, d), torch.empty(T, hq, d, dtype=dtype, device=DEV), torch.empty(T, hq, d, dtype=dtype, device=DEV)
+    kr_a, kr_b = torch.empty_like(sk), torch.empty_like(sk)
+    pws = torch.empty(max(B.earn_prefill_workspace_bytes(desc, batch, T, 200, True), 256), dtype=torch.uint8, device=DEV)
+    B.earn_prefill_attn(desc, qf, sk, sv, cu, None, batch, T, 200, out_a, kr_a, None, pws)
+    B.bind_prefill_attn(desc, qf, sk, sv, cu, None, batch, T, 200, out_b, kr_b, None, pws)()
+    torch.cuda.synchronize()
+    assert torch.equal(out_a, out_b) and torch.equal(kr_a, kr_b)
+
+
 # --------------------------------------------------------------------------------------------------
 def _pipeline_inputs(w, device):
     cfg = w.cfg
