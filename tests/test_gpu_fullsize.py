@@ -170,11 +170,15 @@ def test_full_size_compaction_bit_exact(name):
     assert torch.equal(dst[2].cpu(), w.prefill_tensor("v", cfg.split_k, coords=cc))
 
 
-@pytest.mark.parametrize("name,mode", [(n, m) for n in BF16_CONFIGS for m in ("full", "registers")])
+# "long_beam/20": the long_beam shape at the beam width of the paper's experiments (Appendix, experimental details: beam size 20), 80 query rows per cache
+@pytest.mark.parametrize("name,mode", [(n, m) for n in BF16_CONFIGS for m in ("full", "registers")] +
+                         [("long_beam/20", "full")])
 def test_full_size_decode_sampled_streams(name, mode):
     """One decode step of one layer at full size (full-length cache or register cache), sampled (stream, head) rows."""
     B = _B()
-    cfg = W.CONFIGS[name]
+    cfg = W.CONFIGS[name.split("/")[0]]
+    if "/" in name:
+        cfg = cfg.replace(beams=int(name.split("/")[1]))
     w = W.Workload(cfg)
     layer = 0 if mode == "full" else cfg.split_k
     step = cfg.decode_steps // 2
