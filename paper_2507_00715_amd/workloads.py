@@ -281,7 +281,7 @@ class Workload:
                 "min_len": min(self.seq_lengths), "max_len": self.max_seqlen, "head_regs": c.n_head_reg,
                 "tail_regs": c.n_tail_reg, "layers": c.n_layers, "split_k": c.split_k, "q_heads": c.n_q_heads,
                 "kv_heads": c.n_kv_heads, "head_dim": c.head_dim, "decode_steps": c.decode_steps, "beams": c.beams,
-                "seed": self.seed}
+                "seed": self.seed, "seq_lengths": list(self.seq_lengths)}
 
 
 def to_f64(t: torch.Tensor) -> np.ndarray:
