@@ -137,7 +137,9 @@ int earn_compact_registers(int32_t n_tensors, const void* const* src, void* cons
  *   q_pos              [n_streams] int32: original position of the new token (n_s + step)
  *   shared_k, shared_v [shared_total, Hkv, d]; shared_k already rotated (k_rot_out of the prefill)
  *   shared_cu          [batch+1] int32
- *   stream_to_seq      [n_streams] int32 or NULL (= identity, requires n_streams == batch)
+ *   stream_to_seq      [n_streams] int32 or NULL (= identity, requires n_streams == batch); a sequence may hold any
+ *                      number of streams, none included, but at most 1024 (device-side precondition; the host rejects
+ *                      what it can tell from n_streams and batch alone: n_streams - batch + 1 > 1024 -> UNSUPPORTED)
  *   gen_k, gen_v       [n_streams, gen_cap, Hkv, d]; slot gen_len[u] of stream u is written by this call
  *   gen_len            [n_streams] int32, 0 <= gen_len[u] < gen_cap
  *   max_shared_len     upper bound on shared_cu[s+1] - shared_cu[s]
@@ -145,7 +147,8 @@ int earn_compact_registers(int32_t n_tensors, const void* const* src, void* cons
  *   workspace          at least earn_decode_workspace_bytes(...) bytes, 256-byte aligned
  *
  * Errors: as for earn_prefill_attn, plus gen_cap <= 0, n_streams <= 0, stream_to_seq == NULL with
- * n_streams != batch, max_shared_len < 0 -> INVALID_ARG.
+ * n_streams != batch, max_shared_len < 0 -> INVALID_ARG; more than 8 query heads per kv head -> UNSUPPORTED.
+ * Values in device memory (gen_len < gen_cap, monotone shared_cu, stream_to_seq in [0, batch)) are preconditions.
  */
 int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
                      const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
