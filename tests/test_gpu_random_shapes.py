@@ -137,3 +137,39 @@ def test_prefill_and_register_rows_random_shape(case):
     for s in range(batch):
         check(out_rows[s * r:(s + 1) * r], want[s * r:(s + 1) * r], dtype, f"case {case} register rows of sequence {s}")
     assert torch.equal(k_rot2, k_rot)
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_compaction_random_shape(case):
+    """Random register counts, ragged lengths (sequences that are all registers included), 1 to 112 tensors of random
+    row widths in one launch: bit-exact against the oracle's gather of the same bytes."""
+    B = _B()
+    rng = np.random.default_rng(11000 + case)
+    h, t = int(rng.choice([0, 1, 3, 8, 32])), int(rng.choice([0, 1, 2, 16, 32]))
+    if h + t == 0:
+        h = 1
+    r = h + t
+    batch = int(rng.integers(1, 40))
+    lens = [r + int(x) for x in rng.choice([0, 0, 1, 5, 64, 333, 2000], size=batch)]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    n_tensors = int(rng.choice([1, 2, 7, 40, 112]))
+    widths = [int(x) for x in rng.choice([16, 32, 48, 256, 512, 4096, 8208], size=n_tensors)]   # row bytes
+    if n_tensors > 7:   # keep the byte volume of the many-tensor cases small
+        widths = [min(wd, 512) for wd in widths]
+    print(f"case {case}: h={h} t={t} batch={batch} T={T} tensors={n_tensors} widths={sorted(set(widths))}", flush=True)
+    g = torch.Generator().manual_seed(case)
+    srcs = [torch.randint(0, 256, (T, wd), dtype=torch.uint8, generator=g) for wd in widths]
+    d_src = [s.to(DEV) for s in srcs]
+    d_dst = [torch.full((batch * r, wd), 0xEE, dtype=torch.uint8, device=DEV) for wd in widths]
+    d_cu = torch.from_numpy(cu).to(DEV)
+    idx, pos = (torch.full((batch * r,), -1, dtype=torch.int32, device=DEV) for _ in range(2))
+    cu_c = torch.full((batch + 1,), -1, dtype=torch.int32, device=DEV)
+    B.earn_compact_registers(d_src, d_dst, d_cu, batch, h, t, idx, pos, cu_c)
+    torch.cuda.synchronize()
+    ref = O.compact_registers(None, cu, h, t)
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref["idx"])
+    np.testing.assert_array_equal(pos.cpu().numpy(), ref["pos"])
+    np.testing.assert_array_equal(cu_c.cpu().numpy(), ref["cu"])
+    for s, dd in zip(srcs, d_dst):
+        assert np.array_equal(dd.cpu().numpy(), O.compact_registers(s.numpy(), cu, h, t)["dst"])
