@@ -88,6 +88,41 @@ def test_full_layer_prefill_sampled_rows(name):
     print(f"{name}: worst sampled rel-Frobenius error {worst:.2e}")
 
 
+def test_prefill_beyond_two_to_the_31_elements():
+    """Q and O of more than 2^31 elements (4.4 GB each): the sequence at the far end of the tensors, where 32-bit
+    element offsets would have wrapped, against the oracle on sampled rows."""
+    B = _B()
+    cfg = W.CONFIGS["long_beam"].replace(name="wide", config_id=44, batch=66, len_dist=("fixed", 4096 - 64),
+                                         n_q_heads=64, n_kv_heads=8, head_dim=128, beams=1)
+    w = W.Workload(cfg)
+    assert w.total_tokens * cfg.n_q_heads * cfg.head_dim > 2**31
+    coords = w.token_coords(DEV)
+    q, k, v = (w.prefill_tensor(t, 0, coords=coords) for t in "qkv")
+    out = torch.empty_like(q)
+    krot = torch.empty_like(k)
+    cu = torch.tensor(w.cu_seqlens, dtype=torch.int32, device=DEV)
+    desc = B.make_desc(cfg.torch_dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, 0.0, cfg.rope_base)
+    B.earn_prefill_attn(desc, q, k, v, cu, None, cfg.batch, w.total_tokens, w.max_seqlen, out, krot, None, None)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(44)
+    gq = cfg.n_q_heads // cfg.n_kv_heads
+    for s in (cfg.batch - 1, 0):
+        n, b0 = w.seq_lengths[s], w.cu_seqlens[s]
+        heads = [0, cfg.n_q_heads - 1]
+        kvh = sorted({a // gq for a in heads})
+        qc = W.to_f64(w.prefill_tensor("q", 0, seqs=[s], heads=heads))
+        kc = W.to_f64(w.prefill_tensor("k", 0, seqs=[s], heads=kvh))
+        vc = W.to_f64(w.prefill_tensor("v", 0, seqs=[s], heads=kvh))
+        rows = sample_rows(n, cfg.n_head_reg, cfg.n_tail_reg, rng, n_random=8)
+        sel = np.zeros(n, dtype=np.uint8)
+        sel[rows] = 1
+        ref = O.prefill_attn(qc, kc, vc, [0, n], q_to_kv=[kvh.index(a // gq) for a in heads], rope_base=cfg.rope_base,
+                             row_sel=sel)
+        got = out[b0:b0 + n][rows][:, heads].cpu().double().numpy()
+        assert rel_fro(got, ref["out"][rows]) <= BF16_REL, f"sequence {s}"
+        assert rel_fro(krot[b0:b0 + n][:, kvh].cpu().double().numpy(), ref["k_rot"]) <= BF16_REL
+
+
 @pytest.mark.parametrize("name", BF16_CONFIGS)
 def test_full_size_register_rows_of_last_full_layer(name):
     """earn_prefill_register_rows at full size, as bench.py launches it (query rows gathered by earn_compact_registers):
