@@ -12,9 +12,14 @@
  *   - tensors are row-major, packed ragged over the batch: [tokens, heads, head_dim], element type bf16 or fp32
  *     (earn_attn_desc.dtype); softmax statistics and accumulators are fp32; lengths and indices are int32;
  *   - scalars the host needs for grid sizing (batch, total_tokens, max_seqlen, ...) are passed by value so that no
- *     device-to-host read is needed.  Conditions that live in device memory (monotone cu_seqlens, n_s >= h+t,
- *     gen_len < gen_cap, positions >= 0) are PRECONDITIONS; kernels clamp their loops to the sizes passed by value so
- *     that a violated precondition gives wrong values, not an out-of-bounds access beyond the stated extents;
+ *     device-to-host read is needed.  Conditions that live in device memory (cu_seqlens starting at 0 and
+ *     non-decreasing, n_s >= h+t, 0 <= gen_len < gen_cap, stream_to_seq in [0, batch), positions >= 0) are
+ *     PRECONDITIONS and are NOT checked by a normal call.  What the kernels do guard: gen_len is clamped into
+ *     [0, gen_cap) before the cache append and the walk over the generated rows, stream_to_seq is clamped into
+ *     [0, batch), and the compaction clamps a source row into its sequence (an empty sequence yields zero rows);
+ *     the VALUES of cu_seqlens / shared_cu are trusted: wrong bounds there read or write outside the tensors.
+ *     earn_set_validation(1) switches on a debug mode in which every call first copies these arrays to the host,
+ *     checks them and returns EARN_ERR_INVALID_ARG before any kernel is launched;
  *   - return value: EARN_OK or a negative error code; earn_last_error() returns a thread-local message.
  *
  * The split layer k and the layer count N are not kernel arguments: the caller expresses them by which cache and
@@ -47,8 +52,12 @@ extern "C" {
 typedef struct {
   int32_t dtype;          /* EARN_F32 | EARN_BF16: element type of q, k, v, out and the caches */
   int32_t n_q_heads;      /* Hq */
-  int32_t n_kv_heads;     /* Hkv; Hq % Hkv == 0; query head a reads kv head a / (Hq/Hkv) (grouped-query attention) */
+  int32_t n_kv_heads;     /* Hkv; Hq % Hkv == 0 */
   int32_t head_dim;       /* d: 64 or 128 */
+  const int32_t* q_to_kv; /* HOST array [Hq] or NULL: kv head that query head a reads (grouped-query attention).
+                             NULL means a / (Hq/Hkv).  An explicit map may permute the heads but must give every kv
+                             head exactly Hq/Hkv query heads, and Hq <= 128; anything else -> EARN_ERR_UNSUPPORTED
+                             (the kernels serve the query heads of a kv head together, in groups of equal size) */
   float softmax_scale;    /* <= 0 means 1/sqrt(head_dim) (Eq. 3) */
   float rope_base;        /* rotary base (10000); <= 0 disables the rotation */
 } earn_attn_desc;
@@ -58,6 +67,30 @@ const char* earn_last_error(void);
 
 /* Library version string and the GPU architecture the kernels were built for. */
 const char* earn_version(void);
+
+/*
+ * Debug validation of the preconditions that live in device memory (process-wide switch, off by default; returns the
+ * previous setting).  While it is on, every entry point copies cu_seqlens / positions / gen_len / stream_to_seq /
+ * q_pos / row_pos to the host on `stream`, WAITS for the stream, checks them (cu_seqlens[0] == 0, non-decreasing,
+ * cu_seqlens[batch] == total_tokens, lengths <= max_seqlen / max_shared_len, n_s >= h + t, 0 <= gen_len < gen_cap,
+ * stream_to_seq in [0, batch) with at most 1024 streams per sequence, positions and q_pos in [0, 2^24), row_pos
+ * ascending and inside its sequence) and returns EARN_ERR_INVALID_ARG, with a message naming the first offending
+ * element, BEFORE any kernel is launched.  A call that passes behaves exactly as without validation.
+ */
+int earn_set_validation(int enabled);
+
+/*
+ * Launch-shape overrides for measurements (process-wide; the defaults are what was measured best, a value of 0
+ * restores a default).  Returns EARN_OK, or EARN_ERR_INVALID_ARG for an unknown key.  Keys:
+ *   "prefill_block_rows"    128 | 256: query rows per workgroup of the bf16 full-length prefill
+ *   "decode_mfma_min_len"   shortest shared cache (rows) that always takes the matrix-core decode kernel (128)
+ *   "decode_mfma_short_wgs" shorter caches take it when Hkv * batch is at most this (256)
+ *   "decode_mfma_wgs"       workgroups the matrix-core decode kernel's key splits aim at (256)
+ *   "decode_vec_wgs"        workgroups the vector decode kernel's key splits aim at (1024)
+ *   "decode_vec_waves"      waves per workgroup of the vector decode kernel (1, 2 or 4)
+ *   "compact_blocks"        16 KB blocks one compaction workgroup copies (1..4)
+ */
+int earn_set_tuning(const char* key, int32_t value);
 
 /*
  * Causal prefill attention over a packed ragged batch (paper Section 2.2, Eq. 3; used for the "full computation"

@@ -25,7 +25,8 @@ EARN_MAX_COMPACT_TENSORS = 112
 
 EXPORTS = ["earn_last_error", "earn_version", "earn_prefill_attn", "earn_prefill_workspace_bytes",
            "earn_compact_registers", "earn_decode_attn", "earn_decode_workspace_bytes", "earn_cache_entries",
-           "earn_prefill_register_rows", "earn_prefill_register_rows_workspace_bytes"]
+           "earn_prefill_register_rows", "earn_prefill_register_rows_workspace_bytes", "earn_set_validation",
+           "earn_set_tuning"]
 
 
 class EarnError(RuntimeError):
@@ -36,7 +37,8 @@ class EarnError(RuntimeError):
 
 class AttnDesc(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
-                ("head_dim", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("rope_base", ctypes.c_float)]
+                ("head_dim", ctypes.c_int32), ("q_to_kv", ctypes.POINTER(ctypes.c_int32)),
+                ("softmax_scale", ctypes.c_float), ("rope_base", ctypes.c_float)]
 
 
 def lib():
@@ -68,6 +70,10 @@ def lib():
         L.earn_decode_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), i32, i32, i32, i32]
         L.earn_cache_entries.restype = ctypes.c_int64
         L.earn_cache_entries.argtypes = [i32, i32, ctypes.c_int64, i32, ctypes.c_int64]
+        L.earn_set_validation.restype = ctypes.c_int
+        L.earn_set_validation.argtypes = [ctypes.c_int]
+        L.earn_set_tuning.restype = ctypes.c_int
+        L.earn_set_tuning.argtypes = [ctypes.c_char_p, i32]
         _lib = L
     return _lib
 
@@ -93,9 +99,23 @@ def _stream():
 
 
 def make_desc(dtype: torch.dtype, n_q_heads: int, n_kv_heads: int, head_dim: int, softmax_scale: float = 0.0,
-              rope_base: float = 10000.0) -> AttnDesc:
+              rope_base: float = 10000.0, q_to_kv: Optional[Sequence[int]] = None) -> AttnDesc:
     code = {torch.float32: EARN_F32, torch.bfloat16: EARN_BF16}.get(dtype, 99)
-    return AttnDesc(code, n_q_heads, n_kv_heads, head_dim, softmax_scale, rope_base)
+    desc = AttnDesc(code, n_q_heads, n_kv_heads, head_dim, None, softmax_scale, rope_base)
+    if q_to_kv is not None:
+        arr = (ctypes.c_int32 * len(q_to_kv))(*q_to_kv)
+        desc.q_to_kv = ctypes.cast(arr, ctypes.POINTER(ctypes.c_int32))
+        desc._q_to_kv_keepalive = arr  # the struct holds a bare pointer
+    return desc
+
+
+def earn_set_validation(enabled: bool) -> bool:
+    """Debug validation of device-side preconditions (synchronises the stream on every call). Returns the old setting."""
+    return bool(lib().earn_set_validation(int(bool(enabled))))
+
+
+def earn_set_tuning(key: str, value: int) -> None:
+    _check(lib().earn_set_tuning(key.encode(), int(value)))
 
 
 def earn_prefill_workspace_bytes(desc: AttnDesc, batch: int, total_tokens: int, max_seqlen: int,

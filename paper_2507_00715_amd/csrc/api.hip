@@ -4,6 +4,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+#include <vector>
+
 #include "common.h"
 
 namespace earn {
@@ -63,15 +66,100 @@ int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const vo
                         const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen, int rows_per_seq,
                         void* out_rows, void* workspace, size_t workspace_bytes, hipStream_t stream);
 
+static std::atomic<int> g_tuning[kTuneCount];
+int tuning(Tuning t, int dflt) {
+  const int v = g_tuning[t].load(std::memory_order_relaxed);
+  return v > 0 ? v : dflt;
+}
+
+int make_head_map(const earn_attn_desc* d, HeadMap* m, const char* who) {
+  memset(m, 0, sizeof(*m));
+  if (!d->q_to_kv) return EARN_OK;
+  const int hq = d->n_q_heads, hkv = d->n_kv_heads, gq = hq / hkv;
+  if (hq > kMaxMappedHeads) { set_error("%s: an explicit q_to_kv map takes at most %d query heads", who, kMaxMappedHeads); return EARN_ERR_UNSUPPORTED; }
+  int count[kMaxMappedHeads] = {0};
+  bool identity = true;
+  for (int a = 0; a < hq; ++a) {
+    const int c = d->q_to_kv[a];
+    if (c < 0 || c >= hkv) { set_error("%s: q_to_kv[%d] = %d outside [0, %d)", who, a, c, hkv); return EARN_ERR_INVALID_ARG; }
+    if (count[c] >= gq) {
+      set_error("%s: q_to_kv gives kv head %d more than Hq/Hkv = %d query heads (groups of unequal size are not supported)", who, c, gq);
+      return EARN_ERR_UNSUPPORTED;
+    }
+    m->q_of_slot[c * gq + count[c]++] = (unsigned char)a;
+    identity = identity && c == a / gq;
+  }
+  m->enabled = identity ? 0 : 1;
+  return EARN_OK;
+}
+
 static int check_desc(const earn_attn_desc* d, const char* who) {
   if (!d) { set_error("%s: desc is NULL", who); return EARN_ERR_INVALID_ARG; }
   if (d->dtype != EARN_F32 && d->dtype != EARN_BF16) { set_error("%s: unknown dtype %d", who, d->dtype); return EARN_ERR_UNSUPPORTED; }
   if (d->n_q_heads <= 0 || d->n_kv_heads <= 0) { set_error("%s: head counts must be positive", who); return EARN_ERR_INVALID_ARG; }
   if (d->n_q_heads % d->n_kv_heads != 0) {
     set_error("%s: n_q_heads (%d) is not a multiple of n_kv_heads (%d)", who, d->n_q_heads, d->n_kv_heads);
-    return EARN_ERR_INVALID_ARG;
+    return d->q_to_kv ? EARN_ERR_UNSUPPORTED : EARN_ERR_INVALID_ARG;
   }
   if (d->head_dim != 64 && d->head_dim != 128) { set_error("%s: head_dim %d not in {64,128}", who, d->head_dim); return EARN_ERR_UNSUPPORTED; }
+  HeadMap m;
+  return make_head_map(d, &m, who);
+}
+
+// ---- debug validation of the preconditions that live in device memory ----
+static std::atomic<int> g_validate{0};
+
+// copies n int32 from device to host on the stream and waits for it
+static int fetch_i32(const int32_t* dev, size_t n, std::vector<int32_t>& host, hipStream_t stream, const char* who) {
+  host.resize(n);
+  if (n == 0) return EARN_OK;
+  if (hipMemcpyAsync(host.data(), dev, n * sizeof(int32_t), hipMemcpyDeviceToHost, stream) != hipSuccess ||
+      hipStreamSynchronize(stream) != hipSuccess) {
+    set_error("%s: validation could not read a device array", who);
+    return EARN_ERR_HIP;
+  }
+  return EARN_OK;
+}
+// cu[0] == 0, non-decreasing, every length <= max_len, cu[batch] == total (total < 0: not checked)
+static int validate_cu(const char* who, const char* name, const std::vector<int32_t>& cu, int batch, long long total,
+                       int max_len) {
+  if (cu[0] != 0) { set_error("%s: %s[0] = %d, must be 0", who, name, cu[0]); return EARN_ERR_INVALID_ARG; }
+  for (int s = 0; s < batch; ++s) {
+    if (cu[s + 1] < cu[s]) { set_error("%s: %s decreases at %d (%d -> %d)", who, name, s, cu[s], cu[s + 1]); return EARN_ERR_INVALID_ARG; }
+    if (cu[s + 1] - cu[s] > max_len) {
+      set_error("%s: sequence %d has %d rows, more than the bound %d passed by value", who, s, cu[s + 1] - cu[s], max_len);
+      return EARN_ERR_INVALID_ARG;
+    }
+  }
+  if (total >= 0 && cu[batch] != total) { set_error("%s: %s[batch] = %d, expected %lld", who, name, cu[batch], total); return EARN_ERR_INVALID_ARG; }
+  return EARN_OK;
+}
+static int validate_positions(const char* who, const char* name, const std::vector<int32_t>& p) {
+  for (size_t i = 0; i < p.size(); ++i)
+    if (p[i] < 0 || p[i] >= (1 << 24)) { set_error("%s: %s[%zu] = %d outside [0, 2^24)", who, name, i, p[i]); return EARN_ERR_INVALID_ARG; }
+  return EARN_OK;
+}
+
+static int validate_decode(const char* who, const int32_t* q_pos, const int32_t* shared_cu, const int32_t* stream_to_seq,
+                           const int32_t* gen_len, int gen_cap, int n_streams, int batch, int max_shared_len,
+                           hipStream_t stream) {
+  std::vector<int32_t> cu, qp, gl, s2s;
+  int rc;
+  if ((rc = fetch_i32(shared_cu, (size_t)batch + 1, cu, stream, who)) != EARN_OK) return rc;
+  if ((rc = validate_cu(who, "shared_cu", cu, batch, -1, max_shared_len)) != EARN_OK) return rc;
+  if ((rc = fetch_i32(q_pos, (size_t)n_streams, qp, stream, who)) != EARN_OK) return rc;
+  if ((rc = validate_positions(who, "q_pos", qp)) != EARN_OK) return rc;
+  if ((rc = fetch_i32(gen_len, (size_t)n_streams, gl, stream, who)) != EARN_OK) return rc;
+  for (int u = 0; u < n_streams; ++u)
+    if (gl[u] < 0 || gl[u] >= gen_cap) { set_error("%s: gen_len[%d] = %d outside [0, gen_cap = %d)", who, u, gl[u], gen_cap); return EARN_ERR_INVALID_ARG; }
+  if (stream_to_seq) {
+    if ((rc = fetch_i32(stream_to_seq, (size_t)n_streams, s2s, stream, who)) != EARN_OK) return rc;
+    std::vector<int32_t> per_seq((size_t)batch, 0);
+    for (int u = 0; u < n_streams; ++u) {
+      if (s2s[u] < 0 || s2s[u] >= batch) { set_error("%s: stream_to_seq[%d] = %d outside [0, batch = %d)", who, u, s2s[u], batch); return EARN_ERR_INVALID_ARG; }
+      if (++per_seq[s2s[u]] > 1024) { set_error("%s: sequence %d holds more than 1024 streams", who, s2s[u]); return EARN_ERR_INVALID_ARG; }
+    }
+  }
   return EARN_OK;
 }
 
@@ -83,7 +171,19 @@ extern "C" {
 
 const char* earn_last_error(void) { return g_err; }
 
-const char* earn_version(void) { return "libearn 0.1 (gfx950)"; }
+const char* earn_version(void) { return "libearn 0.2 (gfx950)"; }
+
+int earn_set_validation(int enabled) { return g_validate.exchange(enabled ? 1 : 0); }
+
+int earn_set_tuning(const char* key, int32_t value) {
+  static const char* const names[kTuneCount] = {"prefill_block_rows", "decode_mfma_min_len", "decode_mfma_short_wgs",
+                                                "decode_mfma_wgs", "decode_vec_wgs", "decode_vec_waves", "compact_blocks"};
+  g_err[0] = 0;
+  for (int i = 0; key && i < kTuneCount; ++i)
+    if (strcmp(key, names[i]) == 0) { g_tuning[i].store(value > 0 ? value : 0, std::memory_order_relaxed); return EARN_OK; }
+  set_error("earn_set_tuning: unknown key '%s'", key ? key : "(null)");
+  return EARN_ERR_INVALID_ARG;
+}
 
 size_t earn_prefill_workspace_bytes(const earn_attn_desc* desc, int32_t batch, int32_t total_tokens,
                                     int32_t max_seqlen, int32_t have_k_rot_out) {
@@ -106,6 +206,16 @@ int earn_prefill_attn(const earn_attn_desc* desc, const void* q, const void* k, 
   if (!cu_seqlens) { set_error("earn_prefill_attn: cu_seqlens is NULL"); return EARN_ERR_INVALID_ARG; }
   if (total_tokens == 0) return EARN_OK;
   if (!q || !k || !v || !out) { set_error("earn_prefill_attn: q, k, v and out must not be NULL"); return EARN_ERR_INVALID_ARG; }
+  if (g_validate.load(std::memory_order_relaxed)) {
+    const char* who = "earn_prefill_attn";
+    std::vector<int32_t> cu, pos;
+    if ((rc = fetch_i32(cu_seqlens, (size_t)batch + 1, cu, (hipStream_t)stream, who)) != EARN_OK) return rc;
+    if ((rc = validate_cu(who, "cu_seqlens", cu, batch, total_tokens, max_seqlen)) != EARN_OK) return rc;
+    if (positions) {
+      if ((rc = fetch_i32(positions, (size_t)total_tokens, pos, (hipStream_t)stream, who)) != EARN_OK) return rc;
+      if ((rc = validate_positions(who, "positions", pos)) != EARN_OK) return rc;
+    }
+  }
   if (max_seqlen > total_tokens) max_seqlen = total_tokens;
   return launch_prefill(desc, q, k, v, cu_seqlens, positions, batch, total_tokens, max_seqlen, out, k_rot_out, lse_out,
                         workspace, workspace_bytes, (hipStream_t)stream);
@@ -134,6 +244,18 @@ int earn_compact_registers(int32_t n_tensors, const void* const* src, void* cons
       set_error("earn_compact_registers: row_bytes[%d] = %lld is not a positive multiple of 16", i, (long long)row_bytes[i]);
       return EARN_ERR_INVALID_ARG;
     }
+  }
+  if (g_validate.load(std::memory_order_relaxed)) {
+    const char* who = "earn_compact_registers";
+    std::vector<int32_t> cu;
+    int rc = fetch_i32(cu_seqlens, (size_t)batch + 1, cu, (hipStream_t)stream, who);
+    if (rc != EARN_OK) return rc;
+    if ((rc = validate_cu(who, "cu_seqlens", cu, batch, -1, 0x7fffffff)) != EARN_OK) return rc;
+    for (int s = 0; s < batch; ++s)
+      if (cu[s + 1] - cu[s] < n_head_reg + n_tail_reg) {
+        set_error("%s: sequence %d has %d rows, fewer than h + t = %d", who, s, cu[s + 1] - cu[s], n_head_reg + n_tail_reg);
+        return EARN_ERR_INVALID_ARG;
+      }
   }
   return launch_compact(n_tensors, src, dst, row_bytes, cu_seqlens, batch, n_head_reg, n_tail_reg, idx_out, pos_out,
                         cu_out, (hipStream_t)stream);
@@ -164,6 +286,10 @@ int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_ne
   }
   if (max_shared_len > 0 && (!shared_k || !shared_v)) { set_error("earn_decode_attn: shared_k/shared_v are NULL but max_shared_len > 0"); return EARN_ERR_INVALID_ARG; }
   if (!stream_to_seq && n_streams != batch) { set_error("earn_decode_attn: stream_to_seq is NULL but n_streams (%d) != batch (%d)", n_streams, batch); return EARN_ERR_INVALID_ARG; }
+  if (g_validate.load(std::memory_order_relaxed) &&
+      (rc = validate_decode("earn_decode_attn", q_pos, shared_cu, stream_to_seq, gen_len, gen_cap, n_streams, batch,
+                            max_shared_len, (hipStream_t)stream)) != EARN_OK)
+    return rc;
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
                        gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream);
 }
@@ -195,6 +321,21 @@ int earn_prefill_register_rows(const earn_attn_desc* desc, const void* q_rows, c
   if (!q_rows || !k || !v || !cu_seqlens || !row_pos || !out_rows || !k_rot_out) {
     set_error("earn_prefill_register_rows: a required pointer is NULL");
     return EARN_ERR_INVALID_ARG;
+  }
+  if (g_validate.load(std::memory_order_relaxed)) {
+    const char* who = "earn_prefill_register_rows";
+    std::vector<int32_t> cu, rp;
+    if ((rc = fetch_i32(cu_seqlens, (size_t)batch + 1, cu, (hipStream_t)stream, who)) != EARN_OK) return rc;
+    if ((rc = validate_cu(who, "cu_seqlens", cu, batch, total_tokens, max_seqlen)) != EARN_OK) return rc;
+    if ((rc = fetch_i32(row_pos, (size_t)batch * rows_per_seq, rp, (hipStream_t)stream, who)) != EARN_OK) return rc;
+    for (int s = 0; s < batch; ++s)
+      for (int m = 0; m < rows_per_seq; ++m) {
+        const int p = rp[(size_t)s * rows_per_seq + m], n = cu[s + 1] - cu[s];
+        if (p < 0 || p >= n || (m > 0 && p <= rp[(size_t)s * rows_per_seq + m - 1])) {
+          set_error("%s: row_pos[%d] = %d (row %d of sequence %d, %d tokens) is outside the sequence or not ascending", who, s * rows_per_seq + m, p, m, s, n);
+          return EARN_ERR_INVALID_ARG;
+        }
+      }
   }
   if (desc->dtype == EARN_F32) {
     rc = launch_rope_keys(desc, k, k_rot_out, cu_seqlens, nullptr, batch, total_tokens, (hipStream_t)stream);

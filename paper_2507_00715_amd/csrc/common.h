@@ -28,8 +28,24 @@ struct RopeTable {
   int enabled;
 };
 
+// Query heads in the order the kernels serve them: slot c * gq + i is the i-th query head (ascending) that reads kv
+// head c, gq = Hq / Hkv.  Without an explicit map (enabled == 0) slot and head coincide.
+constexpr int kMaxMappedHeads = 128;
+struct HeadMap {
+  unsigned char q_of_slot[kMaxMappedHeads];
+  int enabled;
+};
+__device__ __forceinline__ int head_of_slot(const HeadMap& m, int slot) { return m.enabled ? (int)m.q_of_slot[slot] : slot; }
+
 void set_error(const char* fmt, ...);
 RopeTable make_rope_table(float base, int head_dim);
+// Fills `m` from desc->q_to_kv; EARN_OK, or an error (message set) for a map the kernels cannot serve.
+int make_head_map(const earn_attn_desc* desc, HeadMap* m, const char* who);
+
+// launch-shape overrides (earn_set_tuning); 0 = default
+enum Tuning { kTunePrefillBlockRows, kTuneDecMfmaMinLen, kTuneDecMfmaShortWgs, kTuneDecMfmaWgs, kTuneDecVecWgs,
+              kTuneDecVecWaves, kTuneCompactBlocks, kTuneCount };
+int tuning(Tuning t, int dflt);
 
 __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) { return __uint_as_float(((unsigned int)b) << 16); }
 __device__ __forceinline__ float bf16_lo(unsigned int w) { return __uint_as_float(w << 16); }

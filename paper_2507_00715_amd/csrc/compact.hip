@@ -3,8 +3,6 @@
 // OUTPUT, which is contiguous: every lane owns 16-byte units of the compacted tensor, a wave stores 1 KiB of
 // consecutive bytes per instruction, and the source of a unit is found with integer arithmetic only.  Source rows
 // of one register group (h head rows, t tail rows) are consecutive in memory as well, so loads coalesce too.
-#include <stdlib.h>
-
 #include "common.h"
 
 namespace earn {
@@ -22,13 +20,15 @@ constexpr int kCompactThreads = 256;
 constexpr int kCompactUnroll = 4;  // 16-byte units per lane: 4 loads in flight before the first store
 constexpr int kCompactBlocksPerWg = 4;  // blocks (kCompactThreads * kCompactUnroll units) a workgroup copies at most
 
-// source row of compacted row m
+// source row of compacted row m; a sequence shorter than h + t (a violated precondition) has its rows clamped into the
+// sequence, an empty one yields -1 (no row)
 __device__ __forceinline__ int source_row(const int32_t* __restrict__ cu, int m, int r, int h, int t, int* pos) {
   int s = m / r, j = m - s * r;
   int b0 = cu[s], n = cu[s + 1] - b0;
   int p = j < h ? j : n - t + (j - h);
+  p = max(min(p, n - 1), 0);
   *pos = p;
-  return b0 + p;
+  return n > 0 ? b0 + p : -1;
 }
 
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactArgs args, const int32_t* __restrict__ cu,
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactArgs ar
         unsigned int off = (unsigned int)(u[i] - (long long)m * upr);
         int pos;
         long long row = source_row(cu, m, r, h, t, &pos);
-        v[i] = __builtin_nontemporal_load(src + row * upr + off);
+        v[i] = row >= 0 ? __builtin_nontemporal_load(src + row * upr + off) : u32x4{0u, 0u, 0u, 0u};
       }
     }
 #pragma unroll
@@ -99,7 +99,7 @@ int launch_compact(int n_tensors, const void* const* src, void* const* dst, cons
   // a dozen workgroups per CU.
   long long total_blocks = 0;
   for (int i = 0; i < n_tensors; ++i) total_blocks += (rows_out * (row_bytes[i] / 16) + per_block - 1) / per_block;
-  static const int iters_env = getenv("EARN_COMPACT_ITERS") ? atoi(getenv("EARN_COMPACT_ITERS")) : 0;
+  const int iters_env = tuning(kTuneCompactBlocks, 0);
   long long iters = iters_env > 0 ? iters_env : 4096 / (rows_out > 0 ? rows_out : 1);
   if (iters_env <= 0 && iters > total_blocks / 4096) iters = total_blocks / 4096;
   if (iters_env <= 0 && iters > kCompactBlocksPerWg) iters = kCompactBlocksPerWg;

@@ -10,8 +10,6 @@
 //     across the 4 waves;
 //   * the key range of a long cache is split over several workgroups (split-K); partial (max, sum, out) triples go to
 //     the workspace and a second kernel merges them.
-#include <stdlib.h>
-
 #include <type_traits>
 
 #include "common.h"
@@ -84,7 +82,12 @@ struct DecodeParams {
   int n_pass;
   float scale_log2;
   RopeTable rope;
+  HeadMap heads;
 };
+
+// gen_len as the kernels use it: inside [0, gen_cap), so that a violated precondition cannot move the cache append or
+// the walk over the generated rows outside the stream's cache
+__device__ __forceinline__ int clamp_gen_len(int g, int gen_cap) { return max(min(g, gen_cap - 1), 0); }
 
 // Sum over the LPK (8 or 16) adjacent lanes that hold one key row, left in every lane of the group.  Data-parallel
 // primitives instead of shuffles through LDS: pairs, quads, the mirrored half (lane i <-> 7-i: the other quad), the
@@ -125,10 +128,10 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
   constexpr int KPW = kWave / LPK;   // key rows per wave instruction
   const int gq = p.hq / p.hkv;       // query heads per kv head
   const int sub = lane % LPK, kk = lane / LPK;
-  const int s = p.stream_to_seq ? p.stream_to_seq[u] : u;
+  const int s = p.stream_to_seq ? max(min(p.stream_to_seq[u], p.batch - 1), 0) : u;
   const int b0 = p.shared_cu[s];
   const int ns = p.shared_cu[s + 1] - b0;
-  const int g = p.gen_len[u];
+  const int g = clamp_gen_len(p.gen_len[u], p.gen_cap);
   const int m_total = ns + g + 1;    // shared rows, earlier generated rows, the new token
   const float pos = (float)p.q_pos[u];
 
@@ -193,7 +196,7 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
 #pragma unroll
   for (int a = 0; a < GQ; ++a) {
     if (a < gq) {
-      Row8<T>::load((const T*)p.q + ((long long)u * p.hq + c * gq + a) * D + sub * 8, qv[a]);
+      Row8<T>::load((const T*)p.q + ((long long)u * p.hq + head_of_slot(p.heads, c * gq + a)) * D + sub * 8, qv[a]);
       rotate(qv[a]);
 #pragma unroll
       for (int i = 0; i < 8; ++i) qv[a][i] *= p.scale_log2;
@@ -294,7 +297,7 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
   }
   // write one finished (head, 8-element group) state: final output or a partial slot
   auto finish = [&](int a, int sb, float m, float l, float* oo) {
-    const int head = c * gq + a;
+    const int head = head_of_slot(p.heads, c * gq + a);
     if (p.n_slots == 1) {
       float inv = 1.f / l;
 #pragma unroll
@@ -481,7 +484,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
       const int u = base + k4 * kWave + lane;
       const bool in = u < p.n_streams;
       seq_of[k4] = in ? p.stream_to_seq[u] : -1;
-      gl[k4] = in ? p.gen_len[u] : 0;
+      gl[k4] = in ? clamp_gen_len(p.gen_len[u], p.gen_cap) : 0;
       qp[k4] = in ? p.q_pos[u] : 0;
     }
   };
@@ -534,7 +537,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         sm.qpos[i] = (float)p.q_pos[s * count + i];
       }
     } else if (!p.stream_to_seq) {
-      gmax = p.gen_len[s];
+      gmax = clamp_gen_len(p.gen_len[s], p.gen_cap);
       if (lane == 0) { sm.streams[0] = s; sm.glen[0] = gmax; sm.qpos[0] = (float)p.q_pos[s]; }
       count = 1;
     } else {
@@ -575,7 +578,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   u32x4 q_lo[KSTEPS / 2], q_hi[KSTEPS / 2];
   auto load_q_raw = [&](int row0) {
     const int m = min(row0 + 32 * grp + r32, M - 1);
-    const __bf16* qrow = (const __bf16*)p.q + ((long long)sm.streams[m / gq] * p.hq + c * gq + m % gq) * D + 8 * hf;
+    const __bf16* qrow = (const __bf16*)p.q + ((long long)sm.streams[m / gq] * p.hq + head_of_slot(p.heads, c * gq + m % gq)) * D + 8 * hf;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS / 2; ++ks) {
       q_lo[ks] = *(const u32x4*)(qrow + 16 * ks);
@@ -671,7 +674,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     if (row0 > row_begin) load_q_raw(row0);
     {
       const int m = min(row0 + 32 * grp + r32, M - 1);
-      row_u = sm.streams[m / gq]; row_a = c * gq + m % gq;
+      row_u = sm.streams[m / gq]; row_a = head_of_slot(p.heads, c * gq + m % gq);
       const float pos = sm.qpos[m / gq];
 #pragma unroll
       for (int ks = 0; ks < KSTEPS / 2; ++ks) {
@@ -1000,9 +1003,9 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
   const int gq = hq / hkv;
   // several query rows per cache (grouped heads or beams) make the shared part a matrix product
   // (short caches are launch-latency bound: the single-launch vector kernel wins there)
-  static const int mfma_min = getenv("EARN_DEC_MFMA_MIN") ? atoi(getenv("EARN_DEC_MFMA_MIN")) : 128;
+  const int mfma_min = tuning(kTuneDecMfmaMinLen, 128);
   // ... unless all its workgroups (one per CU: they hold most of the LDS) fit on the GPU at once
-  static const int mfma_wgs = getenv("EARN_DEC_MFMA_SHORT_WGS") ? atoi(getenv("EARN_DEC_MFMA_SHORT_WGS")) : 256;
+  const int mfma_wgs = tuning(kTuneDecMfmaShortWgs, 256);
   pl.mfma = dtype == EARN_BF16 && (gq > 1 || n_streams > batch) &&
             (max_shared_len >= mfma_min || (long long)hkv * batch <= mfma_wgs);
   pl.n_pass = 1;
@@ -1012,10 +1015,9 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
     // splits: the passes of a (sequence, kv head) then run side by side on one XCD and share the keys in its L2.  (The
     // last pass takes whatever rows a sequence has beyond the plan.)
     const long long rows_bound = (long long)gq * (n_streams - batch + 1), rows_avg = (long long)gq * ((n_streams + batch - 1) / batch);
-    static const int pass_grid = getenv("EARN_DEC_PASS_GRID") ? atoi(getenv("EARN_DEC_PASS_GRID")) : 1;
-    if (pass_grid && rows_bound > 32 && rows_avg > 64) pl.n_pass = (int)((rows_avg + 63) / 64);
+    if (rows_bound > 32 && rows_avg > 64) pl.n_pass = (int)((rows_avg + 63) / 64);
     long long base = (long long)hkv * batch * pl.n_pass;
-    static const int wg_env = getenv("EARN_DEC_WGS") ? atoi(getenv("EARN_DEC_WGS")) : 256;
+    const int wg_env = tuning(kTuneDecMfmaWgs, 256);
     int want = (int)((wg_env + base - 1) / base);               // one workgroup per CU: it holds 8 waves and most of the LDS
     int cap = (max_shared_len + kDsSuper - 1) / kDsSuper;  // at least one super-tile per workgroup
     int n = want < cap ? want : cap;
@@ -1028,7 +1030,7 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
     const int max_total = max_shared_len + gen_cap;
     // aim at >= 1024 workgroups (4 per CU) while keeping at least 256 keys per split
     long long base = (long long)hkv * n_streams;
-    static const int wgs_env = getenv("EARN_DEC_VEC_WGS") ? atoi(getenv("EARN_DEC_VEC_WGS")) : 1024;
+    const int wgs_env = tuning(kTuneDecVecWgs, 1024);
     int want = (int)((wgs_env + base - 1) / base);
     int cap = (max_total + 255) / 256;
     int n = want < cap ? want : cap;
@@ -1062,7 +1064,7 @@ static void launch_vector(const DecodeParams& p, int gq, dim3 grid, hipStream_t 
   // Short key lists are latency bound: every wave repeats the prologue (query rotation), and what counts is that all
   // workgroups are resident at once.  One wave per (stream, kv head) for a single query head, two for grouped heads
   // (more arithmetic per key); long key lists take four.
-  static const int waves_env = getenv("EARN_DEC_VEC_WAVES") ? atoi(getenv("EARN_DEC_VEC_WAVES")) : 0;
+  const int waves_env = tuning(kTuneDecVecWaves, 0);
   const int waves = waves_env ? waves_env : (p.chunk > 128 ? 4 : (gq == 1 ? 1 : 2));
   if (waves == 1) launch_vector_w<T, D, 1>(p, gq, grid, stream);
   else if (waves == 2) launch_vector_w<T, D, 2>(p, gq, grid, stream);
@@ -1126,6 +1128,7 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
   p.rope = make_rope_table(desc->rope_base, d);
+  if (make_head_map(desc, &p.heads, "earn_decode_attn") != EARN_OK) return EARN_ERR_UNSUPPORTED;
   if (desc->dtype == EARN_F32) {
     if (d == 64) launch_decode_t<float, 64>(p, pl, gq, stream); else launch_decode_t<float, 128>(p, pl, gq, stream);
   } else {
@@ -1194,6 +1197,7 @@ int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const vo
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
   p.rope = make_rope_table(desc->rope_base, d);
+  if (make_head_map(desc, &p.heads, "earn_prefill_register_rows") != EARN_OK) return EARN_ERR_UNSUPPORTED;
   const dim3 grid((unsigned)(((long long)batch * p.n_splits * n_pass + 7) / 8 * 8 * hkv), 1, 1);
   const bool one_group = rows_per_seq * gq <= 32;
   if (d == 64) {

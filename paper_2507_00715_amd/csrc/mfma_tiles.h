@@ -27,11 +27,16 @@ __device__ __forceinline__ int swz(int row) {
 // reads such a load may alias and drains the whole vector-memory queue before every later LDS read, which would allow
 // no more than a fraction of one tile's compute time for a tile to arrive.  Here the kernels keep the order themselves:
 // a buffer is read only after a wait for the wave's own loads plus a workgroup barrier.  The kernels use M0 for
-// nothing else.  The wait state between the M0 write and the load is the one the compiler also leaves.
-__device__ __forceinline__ void dma16_to_lds(u32x4 rsrc, unsigned lds_addr, int voff, int soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+// nothing else.  (M0 cannot be named in the clobber list: the compiler treats it as a reserved register and warns that
+// such a clobber is not honoured.  It only places values in M0 itself for instructions that read M0, none of which
+// these kernels contain: no LDS-direct or GWS operations, no relative register indexing, no s_sendmsg.)  The wait
+// state between the M0 write and the load is the one the compiler also leaves.
+// The whole byte offset travels in `voff`: the descriptor's range check covers the vector offset, which is what turns
+// rows past the end of the range into zeros; the scalar offset operand stays 0.
+__device__ __forceinline__ void dma16_to_lds(u32x4 rsrc, unsigned lds_addr, int voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :
-               : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+               : "s"(lds_addr), "v"(voff), "s"(rsrc)
                : "memory");
 }
 // Raw (unstrided, unswizzled) buffer descriptor over [base, base + bytes): accesses are range checked against `bytes`.
@@ -121,9 +126,9 @@ struct TileStager {
   }
   // this wave's share of tile t of one tensor, into the tile buffer at LDS byte address lds_tile
   __device__ __forceinline__ void issue(const u32x4& rsrc, unsigned lds_tile, int t) const {
-    const int soff = t * ROWS * row_bytes;
+    const int toff = t * ROWS * row_bytes;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) dma16_to_lds(rsrc, lds_tile + (unsigned)((wave + WAVES * i) * 1024), voff[i], soff);
+    for (int i = 0; i < NI; ++i) dma16_to_lds(rsrc, lds_tile + (unsigned)((wave + WAVES * i) * 1024), voff[i] + toff);
   }
 };
 

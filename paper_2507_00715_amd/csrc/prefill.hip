@@ -22,8 +22,6 @@
 //   transposing LDS reads (ds_read_b64_tr_b16: 4 consecutive keys of one d column) deliver from a V tile kept in its
 //   natural [key][d] layout.
 //   Each wave owns 32 query rows; the 64-key K/V tile in LDS is shared by the waves of a workgroup.
-#include <stdlib.h>
-
 #include "common.h"
 #include "mfma_tiles.h"
 
@@ -41,6 +39,7 @@ struct PrefillParams {
   int rows_per_seq;
   float scale_log2;
   RopeTable rope;
+  HeadMap heads;
 };
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -133,7 +132,8 @@ __global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T*
 template <typename T, int D>
 __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   constexpr int E = D / 8;  // elements per contiguous piece; a lane holds pieces [qt*E, +E) and [D/2 + qt*E, +E)
-  const int a = blockIdx.y, s = blockIdx.z;
+  const int slot = blockIdx.y, s = blockIdx.z;  // slot: the query heads in kv-head order
+  const int a = head_of_slot(p.heads, slot);
   const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
   const int row0 = blockIdx.x * 64;
   const int r = p.rows_per_seq;           // 0: every row of the sequence
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   const int mc = row_ok ? mrow : n_rows - 1;
   const int ic = r > 0 ? p.row_pos[s * r + mc] : mc;           // its token index: it sees keys 0 .. ic
   const long long io = r > 0 ? (long long)s * r + mc : (long long)b0 + mc;  // its row in q / out / lse
-  const int c = a / (p.hq / p.hkv);
+  const int c = slot / (p.hq / p.hkv);
   const T* qrow = (const T*)p.q + (io * p.hq + a) * D;
   float ql[E], qh[E];
 #pragma unroll
@@ -244,7 +244,7 @@ __device__ __forceinline__ PfBlock pf_map_block(const PrefillParams& p, int bloc
   const int qblk = p.n_qblk - 1 - rem / gq;
   const int s = pair / p.hkv;
   b.c = pair % p.hkv;
-  b.a = b.c * gq + rem % gq;
+  b.a = head_of_slot(p.heads, b.c * gq + rem % gq);
   b.b0 = p.cu[s];
   b.n = p.cu[s + 1] - b.b0;
   b.q0 = qblk * block_rows;
@@ -769,6 +769,7 @@ int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, cons
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
   p.rope = make_rope_table(desc->rope_base, d);
+  if (make_head_map(desc, &p.heads, "earn_prefill_register_rows") != EARN_OK) return EARN_ERR_UNSUPPORTED;
   dim3 grid((rows_per_seq + 63) / 64, p.hq, batch);
   if (d == 64) hipLaunchKernelGGL((prefill_rows_kernel<float, 64>), grid, dim3(256), 0, stream, p);
   else hipLaunchKernelGGL((prefill_rows_kernel<float, 128>), grid, dim3(256), 0, stream, p);
@@ -813,6 +814,7 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
   p.rope = make_rope_table(desc->rope_base, d);
+  if (make_head_map(desc, &p.heads, "earn_prefill_attn") != EARN_OK) return EARN_ERR_UNSUPPORTED;
   const bool f32 = desc->dtype == EARN_F32;
   if (f32) {
     if (d == 64) launch_rope_k<float, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
@@ -834,8 +836,8 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
     else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
     // 128-row workgroups (two per CU) in the plain schedule up to medium lengths, where the ends of a workgroup's
     // life (first tile's latency, output store) and the causal diagonal weigh most; the pipelined 256-row kernel beyond
-    static const int rows_env = getenv("EARN_PREFILL_ROWS") ? atoi(getenv("EARN_PREFILL_ROWS")) : 0;
-    const int block_rows = rows_env == 128 || rows_env == 256 ? rows_env : (max_seqlen <= 3072 ? 128 : 256);
+    const int rows_set = tuning(kTunePrefillBlockRows, 0);
+    const int block_rows = rows_set == 128 || rows_set == 256 ? rows_set : (max_seqlen <= 3072 ? 128 : 256);
     p.n_qblk = (max_seqlen + block_rows - 1) / block_rows;
     const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
     dim3 grid((unsigned)(pairs8 * p.n_qblk * (p.hq / p.hkv)), 1, 1);

@@ -33,7 +33,7 @@ def test_cache_entries_closed_form():
 
 
 def _desc(dtype=B.EARN_BF16, hq=4, hkv=2, d=64):
-    return B.AttnDesc(dtype, hq, hkv, d, 0.0, 10000.0)
+    return B.AttnDesc(dtype, hq, hkv, d, None, 0.0, 10000.0)
 
 
 def test_prefill_argument_errors():

@@ -10,10 +10,10 @@ import torch
 from oracle import earn_oracle as O
 from paper_2507_00715_amd import workloads as W
 
+from parity import check_attn as check
+
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-BF16_REL = 2e-2
-F32_ATOL = 1e-4
 
 
 def _B():
@@ -22,23 +22,10 @@ def _B():
     return binding
 
 
-def rel_fro(got, ref):
-    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30))
-
-
 def draw_heads(rng):
     hkv = int(rng.choice([1, 2, 3, 4, 8]))
     gq = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 7, 8]))
     return hkv * gq, hkv, int(rng.choice([64, 128]))
-
-
-def check(got: torch.Tensor, want: np.ndarray, dtype, what):
-    g = got.detach().cpu().double().numpy()
-    assert np.isfinite(g).all(), f"{what}: non-finite"
-    if dtype == torch.float32:
-        assert np.abs(g - want).max() <= F32_ATOL, f"{what}: max-abs {np.abs(g - want).max():.3e}"
-    else:
-        assert rel_fro(g, want) <= BF16_REL, f"{what}: rel-Frobenius {rel_fro(g, want):.3e}"
 
 
 @pytest.mark.parametrize("case", range(24))

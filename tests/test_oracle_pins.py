@@ -102,6 +102,36 @@ def test_prefill_equals_library_sdpa_without_rope(hq, hkv, d):
         np.testing.assert_allclose(res["out"][sl], ref, rtol=0, atol=1e-12)
 
 
+def test_explicit_softmax_scale_equals_rescaled_queries_and_library_sdpa():
+    """Eq. 3 with the factor 1/sqrt(d) replaced by an explicit scale s.  Scores are linear in q (the rotation is
+    linear too), so scale s on q equals the default scale on q * s * sqrt(d); and without rotation the library
+    routine takes the same scale directly.  Prefill and decode take the explicit branch alike."""
+    lens, hq, hkv, d, s_ = [1, 17, 40], 6, 2, 16, 0.37
+    q, k, v, cu = rand_batch(lens, hq, hkv, d)
+    res = O.prefill_attn(q, k, v, cu, scale=s_, rope_base=10000.0)
+    same = O.prefill_attn(q * (s_ * np.sqrt(d)), k, v, cu, rope_base=10000.0)
+    np.testing.assert_allclose(res["out"], same["out"], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(res["lse"], same["lse"], rtol=0, atol=1e-12)
+    assert np.abs(res["out"] - O.prefill_attn(q, k, v, cu, rope_base=10000.0)["out"]).max() > 1e-3  # it is not ignored
+    plain = O.prefill_attn(q, k, v, cu, scale=s_, rope_base=0.0)
+    for s in range(len(lens)):
+        sl = slice(cu[s], cu[s + 1])
+        tq = torch.from_numpy(q[sl]).permute(1, 0, 2)[None]
+        tk = torch.from_numpy(np.repeat(k[sl], hq // hkv, axis=1)).permute(1, 0, 2)[None]
+        tv = torch.from_numpy(np.repeat(v[sl], hq // hkv, axis=1)).permute(1, 0, 2)[None]
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=s_)[0]
+        np.testing.assert_allclose(plain["out"][sl], ref.permute(1, 0, 2).numpy(), rtol=0, atol=1e-12)
+    # decode step
+    S, gen_cap = 3, 2
+    dq, dk, dv = RNG.standard_normal((S, hq, d)), RNG.standard_normal((S, hkv, d)), RNG.standard_normal((S, hkv, d))
+    args = lambda qq: (qq, dk, dv, [l + 1 for l in lens], res["k_rot"], v, cu, None)
+    gk1, gv1 = np.zeros((S, gen_cap, hkv, d)), np.zeros((S, gen_cap, hkv, d))
+    gk2, gv2 = gk1.copy(), gv1.copy()
+    a = O.decode_attn(*args(dq), gk1, gv1, [0, 1, 0], scale=s_)
+    b = O.decode_attn(*args(dq * (s_ * np.sqrt(d))), gk2, gv2, [0, 1, 0])
+    np.testing.assert_allclose(a["out"], b["out"], rtol=0, atol=1e-12)
+
+
 def test_prefill_with_rope_equals_dense_mask_reference():
     lens = [23, 9]
     q, k, v, cu = rand_batch(lens, 4, 2, 16)
