@@ -194,6 +194,30 @@ size_t earn_decode_workspace_bytes(const earn_attn_desc* desc, int32_t n_streams
                                    int32_t max_shared_len, int32_t gen_cap);
 
 /*
+ * earn_decode_attn for callers that cannot allocate or pass device scratch memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as
+ * earn_decode_attn, without the workspace: the split-key partial results go to a buffer that lives inside the library
+ * (a file-scope device array of EARN_STATIC_SCRATCH_BYTES bytes, one copy per GPU, held until the process ends; its
+ * device address is looked up once per GPU, on the first call made with that GPU current).  The call allocates
+ * nothing and frees nothing (with earn_set_validation on, the debug checks do allocate host memory and wait for the
+ * stream: keep validation off in such callers).
+ *
+ * Every call on a GPU uses that GPU's one buffer, which keeps the previous call's contents; nothing in it has to
+ * start at zero (each partial result is written before it is read within a call).  Calls that overlap in time on one
+ * GPU (different streams, or threads) RACE on the buffer: serialise them, or use earn_decode_attn with a workspace
+ * per stream.
+ *
+ * Errors: as earn_decode_attn; a problem whose partial results need more than EARN_STATIC_SCRATCH_BYTES
+ * (earn_decode_workspace_bytes tells) -> EARN_ERR_WORKSPACE_TOO_SMALL, nothing is launched.
+ */
+#define EARN_STATIC_SCRATCH_BYTES (8u << 20)
+int earn_decode_attn_static(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
+                            const int32_t* q_pos, const void* shared_k, const void* shared_v,
+                            const int32_t* shared_cu, const int32_t* stream_to_seq, void* gen_k, void* gen_v,
+                            const int32_t* gen_len, int32_t gen_cap, int32_t n_streams, int32_t batch,
+                            int32_t max_shared_len, void* out, void* stream);
+
+/*
  * Prefill attention of the LAST full-length layer (layer k-1) at the register rows only.
  *
  * Section 3.2 (inference): the input of layer k keeps only the register tokens, so of layer k-1's attention outputs

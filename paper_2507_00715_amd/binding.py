@@ -26,7 +26,8 @@ EARN_MAX_COMPACT_TENSORS = 112
 EXPORTS = ["earn_last_error", "earn_version", "earn_prefill_attn", "earn_prefill_workspace_bytes",
            "earn_compact_registers", "earn_decode_attn", "earn_decode_workspace_bytes", "earn_cache_entries",
            "earn_prefill_register_rows", "earn_prefill_register_rows_workspace_bytes", "earn_set_validation",
-           "earn_set_tuning"]
+           "earn_set_tuning", "earn_decode_attn_static"]
+EARN_STATIC_SCRATCH_BYTES = 8 << 20
 
 
 class EarnError(RuntimeError):
@@ -61,6 +62,9 @@ def lib():
         L.earn_decode_attn.restype = ctypes.c_int
         L.earn_decode_attn.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
                                        i32, i32, vp, vp, sz, vp]
+        L.earn_decode_attn_static.restype = ctypes.c_int
+        L.earn_decode_attn_static.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                              i32, i32, i32, vp, vp]
         L.earn_prefill_register_rows.restype = ctypes.c_int
         L.earn_prefill_register_rows.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp,
                                                  vp, sz, vp]
@@ -177,6 +181,16 @@ def earn_decode_attn(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, shared_v,
                                   _ptr(shared_v), _ptr(shared_cu), _ptr(stream_to_seq), _ptr(gen_k), _ptr(gen_v),
                                   _ptr(gen_len), gen_cap, n_streams, batch, max_shared_len, _ptr(out),
                                   _ptr(workspace), ws_bytes, _stream()))
+
+
+def earn_decode_attn_static(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq,
+                            gen_k, gen_v, gen_len, gen_cap: int, n_streams: int, batch: int, max_shared_len: int,
+                            out) -> None:
+    """earn_decode_attn without a workspace: partial results go to the library's own per-GPU buffer."""
+    _check(lib().earn_decode_attn_static(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos),
+                                         _ptr(shared_k), _ptr(shared_v), _ptr(shared_cu), _ptr(stream_to_seq),
+                                         _ptr(gen_k), _ptr(gen_v), _ptr(gen_len), gen_cap, n_streams, batch,
+                                         max_shared_len, _ptr(out), _stream()))
 
 
 class BoundCall:

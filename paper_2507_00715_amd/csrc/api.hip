@@ -56,6 +56,10 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
                   hipStream_t stream);
 size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, int batch, int max_shared_len,
                               int gen_cap);
+int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
+                         const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
+                         const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
+                         int n_streams, int batch, int max_shared_len, void* out, hipStream_t stream);
 int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, const int32_t* cu_seqlens,
                      const int32_t* positions, int batch, int total_tokens, hipStream_t stream);
 int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
@@ -268,28 +272,54 @@ size_t earn_decode_workspace_bytes(const earn_attn_desc* desc, int32_t n_streams
                                 max_shared_len, gen_cap);
 }
 
+// the host-side checks earn_decode_attn and earn_decode_attn_static share
+static int check_decode_args(const char* who, const earn_attn_desc* desc, const void* q, const void* k_new,
+                             const void* v_new, const int32_t* q_pos, const void* shared_k, const void* shared_v,
+                             const int32_t* shared_cu, const int32_t* stream_to_seq, void* gen_k, void* gen_v,
+                             const int32_t* gen_len, int32_t gen_cap, int32_t n_streams, int32_t batch,
+                             int32_t max_shared_len, void* out, void* stream) {
+  g_err[0] = 0;
+  int rc = check_desc(desc, who);
+  if (rc != EARN_OK) return rc;
+  if (n_streams <= 0 || batch <= 0 || gen_cap <= 0 || max_shared_len < 0) {
+    set_error("%s: n_streams (%d), batch (%d), gen_cap (%d) must be positive and max_shared_len (%d) non-negative", who, n_streams, batch, gen_cap, max_shared_len);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (!q || !k_new || !v_new || !q_pos || !shared_cu || !gen_k || !gen_v || !gen_len || !out) {
+    set_error("%s: a required pointer is NULL", who);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (max_shared_len > 0 && (!shared_k || !shared_v)) { set_error("%s: shared_k/shared_v are NULL but max_shared_len > 0", who); return EARN_ERR_INVALID_ARG; }
+  if (!stream_to_seq && n_streams != batch) { set_error("%s: stream_to_seq is NULL but n_streams (%d) != batch (%d)", who, n_streams, batch); return EARN_ERR_INVALID_ARG; }
+  if (g_validate.load(std::memory_order_relaxed) &&
+      (rc = validate_decode(who, q_pos, shared_cu, stream_to_seq, gen_len, gen_cap, n_streams, batch, max_shared_len,
+                            (hipStream_t)stream)) != EARN_OK)
+    return rc;
+  return EARN_OK;
+}
+
+int earn_decode_attn_static(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
+                            const int32_t* q_pos, const void* shared_k, const void* shared_v,
+                            const int32_t* shared_cu, const int32_t* stream_to_seq, void* gen_k, void* gen_v,
+                            const int32_t* gen_len, int32_t gen_cap, int32_t n_streams, int32_t batch,
+                            int32_t max_shared_len, void* out, void* stream) {
+  const int rc = check_decode_args("earn_decode_attn_static", desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu,
+                                   stream_to_seq, gen_k, gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, out,
+                                   stream);
+  if (rc != EARN_OK) return rc;
+  return launch_decode_static(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v,
+                              gen_len, gen_cap, n_streams, batch, max_shared_len, out, (hipStream_t)stream);
+}
+
 int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
                      const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                      const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int32_t gen_cap,
                      int32_t n_streams, int32_t batch, int32_t max_shared_len, void* out, void* workspace,
                      size_t workspace_bytes, void* stream) {
-  g_err[0] = 0;
-  int rc = check_desc(desc, "earn_decode_attn");
+  const int rc = check_decode_args("earn_decode_attn", desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu,
+                                   stream_to_seq, gen_k, gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, out,
+                                   stream);
   if (rc != EARN_OK) return rc;
-  if (n_streams <= 0 || batch <= 0 || gen_cap <= 0 || max_shared_len < 0) {
-    set_error("earn_decode_attn: n_streams (%d), batch (%d), gen_cap (%d) must be positive and max_shared_len (%d) non-negative", n_streams, batch, gen_cap, max_shared_len);
-    return EARN_ERR_INVALID_ARG;
-  }
-  if (!q || !k_new || !v_new || !q_pos || !shared_cu || !gen_k || !gen_v || !gen_len || !out) {
-    set_error("earn_decode_attn: a required pointer is NULL");
-    return EARN_ERR_INVALID_ARG;
-  }
-  if (max_shared_len > 0 && (!shared_k || !shared_v)) { set_error("earn_decode_attn: shared_k/shared_v are NULL but max_shared_len > 0"); return EARN_ERR_INVALID_ARG; }
-  if (!stream_to_seq && n_streams != batch) { set_error("earn_decode_attn: stream_to_seq is NULL but n_streams (%d) != batch (%d)", n_streams, batch); return EARN_ERR_INVALID_ARG; }
-  if (g_validate.load(std::memory_order_relaxed) &&
-      (rc = validate_decode("earn_decode_attn", q_pos, shared_cu, stream_to_seq, gen_len, gen_cap, n_streams, batch,
-                            max_shared_len, (hipStream_t)stream)) != EARN_OK)
-    return rc;
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
                        gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream);
 }

@@ -10,6 +10,7 @@
 //     across the 4 waves;
 //   * the key range of a long cache is split over several workgroups (split-K); partial (max, sum, out) triples go to
 //     the workspace and a second kernel merges them.
+#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -1135,6 +1136,54 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
     if (d == 64) launch_decode_t<__bf16, 64>(p, pl, gq, stream); else launch_decode_t<__bf16, 128>(p, pl, gq, stream);
   }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
+}
+
+// ---- the entry point that allocates nothing: split-key partials in a buffer inside the library ----
+// One copy of the array exists per GPU, each at its own address; in host code its name is only a handle for
+// hipGetSymbolAddress, never a pointer a kernel could take.
+constexpr size_t kStaticScratchBytes = EARN_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// device address of `scratch` on the current GPU, looked up on the first call made with that GPU current
+static int static_scratch_of_current_device(void** ptr) {
+  static std::mutex mu;
+  static void* address[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    set_error("earn_decode_attn_static: no current GPU (device %d)", dev);
+    return EARN_ERR_HIP;
+  }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!address[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      set_error("earn_decode_attn_static: hipGetSymbolAddress failed on device %d: %s", dev, hipGetErrorString(e));
+      return EARN_ERR_HIP;
+    }
+    address[dev] = p;
+  }
+  *ptr = address[dev];
+  return EARN_OK;
+}
+
+int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
+                         const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
+                         const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
+                         int n_streams, int batch, int max_shared_len, void* out, hipStream_t stream) {
+  const size_t need = decode_workspace_bytes(desc->dtype, desc->n_q_heads, desc->n_kv_heads, desc->head_dim, n_streams,
+                                             batch, max_shared_len, gen_cap);
+  if (need > kStaticScratchBytes) {
+    set_error("earn_decode_attn_static: the partial results of this problem need %zu bytes, the library's buffer holds "
+              "%zu; use earn_decode_attn with a workspace", need, kStaticScratchBytes);
+    return EARN_ERR_WORKSPACE_TOO_SMALL;
+  }
+  void* ptr = nullptr;
+  const int rc = static_scratch_of_current_device(&ptr);
+  if (rc != EARN_OK) return rc;
+  return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
+                       gen_cap, n_streams, batch, max_shared_len, out, ptr, kStaticScratchBytes, stream);
 }
 
 // ---- causal attention of r chosen rows per sequence over the sequence's full-length keys, on the shared-cache kernel:
