@@ -154,6 +154,19 @@ int earn_compact_registers(int32_t n_tensors, const void* const* src, void* cons
                            int32_t* idx_out, int32_t* pos_out, int32_t* cu_out, void* stream);
 
 /*
+ * Positions of decode step `step` (the reading of Section 3.2's decoding bullet that this library takes: a generated
+ * token keeps the position it would have without compaction): for every stream u of sequence s = stream_to_seq[u]
+ *   q_pos[u] = n_s + step     (n_s = cu_seqlens[s+1] - cu_seqlens[s], the FULL sequence length, registers included)
+ *   gen_len[u] = step         (rows already in the stream's generated cache)
+ * which are the q_pos / gen_len arguments of earn_decode_attn for that step.
+ *   cu_seqlens [batch+1] device (of the full-length sequences, also for layers >= k); stream_to_seq [n_streams] device
+ *   or NULL (identity, n_streams == batch); q_pos, gen_len [n_streams] device, either may be NULL.
+ * Errors: NULL cu_seqlens, n_streams <= 0, batch <= 0, step < 0, NULL map with n_streams != batch -> INVALID_ARG.
+ */
+int earn_decode_step_positions(const int32_t* cu_seqlens, const int32_t* stream_to_seq, int32_t n_streams,
+                               int32_t batch, int32_t step, int32_t* q_pos, int32_t* gen_len, void* stream);
+
+/*
  * One decode step of attention (paper Section 2.2, Eq. 4: append K_t, V_t to the cache, then Q_t K_{1:t}^T;
  * Section 3.2, Inference, decoding bullet: layers >= k see [prefix; suffix; generated] only).
  *
@@ -192,6 +205,36 @@ int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_ne
 /* Workspace earn_decode_attn needs (bytes) for split-key partial results. 0 on invalid desc. */
 size_t earn_decode_workspace_bytes(const earn_attn_desc* desc, int32_t n_streams, int32_t batch,
                                    int32_t max_shared_len, int32_t gen_cap);
+
+/*
+ * Several INDEPENDENT layers in one launch (harness throughput mode; n_layers = 1 is the real-model use, in which layer
+ * l+1 depends on layer l).  The register-focused layers k..N-1 of the paper's Section 3.2 work on a few dozen rows per
+ * sequence, so a launch per layer is bound by launch latency, not by the arithmetic or the bytes of Eq. 3 / Eq. 4; with
+ * synthetic per-layer inputs the layers do not depend on each other and one grid dimension can index the layer.
+ * Layer l of a tensor starts `*_layer_stride` BYTES (a positive multiple of 16; of 4 for lse_out) after layer l-1; cu_seqlens, positions,
+ * q_pos, gen_len and stream_to_seq are shared by all layers.  Every layer computes exactly what the single-layer call
+ * computes (same kernels; only the number of key splits may differ, because the layers share the GPU).
+ *
+ * earn_prefill_attn_layers: k_rot_out is required; lse_out may be NULL; workspace as for earn_prefill_attn with
+ * k_rot_out given (earn_prefill_workspace_bytes(desc, batch, total_tokens, max_seqlen, 1)), shared by the layers.
+ * earn_decode_attn_layers: workspace of earn_decode_layers_workspace_bytes(...) bytes.
+ * Errors: as the single-layer calls; n_layers outside [1, 65535] or a bad stride -> INVALID_ARG.
+ */
+int earn_prefill_attn_layers(const earn_attn_desc* desc, int32_t n_layers, const void* q, int64_t q_layer_stride,
+                             const void* k, const void* v, int64_t kv_layer_stride, const int32_t* cu_seqlens,
+                             const int32_t* positions, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                             void* out, int64_t out_layer_stride, void* k_rot_out, int64_t k_rot_layer_stride,
+                             float* lse_out, int64_t lse_layer_stride, void* workspace, size_t workspace_bytes,
+                             void* stream);
+int earn_decode_attn_layers(const earn_attn_desc* desc, int32_t n_layers, const void* q, int64_t q_layer_stride,
+                            const void* k_new, const void* v_new, int64_t kv_new_layer_stride, const int32_t* q_pos,
+                            const void* shared_k, const void* shared_v, int64_t shared_layer_stride,
+                            const int32_t* shared_cu, const int32_t* stream_to_seq, void* gen_k, void* gen_v,
+                            int64_t gen_layer_stride, const int32_t* gen_len, int32_t gen_cap, int32_t n_streams,
+                            int32_t batch, int32_t max_shared_len, void* out, int64_t out_layer_stride, void* workspace,
+                            size_t workspace_bytes, void* stream);
+size_t earn_decode_layers_workspace_bytes(const earn_attn_desc* desc, int32_t n_layers, int32_t n_streams,
+                                          int32_t batch, int32_t max_shared_len, int32_t gen_cap);
 
 /*
  * earn_decode_attn for callers that cannot allocate or pass device scratch memory: code under HIP graph capture,

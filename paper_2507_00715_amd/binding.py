@@ -26,7 +26,8 @@ EARN_MAX_COMPACT_TENSORS = 112
 EXPORTS = ["earn_last_error", "earn_version", "earn_prefill_attn", "earn_prefill_workspace_bytes",
            "earn_compact_registers", "earn_decode_attn", "earn_decode_workspace_bytes", "earn_cache_entries",
            "earn_prefill_register_rows", "earn_prefill_register_rows_workspace_bytes", "earn_set_validation",
-           "earn_set_tuning", "earn_decode_attn_static"]
+           "earn_set_tuning", "earn_decode_attn_static", "earn_prefill_attn_layers", "earn_decode_attn_layers",
+           "earn_decode_layers_workspace_bytes", "earn_decode_step_positions"]
 EARN_STATIC_SCRATCH_BYTES = 8 << 20
 
 
@@ -65,6 +66,17 @@ def lib():
         L.earn_decode_attn_static.restype = ctypes.c_int
         L.earn_decode_attn_static.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
                                               i32, i32, i32, vp, vp]
+        i64 = ctypes.c_int64
+        L.earn_prefill_attn_layers.restype = ctypes.c_int
+        L.earn_prefill_attn_layers.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, i64, vp, vp, i64, vp, vp, i32, i32, i32,
+                                               vp, i64, vp, i64, vp, i64, vp, sz, vp]
+        L.earn_decode_attn_layers.restype = ctypes.c_int
+        L.earn_decode_attn_layers.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, i64, vp, vp, i64, vp, vp, vp, i64, vp,
+                                              vp, vp, vp, i64, vp, i32, i32, i32, i32, vp, i64, vp, sz, vp]
+        L.earn_decode_layers_workspace_bytes.restype = sz
+        L.earn_decode_layers_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), i32, i32, i32, i32, i32]
+        L.earn_decode_step_positions.restype = ctypes.c_int
+        L.earn_decode_step_positions.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
         L.earn_prefill_register_rows.restype = ctypes.c_int
         L.earn_prefill_register_rows.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp,
                                                  vp, sz, vp]
@@ -228,6 +240,88 @@ def bind_prefill_attn(desc: AttnDesc, q, k, v, cu_seqlens, positions, batch: int
     args = (ctypes.byref(desc), *[_ptr(t) for t in tensors], batch, total_tokens, max_seqlen, _ptr(out),
             _ptr(k_rot_out), _ptr(lse_out), _ptr(workspace), ws_bytes)
     return BoundCall(lib().earn_prefill_attn, args, (desc, tensors, out, k_rot_out, lse_out, workspace))
+
+
+def earn_decode_step_positions(cu_seqlens, stream_to_seq, n_streams: int, batch: int, step: int, q_pos,
+                               gen_len) -> None:
+    _check(lib().earn_decode_step_positions(_ptr(cu_seqlens), _ptr(stream_to_seq), n_streams, batch, step, _ptr(q_pos),
+                                            _ptr(gen_len), _stream()))
+
+
+def bind_decode_step_positions(cu_seqlens, stream_to_seq, n_streams: int, batch: int, step: int, q_pos,
+                               gen_len) -> "BoundCall":
+    args = (_ptr(cu_seqlens), _ptr(stream_to_seq), n_streams, batch, step, _ptr(q_pos), _ptr(gen_len))
+    return BoundCall(lib().earn_decode_step_positions, args, (cu_seqlens, stream_to_seq, q_pos, gen_len))
+
+
+def _layer_stride(t: Optional[torch.Tensor]) -> int:
+    """Bytes from one layer to the next of a [layers, ...] tensor (its layers must be contiguous blocks)."""
+    if t is None:
+        return 0
+    assert t.is_cuda and t[0].is_contiguous(), "every layer of a layer-batched tensor must be contiguous"
+    return t.stride(0) * t.element_size()
+
+
+def earn_decode_layers_workspace_bytes(desc: AttnDesc, n_layers: int, n_streams: int, batch: int, max_shared_len: int,
+                                       gen_cap: int) -> int:
+    return int(lib().earn_decode_layers_workspace_bytes(ctypes.byref(desc), n_layers, n_streams, batch, max_shared_len,
+                                                        gen_cap))
+
+
+def _layers_ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def bind_prefill_attn_layers(desc: AttnDesc, q, k, v, cu_seqlens, positions, batch: int, total_tokens: int,
+                             max_seqlen: int, out, k_rot_out, lse_out, workspace) -> BoundCall:
+    """earn_prefill_attn_layers over [layers, tokens, heads, d] tensors (q, k, v, out, k_rot_out; lse_out
+    [layers, tokens, Hq] or None), marshalled once; the layer strides are the tensors' own."""
+    n_layers = q.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    args = (ctypes.byref(desc), n_layers, _layers_ptr(q), _layer_stride(q), _layers_ptr(k), _layers_ptr(v),
+            _layer_stride(k), _ptr(cu_seqlens), _ptr(positions), batch, total_tokens, max_seqlen, _layers_ptr(out),
+            _layer_stride(out), _layers_ptr(k_rot_out), _layer_stride(k_rot_out), _layers_ptr(lse_out),
+            _layer_stride(lse_out), _ptr(workspace), ws_bytes)
+    assert _layer_stride(k) == _layer_stride(v)
+    return BoundCall(lib().earn_prefill_attn_layers, args, (desc, q, k, v, cu_seqlens, positions, out, k_rot_out, lse_out,
+                                                            workspace))
+
+
+def earn_prefill_attn_layers(desc: AttnDesc, q, k, v, cu_seqlens, positions, batch: int, total_tokens: int,
+                             max_seqlen: int, out, k_rot_out, lse_out=None, workspace=None) -> None:
+    if workspace is None:
+        need = earn_prefill_workspace_bytes(desc, batch, total_tokens, max_seqlen, True)
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    bind_prefill_attn_layers(desc, q, k, v, cu_seqlens, positions, batch, total_tokens, max_seqlen, out, k_rot_out,
+                             lse_out, workspace)()
+
+
+def bind_decode_attn_layers(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k,
+                            gen_v, gen_len, gen_cap: int, n_streams: int, batch: int, max_shared_len: int, out,
+                            workspace) -> BoundCall:
+    """earn_decode_attn_layers over [layers, ...] tensors (q, k_new, v_new, shared_k, shared_v, gen_k, gen_v, out),
+    marshalled once; the layer strides are the tensors' own."""
+    n_layers = q.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    assert _layer_stride(k_new) == _layer_stride(v_new) and _layer_stride(shared_k) == _layer_stride(shared_v)
+    assert _layer_stride(gen_k) == _layer_stride(gen_v)
+    args = (ctypes.byref(desc), n_layers, _layers_ptr(q), _layer_stride(q), _layers_ptr(k_new), _layers_ptr(v_new),
+            _layer_stride(k_new), _ptr(q_pos), _layers_ptr(shared_k), _layers_ptr(shared_v), _layer_stride(shared_k),
+            _ptr(shared_cu), _ptr(stream_to_seq), _layers_ptr(gen_k), _layers_ptr(gen_v), _layer_stride(gen_k),
+            _ptr(gen_len), gen_cap, n_streams, batch, max_shared_len, _layers_ptr(out), _layer_stride(out),
+            _ptr(workspace), ws_bytes)
+    return BoundCall(lib().earn_decode_attn_layers, args, (desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu,
+                                                           stream_to_seq, gen_k, gen_v, gen_len, out, workspace))
+
+
+def earn_decode_attn_layers(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k,
+                            gen_v, gen_len, gen_cap: int, n_streams: int, batch: int, max_shared_len: int, out,
+                            workspace=None) -> None:
+    if workspace is None:
+        need = earn_decode_layers_workspace_bytes(desc, q.shape[0], n_streams, batch, max_shared_len, gen_cap)
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    bind_decode_attn_layers(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v,
+                            gen_len, gen_cap, n_streams, batch, max_shared_len, out, workspace)()
 
 
 def earn_cache_entries(n_layers: int, split_k: int, seq_len: int, n_registers: int, gen: int = 0) -> int:

@@ -47,19 +47,22 @@ int launch_compact(int n_tensors, const void* const* src, void* const* dst, cons
                    int32_t* cu_out, hipStream_t stream);
 int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
                    const int32_t* positions, int batch, int total_tokens, int max_seqlen, void* out, void* k_rot_out,
-                   float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t stream);
+                   float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t stream,
+                   const PrefillLayers* layers);
 size_t prefill_workspace_bytes(const earn_attn_desc* desc, int total_tokens, int have_k_rot_out);
 int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
                   const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                   const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
                   int n_streams, int batch, int max_shared_len, void* out, void* workspace, size_t workspace_bytes,
-                  hipStream_t stream);
+                  hipStream_t stream, const DecodeLayers* layers);
 size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, int batch, int max_shared_len,
-                              int gen_cap);
+                              int gen_cap, int n_layers);
 int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
                          const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                          const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
                          int n_streams, int batch, int max_shared_len, void* out, hipStream_t stream);
+int launch_step_positions(const int32_t* cu, const int32_t* stream_to_seq, int n_streams, int batch, int step,
+                          int32_t* q_pos, int32_t* gen_len, hipStream_t stream);
 int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, const int32_t* cu_seqlens,
                      const int32_t* positions, int batch, int total_tokens, hipStream_t stream);
 int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
@@ -196,22 +199,21 @@ size_t earn_prefill_workspace_bytes(const earn_attn_desc* desc, int32_t batch, i
   return prefill_workspace_bytes(desc, total_tokens, have_k_rot_out);
 }
 
-int earn_prefill_attn(const earn_attn_desc* desc, const void* q, const void* k, const void* v,
-                      const int32_t* cu_seqlens, const int32_t* positions, int32_t batch, int32_t total_tokens,
-                      int32_t max_seqlen, void* out, void* k_rot_out, float* lse_out, void* workspace,
-                      size_t workspace_bytes, void* stream) {
+static int prefill_entry(const char* who, const earn_attn_desc* desc, const void* q, const void* k, const void* v,
+                         const int32_t* cu_seqlens, const int32_t* positions, int32_t batch, int32_t total_tokens,
+                         int32_t max_seqlen, void* out, void* k_rot_out, float* lse_out, void* workspace,
+                         size_t workspace_bytes, void* stream, const PrefillLayers* layers) {
   g_err[0] = 0;
-  int rc = check_desc(desc, "earn_prefill_attn");
+  int rc = check_desc(desc, who);
   if (rc != EARN_OK) return rc;
   if (batch <= 0 || total_tokens < 0 || max_seqlen <= 0) {
-    set_error("earn_prefill_attn: batch (%d) and max_seqlen (%d) must be positive, total_tokens (%d) non-negative", batch, max_seqlen, total_tokens);
+    set_error("%s: batch (%d) and max_seqlen (%d) must be positive, total_tokens (%d) non-negative", who, batch, max_seqlen, total_tokens);
     return EARN_ERR_INVALID_ARG;
   }
-  if (!cu_seqlens) { set_error("earn_prefill_attn: cu_seqlens is NULL"); return EARN_ERR_INVALID_ARG; }
+  if (!cu_seqlens) { set_error("%s: cu_seqlens is NULL", who); return EARN_ERR_INVALID_ARG; }
   if (total_tokens == 0) return EARN_OK;
-  if (!q || !k || !v || !out) { set_error("earn_prefill_attn: q, k, v and out must not be NULL"); return EARN_ERR_INVALID_ARG; }
+  if (!q || !k || !v || !out) { set_error("%s: q, k, v and out must not be NULL", who); return EARN_ERR_INVALID_ARG; }
   if (g_validate.load(std::memory_order_relaxed)) {
-    const char* who = "earn_prefill_attn";
     std::vector<int32_t> cu, pos;
     if ((rc = fetch_i32(cu_seqlens, (size_t)batch + 1, cu, (hipStream_t)stream, who)) != EARN_OK) return rc;
     if ((rc = validate_cu(who, "cu_seqlens", cu, batch, total_tokens, max_seqlen)) != EARN_OK) return rc;
@@ -222,7 +224,45 @@ int earn_prefill_attn(const earn_attn_desc* desc, const void* q, const void* k, 
   }
   if (max_seqlen > total_tokens) max_seqlen = total_tokens;
   return launch_prefill(desc, q, k, v, cu_seqlens, positions, batch, total_tokens, max_seqlen, out, k_rot_out, lse_out,
-                        workspace, workspace_bytes, (hipStream_t)stream);
+                        workspace, workspace_bytes, (hipStream_t)stream, layers);
+}
+
+int earn_prefill_attn(const earn_attn_desc* desc, const void* q, const void* k, const void* v,
+                      const int32_t* cu_seqlens, const int32_t* positions, int32_t batch, int32_t total_tokens,
+                      int32_t max_seqlen, void* out, void* k_rot_out, float* lse_out, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  return prefill_entry("earn_prefill_attn", desc, q, k, v, cu_seqlens, positions, batch, total_tokens, max_seqlen, out,
+                       k_rot_out, lse_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+static int check_layer_stride(const char* who, const char* name, int64_t stride, int n_layers, int align = 16) {
+  if (n_layers > 1 && (stride <= 0 || stride % align != 0)) {
+    set_error("%s: %s = %lld must be a positive multiple of %d bytes", who, name, (long long)stride, align);
+    return EARN_ERR_INVALID_ARG;
+  }
+  return EARN_OK;
+}
+
+int earn_prefill_attn_layers(const earn_attn_desc* desc, int32_t n_layers, const void* q, int64_t q_layer_stride,
+                             const void* k, const void* v, int64_t kv_layer_stride, const int32_t* cu_seqlens,
+                             const int32_t* positions, int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                             void* out, int64_t out_layer_stride, void* k_rot_out, int64_t k_rot_layer_stride,
+                             float* lse_out, int64_t lse_layer_stride, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  const char* who = "earn_prefill_attn_layers";
+  g_err[0] = 0;
+  if (n_layers <= 0 || n_layers > 65535) { set_error("%s: n_layers (%d) outside [1, 65535]", who, n_layers); return EARN_ERR_INVALID_ARG; }
+  if (!k_rot_out) { set_error("%s: k_rot_out is required (every layer keeps its rotated keys)", who); return EARN_ERR_INVALID_ARG; }
+  int rc;
+  if ((rc = check_layer_stride(who, "q_layer_stride", q_layer_stride, n_layers)) != EARN_OK ||
+      (rc = check_layer_stride(who, "kv_layer_stride", kv_layer_stride, n_layers)) != EARN_OK ||
+      (rc = check_layer_stride(who, "out_layer_stride", out_layer_stride, n_layers)) != EARN_OK ||
+      (rc = check_layer_stride(who, "k_rot_layer_stride", k_rot_layer_stride, n_layers)) != EARN_OK ||
+      (lse_out && (rc = check_layer_stride(who, "lse_layer_stride", lse_layer_stride, n_layers, 4)) != EARN_OK))
+    return rc;
+  const PrefillLayers layers = {n_layers, q_layer_stride, kv_layer_stride, out_layer_stride, k_rot_layer_stride, lse_layer_stride};
+  return prefill_entry(who, desc, q, k, v, cu_seqlens, positions, batch, total_tokens, max_seqlen, out, k_rot_out, lse_out,
+                       workspace, workspace_bytes, stream, &layers);
 }
 
 int earn_compact_registers(int32_t n_tensors, const void* const* src, void* const* dst, const int64_t* row_bytes,
@@ -265,11 +305,26 @@ int earn_compact_registers(int32_t n_tensors, const void* const* src, void* cons
                         cu_out, (hipStream_t)stream);
 }
 
+int earn_decode_step_positions(const int32_t* cu_seqlens, const int32_t* stream_to_seq, int32_t n_streams,
+                               int32_t batch, int32_t step, int32_t* q_pos, int32_t* gen_len, void* stream) {
+  g_err[0] = 0;
+  if (!cu_seqlens || n_streams <= 0 || batch <= 0 || step < 0) {
+    set_error("earn_decode_step_positions: cu_seqlens must not be NULL, n_streams (%d) and batch (%d) positive, step (%d) non-negative", n_streams, batch, step);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (!stream_to_seq && n_streams != batch) {
+    set_error("earn_decode_step_positions: stream_to_seq is NULL but n_streams (%d) != batch (%d)", n_streams, batch);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (!q_pos && !gen_len) return EARN_OK;
+  return launch_step_positions(cu_seqlens, stream_to_seq, n_streams, batch, step, q_pos, gen_len, (hipStream_t)stream);
+}
+
 size_t earn_decode_workspace_bytes(const earn_attn_desc* desc, int32_t n_streams, int32_t batch,
                                    int32_t max_shared_len, int32_t gen_cap) {
   if (check_desc(desc, "earn_decode_workspace_bytes") != EARN_OK || n_streams <= 0 || batch <= 0 || max_shared_len < 0 || gen_cap <= 0) return 0;
   return decode_workspace_bytes(desc->dtype, desc->n_q_heads, desc->n_kv_heads, desc->head_dim, n_streams, batch,
-                                max_shared_len, gen_cap);
+                                max_shared_len, gen_cap, 1);
 }
 
 // the host-side checks earn_decode_attn and earn_decode_attn_static share
@@ -321,7 +376,41 @@ int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_ne
                                    stream);
   if (rc != EARN_OK) return rc;
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
-                       gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream);
+                       gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream,
+                       nullptr);
+}
+
+size_t earn_decode_layers_workspace_bytes(const earn_attn_desc* desc, int32_t n_layers, int32_t n_streams, int32_t batch,
+                                          int32_t max_shared_len, int32_t gen_cap) {
+  if (check_desc(desc, "earn_decode_layers_workspace_bytes") != EARN_OK || n_layers <= 0 || n_layers > 65535 ||
+      n_streams <= 0 || batch <= 0 || max_shared_len < 0 || gen_cap <= 0)
+    return 0;
+  return decode_workspace_bytes(desc->dtype, desc->n_q_heads, desc->n_kv_heads, desc->head_dim, n_streams, batch,
+                                max_shared_len, gen_cap, n_layers);
+}
+
+int earn_decode_attn_layers(const earn_attn_desc* desc, int32_t n_layers, const void* q, int64_t q_layer_stride,
+                            const void* k_new, const void* v_new, int64_t kv_new_layer_stride, const int32_t* q_pos,
+                            const void* shared_k, const void* shared_v, int64_t shared_layer_stride,
+                            const int32_t* shared_cu, const int32_t* stream_to_seq, void* gen_k, void* gen_v,
+                            int64_t gen_layer_stride, const int32_t* gen_len, int32_t gen_cap, int32_t n_streams,
+                            int32_t batch, int32_t max_shared_len, void* out, int64_t out_layer_stride, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  const char* who = "earn_decode_attn_layers";
+  int rc = check_decode_args(who, desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k,
+                             gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, out, stream);
+  if (rc != EARN_OK) return rc;
+  if (n_layers <= 0 || n_layers > 65535) { set_error("%s: n_layers (%d) outside [1, 65535]", who, n_layers); return EARN_ERR_INVALID_ARG; }
+  if ((rc = check_layer_stride(who, "q_layer_stride", q_layer_stride, n_layers)) != EARN_OK ||
+      (rc = check_layer_stride(who, "kv_new_layer_stride", kv_new_layer_stride, n_layers)) != EARN_OK ||
+      (max_shared_len > 0 && (rc = check_layer_stride(who, "shared_layer_stride", shared_layer_stride, n_layers)) != EARN_OK) ||
+      (rc = check_layer_stride(who, "gen_layer_stride", gen_layer_stride, n_layers)) != EARN_OK ||
+      (rc = check_layer_stride(who, "out_layer_stride", out_layer_stride, n_layers)) != EARN_OK)
+    return rc;
+  const DecodeLayers layers = {n_layers, q_layer_stride, kv_new_layer_stride, shared_layer_stride, gen_layer_stride, out_layer_stride};
+  return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
+                       gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream,
+                       &layers);
 }
 
 size_t earn_prefill_register_rows_workspace_bytes(const earn_attn_desc* desc, int32_t batch, int32_t max_seqlen,

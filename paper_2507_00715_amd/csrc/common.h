@@ -42,6 +42,11 @@ RopeTable make_rope_table(float base, int head_dim);
 // Fills `m` from desc->q_to_kv; EARN_OK, or an error (message set) for a map the kernels cannot serve.
 int make_head_map(const earn_attn_desc* desc, HeadMap* m, const char* who);
 
+// Several independent layers in one launch: grid row y works on layer y of per-layer-contiguous tensors.  Byte strides
+// from one layer to the next; sequence bounds, positions and stream lists are shared by the layers.
+struct DecodeLayers { int n_layers; long long q, kv_new, shared, gen, out; };
+struct PrefillLayers { int n_layers; long long q, kv, out, k_rot, lse; };
+
 // launch-shape overrides (earn_set_tuning); 0 = default
 enum Tuning { kTunePrefillBlockRows, kTuneDecMfmaMinLen, kTuneDecMfmaShortWgs, kTuneDecMfmaWgs, kTuneDecVecWgs,
               kTuneDecVecWaves, kTuneCompactBlocks, kTuneCount };

@@ -86,6 +86,25 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactArgs ar
   }
 }
 
+// q_pos / gen_len of one decode step: a generated token sits at position n_s + step of its sequence
+__global__ __launch_bounds__(256) void step_positions_kernel(const int32_t* __restrict__ cu,
+                                                             const int32_t* __restrict__ stream_to_seq, int n_streams,
+                                                             int batch, int step, int32_t* __restrict__ q_pos,
+                                                             int32_t* __restrict__ gen_len) {
+  const int u = blockIdx.x * 256 + threadIdx.x;
+  if (u >= n_streams) return;
+  const int s = stream_to_seq ? max(min(stream_to_seq[u], batch - 1), 0) : u;
+  if (q_pos) q_pos[u] = cu[s + 1] - cu[s] + step;
+  if (gen_len) gen_len[u] = step;
+}
+
+int launch_step_positions(const int32_t* cu, const int32_t* stream_to_seq, int n_streams, int batch, int step,
+                          int32_t* q_pos, int32_t* gen_len, hipStream_t stream) {
+  hipLaunchKernelGGL(step_positions_kernel, dim3((n_streams + 255) / 256), dim3(256), 0, stream, cu, stream_to_seq,
+                     n_streams, batch, step, q_pos, gen_len);
+  return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
+}
+
 int launch_compact(int n_tensors, const void* const* src, void* const* dst, const int64_t* row_bytes,
                    const int32_t* cu_seqlens, int batch, int h, int t, int32_t* idx_out, int32_t* pos_out,
                    int32_t* cu_out, hipStream_t stream) {

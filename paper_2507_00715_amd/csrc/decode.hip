@@ -82,9 +82,37 @@ struct DecodeParams {
   // side by side on one XCD, sharing the keys in its L2.
   int n_pass;
   float scale_log2;
+  // byte strides between the layers of a layer-batched launch (grid row y = layer); all zero for a single layer
+  long long ls_q, ls_kv_new, ls_shared, ls_gen, ls_out, ls_part_o, ls_part_ml;
   RopeTable rope;
   HeadMap heads;
 };
+
+template <typename P>
+__device__ __forceinline__ P* layer_ptr(P* base, long long stride, int layer) {
+  return (P*)((const char*)base + stride * layer);
+}
+// The per-layer pointers of this grid row's layer.  (A view beside the parameter block, not a modified copy of it: the
+// block holds arrays that are indexed at run time, so a modified copy would live in scratch memory and nothing read
+// from it would count as wave-uniform any more.)
+struct DecodeLayer {
+  const void* q; const void* k_new; const void* v_new; const void* shared_k; const void* shared_v;
+  void* gen_k; void* gen_v; void* out; float* part_o; float* part_ml;
+};
+__device__ __forceinline__ DecodeLayer layer_view(const DecodeParams& p, int layer) {
+  DecodeLayer v;
+  v.q = layer_ptr(p.q, p.ls_q, layer);
+  v.k_new = layer_ptr(p.k_new, p.ls_kv_new, layer);
+  v.v_new = layer_ptr(p.v_new, p.ls_kv_new, layer);
+  v.shared_k = layer_ptr(p.shared_k, p.ls_shared, layer);
+  v.shared_v = layer_ptr(p.shared_v, p.ls_shared, layer);
+  v.gen_k = layer_ptr(p.gen_k, p.ls_gen, layer);
+  v.gen_v = layer_ptr(p.gen_v, p.ls_gen, layer);
+  v.out = layer_ptr(p.out, p.ls_out, layer);
+  v.part_o = layer_ptr(p.part_o, p.ls_part_o, layer);
+  v.part_ml = layer_ptr(p.part_ml, p.ls_part_ml, layer);
+  return v;
+}
 
 // gen_len as the kernels use it: inside [0, gen_cap), so that a violated precondition cannot move the cache append or
 // the walk over the generated rows outside the stream's cache
@@ -123,8 +151,9 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* o, float 
 // (WAVES > 1: states merged through `sm`; WAVES = 1: a single wave, no LDS, no barrier — used for short key lists,
 // where the per-wave prologue dominates).
 template <typename T, int D, int GQ, int WAVES>
-__device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, const int u, const int z,
-                                            const int wave, const int lane, const int chunk, float* sm_base) {
+__device__ __forceinline__ void decode_rows(const DecodeParams& p, const DecodeLayer& lv, const int c, const int u,
+                                            const int z, const int wave, const int lane, const int chunk,
+                                            float* sm_base) {
   constexpr int LPK = D / 8;         // lanes per key row
   constexpr int KPW = kWave / LPK;   // key rows per wave instruction
   const int gq = p.hq / p.hkv;       // query heads per kv head
@@ -136,10 +165,10 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
   const int m_total = ns + g + 1;    // shared rows, earlier generated rows, the new token
   const float pos = (float)p.q_pos[u];
 
-  const T* Kc = (const T*)p.shared_k + ((long long)b0 * p.hkv + c) * D + sub * 8;
-  const T* Vc = (const T*)p.shared_v + ((long long)b0 * p.hkv + c) * D + sub * 8;
-  T* Gk = (T*)p.gen_k + (((long long)u * p.gen_cap) * p.hkv + c) * D + sub * 8;
-  T* Gv = (T*)p.gen_v + (((long long)u * p.gen_cap) * p.hkv + c) * D + sub * 8;
+  const T* Kc = (const T*)lv.shared_k + ((long long)b0 * p.hkv + c) * D + sub * 8;
+  const T* Vc = (const T*)lv.shared_v + ((long long)b0 * p.hkv + c) * D + sub * 8;
+  T* Gk = (T*)lv.gen_k + (((long long)u * p.gen_cap) * p.hkv + c) * D + sub * 8;
+  T* Gv = (T*)lv.gen_v + (((long long)u * p.gen_cap) * p.hkv + c) * D + sub * 8;
   const long long row_stride = (long long)p.hkv * D;
 
   // The wave's keys are j_begin + wave*KPW + kk + i*WAVES*KPW.  NP iterations' rows are requested together, then
@@ -197,7 +226,7 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
 #pragma unroll
   for (int a = 0; a < GQ; ++a) {
     if (a < gq) {
-      Row8<T>::load((const T*)p.q + ((long long)u * p.hq + head_of_slot(p.heads, c * gq + a)) * D + sub * 8, qv[a]);
+      Row8<T>::load((const T*)lv.q + ((long long)u * p.hq + head_of_slot(p.heads, c * gq + a)) * D + sub * 8, qv[a]);
       rotate(qv[a]);
 #pragma unroll
       for (int i = 0; i < 8; ++i) qv[a][i] *= p.scale_log2;
@@ -209,8 +238,8 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
 
   // the new token's key (rotated, rounded as stored) and value
   float kn[8], vn[8];
-  Row8<T>::load((const T*)p.k_new + ((long long)u * p.hkv + c) * D + sub * 8, kn);
-  Row8<T>::load((const T*)p.v_new + ((long long)u * p.hkv + c) * D + sub * 8, vn);
+  Row8<T>::load((const T*)lv.k_new + ((long long)u * p.hkv + c) * D + sub * 8, kn);
+  Row8<T>::load((const T*)lv.v_new + ((long long)u * p.hkv + c) * D + sub * 8, vn);
   rotate(kn);
 #pragma unroll
   for (int i = 0; i < 8; ++i) kn[i] = Row8<T>::round(kn[i]);
@@ -303,13 +332,13 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const int c, 
       float inv = 1.f / l;
 #pragma unroll
       for (int i = 0; i < 8; ++i) oo[i] *= inv;
-      Row8<T>::store((T*)p.out + ((long long)u * p.hq + head) * D + sb * 8, oo);
+      Row8<T>::store((T*)lv.out + ((long long)u * p.hq + head) * D + sb * 8, oo);
     } else {
       const long long slot = ((long long)u * p.hq + head) * p.n_slots + z;
-      float* po = p.part_o + slot * D + sb * 8;
+      float* po = lv.part_o + slot * D + sb * 8;
 #pragma unroll
       for (int i = 0; i < 8; ++i) po[i] = oo[i];
-      if (sb == 0) { p.part_ml[slot * 2] = m; p.part_ml[slot * 2 + 1] = l; }
+      if (sb == 0) { lv.part_ml[slot * 2] = m; lv.part_ml[slot * 2 + 1] = l; }
     }
   };
   if constexpr (WAVES == 1) {
@@ -356,7 +385,8 @@ __global__ __launch_bounds__(kWave * WAVES) void decode_kernel(DecodeParams p) {
   const int uz = (L / (8 * p.hkv)) * 8 + L % 8;
   const int c = (L / 8) % p.hkv;
   if (uz >= n_uz || L >= n_uz8 * p.hkv) return;
-  decode_rows<T, D, GQ, WAVES>(p, c, uz % p.n_streams, uz / p.n_streams, threadIdx.x / kWave, threadIdx.x % kWave,
+  const DecodeLayer lv = layer_view(p, blockIdx.y);
+  decode_rows<T, D, GQ, WAVES>(p, lv, c, uz % p.n_streams, uz / p.n_streams, threadIdx.x / kWave, threadIdx.x % kWave,
                                p.chunk, sm);
 }
 
@@ -364,10 +394,14 @@ __global__ __launch_bounds__(kWave * WAVES) void decode_kernel(DecodeParams p) {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_combine_kernel(const float* __restrict__ part_o,
                                                              const float* __restrict__ part_ml, T* __restrict__ out,
-                                                             int rows /* n_streams*hq */, int n_slots) {
+                                                             int rows /* n_streams*hq */, int n_slots,
+                                                             long long ls_part_o, long long ls_part_ml, long long ls_out) {
   constexpr int LPK = D / 8;
   const int t = blockIdx.x * 256 + threadIdx.x;
   if (t >= rows * LPK) return;
+  part_o = layer_ptr(part_o, ls_part_o, blockIdx.y);   // grid row y = layer
+  part_ml = layer_ptr(part_ml, ls_part_ml, blockIdx.y);
+  out = layer_ptr(out, ls_out, blockIdx.y);
   const int row = t / LPK, sb = t % LPK;
   float m = -INFINITY, l = 0.f, o[8];
 #pragma unroll
@@ -468,6 +502,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
     if (sz >= n_sz || L >= n_sz8 * p.hkv) return;
     s = sz % p.batch; z = (sz / p.batch) % p.n_splits; own_pass = p.n_pass - 1 - sz / (p.batch * p.n_splits);
   }
+  const DecodeLayer lv = layer_view(p, blockIdx.y);
   const int gq = p.hq / p.hkv;
   // the wave index is the same in all 64 lanes: saying so keeps the key loop and everything derived from the wave's
   // place in the workgroup in scalar registers
@@ -497,8 +532,8 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   const int n_keys = max(j_end - j_begin, 0);
   const int n_tiles = (n_keys + kTileKeys - 1) / kTileKeys;
 
-  const __bf16* Kg = (const __bf16*)p.shared_k + ((long long)b0 * p.hkv + c) * D;
-  const __bf16* Vg = (const __bf16*)p.shared_v + ((long long)b0 * p.hkv + c) * D;
+  const __bf16* Kg = (const __bf16*)lv.shared_k + ((long long)b0 * p.hkv + c) * D;
+  const __bf16* Vg = (const __bf16*)lv.shared_v + ((long long)b0 * p.hkv + c) * D;
   const long long kv_stride = (long long)p.hkv * D;
   FragOffsets<D> fo;
   fo.init(lane);
@@ -579,7 +614,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   u32x4 q_lo[KSTEPS / 2], q_hi[KSTEPS / 2];
   auto load_q_raw = [&](int row0) {
     const int m = min(row0 + 32 * grp + r32, M - 1);
-    const __bf16* qrow = (const __bf16*)p.q + ((long long)sm.streams[m / gq] * p.hq + head_of_slot(p.heads, c * gq + m % gq)) * D + 8 * hf;
+    const __bf16* qrow = (const __bf16*)lv.q + ((long long)sm.streams[m / gq] * p.hq + head_of_slot(p.heads, c * gq + m % gq)) * D + 8 * hf;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS / 2; ++ks) {
       q_lo[ks] = *(const u32x4*)(qrow + 16 * ks);
@@ -618,14 +653,14 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         const int u = sm.streams[si], g = sm.glen[si];
         const long long row0_of_u = (((long long)u * p.gen_cap) * p.hkv + c) * D + ch * 8;
         if (ri < g) {
-          kx = *(const u32x4*)((const __bf16*)p.gen_k + row0_of_u + ri * kv_stride);
-          vx = *(const u32x4*)((const __bf16*)p.gen_v + row0_of_u + ri * kv_stride);
+          kx = *(const u32x4*)((const __bf16*)lv.gen_k + row0_of_u + ri * kv_stride);
+          vx = *(const u32x4*)((const __bf16*)lv.gen_v + row0_of_u + ri * kv_stride);
         } else if (ri == g) {
           const long long tok = ((long long)u * p.hkv + c) * D;
           float x[8], y[8];  // this unit's elements and their rotary partners (the unit half a row away)
-          Row8<__bf16>::load((const __bf16*)p.k_new + tok + ch * 8, x);
-          Row8<__bf16>::load((const __bf16*)p.k_new + tok + (ch ^ (UPR / 2)) * 8, y);
-          vx = *(const u32x4*)((const __bf16*)p.v_new + tok + ch * 8);
+          Row8<__bf16>::load((const __bf16*)lv.k_new + tok + ch * 8, x);
+          Row8<__bf16>::load((const __bf16*)lv.k_new + tok + (ch ^ (UPR / 2)) * 8, y);
+          vx = *(const u32x4*)((const __bf16*)lv.v_new + tok + ch * 8);
           const bool upper = ch >= UPR / 2;
           const float pos = sm.qpos[si];
 #pragma unroll
@@ -641,8 +676,8 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
 #pragma unroll
           for (int j = 0; j < 4; ++j) kx[j] = pack_bf16(x[2 * j], x[2 * j + 1]);
           if (append) {
-            *(u32x4*)((__bf16*)p.gen_k + row0_of_u + g * kv_stride) = kx;
-            *(u32x4*)((__bf16*)p.gen_v + row0_of_u + g * kv_stride) = vx;
+            *(u32x4*)((__bf16*)lv.gen_k + row0_of_u + g * kv_stride) = kx;
+            *(u32x4*)((__bf16*)lv.gen_v + row0_of_u + g * kv_stride) = vx;
           }
         }
       }
@@ -960,7 +995,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         // nothing was split: this is the whole key list of the row (the new token is always among the keys, so the
         // sum is positive); normalise and store the final output
         const float inv = 1.f / ltot;
-        __bf16* po = (__bf16*)p.out + ((long long)row_u * p.hq + row_a) * D + dh * (D / 2) + 4 * hf;
+        __bf16* po = (__bf16*)lv.out + ((long long)row_u * p.hq + row_a) * D + dh * (D / 2) + 4 * hf;
 #pragma unroll
         for (int db = 0; db < DBH; ++db)
 #pragma unroll
@@ -971,7 +1006,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
           }
       } else if (m < M) {
         const long long slot = ((long long)row_u * p.hq + row_a) * p.n_slots + z;
-        float* po = p.part_o + slot * D + dh * (D / 2) + 4 * hf;
+        float* po = lv.part_o + slot * D + dh * (D / 2) + 4 * hf;
 #pragma unroll
         for (int db = 0; db < DBH; ++db)
 #pragma unroll
@@ -979,7 +1014,7 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
             f32x4 w = {o[db][4 * j], o[db][4 * j + 1], o[db][4 * j + 2], o[db][4 * j + 3]};
             *(f32x4*)(po + 32 * db + 8 * j) = w;
           }
-        if (hf == 0 && dh == 0) { p.part_ml[slot * 2] = mrow; p.part_ml[slot * 2 + 1] = ltot; }
+        if (hf == 0 && dh == 0) { lv.part_ml[slot * 2] = mrow; lv.part_ml[slot * 2 + 1] = ltot; }
       }
     }
     __syncthreads();  // the merge buffers are tile memory again in the next row chunk
@@ -999,7 +1034,8 @@ struct DecodePlan {
                   // beyond the first 64, if any, are taken in further passes of the same workgroup)
 };
 
-static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int batch, int max_shared_len, int gen_cap) {
+static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int batch, int max_shared_len, int gen_cap,
+                              int n_layers = 1) {
   DecodePlan pl;
   const int gq = hq / hkv;
   // several query rows per cache (grouped heads or beams) make the shared part a matrix product
@@ -1017,7 +1053,7 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
     // last pass takes whatever rows a sequence has beyond the plan.)
     const long long rows_bound = (long long)gq * (n_streams - batch + 1), rows_avg = (long long)gq * ((n_streams + batch - 1) / batch);
     if (rows_bound > 32 && rows_avg > 64) pl.n_pass = (int)((rows_avg + 63) / 64);
-    long long base = (long long)hkv * batch * pl.n_pass;
+    long long base = (long long)hkv * batch * pl.n_pass * n_layers;
     const int wg_env = tuning(kTuneDecMfmaWgs, 256);
     int want = (int)((wg_env + base - 1) / base);               // one workgroup per CU: it holds 8 waves and most of the LDS
     int cap = (max_shared_len + kDsSuper - 1) / kDsSuper;  // at least one super-tile per workgroup
@@ -1030,7 +1066,7 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
   } else {
     const int max_total = max_shared_len + gen_cap;
     // aim at >= 1024 workgroups (4 per CU) while keeping at least 256 keys per split
-    long long base = (long long)hkv * n_streams;
+    long long base = (long long)hkv * n_streams * n_layers;
     const int wgs_env = tuning(kTuneDecVecWgs, 1024);
     int want = (int)((wgs_env + base - 1) / base);
     int cap = (max_total + 255) / 256;
@@ -1044,11 +1080,12 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
   return pl;
 }
 
+// partial results: [layers][rows][d] floats, then [layers][rows][2] floats
 size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, int batch, int max_shared_len,
-                              int gen_cap) {
-  DecodePlan pl = plan_decode(dtype, hq, hkv, n_streams, batch, max_shared_len, gen_cap);
+                              int gen_cap, int n_layers) {
+  DecodePlan pl = plan_decode(dtype, hq, hkv, n_streams, batch, max_shared_len, gen_cap, n_layers);
   if (pl.n_slots == 1) return 0;  // nothing is split: the kernels write the final outputs themselves
-  size_t rows = (size_t)n_streams * hq * pl.n_slots;
+  size_t rows = (size_t)n_streams * hq * pl.n_slots * n_layers;
   return rows * d * sizeof(float) + rows * 2 * sizeof(float);
 }
 
@@ -1073,27 +1110,27 @@ static void launch_vector(const DecodeParams& p, int gq, dim3 grid, hipStream_t 
 }
 
 template <typename T, int D>
-static void launch_combine(const DecodeParams& p, hipStream_t stream) {
+static void launch_combine(const DecodeParams& p, hipStream_t stream, int n_layers = 1) {
   const int rows = p.n_streams * p.hq;
   const int threads = rows * (D / 8);
-  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3((threads + 255) / 256), dim3(256), 0, stream, p.part_o,
-                     p.part_ml, (T*)p.out, rows, p.n_slots);
+  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3((threads + 255) / 256, n_layers), dim3(256), 0, stream, p.part_o,
+                     p.part_ml, (T*)p.out, rows, p.n_slots, p.ls_part_o, p.ls_part_ml, p.ls_out);
 }
 
 template <typename T, int D>
-static void launch_decode_t(DecodeParams& p, const DecodePlan& pl, int gq, hipStream_t stream) {
+static void launch_decode_t(DecodeParams& p, const DecodePlan& pl, int gq, hipStream_t stream, int n_layers) {
   if (!pl.mfma) {
-    launch_vector<T, D>(p, gq, dim3((unsigned)(((long long)p.n_streams * p.n_splits + 7) / 8 * 8 * p.hkv), 1, 1), stream);
-    if (p.n_slots > 1) launch_combine<T, D>(p, stream);
+    launch_vector<T, D>(p, gq, dim3((unsigned)(((long long)p.n_streams * p.n_splits + 7) / 8 * 8 * p.hkv), n_layers, 1), stream);
+    if (p.n_slots > 1) launch_combine<T, D>(p, stream, n_layers);
     return;
   }
   if constexpr (sizeof(T) == 2) {
-    dim3 grid((unsigned)(((long long)p.batch * p.n_splits * p.n_pass + 7) / 8 * 8 * p.hkv), 1, 1);
+    dim3 grid((unsigned)(((long long)p.batch * p.n_splits * p.n_pass + 7) / 8 * 8 * p.hkv), n_layers, 1);
     // one 32-row group is enough when a cache serves at most 32 query rows; with beams the host only has an upper bound
     const bool one_group = (long long)gq * (p.n_streams - p.batch + 1) <= 32;
     if (one_group) hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 1>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((decode_shared_mfma_kernel<D, 2>), grid, dim3(512), 0, stream, p);
-    if (p.n_slots > 1) launch_combine<T, D>(p, stream);
+    if (p.n_slots > 1) launch_combine<T, D>(p, stream, n_layers);
   }
 }
 
@@ -1101,10 +1138,11 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
                   const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                   const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
                   int n_streams, int batch, int max_shared_len, void* out, void* workspace, size_t workspace_bytes,
-                  hipStream_t stream) {
+                  hipStream_t stream, const DecodeLayers* layers) {
   const int hq = desc->n_q_heads, hkv = desc->n_kv_heads, d = desc->head_dim, gq = hq / hkv;
+  const int n_layers = layers ? layers->n_layers : 1;
   if (gq > 8) { set_error("earn_decode_attn: more than 8 query heads per kv head is not supported"); return EARN_ERR_UNSUPPORTED; }
-  const DecodePlan pl = plan_decode(desc->dtype, hq, hkv, n_streams, batch, max_shared_len, gen_cap);
+  const DecodePlan pl = plan_decode(desc->dtype, hq, hkv, n_streams, batch, max_shared_len, gen_cap, n_layers);
   if (pl.mfma && (long long)(max_shared_len + kDsSuper) * hkv * d * 2 >= (1ll << 31)) {
     set_error("earn_decode_attn: a shared cache of %d rows exceeds the 2 GiB addressing range of one sequence", max_shared_len);
     return EARN_ERR_UNSUPPORTED;
@@ -1119,21 +1157,26 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
   p.gen_k = gen_k; p.gen_v = gen_v; p.gen_len = gen_len; p.out = out;
   p.gen_cap = gen_cap; p.n_streams = n_streams; p.batch = batch; p.hq = hq; p.hkv = hkv;
   p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = 0; p.n_pass = pl.n_pass;
-  const size_t need = decode_workspace_bytes(desc->dtype, hq, hkv, d, n_streams, batch, max_shared_len, gen_cap);
+  const size_t need = decode_workspace_bytes(desc->dtype, hq, hkv, d, n_streams, batch, max_shared_len, gen_cap, n_layers);
   if (need > workspace_bytes || (need > 0 && !workspace)) {
     set_error("earn_decode_attn: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
     return EARN_ERR_WORKSPACE_TOO_SMALL;
   }
+  const size_t part_rows = (size_t)n_streams * hq * p.n_slots;  // per layer
   p.part_o = (float*)workspace;
-  p.part_ml = p.part_o + (size_t)n_streams * hq * p.n_slots * d;
+  p.part_ml = p.part_o + part_rows * d * n_layers;
+  p.ls_part_o = (long long)(part_rows * d * sizeof(float));
+  p.ls_part_ml = (long long)(part_rows * 2 * sizeof(float));
+  p.ls_q = layers ? layers->q : 0; p.ls_kv_new = layers ? layers->kv_new : 0; p.ls_shared = layers ? layers->shared : 0;
+  p.ls_gen = layers ? layers->gen : 0; p.ls_out = layers ? layers->out : 0;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
   p.rope = make_rope_table(desc->rope_base, d);
   if (make_head_map(desc, &p.heads, "earn_decode_attn") != EARN_OK) return EARN_ERR_UNSUPPORTED;
   if (desc->dtype == EARN_F32) {
-    if (d == 64) launch_decode_t<float, 64>(p, pl, gq, stream); else launch_decode_t<float, 128>(p, pl, gq, stream);
+    if (d == 64) launch_decode_t<float, 64>(p, pl, gq, stream, n_layers); else launch_decode_t<float, 128>(p, pl, gq, stream, n_layers);
   } else {
-    if (d == 64) launch_decode_t<__bf16, 64>(p, pl, gq, stream); else launch_decode_t<__bf16, 128>(p, pl, gq, stream);
+    if (d == 64) launch_decode_t<__bf16, 64>(p, pl, gq, stream, n_layers); else launch_decode_t<__bf16, 128>(p, pl, gq, stream, n_layers);
   }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
 }
@@ -1173,7 +1216,7 @@ int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* 
                          const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
                          int n_streams, int batch, int max_shared_len, void* out, hipStream_t stream) {
   const size_t need = decode_workspace_bytes(desc->dtype, desc->n_q_heads, desc->n_kv_heads, desc->head_dim, n_streams,
-                                             batch, max_shared_len, gen_cap);
+                                             batch, max_shared_len, gen_cap, 1);
   if (need > kStaticScratchBytes) {
     set_error("earn_decode_attn_static: the partial results of this problem need %zu bytes, the library's buffer holds "
               "%zu; use earn_decode_attn with a workspace", need, kStaticScratchBytes);
@@ -1183,7 +1226,7 @@ int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* 
   const int rc = static_scratch_of_current_device(&ptr);
   if (rc != EARN_OK) return rc;
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
-                       gen_cap, n_streams, batch, max_shared_len, out, ptr, kStaticScratchBytes, stream);
+                       gen_cap, n_streams, batch, max_shared_len, out, ptr, kStaticScratchBytes, stream, nullptr);
 }
 
 // ---- causal attention of r chosen rows per sequence over the sequence's full-length keys, on the shared-cache kernel:
@@ -1243,6 +1286,7 @@ int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const vo
   p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = rows_per_seq; p.n_pass = n_pass;
   p.part_o = (float*)workspace;
   p.part_ml = p.part_o + (size_t)p.n_streams * hq * p.n_slots * d;
+  p.ls_q = p.ls_kv_new = p.ls_shared = p.ls_gen = p.ls_out = p.ls_part_o = p.ls_part_ml = 0;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
   p.rope = make_rope_table(desc->rope_base, d);

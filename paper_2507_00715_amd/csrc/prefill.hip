@@ -38,9 +38,29 @@ struct PrefillParams {
   const int32_t* row_pos;
   int rows_per_seq;
   float scale_log2;
+  // byte strides between the layers of a layer-batched launch (one grid dimension indexes the layer); zero otherwise.
+  // The sequence bounds, the positions and the cos/sin table are shared by the layers.
+  long long ls_q, ls_k_rot, ls_v, ls_out, ls_lse;
   RopeTable rope;
   HeadMap heads;
 };
+
+template <typename P>
+__device__ __forceinline__ P* pf_layer_ptr(P* base, long long stride, int layer) {
+  return (P*)((const char*)base + stride * layer);
+}
+// The per-layer pointers of one layer, as a view beside the parameter block (a modified copy of the block would live
+// in scratch memory: it holds arrays indexed at run time).
+struct PfLayer { const void* q; const void* k_rot; const void* v; void* out; float* lse; };
+__device__ __forceinline__ PfLayer pf_layer_view(const PrefillParams& p, int layer) {
+  PfLayer v;
+  v.q = pf_layer_ptr(p.q, p.ls_q, layer);
+  v.k_rot = pf_layer_ptr(p.k_rot, p.ls_k_rot, layer);
+  v.v = pf_layer_ptr(p.v, p.ls_v, layer);
+  v.out = pf_layer_ptr(p.out, p.ls_out, layer);
+  v.lse = p.lse ? pf_layer_ptr(p.lse, p.ls_lse, layer) : nullptr;
+  return v;
+}
 
 // ------------------------------------------------------------------------------------------------------------------
 // K rotation
@@ -80,10 +100,12 @@ __global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T*
                                                      const int32_t* __restrict__ cu,
                                                      const int32_t* __restrict__ positions, int batch, int total,
                                                      int hkv, RopeTable rope, f32x2* __restrict__ cs_out,
-                                                     int heads_per_thread) {
+                                                     int heads_per_thread, long long ls_k, long long ls_k_rot) {
   constexpr int G = D / 16;  // groups of 8 pairs per head
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
   if (t >= (long long)total * G) return;
+  k = pf_layer_ptr(k, ls_k, blockIdx.z);           // grid layer z = layer of a layer-batched launch
+  k_rot = pf_layer_ptr(k_rot, ls_k_rot, blockIdx.z);
   const int g = (int)(t % G);
   const int token = (int)(t / G);
   float sn[8], cs[8];
@@ -101,7 +123,7 @@ __global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T*
 #pragma unroll
     for (int i = 0; i < 8; ++i) { sn[i] = 0.f; cs[i] = 1.f; }
   }
-  if (cs_out && blockIdx.y == 0) {
+  if (cs_out && blockIdx.y == 0 && blockIdx.z == 0) {
     f32x4* dst4 = (f32x4*)(cs_out + (long long)token * (D / 2) + g * 8);
 #pragma unroll
     for (int i = 0; i < 8; i += 2) dst4[i / 2] = f32x4{cs[i], sn[i], cs[i + 1], sn[i + 1]};
@@ -132,7 +154,8 @@ __global__ __launch_bounds__(256) void rope_k_kernel(const T* __restrict__ k, T*
 template <typename T, int D>
 __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   constexpr int E = D / 8;  // elements per contiguous piece; a lane holds pieces [qt*E, +E) and [D/2 + qt*E, +E)
-  const int slot = blockIdx.y, s = blockIdx.z;  // slot: the query heads in kv-head order
+  const int slot = blockIdx.y, s = blockIdx.z % p.batch;  // slot: the query heads in kv-head order
+  const PfLayer lv = pf_layer_view(p, blockIdx.z / p.batch);
   const int a = head_of_slot(p.heads, slot);
   const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
   const int row0 = blockIdx.x * 64;
@@ -146,7 +169,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   const int ic = r > 0 ? p.row_pos[s * r + mc] : mc;           // its token index: it sees keys 0 .. ic
   const long long io = r > 0 ? (long long)s * r + mc : (long long)b0 + mc;  // its row in q / out / lse
   const int c = slot / (p.hq / p.hkv);
-  const T* qrow = (const T*)p.q + (io * p.hq + a) * D;
+  const T* qrow = (const T*)lv.q + (io * p.hq + a) * D;
   float ql[E], qh[E];
 #pragma unroll
   for (int e = 0; e < E; e += 8) { Vec8<T>::load(qrow + qt * E + e, ql + e); Vec8<T>::load(qrow + D / 2 + qt * E + e, qh + e); }
@@ -165,8 +188,8 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   // all rows of a wave walk the keys together up to the wave's last row
   const int wave_last_row = min(n_rows - 1, row0 + (int)(threadIdx.x / kWave) * 16 + 15);
   const int wave_last = r > 0 ? p.row_pos[s * r + wave_last_row] : wave_last_row;
-  const T* kbase = (const T*)p.k_rot + ((long long)b0 * p.hkv + c) * D;
-  const T* vbase = (const T*)p.v + ((long long)b0 * p.hkv + c) * D;
+  const T* kbase = (const T*)lv.k_rot + ((long long)b0 * p.hkv + c) * D;
+  const T* vbase = (const T*)lv.v + ((long long)b0 * p.hkv + c) * D;
   const long long rs = (long long)p.hkv * D;
   // NB keys per step: their rows are requested together and their scores formed side by side (the walk is otherwise a
   // chain of memory round trips); the softmax state still takes them one after the other, in key order
@@ -210,10 +233,10 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   const float inv = 1.f / l;
 #pragma unroll
   for (int e = 0; e < E; ++e) { ol[e] *= inv; oh[e] *= inv; }
-  T* orow = (T*)p.out + (io * p.hq + a) * D;
+  T* orow = (T*)lv.out + (io * p.hq + a) * D;
 #pragma unroll
   for (int e = 0; e < E; e += 8) { Vec8<T>::store(orow + qt * E + e, ol + e); Vec8<T>::store(orow + D / 2 + qt * E + e, oh + e); }
-  if (p.lse && qt == 0) p.lse[io * p.hq + a] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
+  if (lv.lse && qt == 0) lv.lse[io * p.hq + a] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -354,6 +377,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
 
   const PfBlock blk = pf_map_block(p, kBlockRows);
   if (!blk.valid) return;
+  const PfLayer lv = pf_layer_view(p, blockIdx.y);
   const int b0 = blk.b0, n = blk.n;
   // the wave index is the same in all 64 lanes: say so, and everything derived from it (the wave's query window, its
   // diagonal tile, the tile loop) lives in scalar registers and branches without touching the execution mask
@@ -366,7 +390,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
   const int n_tiles = (min(blk.q0 + kBlockRows, n) + kTileKeys - 1) / kTileKeys;
 
   TileStager<D, WAVES> stager;
-  stager.init((const __bf16*)p.k_rot + ((long long)b0 * p.hkv + blk.c) * D, (const __bf16*)p.v + ((long long)b0 * p.hkv + blk.c) * D,
+  stager.init((const __bf16*)lv.k_rot + ((long long)b0 * p.hkv + blk.c) * D, (const __bf16*)lv.v + ((long long)b0 * p.hkv + blk.c) * D,
               n, p.hkv, wave, lane);
   const unsigned lds_k = (unsigned)(size_t)(lds_void_ptr)&smk[0][0], lds_v = (unsigned)(size_t)(lds_void_ptr)&smv[0][0];
   auto issue_tile = [&](int t) {
@@ -387,7 +411,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
   bf16x8 qf[D / 16];
   {
     const int qi = min(qw + r32, n - 1);
-    pf_load_q<D>(p, (const __bf16*)p.q + ((long long)(b0 + qi) * p.hq + blk.a) * D + 8 * hf,
+    pf_load_q<D>(p, (const __bf16*)lv.q + ((long long)(b0 + qi) * p.hq + blk.a) * D + 8 * hf,
                  p.cs + (long long)(b0 + qi) * (D / 2) + 8 * hf, qf);
   }
   FragOffsets<D> fo;
@@ -495,8 +519,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
   const int qi = qw + r32;
   const float ltot = half_sum(lrow);
   if (qi >= n) return;
-  pf_store_row<D>((__bf16*)p.out + ((long long)(b0 + qi) * p.hq + blk.a) * D + 4 * hf, o, 1.f / ltot);
-  if (p.lse && hf == 0) p.lse[(long long)(b0 + qi) * p.hq + blk.a] = (mrow + __builtin_log2f(ltot)) * 0.6931471805599453f;
+  pf_store_row<D>((__bf16*)lv.out + ((long long)(b0 + qi) * p.hq + blk.a) * D + 4 * hf, o, 1.f / ltot);
+  if (lv.lse && hf == 0) lv.lse[(long long)(b0 + qi) * p.hq + blk.a] = (mrow + __builtin_log2f(ltot)) * 0.6931471805599453f;
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -528,6 +552,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_pipe_k
 
   const PfBlock blk = pf_map_block(p, kBlockRows);
   if (!blk.valid) return;
+  const PfLayer lv = pf_layer_view(p, blockIdx.y);
   const int b0 = blk.b0, n = blk.n;
   const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int r32 = lane & 31, hf = lane >> 5;
@@ -538,7 +563,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_pipe_k
   const int n_tiles = (min(blk.q0 + kBlockRows, n) + kTileKeys - 1) / kTileKeys;
 
   TileStager<D, WAVES> stager;
-  stager.init((const __bf16*)p.k_rot + ((long long)b0 * p.hkv + blk.c) * D, (const __bf16*)p.v + ((long long)b0 * p.hkv + blk.c) * D,
+  stager.init((const __bf16*)lv.k_rot + ((long long)b0 * p.hkv + blk.c) * D, (const __bf16*)lv.v + ((long long)b0 * p.hkv + blk.c) * D,
               n, p.hkv, wave, lane);
   const unsigned lds_k = (unsigned)(size_t)(lds_void_ptr)&smk[0][0], lds_v = (unsigned)(size_t)(lds_void_ptr)&smv[0][0];
   auto issue_k = [&](int t) { stager.issue(stager.k_rsrc, lds_k + (unsigned)((t % 3) * kTileKeys * D * 2), t); };
@@ -558,7 +583,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_pipe_k
   bf16x8 qf[KSTEPS];
   {
     const int qi = min(qw + r32, n - 1);
-    pf_load_q<D>(p, (const __bf16*)p.q + ((long long)(b0 + qi) * p.hq + blk.a) * D + 8 * hf,
+    pf_load_q<D>(p, (const __bf16*)lv.q + ((long long)(b0 + qi) * p.hq + blk.a) * D + 8 * hf,
                  p.cs + (long long)(b0 + qi) * (D / 2) + 8 * hf, qf);
   }
   FragOffsets<D> fo;
@@ -724,8 +749,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_pipe_k
   const int qi = qw + r32;
   const float ltot = half_sum(lrow);
   if (qi >= n) return;
-  pf_store_row<D>((__bf16*)p.out + ((long long)(b0 + qi) * p.hq + blk.a) * D + 4 * hf, o, 1.f / ltot);
-  if (p.lse && hf == 0) p.lse[(long long)(b0 + qi) * p.hq + blk.a] = (mrow + __builtin_log2f(ltot)) * 0.6931471805599453f;
+  pf_store_row<D>((__bf16*)lv.out + ((long long)(b0 + qi) * p.hq + blk.a) * D + 4 * hf, o, 1.f / ltot);
+  if (lv.lse && hf == 0) lv.lse[(long long)(b0 + qi) * p.hq + blk.a] = (mrow + __builtin_log2f(ltot)) * 0.6931471805599453f;
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -748,13 +773,14 @@ size_t prefill_workspace_bytes(const earn_attn_desc* desc, int total_tokens, int
 
 template <typename T, int D>
 static void launch_rope_k(const void* k, void* k_rot, const int32_t* cu, const int32_t* positions, int batch, int total,
-                          int hkv, const RopeTable& rope, f32x2* cs_out, hipStream_t stream) {
+                          int hkv, const RopeTable& rope, f32x2* cs_out, hipStream_t stream, int n_layers = 1,
+                          long long ls_k = 0, long long ls_k_rot = 0) {
   long long threads = (long long)total * (D / 16);
   const unsigned gx = (unsigned)((threads + 255) / 256);
   // fewer than about two workgroups per CU: split the heads over grid rows as well
-  const int hpt = gx >= 512 ? hkv : (hkv + 7) / 8;
-  hipLaunchKernelGGL((rope_k_kernel<T, D>), dim3(gx, (unsigned)((hkv + hpt - 1) / hpt)), dim3(256), 0, stream,
-                     (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope, cs_out, hpt);
+  const int hpt = (long long)gx * n_layers >= 512 ? hkv : (hkv + 7) / 8;
+  hipLaunchKernelGGL((rope_k_kernel<T, D>), dim3(gx, (unsigned)((hkv + hpt - 1) / hpt), n_layers), dim3(256), 0, stream,
+                     (const T*)k, (T*)k_rot, cu, positions, batch, total, hkv, rope, cs_out, hpt, ls_k, ls_k_rot);
 }
 
 // fp32: the chosen rows of every sequence (q_rows, out_rows: [batch * r, Hq, d]) against the rotated keys, vector kernel
@@ -766,6 +792,7 @@ int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, cons
   p.cs = nullptr; p.row_pos = row_pos; p.rows_per_seq = rows_per_seq;
   p.q = q_rows; p.k_rot = k_rot; p.v = v; p.cu = cu_seqlens; p.positions = nullptr; p.out = out_rows; p.lse = nullptr;
   p.batch = batch; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.max_seqlen = max_seqlen; p.n_qblk = 1;
+  p.ls_q = p.ls_k_rot = p.ls_v = p.ls_out = p.ls_lse = 0;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
   p.rope = make_rope_table(desc->rope_base, d);
@@ -793,8 +820,15 @@ int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, con
 
 int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
                    const int32_t* positions, int batch, int total_tokens, int max_seqlen, void* out, void* k_rot_out,
-                   float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+                   float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t stream,
+                   const PrefillLayers* layers) {
   const int d = desc->head_dim;
+  const int n_layers = layers ? layers->n_layers : 1;
+  const long long ls_k = layers ? layers->kv : 0, ls_kr = layers ? layers->k_rot : 0;
+  if ((long long)batch * n_layers > 65535 && desc->dtype == EARN_F32) {
+    set_error("earn_prefill_attn_layers: batch * n_layers = %lld exceeds 65535 (fp32 launch shape)", (long long)batch * n_layers);
+    return EARN_ERR_UNSUPPORTED;
+  }
   const size_t need = prefill_workspace_bytes(desc, total_tokens, k_rot_out != nullptr);
   if (need > workspace_bytes || (need > 0 && !workspace)) {
     set_error("earn_prefill_attn: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
@@ -811,36 +845,38 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
   p.cs = cs; p.row_pos = nullptr; p.rows_per_seq = 0;
   p.q = q; p.k_rot = k_rot; p.v = v; p.cu = cu_seqlens; p.positions = positions; p.out = out; p.lse = lse_out;
   p.batch = batch; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.max_seqlen = max_seqlen;
+  p.ls_q = layers ? layers->q : 0; p.ls_k_rot = ls_kr; p.ls_v = ls_k; p.ls_out = layers ? layers->out : 0;
+  p.ls_lse = layers ? layers->lse : 0;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
   p.rope = make_rope_table(desc->rope_base, d);
   if (make_head_map(desc, &p.heads, "earn_prefill_attn") != EARN_OK) return EARN_ERR_UNSUPPORTED;
   const bool f32 = desc->dtype == EARN_F32;
   if (f32) {
-    if (d == 64) launch_rope_k<float, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
-    else launch_rope_k<float, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
-    dim3 grid((max_seqlen + 63) / 64, p.hq, batch);
+    if (d == 64) launch_rope_k<float, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+    else launch_rope_k<float, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+    dim3 grid((max_seqlen + 63) / 64, p.hq, batch * n_layers);
     if (d == 64) hipLaunchKernelGGL((prefill_rows_kernel<float, 64>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((prefill_rows_kernel<float, 128>), grid, dim3(256), 0, stream, p);
   } else if (max_seqlen <= kTileKeys) {
     // register-only layers: every sequence is a single K/V tile
-    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
-    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
+    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
     p.n_qblk = 1;
     const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
-    dim3 grid((unsigned)(pairs8 * (p.hq / p.hkv)), 1, 1);
+    dim3 grid((unsigned)(pairs8 * (p.hq / p.hkv)), n_layers, 1);
     if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 2, 1>), grid, dim3(128), 0, stream, p);
     else hipLaunchKernelGGL((prefill_mfma_kernel<128, 2, 1>), grid, dim3(128), 0, stream, p);
   } else {
-    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
-    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream);
+    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
     // 128-row workgroups (two per CU) in the plain schedule up to medium lengths, where the ends of a workgroup's
     // life (first tile's latency, output store) and the causal diagonal weigh most; the pipelined 256-row kernel beyond
     const int rows_set = tuning(kTunePrefillBlockRows, 0);
     const int block_rows = rows_set == 128 || rows_set == 256 ? rows_set : (max_seqlen <= 3072 ? 128 : 256);
     p.n_qblk = (max_seqlen + block_rows - 1) / block_rows;
     const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
-    dim3 grid((unsigned)(pairs8 * p.n_qblk * (p.hq / p.hkv)), 1, 1);
+    dim3 grid((unsigned)(pairs8 * p.n_qblk * (p.hq / p.hkv)), n_layers, 1);
     if (block_rows == 128) {
       if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 4, 2>), grid, dim3(256), 0, stream, p);
       else hipLaunchKernelGGL((prefill_mfma_kernel<128, 4, 2>), grid, dim3(256), 0, stream, p);

@@ -11,6 +11,12 @@ input of layer k keeps the register rows only — is evaluated at the register r
 the gathered query rows); its keys and values stay full length, they are the layer's cache.  prefill_out[k-1] then
 holds the B*r register rows in compacted order.
 
+Per-layer buffers of one kind are slices of ONE tensor with a leading layer dimension (register layers k..N-1: gathered
+q/k/v, caches, outputs; full layers 0..k-1: key caches, decode outputs; generated caches of all layers), so that the
+layer-batched entry points (earn_prefill_attn_layers, earn_decode_attn_layers) can take a run of layers in one launch
+when the layers are independent of each other, as they are with synthetic per-layer inputs; the per-layer methods work
+on the same slices.
+
 All buffers are allocated once in the constructor; the methods only enqueue kernels on the current stream.
 """
 from __future__ import annotations
@@ -46,30 +52,43 @@ class EarnPath:
         # one stream per sequence in order: the library takes "no map" and saves every decode workgroup a dependent load
         identity = list(stream_to_seq) == list(range(self.batch))
         self.stream_to_seq = None if identity else torch.tensor(list(stream_to_seq), dtype=i32, device=dev)
-        self.seq_len_of_stream = torch.tensor([lens[s] for s in stream_to_seq], dtype=i32, device=dev)
         self.idx = torch.empty(self.Tc, dtype=i32, device=dev)
         self.pos = torch.empty(self.Tc, dtype=i32, device=dev)
         self.cu_c = torch.empty(self.batch + 1, dtype=i32, device=dev)
         e = lambda *shape: torch.empty(shape, dtype=dtype, device=dev)
         N, k = self.N, self.k
         rows_layer = k - 1 if self.rows_only else -1
-        self.prefill_out = [e(self.T if l < k and l != rows_layer else self.Tc, self.hq, self.d) for l in range(N)]
+        R = N - k                                                     # register-focused layers
+        # stacks with a leading layer dimension; the per-layer lists below are slices of them
+        self.reg_prefill_out = e(R, self.Tc, self.hq, self.d)
+        self.reg_q, self.reg_k, self.reg_v = e(R, self.Tc, self.hq, self.d), e(R, self.Tc, self.hkv, self.d), e(R, self.Tc, self.hkv, self.d)
+        self.reg_k_cache = e(R, self.Tc, self.hkv, self.d)
+        self.full_k_cache = e(k, self.T, self.hkv, self.d)
+        self.gen_k_all = torch.zeros(N, self.S, gen_cap, self.hkv, self.d, dtype=dtype, device=dev)
+        self.gen_v_all = torch.zeros(N, self.S, gen_cap, self.hkv, self.d, dtype=dtype, device=dev)
+        self.decode_out_all = e(N, self.S, self.hq, self.d)
+        self.prefill_out = [(e(self.T, self.hq, self.d) if l != rows_layer else e(self.Tc, self.hq, self.d)) if l < k
+                            else self.reg_prefill_out[l - k] for l in range(N)]
         self.q_rows = e(self.Tc, self.hq, self.d) if self.rows_only else None
-        self.k_cache = [e(self.T if l < k else self.Tc, self.hkv, self.d) for l in range(N)]
+        self.k_cache = [self.full_k_cache[l] if l < k else self.reg_k_cache[l - k] for l in range(N)]
         self.v_cache: List[Optional[torch.Tensor]] = [None] * N       # layers < k alias the caller's V
+        self.v_full_stack: Optional[torch.Tensor] = None              # [k, T, Hkv, d], if the caller keeps V that way
         self.x_c: Optional[torch.Tensor] = None
-        self.q_c = {l: e(self.Tc, self.hq, self.d) for l in range(k, N)}
-        self.k_c = {l: e(self.Tc, self.hkv, self.d) for l in range(k, N)}
-        self.v_c = {l: e(self.Tc, self.hkv, self.d) for l in range(k, N)}
-        self.lse = ([torch.empty(self.T if l < k else self.Tc, self.hq, dtype=torch.float32, device=dev)
+        self.q_c = {l: self.reg_q[l - k] for l in range(k, N)}
+        self.k_c = {l: self.reg_k[l - k] for l in range(k, N)}
+        self.v_c = {l: self.reg_v[l - k] for l in range(k, N)}
+        self.reg_lse = torch.empty(R, self.Tc, self.hq, dtype=torch.float32, device=dev) if want_lse else None
+        self.lse = ([torch.empty(self.T, self.hq, dtype=torch.float32, device=dev) if l < k else self.reg_lse[l - k]
                      for l in range(N)] if want_lse else [None] * N)
-        self.gen_k = [torch.zeros(self.S, gen_cap, self.hkv, self.d, dtype=dtype, device=dev) for _ in range(N)]
-        self.gen_v = [torch.zeros(self.S, gen_cap, self.hkv, self.d, dtype=dtype, device=dev) for _ in range(N)]
+        self.gen_k = [self.gen_k_all[l] for l in range(N)]
+        self.gen_v = [self.gen_v_all[l] for l in range(N)]
         self.gen_len = torch.zeros(self.S, dtype=i32, device=dev)
         self.q_pos = torch.zeros(self.S, dtype=i32, device=dev)
-        self.decode_out = [e(self.S, self.hq, self.d) for _ in range(N)]
+        self.decode_out = [self.decode_out_all[l] for l in range(N)]
         ws = max(B.earn_decode_workspace_bytes(self.desc, self.S, self.batch, self.max_seqlen, gen_cap),
-                 B.earn_decode_workspace_bytes(self.desc, self.S, self.batch, self.r, gen_cap), 256)
+                 B.earn_decode_workspace_bytes(self.desc, self.S, self.batch, self.r, gen_cap),
+                 B.earn_decode_layers_workspace_bytes(self.desc, max(k, 1), self.S, self.batch, self.max_seqlen, gen_cap),
+                 B.earn_decode_layers_workspace_bytes(self.desc, max(R, 1), self.S, self.batch, self.r, gen_cap), 256)
         self.workspace = torch.empty(ws, dtype=torch.uint8, device=dev)
         pws = max(B.earn_prefill_workspace_bytes(self.desc, self.batch, self.T, self.max_seqlen, True),
                   B.earn_prefill_workspace_bytes(self.desc, self.batch, self.Tc, self.r, True), 256)
@@ -128,11 +147,38 @@ class EarnPath:
             for l in range(self.k, self.N):
                 self.prefill_register_layer(l)
 
+    def bind_prefill_register_layers(self) -> "B.BoundCall":
+        """All register-focused layers k..N-1 in one launch (valid when the layers' inputs do not depend on each other:
+        the gathered q/k/v of the synthetic workloads), marshalled once."""
+        for l in range(self.k, self.N):
+            self.v_cache[l] = self.v_c[l]
+        return B.bind_prefill_attn_layers(self.desc, self.reg_q, self.reg_k, self.reg_v, self.cu_c, self.pos, self.batch,
+                                          self.Tc, self.r, self.reg_prefill_out, self.reg_k_cache, self.reg_lse,
+                                          self.prefill_workspace)
+
     # ---- decode ----
     def set_step(self, g: int) -> None:
-        """gen_len = g and q_pos = n_s + g for every stream (tiny fill kernels, no host sync)."""
-        self.gen_len.fill_(g)
-        torch.add(self.seq_len_of_stream, g, out=self.q_pos)
+        """gen_len = g and q_pos = n_s + g for every stream (one small kernel of the library, no host sync)."""
+        B.earn_decode_step_positions(self.cu, self.stream_to_seq, self.S, self.batch, g, self.q_pos, self.gen_len)
+
+    def bind_set_step(self, g: int) -> "B.BoundCall":
+        return B.bind_decode_step_positions(self.cu, self.stream_to_seq, self.S, self.batch, g, self.q_pos, self.gen_len)
+
+    def bind_decode_register_layers(self, dq, dk, dv) -> "B.BoundCall":
+        """One decode step of all register-focused layers in one launch; dq/dk/dv: [N-k, S, H, d]."""
+        return B.bind_decode_attn_layers(self.desc, dq, dk, dv, self.q_pos, self.reg_k_cache, self.reg_v, self.cu_c,
+                                         self.stream_to_seq, self.gen_k_all[self.k:], self.gen_v_all[self.k:],
+                                         self.gen_len, self.gen_cap, self.S, self.batch, self.r,
+                                         self.decode_out_all[self.k:], self.workspace)
+
+    def bind_decode_full_layers(self, dq, dk, dv) -> "B.BoundCall":
+        """One decode step of the first k layers in one launch; dq/dk/dv: [k, S, H, d]; needs v_full_stack [k, T, Hkv, d]
+        (the values the prefill of those layers was given, kept as one tensor)."""
+        assert self.v_full_stack is not None and self.v_full_stack.shape[0] == self.k
+        return B.bind_decode_attn_layers(self.desc, dq, dk, dv, self.q_pos, self.full_k_cache, self.v_full_stack, self.cu,
+                                         self.stream_to_seq, self.gen_k_all[:self.k], self.gen_v_all[:self.k],
+                                         self.gen_len, self.gen_cap, self.S, self.batch, self.max_seqlen,
+                                         self.decode_out_all[:self.k], self.workspace)
 
     def decode_layer(self, l: int, dq, dk, dv) -> None:
         full = l < self.k
