@@ -6,6 +6,12 @@ A "step" is one pass of the whole path over one synthetic batch of a configurati
     (each decode step runs all N layers: full cache for layers < k, register cache for layers >= k).
 Inputs are generated on the GPU before the timed region (seeded, synthetic, see paper_2507_00715_amd/workloads.py).
 
+The timed steps run in the harness throughput mode: the synthetic layers are independent of each other, so the
+register-only prefill layers and, per decode step, the k full-cache layers and the N-k register-cache layers each go
+out as ONE layer-batched launch (earn_prefill_attn_layers / earn_decode_attn_layers); the full-length prefill layers
+stay one launch per layer.  The same steps with one launch per layer (the form a real model needs, where layer l+1
+depends on layer l) are timed right after and reported under "per_layer_launch".
+
 Prints ONE JSON line.  `value` is the prefill-attention rate in algorithmic causal TFLOP/s
 (4*d*Hq*sum_s m_s(m_s+1)/2 per layer, summed over all N prefill launches, divided by the time the prefill
 launches took inside the timed steps); decode and compaction figures, a roofline object for the dominant
@@ -32,10 +38,21 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3     # fp32 vector
 PEAK_HBM_GBPS = 8000.0      # HBM3E
 HEADLINE = "long_beam"
-# HBM bytes per full-length prefill layer (K rotation + attention kernel), from the rocprofv3 FETCH_SIZE / WRITE_SIZE
-# runs summarised in profiles/long_beam_hbm_traffic.txt (counters scaled by a 1 GiB copy: x2.0 and x1.0).
-MEASURED_TRAFFIC = {"long_beam": {"fetch_bytes": 3.537e9, "write_bytes": 1.422e9}}
 DOMINANT_KERNEL = "prefill_pipe_kernel + rope_k_kernel (one full-length causal layer)"
+
+
+def measured_traffic(name: str):
+    """HBM bytes per full-length prefill layer (K rotation + attention kernel) from the rocprofv3 FETCH_SIZE /
+    WRITE_SIZE passes: read from the summary profiles/<name>_hbm_traffic.txt, which carries them in one line
+    `bench: fetch_bytes=... write_bytes=...` (counters already scaled by what a plain copy of known size reads).
+    None when the summary is not there."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"{name}_hbm_traffic.txt")
+    try:
+        m = re.search(r"^bench:\s*fetch_bytes=([0-9.e+]+)\s+write_bytes=([0-9.e+]+)", open(path).read(), flags=re.M)
+    except OSError:
+        return None
+    return {"fetch_bytes": float(m.group(1)), "write_bytes": float(m.group(2)), "source": os.path.relpath(path, ROOT)} if m else None
 
 
 def log(*a):
@@ -102,19 +119,29 @@ def algorithmic_prefill_bytes(name: str) -> float:
 
 
 def build_inputs(w: W.Workload, dev):
+    """Per-layer Q, K, V (the values of the first k layers as slices of one [k, T, Hkv, d] tensor, so that their
+    decode steps can go out as one launch) and, per decode step, q / k_new / v_new of all layers as [N, S, H, d]."""
     c = w.cfg
     t0 = time.time()
     seq, pos = w.token_coords(dev)
     mk = lambda which: [w.prefill_tensor(which, l, coords=(seq, pos)) for l in range(c.n_layers)]
-    q, k, v = mk("q"), mk("k"), mk("v")
+    q, k = mk("q"), mk("k")
+    v_full = torch.empty(c.split_k, w.total_tokens, c.n_kv_heads, c.head_dim, dtype=c.torch_dtype, device=dev)
+    v = []
+    for l in range(c.n_layers):
+        if l < c.split_k:
+            v_full[l].copy_(w.prefill_tensor("v", l, coords=(seq, pos)))
+            v.append(v_full[l])
+        else:
+            v.append(w.prefill_tensor("v", l, coords=(seq, pos)))
     x = w.prefill_tensor("x", 0, coords=(seq, pos))
-    dmk = lambda which: [[w.decode_tensor(which, l, g, device=dev) for l in range(c.n_layers)]
+    dmk = lambda which: [torch.stack([w.decode_tensor(which, l, g, device=dev) for l in range(c.n_layers)])
                          for g in range(c.decode_steps)]
     dq, dk, dv = dmk("q"), dmk("k"), dmk("v")
     torch.cuda.synchronize()
     log(f"[bench] {c.name}: inputs generated on GPU in {time.time() - t0:.1f}s "
         f"({torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated)")
-    return q, k, v, x, dq, dk, dv
+    return q, k, v, v_full, x, dq, dk, dv
 
 
 def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
@@ -122,7 +149,7 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
     cfg = W.CONFIGS[name]
     w = W.Workload(cfg)
     c = cfg
-    q, k, v, x, dq, dk, dv = build_inputs(w, dev)
+    q, k, v, v_full, x, dq, dk, dv = build_inputs(w, dev)
     path = EarnPath(n_layers=c.n_layers, split_k=c.split_k, n_head_reg=c.n_head_reg, n_tail_reg=c.n_tail_reg,
                     n_q_heads=c.n_q_heads, n_kv_heads=c.n_kv_heads, head_dim=c.head_dim, dtype=c.torch_dtype,
                     cu_seqlens=w.cu_seqlens, stream_to_seq=w.stream_to_seq, gen_cap=c.decode_steps,
@@ -133,10 +160,17 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
     # first k layers are the caller's V tensors, known here; everything else is pre-allocated inside the path).
     for l in range(kk):
         path.v_cache[l] = v[l]
+    path.v_full_stack = v_full
+    steps_pos = [path.bind_set_step(g) for g in range(G)]
+    # one launch per layer
     reg_prefill = [path.bind_prefill_register_layer(l) for l in range(kk, N)]
     dec = [[path.bind_decode_layer(l, dq[g][l], dk[g][l], dv[g][l]) for l in range(N)] for g in range(G)]
+    # one launch per run of independent layers
+    reg_prefill_b = path.bind_prefill_register_layers()
+    dec_full_b = [path.bind_decode_full_layers(dq[g][:kk], dk[g][:kk], dv[g][:kk]) for g in range(G)]
+    dec_reg_b = [path.bind_decode_register_layers(dq[g][kk:], dk[g][kk:], dv[g][kk:]) for g in range(G)]
 
-    def one_step(tm: PhaseTimer | None):
+    def one_step(tm: PhaseTimer | None, batched: bool):
         ph = (lambda n: tm.start(n)) if tm else (lambda n: None)
         pe = (lambda n: tm.stop(n)) if tm else (lambda n: None)
         ph("prefill_full")
@@ -147,31 +181,61 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
         path.compact(x, q, k, v)
         pe("compact")
         ph("prefill_reg")
-        for call in reg_prefill:
-            call()
+        if batched:
+            reg_prefill_b()
+        else:
+            for call in reg_prefill:
+                call()
         pe("prefill_reg")
         for g in range(G):
-            path.set_step(g)
+            steps_pos[g]()
             ph("decode_full")
-            for l in range(kk):
-                dec[g][l]()
+            if batched:
+                dec_full_b[g]()
+            else:
+                for l in range(kk):
+                    dec[g][l]()
             pe("decode_full")
             ph("decode_reg")
-            for l in range(kk, N):
-                dec[g][l]()
+            if batched:
+                dec_reg_b[g]()
+            else:
+                for l in range(kk, N):
+                    dec[g][l]()
             pe("decode_reg")
 
-    for _ in range(warmup):
-        one_step(None)
-    torch.cuda.synchronize()
-    tm = PhaseTimer()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        one_step(tm)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms = tm.totals_ms()
+    def timed(batched: bool, n_steps: int):
+        for _ in range(warmup):
+            one_step(None, batched)
+        torch.cuda.synchronize()
+        tm = PhaseTimer()
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            one_step(tm, batched)
+        torch.cuda.synchronize()
+        return tm.totals_ms(), time.perf_counter() - t0
+
+    ms, wall = timed(True, steps)
+    ms_pl, wall_pl = timed(False, steps)
     alg = algorithmic_counts(w)
+
+    # The same N layers the vanilla way (Section 3.3's baseline: every layer full length), measured: N full-length
+    # prefill launches and N full-cache decode launches, cycling over the tensors of layers 0..k-1.
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for l in range(N):
+        path.prefill_full_layer(l % kk, q[l % kk], k[l % kk], v[l % kk])
+    e1.record()
+    torch.cuda.synchronize()
+    vanilla_prefill_ms = e0.elapsed_time(e1)
+    steps_pos[G // 2]()
+    e0.record()
+    for l in range(N):
+        dec[G // 2][l % kk]()
+    e1.record()
+    torch.cuda.synchronize()
+    vanilla_decode_ms = e0.elapsed_time(e1)
 
     # Beyond the paper's method, exact: layer k-1 evaluated at the register rows only (its other outputs are dropped by
     # the compaction).  Timed on its own, gather of the query rows included; the timed steps above do not use it.
@@ -190,7 +254,6 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
                                          path.max_seqlen, path.r, out_rows, path.k_cache[l], ws)
         rows_layer()
         reps = 10
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
         for _ in range(reps):
@@ -200,53 +263,67 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
         rows_only = e0.elapsed_time(e1) / reps
         del q_rows, out_rows, ws
 
-    full_ms = ms["prefill_full"] / (steps * kk)              # per launch of the dominant kernel (+ its K rotation)
-    reg_ms = ms["prefill_reg"] / (steps * max(N - kk, 1))
-    prefill_flops = kk * alg["flops_full"] + (N - kk) * alg["flops_reg"]
-    prefill_tflops = prefill_flops * steps / ((ms["prefill_full"] + ms["prefill_reg"]) * 1e-3) / 1e12
-    full_tflops = alg["flops_full"] / (full_ms * 1e-3) / 1e12
-    dec_bytes_step = [kk * alg["dec_full"][g] + (N - kk) * alg["dec_reg"][g] for g in range(G)]
-    dec_ms_total = ms["decode_full"] + ms["decode_reg"]
-    dec_us_per_step = dec_ms_total * 1e3 / (steps * G)
-    dec_gbps = sum(dec_bytes_step) * steps / (dec_ms_total * 1e-3) / 1e9
-    dec_full_gbps = kk * sum(alg["dec_full"]) * steps / (ms["decode_full"] * 1e-3) / 1e9
-    dec_reg_gbps = (N - kk) * sum(alg["dec_reg"]) * steps / (ms["decode_reg"] * 1e-3) / 1e9
-    comp_us = ms["compact"] * 1e3 / steps
-    comp_gbps = alg["compaction"] / (comp_us * 1e-6) / 1e9
     peak = PEAK_BF16_TFLOPS if c.dtype == "bf16" else PEAK_F32_TFLOPS
-    res = {
-        "workload": w.describe(),
-        "ms_per_step": wall * 1e3 / steps,
-        "prefill_tflops": prefill_tflops,
-        "prefill_full_layer": {"ms_per_launch": full_ms, "tflops": full_tflops, "frac_of_peak": full_tflops / peak,
-                               "flops_per_launch": alg["flops_full"],
-                               "executed_tile_flops_per_launch": executed_tile_flops(w) if c.dtype == "bf16" else None},
-        "prefill_register_layer": {"us_per_launch": reg_ms * 1e3, "flops_per_launch": alg["flops_reg"]},
-        "compaction": {"us": comp_us, "bytes": alg["compaction"], "GBps": comp_gbps,
-                       "frac_of_hbm_peak": comp_gbps / PEAK_HBM_GBPS},
-        "decode": {"us_per_step": dec_us_per_step, "bytes_first_step": dec_bytes_step[0],
-                   "bytes_last_step": dec_bytes_step[-1], "GBps": dec_gbps, "frac_of_hbm_peak": dec_gbps / PEAK_HBM_GBPS,
-                   "full_cache_layers": {"us_per_layer": ms["decode_full"] * 1e3 / (steps * G * kk),
-                                         "GBps": dec_full_gbps, "frac_of_hbm_peak": dec_full_gbps / PEAK_HBM_GBPS},
-                   "register_cache_layers": {"us_per_layer": ms["decode_reg"] * 1e3 / (steps * G * max(N - kk, 1)),
-                                             "GBps": dec_reg_gbps, "frac_of_hbm_peak": dec_reg_gbps / PEAK_HBM_GBPS}},
-        "phase_ms_per_step": {k_: v_ / steps for k_, v_ in ms.items()},
-        "last_full_layer_register_rows_only": None if rows_only is None else {
-            "ms_per_launch": rows_only, "full_layer_ms_per_launch": ms["prefill_full"] / (steps * kk),
-            "ms_per_step_with_it": (wall * 1e3 - ms["prefill_full"] / kk) / steps + rows_only,
-            "note": "layer k-1 at the B*r register rows only (gather of the query rows + K rotation + attention); "
-                    "exact, beyond the paper's method; not used inside the timed steps"},
-        # Context, attention only (not comparable with the paper's end-to-end figures): the same N layers run the
-        # vanilla way (every layer full length) would cost N full-layer launches; next to it the closed forms of
-        # Section 3.3 (k/N for attention work, (k n + (N-k) r)/(N n) for cache entries).
-        "attention_only_vs_vanilla": {
-            "prefill_speedup": N * full_ms / (kk * full_ms + (N - kk) * reg_ms),
-            "decode_speedup": (N * ms["decode_full"] / max(kk, 1)) / (ms["decode_full"] + ms["decode_reg"]),
-            "closed_form_attention_ratio": kk / N,
-            "closed_form_cache_ratio": sum(kk * n + (N - kk) * c.r for n in w.seq_lengths) / float(N * sum(w.seq_lengths)),
-        },
+    dec_bytes_step = [kk * alg["dec_full"][g] + (N - kk) * alg["dec_reg"][g] for g in range(G)]
+
+    def figures(ms, wall):
+        full_ms = ms["prefill_full"] / (steps * kk)              # per launch of the dominant kernel (+ its K rotation)
+        reg_ms = ms["prefill_reg"] / (steps * max(N - kk, 1))    # per register-only layer
+        prefill_flops = kk * alg["flops_full"] + (N - kk) * alg["flops_reg"]
+        prefill_tflops = prefill_flops * steps / ((ms["prefill_full"] + ms["prefill_reg"]) * 1e-3) / 1e12
+        full_tflops = alg["flops_full"] / (full_ms * 1e-3) / 1e12
+        dec_ms_total = ms["decode_full"] + ms["decode_reg"]
+        dec_gbps = sum(dec_bytes_step) * steps / (dec_ms_total * 1e-3) / 1e9
+        dec_full_gbps = kk * sum(alg["dec_full"]) * steps / (ms["decode_full"] * 1e-3) / 1e9
+        dec_reg_gbps = (N - kk) * sum(alg["dec_reg"]) * steps / (ms["decode_reg"] * 1e-3) / 1e9
+        comp_us = ms["compact"] * 1e3 / steps
+        comp_gbps = alg["compaction"] / (comp_us * 1e-6) / 1e9
+        return {
+            "ms_per_step": wall * 1e3 / steps,
+            "prefill_tflops": prefill_tflops,
+            "prefill_full_layer": {"ms_per_launch": full_ms, "tflops": full_tflops, "frac_of_peak": full_tflops / peak,
+                                   "flops_per_launch": alg["flops_full"],
+                                   "executed_tile_flops_per_launch": executed_tile_flops(w) if c.dtype == "bf16" else None},
+            "prefill_register_layer": {"us_per_layer": reg_ms * 1e3, "flops_per_layer": alg["flops_reg"]},
+            "compaction": {"us": comp_us, "bytes": alg["compaction"], "GBps": comp_gbps,
+                           "frac_of_hbm_peak": comp_gbps / PEAK_HBM_GBPS},
+            "decode": {"us_per_step": dec_ms_total * 1e3 / (steps * G), "bytes_first_step": dec_bytes_step[0],
+                       "bytes_last_step": dec_bytes_step[-1], "GBps": dec_gbps,
+                       "frac_of_hbm_peak": dec_gbps / PEAK_HBM_GBPS,
+                       "full_cache_layers": {"us_per_layer": ms["decode_full"] * 1e3 / (steps * G * kk),
+                                             "GBps": dec_full_gbps, "frac_of_hbm_peak": dec_full_gbps / PEAK_HBM_GBPS},
+                       "register_cache_layers": {"us_per_layer": ms["decode_reg"] * 1e3 / (steps * G * max(N - kk, 1)),
+                                                 "GBps": dec_reg_gbps, "frac_of_hbm_peak": dec_reg_gbps / PEAK_HBM_GBPS}},
+            "phase_ms_per_step": {k_: v_ / steps for k_, v_ in ms.items()},
+        }
+
+    res = {"workload": w.describe(), "launch_mode": "layer-batched register-cache and decode phases"}
+    res.update(figures(ms, wall))
+    pl = figures(ms_pl, wall_pl)
+    res["per_layer_launch"] = {k_: pl[k_] for k_ in ("ms_per_step", "prefill_tflops", "prefill_register_layer", "decode",
+                                                     "phase_ms_per_step")}
+    full_ms = res["prefill_full_layer"]["ms_per_launch"]
+    res["last_full_layer_register_rows_only"] = None if rows_only is None else {
+        "ms_per_launch": rows_only, "full_layer_ms_per_launch": full_ms,
+        "ms_per_step_with_it": res["ms_per_step"] - full_ms + rows_only,
+        "note": "layer k-1 at the B*r register rows only (gather of the query rows + K rotation + attention); "
+                "exact, beyond the paper's method; not used inside the timed steps"}
+    # Context, attention only (not comparable with the paper's end-to-end figures): the measured phases against the
+    # same N layers run the vanilla way (measured above), next to the closed forms of Section 3.3 (k/N for attention
+    # work, (k n + (N-k) r)/(N n) for cache entries).
+    earn_prefill_ms = (ms["prefill_full"] + ms["compact"] + ms["prefill_reg"]) / steps
+    earn_decode_ms = (ms["decode_full"] + ms["decode_reg"]) / (steps * G)
+    res["attention_only_vs_vanilla"] = {
+        "vanilla_prefill_ms": vanilla_prefill_ms, "earn_prefill_ms": earn_prefill_ms,
+        "prefill_speedup": vanilla_prefill_ms / earn_prefill_ms,
+        "vanilla_decode_step_ms": vanilla_decode_ms, "earn_decode_step_ms": earn_decode_ms,
+        "decode_speedup": vanilla_decode_ms / earn_decode_ms,
+        "closed_form_attention_ratio": kk / N,
+        "closed_form_cache_ratio": sum(kk * n + (N - kk) * c.r for n in w.seq_lengths) / float(N * sum(w.seq_lengths)),
+        "note": "vanilla = N full-length prefill launches / N full-cache decode launches (one launch per layer), "
+                "measured, cycling over the tensors of layers 0..k-1",
     }
-    del path, q, k, v, x, dq, dk, dv
+    del path, q, k, v, v_full, x, dq, dk, dv
     torch.cuda.empty_cache()
     return res
 
@@ -262,7 +339,7 @@ def run_single(name: str, kind: str, dev) -> dict:
                     n_q_heads=c.n_q_heads, n_kv_heads=c.n_kv_heads, head_dim=c.head_dim, dtype=c.torch_dtype,
                     cu_seqlens=w.cu_seqlens, stream_to_seq=w.stream_to_seq, gen_cap=c.decode_steps,
                     rope_base=c.rope_base, device=dev)
-    q0, k0, v0 = (w.prefill_tensor(t, 0, coords=(seq, pos)) for t in "qkv")
+    q0, k0, v0 = (w.prefill_tensor(t, 0, coords=(seq, pos)) for t in "qkv") if kind != "compact" else (None,) * 3
     if kind == "prefill_full":
         launch = lambda: path.prefill_full_layer(0, q0, k0, v0)
     elif kind == "decode_full":
@@ -271,9 +348,21 @@ def run_single(name: str, kind: str, dev) -> dict:
         dq, dk, dv = (w.decode_tensor(t, 0, 0, device=dev) for t in "qkv")
         launch = lambda: path.decode_layer(0, dq, dk, dv)
     elif kind == "compact":
+        # a byte gather does not care what the bytes are: ONE fill dispatch for all sources (under the counters every
+        # dispatch is serialised, and drawing the 85 tensors with the generator took minutes there)
         N, kk = c.n_layers, c.split_k
-        mk = lambda which: [w.prefill_tensor(which, l, coords=(seq, pos)) if l >= kk else None for l in range(N)]
-        x, q, k, v = w.prefill_tensor("x", 0, coords=(seq, pos)), mk("q"), mk("k"), mk("v")
+        T, hq, hkv, d = w.total_tokens, c.n_q_heads, c.n_kv_heads, c.head_dim
+        sizes = [T * hq * d] + [T * hq * d, T * hkv * d, T * hkv * d] * (N - kk)
+        flat = torch.empty(sum(sizes), dtype=torch.int16, device=dev)
+        flat.copy_((torch.arange(flat.numel(), device=dev, dtype=torch.int32) * 40503).to(torch.int16))
+        views, off = [], 0
+        for sz in sizes:
+            views.append(flat[off:off + sz].view(c.torch_dtype))
+            off += sz
+        x = views[0].view(T, hq * d)
+        q = [None] * kk + [views[1 + 3 * i].view(T, hq, d) for i in range(N - kk)]
+        k = [None] * kk + [views[2 + 3 * i].view(T, hkv, d) for i in range(N - kk)]
+        v = [None] * kk + [views[3 + 3 * i].view(T, hkv, d) for i in range(N - kk)]
         launch = lambda: path.compact(x, q, k, v)
     else:
         raise SystemExit(f"bench.py: unknown --single kind {kind!r}")
@@ -306,6 +395,122 @@ def launch_floor_us(dev, launches: int = 200) -> float:
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) * 1e3 / launches
+
+
+def measured_peaks(dev) -> dict:
+    """Ceilings measured in this process with the calibration micro-kernels of libearn_calib.so (plain loops, no
+    attention code): what the published peaks come to on this machine under this power limit."""
+    import ctypes
+    from paper_2507_00715_amd import build as earn_build
+    if not os.path.exists(earn_build.CALIB_LIB):
+        return {"error": "libearn_calib.so not built"}
+    L = ctypes.CDLL(earn_build.CALIB_LIB)
+    vp = ctypes.c_void_p
+    L.earn_calib_sink_floats.restype = ctypes.c_size_t
+    L.earn_calib_mfma.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp]
+    L.earn_calib_mfma_flops.restype = ctypes.c_double
+    L.earn_calib_mfma_flops.argtypes = [ctypes.c_int]
+    L.earn_calib_attention_mix.argtypes = [vp, ctypes.c_int, vp]
+    L.earn_calib_attention_mix_flops.restype = ctypes.c_double
+    L.earn_calib_attention_mix_flops.argtypes = [ctypes.c_int]
+    L.earn_calib_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    L.earn_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    sink = torch.zeros(int(L.earn_calib_sink_floats()), dtype=torch.float32, device=dev)
+    word = torch.zeros(1, dtype=torch.int32, device=dev)
+    nbytes = 1 << 30
+    a = torch.full((nbytes // 4,), 0x01010101, dtype=torch.int32, device=dev)
+    b = torch.empty_like(a)
+    stream = lambda: ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def best_ms(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            rc = fn()
+            e1.record()
+            torch.cuda.synchronize()
+            assert rc == 0
+            best = min(best, e0.elapsed_time(e1))
+        return best
+
+    it_mfma, it_mix = 40000, 6000     # 5-20 ms per launch: long enough for the clock to settle under load
+    out = {"note": "plain loops timed with HIP events in this process; best of 3 launches each"}
+    for label, rnd in (("mfma_bf16_constant_operands_tflops", 0), ("mfma_bf16_random_operands_tflops", 1)):
+        ms = best_ms(lambda: L.earn_calib_mfma(vp(sink.data_ptr()), it_mfma, rnd, stream()))
+        out[label] = L.earn_calib_mfma_flops(it_mfma) / (ms * 1e-3) / 1e12
+    ms = best_ms(lambda: L.earn_calib_attention_mix(vp(sink.data_ptr()), it_mix, stream()))
+    out["attention_tile_mix_random_operands_tflops"] = L.earn_calib_attention_mix_flops(it_mix) / (ms * 1e-3) / 1e12
+    ms = best_ms(lambda: L.earn_calib_read(vp(a.data_ptr()), nbytes, vp(word.data_ptr()), stream()))
+    out["hbm_read_GBps"] = nbytes / (ms * 1e-3) / 1e9
+    ms = best_ms(lambda: L.earn_calib_copy(vp(b.data_ptr()), vp(a.data_ptr()), nbytes, stream()))
+    out["hbm_copy_GBps_read_plus_write"] = 2 * nbytes / (ms * 1e-3) / 1e9
+    del a, b
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline_extras(name: str) -> dict:
+    """The other oracle functions on bounded samples: one decode step of one full-cache layer of the headline workload
+    (the streams of its first sequences), the compaction of its hidden-state stand-in, one full-length prefill layer of
+    the small grouped-query configuration in full, and the whole path of the tiny fp32 configuration."""
+    from oracle import earn_oracle as O
+    from oracle import pipeline as OP
+    out = {}
+    cfg = W.CONFIGS[name]
+    w = W.Workload(cfg)
+    # decode: streams of the first two sequences, full-length cache of layer 0, step G/2
+    seqs = list(range(min(2, cfg.batch)))
+    streams = [u for u in range(w.n_streams) if w.stream_to_seq[u] in seqs]
+    g, G = cfg.decode_steps // 2, cfg.decode_steps
+    sk = W.to_f64(w.prefill_tensor("k", 0, seqs=seqs))
+    sv = W.to_f64(w.prefill_tensor("v", 0, seqs=seqs))
+    lens = [w.seq_lengths[s] for s in seqs]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    dq, dk, dv = (W.to_f64(w.decode_tensor(t, 0, g, streams=streams)) for t in "qkv")
+    gk = np.zeros((len(streams), G, cfg.n_kv_heads, cfg.head_dim))
+    gv = np.zeros_like(gk)
+    t0 = time.perf_counter()
+    O.decode_attn(dq, dk, dv, [w.seq_lengths[w.stream_to_seq[u]] + g for u in streams], sk, sv, cu,
+                  [seqs.index(w.stream_to_seq[u]) for u in streams], gk, gv, [g] * len(streams), rope_base=cfg.rope_base)
+    dt = time.perf_counter() - t0
+    e = cfg.elem_bytes
+    nbytes = 2 * cfg.n_kv_heads * cfg.head_dim * e * (sum(lens) + len(streams) * (g + 1)) + \
+        (2 * cfg.n_q_heads + 4 * cfg.n_kv_heads) * cfg.head_dim * e * len(streams)
+    out["decode_full_cache_layer"] = {"value": nbytes / dt / 1e9, "unit": "GB/s (algorithmic bytes of the sample)", "seconds": dt,
+                                      "sample": f"{name} layer 0, step {g}: the {len(streams)} streams of sequences {seqs}"}
+    # compaction of the hidden-state stand-in (all sequences)
+    x = w.prefill_tensor("x", 0)
+    xb = x.view(torch.uint8).reshape(x.shape[0], -1).numpy()
+    t0 = time.perf_counter()
+    O.compact_registers(xb, np.asarray(w.cu_seqlens, dtype=np.int32), cfg.n_head_reg, cfg.n_tail_reg)
+    dt = time.perf_counter() - t0
+    out["compaction"] = {"value": 2 * cfg.batch * cfg.r * xb.shape[1] / dt / 1e9, "unit": "GB/s", "seconds": dt,
+                         "sample": f"{name}: hidden-state stand-in [{x.shape[0]}, {x.shape[1]}], {cfg.batch * cfg.r} rows kept"}
+    # one full-length layer of small_gqa, in full
+    c2 = W.CONFIGS["small_gqa"]
+    w2 = W.Workload(c2)
+    q2, k2, v2 = (W.to_f64(w2.prefill_tensor(t, 0)) for t in "qkv")
+    t0 = time.perf_counter()
+    O.prefill_attn(q2, k2, v2, w2.cu_seqlens, rope_base=c2.rope_base)
+    dt = time.perf_counter() - t0
+    fl = 4.0 * c2.head_dim * c2.n_q_heads * w2.causal_pairs(False)
+    out["small_gqa_full_layer"] = {"value": fl / dt / 1e12, "unit": "TFLOP/s", "seconds": dt,
+                                   "sample": "small_gqa layer 0, every row of every sequence"}
+    # the whole path of tiny_f32
+    c1 = W.CONFIGS["tiny_f32"]
+    w1 = W.Workload(c1)
+    mk = lambda which: [w1.prefill_tensor(which, l) for l in range(c1.n_layers)]
+    dmk = lambda which: [[w1.decode_tensor(which, l, gg) for l in range(c1.n_layers)] for gg in range(c1.decode_steps)]
+    t0 = time.perf_counter()
+    OP.run(n_layers=c1.n_layers, split_k=c1.split_k, n_head_reg=c1.n_head_reg, n_tail_reg=c1.n_tail_reg,
+           cu_seqlens=w1.cu_seqlens, q=mk("q"), k=mk("k"), v=mk("v"), x=w1.prefill_tensor("x", 0), dq=dmk("q"), dk=dmk("k"),
+           dv=dmk("v"), stream_to_seq=w1.stream_to_seq, rope_base=c1.rope_base)
+    out["tiny_f32_whole_path"] = {"value": (time.perf_counter() - t0) * 1e3, "unit": "ms per step (input draws included)",
+                                  "sample": "tiny_f32: prefill, compaction and 4 decode steps of all 4 layers"}
+    return out
 
 
 def cpu_baseline(name: str, threads: int = 0, rows_target: int = 4096) -> dict:
@@ -381,9 +586,12 @@ def main():
     if cpu is not None:  # the same oracle on one thread, on a sixteenth of the rows
         one = cpu_baseline(args.workload, threads=1, rows_target=256)
         cpu["single_thread"] = {k_: one[k_] for k_ in ("value", "unit", "cores", "seconds", "sample")}
+        cpu["other_oracle_functions"] = cpu_baseline_extras(args.workload)
     floor_us = launch_floor_us(dev)
+    peaks = measured_peaks(dev)
 
     cfg = W.CONFIGS[args.workload]
+    traffic = measured_traffic(args.workload)
     pf = head["prefill_full_layer"]
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
     line = {
@@ -394,12 +602,12 @@ def main():
         "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
-        "config": head["workload"],
+        "config": dict(head["workload"], launch_mode=head["launch_mode"]),
         "roofline": {"kernel": DOMINANT_KERNEL, "bound": "mfma",
                      "achieved": pf["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": pf["tflops"] / peak,
-                     "traffic": (sum(MEASURED_TRAFFIC[args.workload].values())
-                                 if args.workload in MEASURED_TRAFFIC else None),
-                     "traffic_detail": MEASURED_TRAFFIC.get(args.workload),
+                     "traffic": None if traffic is None else traffic["fetch_bytes"] + traffic["write_bytes"],
+                     "traffic_detail": traffic,
+                     "measured_peak": peaks,
                      "algorithmic_bytes": algorithmic_prefill_bytes(args.workload),
                      "ms_per_launch": pf["ms_per_launch"], "flops_per_launch": pf["flops_per_launch"],
                      "executed_tile_flops_per_launch": pf["executed_tile_flops_per_launch"]},
@@ -408,6 +616,7 @@ def main():
         "compaction": head["compaction"],
         "prefill_register_layer": head["prefill_register_layer"],
         "phase_ms_per_step": head["phase_ms_per_step"],
+        "per_layer_launch": head["per_layer_launch"],
         "launch_floor_us": floor_us,
         "last_full_layer_register_rows_only": head["last_full_layer_register_rows_only"],
         "attention_only_vs_vanilla": head["attention_only_vs_vanilla"],

@@ -1,0 +1,178 @@
+// Calibration micro-kernels for the benchmark (libearn_calib.so; NOT part of libearn.so and not on the product path).
+// They measure, on the machine the benchmark runs on, the ceilings that the attention kernels are set against beside
+// the published peaks: the rate of a pure v_mfma_f32_32x32x16_bf16 loop on constant and on random operands (the matrix
+// cores are power-limited: the clock, hence the rate, depends on how many operand bits toggle), the rate of a loop with
+// the instruction mix of one attention tile (matrix products, exponentials, packing, LDS fragment reads; no barriers,
+// no global loads), and the bandwidth of a plain streaming read and a plain copy.
+// Every entry point only launches; the caller times it with events on the stream it passes.  All loops are bounded and
+// all accesses are in bounds by construction (indices are taken modulo the buffer sizes).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kWgs = 1024;        // 4 workgroups per CU
+constexpr int kThreads = 256;     // one wave per SIMD and workgroup
+constexpr int kMfmaPerIter = 16;
+
+__device__ __forceinline__ unsigned mix32(unsigned x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+// bf16 operand words: random mantissas and signs with exponents near 1.0 (values in +-[0.5, 2)), or one constant
+__device__ __forceinline__ bf16x8 operand(unsigned seed, bool random) {
+  u32x4 w;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const unsigned r = mix32(seed * 4u + i);
+    const unsigned lo = 0x3f00u | (r & 0x80ffu), hi = 0x3f00u | ((r >> 16) & 0x80ffu);
+    w[i] = random ? (lo | (hi << 16)) : 0x3f803f80u;
+  }
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+__global__ __launch_bounds__(kThreads) void mfma_loop_kernel(float* __restrict__ sink, int iters, int random) {
+  const unsigned t = blockIdx.x * kThreads + threadIdx.x;
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { a[i] = operand(t * 8 + i, random); b[i] = operand(t * 8 + 4 + i, random); }
+  f32x16 c[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) c[i][j] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < kMfmaPerIter / 4; ++r)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) c[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(i + r) & 3], b[i], c[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s += c[i][j];
+  sink[t] = s;
+}
+
+// One iteration = one 64-key tile of a 32-query wave at head dimension 128: 16 MFMAs for the scores, 32 exponentials,
+// 16 packs, 16 MFMAs for the output, 16 + 32 LDS fragment reads.  Values stay bounded (the scores are re-centred).
+__global__ __launch_bounds__(kThreads) void attention_mix_kernel(float* __restrict__ sink, int iters) {
+  __shared__ u32x4 lds[2048];  // 32 KB of random operand bits
+  for (int i = threadIdx.x; i < 2048; i += kThreads) lds[i] = __builtin_bit_cast(u32x4, operand(blockIdx.x * 2048 + i, true));
+  __syncthreads();
+  const unsigned t = blockIdx.x * kThreads + threadIdx.x;
+  bf16x8 q[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) q[i] = operand(t * 8 + i, true);
+  f32x16 o[4], s[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) o[i][j] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+    const int base = (it * 64 + threadIdx.x) & 1023;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) s[kb][j] = -40.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, lds[(base + 64 * (kb * 8 + ks)) & 2047]), q[ks], s[kb], 0, 0, 0);
+    }
+    u32x4 w[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int r = 8 * (kk & 1) + 2 * j;
+        f32x2 e = {__builtin_amdgcn_exp2f(s[kk >> 1][r] * 0.01f), __builtin_amdgcn_exp2f(s[kk >> 1][r + 1] * 0.01f)};
+        w[kk][j] = __builtin_bit_cast(unsigned, __builtin_convertvector(e, bf16x2));
+      }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const u32x4 v = lds[(base + 1024 + 64 * (kk * 4 + db)) & 2047];  // two 8-byte transposing reads in the kernels
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v), __builtin_bit_cast(bf16x8, w[kk]), o[db], 0, 0, 0);
+      }
+    if ((it & 63) == 63) {  // keep the accumulators finite without touching the steady state
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o[i][j] *= 0x1p-20f;
+    }
+  }
+  float r = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) r += o[i][j];
+  sink[t] = r;
+}
+
+constexpr int kUnroll = 8;
+__global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src, unsigned* __restrict__ sink, size_t n) {
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  const size_t stride = (size_t)gridDim.x * 256 * kUnroll;
+  for (size_t base = (size_t)blockIdx.x * 256 * kUnroll + threadIdx.x; base < n; base += stride) {
+    u32x4 v[kUnroll];
+#pragma unroll
+    for (int i = 0; i < kUnroll; ++i) v[i] = base + i * 256 < n ? __builtin_nontemporal_load(src + base + i * 256) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < kUnroll; ++i) acc ^= v[i];
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345679u) sink[0] = 1u;
+}
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n) {
+  constexpr int U = 4;
+  const size_t stride = (size_t)gridDim.x * 256 * U;
+  for (size_t base = (size_t)blockIdx.x * 256 * U + threadIdx.x; base < n; base += stride) {
+    u32x4 v[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) if (base + i * 256 < n) v[i] = __builtin_nontemporal_load(src + base + i * 256);
+#pragma unroll
+    for (int i = 0; i < U; ++i) if (base + i * 256 < n) __builtin_nontemporal_store(v[i], dst + base + i * 256);
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+// floats the sink of the two arithmetic loops must hold
+size_t earn_calib_sink_floats(void) { return (size_t)kWgs * kThreads; }
+// pure MFMA loop; FLOPs of one launch = earn_calib_mfma_flops(iters)
+int earn_calib_mfma(float* sink, int iters, int random_operands, void* stream) {
+  if (!sink || iters <= 0 || iters > (1 << 20)) return -1;
+  hipLaunchKernelGGL(mfma_loop_kernel, dim3(kWgs), dim3(kThreads), 0, (hipStream_t)stream, sink, iters, random_operands);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+double earn_calib_mfma_flops(int iters) { return (double)kWgs * (kThreads / 64) * iters * kMfmaPerIter * 2.0 * 32 * 32 * 16; }
+// attention-tile instruction mix; matrix-core FLOPs of one launch = earn_calib_attention_mix_flops(iters)
+int earn_calib_attention_mix(float* sink, int iters, void* stream) {
+  if (!sink || iters <= 0 || iters > (1 << 20)) return -1;
+  hipLaunchKernelGGL(attention_mix_kernel, dim3(kWgs), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+double earn_calib_attention_mix_flops(int iters) { return (double)kWgs * (kThreads / 64) * iters * 32 * 2.0 * 32 * 32 * 16; }
+// streaming read of `bytes` (multiple of 16) from src; sink: one device word
+int earn_calib_read(const void* src, size_t bytes, unsigned* sink, void* stream) {
+  if (!src || !sink || bytes % 16) return -1;
+  hipLaunchKernelGGL(read_kernel, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const u32x4*)src, sink, bytes / 16);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+// copy of `bytes` (multiple of 16) from src to dst (non-overlapping)
+int earn_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!src || !dst || bytes % 16) return -1;
+  hipLaunchKernelGGL(copy_kernel, dim3(8192), dim3(256), 0, (hipStream_t)stream, (const u32x4*)src, (u32x4*)dst, bytes / 16);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+}  // extern "C"

@@ -1041,10 +1041,12 @@ static DecodePlan plan_decode(int dtype, int hq, int hkv, int n_streams, int bat
   // several query rows per cache (grouped heads or beams) make the shared part a matrix product
   // (short caches are launch-latency bound: the single-launch vector kernel wins there)
   const int mfma_min = tuning(kTuneDecMfmaMinLen, 128);
-  // ... unless all its workgroups (one per CU: they hold most of the LDS) fit on the GPU at once
+  // ... unless all its workgroups (one per CU: they hold most of the LDS) fit on the GPU at once, or beams share the
+  // caches (measured on 28 layers of 64-row caches in one launch: 10 beams x 4 grouped heads per cache, 194 us against
+  // 372 us for the vector kernel, which reads a cache once per beam; 7 grouped heads without beams, 37 against 23 us)
   const int mfma_wgs = tuning(kTuneDecMfmaShortWgs, 256);
   pl.mfma = dtype == EARN_BF16 && (gq > 1 || n_streams > batch) &&
-            (max_shared_len >= mfma_min || (long long)hkv * batch <= mfma_wgs);
+            (max_shared_len >= mfma_min || (long long)hkv * batch * n_layers <= mfma_wgs || n_streams >= 2 * batch);
   pl.n_pass = 1;
   if (pl.mfma) {
     // Beams beyond 64 query rows per cache (say 20 beams of 7 grouped heads) would make a workgroup walk its keys once
