@@ -152,9 +152,9 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
     q, k, v, v_full, x, dq, dk, dv = build_inputs(w, dev)
     path = EarnPath(n_layers=c.n_layers, split_k=c.split_k, n_head_reg=c.n_head_reg, n_tail_reg=c.n_tail_reg,
                     n_q_heads=c.n_q_heads, n_kv_heads=c.n_kv_heads, head_dim=c.head_dim, dtype=c.torch_dtype,
-                    cu_seqlens=w.cu_seqlens, stream_to_seq=w.stream_to_seq, gen_cap=c.decode_steps,
+                    cu_seqlens=w.cu_seqlens, stream_to_seq=w.stream_to_seq, gen_cap=max(c.decode_steps, 1),
                     rope_base=c.rope_base, device=dev)
-    N, kk, G = c.n_layers, c.split_k, c.decode_steps
+    N, kk, G = c.n_layers, c.split_k, c.decode_steps       # G = 0: a prefill-only workload
 
     # The launch-bound phases replay the same buffers every step: their calls are marshalled once (the caches of the
     # first k layers are the caller's V tensors, known here; everything else is pre-allocated inside the path).
@@ -229,19 +229,51 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
     e1.record()
     torch.cuda.synchronize()
     vanilla_prefill_ms = e0.elapsed_time(e1)
-    steps_pos[G // 2]()
-    e0.record()
-    for l in range(N):
-        dec[G // 2][l % kk]()
-    e1.record()
-    torch.cuda.synchronize()
-    vanilla_decode_ms = e0.elapsed_time(e1)
+    vanilla_decode_ms = None
+    if G > 0:
+        steps_pos[G // 2]()
+        e0.record()
+        for l in range(N):
+            dec[G // 2][l % kk]()
+        e1.record()
+        torch.cuda.synchronize()
+        vanilla_decode_ms = e0.elapsed_time(e1)
+
+    # Attention-score statistics (Sparsity, Sink_head, Sink_tail of the paper's appendix) of the register rows, and of
+    # the last row of every sequence alone, over the cache of layer k-1.
+    from paper_2507_00715_amd import binding as B
+    stats = {}
+    if kk > 0:
+        l = kk - 1
+        q_rows = torch.empty(path.Tc, c.n_q_heads, c.head_dim, dtype=c.torch_dtype, device=dev)
+        B.earn_compact_registers([q[l]], [q_rows], path.cu, path.batch, path.h, path.t, path.idx, path.pos, path.cu_c)
+        last_pos = torch.tensor([n - 1 for n in w.seq_lengths], dtype=torch.int32, device=dev)
+        last_q = q[l][torch.tensor([w.cu_seqlens[s + 1] - 1 for s in range(c.batch)], device=dev)].contiguous()
+        for label, rows, qr, pos_t, top in (("register_rows", path.r, q_rows, path.pos, None),
+                                           ("last_row", 1, last_q, last_pos, None)):
+            out = torch.empty(c.batch * rows, c.n_q_heads, 3, dtype=torch.float32, device=dev)
+            call = lambda: B.earn_attn_stats(path.desc, qr, path.k_cache[l], path.cu, pos_t, c.batch, rows, out)
+            call()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(5):
+                call()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 5
+            # every key a row can see, once per (sequence, kv head): the longest row of the sequence
+            pmax = pos_t.view(c.batch, rows).max(dim=1).values.cpu().tolist()
+            nbytes = sum(p_ + 1 for p_ in pmax) * c.n_kv_heads * c.head_dim * c.elem_bytes + qr.numel() * c.elem_bytes + out.numel() * 4
+            mean = out.mean(dim=(0, 1)).cpu().tolist()
+            stats[label] = {"us": us, "algorithmic_bytes": nbytes, "GBps": nbytes / us / 1e3,
+                            "frac_of_hbm_peak": nbytes / us / 1e3 / PEAK_HBM_GBPS,
+                            "mean_sparsity_sink_head_sink_tail": mean}
+        del q_rows, last_q
 
     # Beyond the paper's method, exact: layer k-1 evaluated at the register rows only (its other outputs are dropped by
     # the compaction).  Timed on its own, gather of the query rows included; the timed steps above do not use it.
     rows_only = None
     if 0 < kk < N:
-        from paper_2507_00715_amd import binding as B
         l = kk - 1
         q_rows = torch.empty(path.Tc, c.n_q_heads, c.head_dim, dtype=c.torch_dtype, device=dev)
         out_rows = torch.empty_like(q_rows)
@@ -272,10 +304,19 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
         prefill_flops = kk * alg["flops_full"] + (N - kk) * alg["flops_reg"]
         prefill_tflops = prefill_flops * steps / ((ms["prefill_full"] + ms["prefill_reg"]) * 1e-3) / 1e12
         full_tflops = alg["flops_full"] / (full_ms * 1e-3) / 1e12
-        dec_ms_total = ms["decode_full"] + ms["decode_reg"]
-        dec_gbps = sum(dec_bytes_step) * steps / (dec_ms_total * 1e-3) / 1e9
-        dec_full_gbps = kk * sum(alg["dec_full"]) * steps / (ms["decode_full"] * 1e-3) / 1e9
-        dec_reg_gbps = (N - kk) * sum(alg["dec_reg"]) * steps / (ms["decode_reg"] * 1e-3) / 1e9
+        decode = None
+        if G > 0:
+            dec_ms_total = ms["decode_full"] + ms["decode_reg"]
+            dec_gbps = sum(dec_bytes_step) * steps / (dec_ms_total * 1e-3) / 1e9
+            dec_full_gbps = kk * sum(alg["dec_full"]) * steps / (ms["decode_full"] * 1e-3) / 1e9
+            dec_reg_gbps = (N - kk) * sum(alg["dec_reg"]) * steps / (ms["decode_reg"] * 1e-3) / 1e9
+            decode = {"us_per_step": dec_ms_total * 1e3 / (steps * G), "bytes_first_step": dec_bytes_step[0],
+                      "bytes_last_step": dec_bytes_step[-1], "GBps": dec_gbps,
+                      "frac_of_hbm_peak": dec_gbps / PEAK_HBM_GBPS,
+                      "full_cache_layers": {"us_per_layer": ms["decode_full"] * 1e3 / (steps * G * kk),
+                                            "GBps": dec_full_gbps, "frac_of_hbm_peak": dec_full_gbps / PEAK_HBM_GBPS},
+                      "register_cache_layers": {"us_per_layer": ms["decode_reg"] * 1e3 / (steps * G * max(N - kk, 1)),
+                                                "GBps": dec_reg_gbps, "frac_of_hbm_peak": dec_reg_gbps / PEAK_HBM_GBPS}}
         comp_us = ms["compact"] * 1e3 / steps
         comp_gbps = alg["compaction"] / (comp_us * 1e-6) / 1e9
         return {
@@ -287,13 +328,7 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
             "prefill_register_layer": {"us_per_layer": reg_ms * 1e3, "flops_per_layer": alg["flops_reg"]},
             "compaction": {"us": comp_us, "bytes": alg["compaction"], "GBps": comp_gbps,
                            "frac_of_hbm_peak": comp_gbps / PEAK_HBM_GBPS},
-            "decode": {"us_per_step": dec_ms_total * 1e3 / (steps * G), "bytes_first_step": dec_bytes_step[0],
-                       "bytes_last_step": dec_bytes_step[-1], "GBps": dec_gbps,
-                       "frac_of_hbm_peak": dec_gbps / PEAK_HBM_GBPS,
-                       "full_cache_layers": {"us_per_layer": ms["decode_full"] * 1e3 / (steps * G * kk),
-                                             "GBps": dec_full_gbps, "frac_of_hbm_peak": dec_full_gbps / PEAK_HBM_GBPS},
-                       "register_cache_layers": {"us_per_layer": ms["decode_reg"] * 1e3 / (steps * G * max(N - kk, 1)),
-                                                 "GBps": dec_reg_gbps, "frac_of_hbm_peak": dec_reg_gbps / PEAK_HBM_GBPS}},
+            "decode": decode,
             "phase_ms_per_step": {k_: v_ / steps for k_, v_ in ms.items()},
         }
 
@@ -312,12 +347,13 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
     # same N layers run the vanilla way (measured above), next to the closed forms of Section 3.3 (k/N for attention
     # work, (k n + (N-k) r)/(N n) for cache entries).
     earn_prefill_ms = (ms["prefill_full"] + ms["compact"] + ms["prefill_reg"]) / steps
-    earn_decode_ms = (ms["decode_full"] + ms["decode_reg"]) / (steps * G)
+    earn_decode_ms = (ms["decode_full"] + ms["decode_reg"]) / (steps * G) if G > 0 else None
+    res["attention_statistics"] = stats
     res["attention_only_vs_vanilla"] = {
         "vanilla_prefill_ms": vanilla_prefill_ms, "earn_prefill_ms": earn_prefill_ms,
         "prefill_speedup": vanilla_prefill_ms / earn_prefill_ms,
         "vanilla_decode_step_ms": vanilla_decode_ms, "earn_decode_step_ms": earn_decode_ms,
-        "decode_speedup": vanilla_decode_ms / earn_decode_ms,
+        "decode_speedup": vanilla_decode_ms / earn_decode_ms if G > 0 else None,
         "closed_form_attention_ratio": kk / N,
         "closed_form_cache_ratio": sum(kk * n + (N - kk) * c.r for n in w.seq_lengths) / float(N * sum(w.seq_lengths)),
         "note": "vanilla = N full-length prefill launches / N full-cache decode launches (one launch per layer), "
@@ -556,7 +592,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default=HEADLINE, choices=W.CONFIG_ORDER)
-    ap.add_argument("--others", default="tiny_f32,small_gqa,mid_mha,serving",
+    ap.add_argument("--others", default="tiny_f32,small_gqa,mid_mha,serving,hstu_prefill",
                     help="comma-separated workloads also measured and reported under 'other_workloads' ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--single", default="", choices=["", "prefill_full", "decode_full", "compact"],
@@ -617,6 +653,7 @@ def main():
         "prefill_register_layer": head["prefill_register_layer"],
         "phase_ms_per_step": head["phase_ms_per_step"],
         "per_layer_launch": head["per_layer_launch"],
+        "attention_statistics": head["attention_statistics"],
         "launch_floor_us": floor_us,
         "last_full_layer_register_rows_only": head["last_full_layer_register_rows_only"],
         "attention_only_vs_vanilla": head["attention_only_vs_vanilla"],

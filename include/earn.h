@@ -294,6 +294,67 @@ size_t earn_prefill_register_rows_workspace_bytes(const earn_attn_desc* desc, in
                                                   int32_t rows_per_seq);
 
 /*
+ * Beam search around the decode step (paper Appendix, implementation details: inference decodes with beam search, beam
+ * size 20).  The attention path has no logits; these calls take the per-beam token log-probabilities from the caller.
+ *
+ * earn_beam_topk: for every sequence b (beams live beams, streams b*beams .. b*beams + beams - 1) keeps the `beams` best of
+ * the beams * vocab candidates  beam_scores[b*beams + w] + token_logprobs[b*beams + w][t]  (fp32 sum), best first, equal
+ * scores in order of the candidate index w * vocab + t; NaN candidates never win.
+ *   beam_scores    device, [batch*beams] fp32, or NULL (all zero)
+ *   token_logprobs device, [batch*beams, vocab] fp32
+ *   parent_out     device, [batch*beams] int32: STREAM index (b*beams + w) of each kept candidate's parent beam
+ *   token_out      device, [batch*beams] int32;  score_out  device, [batch*beams] fp32
+ *   (-1, -1, -inf for picks beyond the number of candidates)
+ *   workspace      at least earn_beam_topk_workspace_bytes(batch, beams, vocab) bytes (0 when beams * vocab <= 8192)
+ * Errors: NULL pointer, non-positive size -> INVALID_ARG; beams > 64 or beams * vocab beyond 3.3e6 -> UNSUPPORTED.
+ *
+ * earn_beam_reorder: the ancestor table after a beam step at decode step `step` (the step whose rows were just appended).
+ * gen_src[u][g] names the physical stream whose cache slot g holds row g of stream u's generated history; the decode
+ * entry point reads generated rows through it (earn_decode_attn_beams), so a beam step moves n_streams * step integers,
+ * shared by all layers, instead of copying n_streams * step K/V rows in every layer.
+ *   gen_src_out[u][g] = gen_src_in[parent[u]][g] for g < step (parent[u] itself when gen_src_in is NULL),
+ *                       parent[u] for g == step, u for g > step.
+ *   parent device [n_streams]; gen_src_in device [n_streams, gen_cap] or NULL (identity); gen_src_out device
+ *   [n_streams, gen_cap], must not alias gen_src_in.
+ * Errors: NULL parent / gen_src_out, aliasing, n_streams <= 0, gen_cap <= 0, step outside [0, gen_cap) -> INVALID_ARG.
+ *
+ * earn_decode_attn_beams: earn_decode_attn with the ancestor table: row g < gen_len[u] of stream u's generated cache is
+ * read from slot (gen_src[u][g], g) of gen_k / gen_v; the new row is still appended at (u, gen_len[u]).
+ * gen_src NULL = earn_decode_attn.
+ */
+int earn_beam_topk(const float* beam_scores, const float* token_logprobs, int32_t batch, int32_t beams, int32_t vocab,
+                   int32_t* parent_out, int32_t* token_out, float* score_out, void* workspace, size_t workspace_bytes,
+                   void* stream);
+size_t earn_beam_topk_workspace_bytes(int32_t batch, int32_t beams, int32_t vocab);
+int earn_beam_reorder(const int32_t* parent, const int32_t* gen_src_in, int32_t* gen_src_out, int32_t n_streams,
+                      int32_t gen_cap, int32_t step, void* stream);
+int earn_decode_attn_beams(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
+                           const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
+                           const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len,
+                           const int32_t* gen_src, int32_t gen_cap, int32_t n_streams, int32_t batch,
+                           int32_t max_shared_len, void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Attention-score statistics of chosen query rows (paper Appendix, "Quantitative Measurements of Attention Score
+ * Distributions"): for the causal softmax row p_1 .. p_n of a query row (Eq. 3; n = the row's token index + 1)
+ *   stats[0] = Sparsity  = (1/n) * #{ j : p_j > epsilon }        (the paper sets epsilon = 0.05)
+ *   stats[1] = Sink_head = sum_{j = 1}^{t_head} p_j              (t_head = 3)
+ *   stats[2] = Sink_tail = sum_{j = n - tail_back}^{n} p_j       (tail_back = 3, i.e. T_t = n - 3: the last FOUR keys)
+ * (rows shorter than a window sum what exists).  The rows are given as in earn_prefill_register_rows: r rows per
+ * sequence, row m of sequence s being token row_pos[s*r + m] of the sequence, un-rotated queries; the keys are the
+ * layer's cache (ROTATED keys, k_rot_out of the prefill).  The probabilities are recomputed in fp32.
+ *
+ *   q_rows     device, [batch*r, Hq, d], un-rotated      k_rot      device, [total_tokens, Hkv, d], rotated
+ *   cu_seqlens device, [batch+1]                         row_pos    device, [batch*r], each inside its sequence
+ *   stats_out  device, [batch*r, Hq, 3] fp32
+ * Errors: NULL pointer, batch <= 0, rows_per_seq <= 0, epsilon < 0, t_head < 0, tail_back < 0 -> INVALID_ARG; desc as
+ * for earn_prefill_attn.  Enqueues on `stream`, allocates nothing.
+ */
+int earn_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const int32_t* cu_seqlens,
+                    const int32_t* row_pos, int32_t batch, int32_t rows_per_seq, float epsilon, int32_t t_head,
+                    int32_t tail_back, float* stats_out, void* stream);
+
+/*
  * KV-cache entries per attention head one sequence holds under EARN (paper Section 3.3, "KV Cache Size":
  * N_KV = n_h (k L + (N-k) r), here per head and with L = the length the first k layers see, plus `gen`
  * generated tokens kept by every layer).  Used for allocation and as an invariant.

@@ -290,3 +290,108 @@ double oracle_causal_attn_flops(const int32_t *lengths, int32_t batch, int32_t h
     for (int s = 0; s < batch; ++s) pairs += 0.5 * (double)lengths[s] * ((double)lengths[s] + 1.0);
     return 4.0 * (double)d * (double)hq * pairs;
 }
+
+/*
+ * Attention-score statistics of chosen query rows (Appendix, "Quantitative Measurements of Attention Score
+ * Distributions").  For the causal softmax row p_1..p_n of query row i (n = i + 1 visible keys, Eq. 3):
+ *   Sparsity  = (1/n) * #{ j : p_j > epsilon }                      (epsilon = 0.05 in the paper)
+ *   Sink_head = sum_{j = 1}^{T_h} p_j                               (T_h = 3)
+ *   Sink_tail = sum_{j = T_t}^{n} p_j, T_t = n - tail_back          (tail_back = 3: the LAST FOUR keys, as printed)
+ * Rows shorter than the windows sum what exists.  The probabilities are materialised exactly as in
+ * oracle_prefill_attn (rotation at the original positions, scale, one softmax row at a time).
+ *   q [T,Hq,d], k [T,Hkv,d] (un-rotated), rows: row_sel [T] != 0.  stats_out [T,Hq,3], rows not selected untouched.
+ */
+int oracle_attn_stats(const double *q, const double *k, const int32_t *cu_seqlens, const int32_t *positions,
+                      int32_t batch, int32_t hq, int32_t hkv, int32_t d, const int32_t *q_to_kv, double scale,
+                      double rope_base, const uint8_t *row_sel, double epsilon, int32_t t_head, int32_t tail_back,
+                      double *stats_out)
+{
+    if (!q || !k || !cu_seqlens || !stats_out || batch <= 0 || t_head < 0 || tail_back < 0) return ORC_BAD_ARG;
+    int rc = check_heads(hq, hkv, d, q_to_kv);
+    if (rc) return rc;
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)d);
+    int err = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int s = 0; s < batch; ++s)
+        for (int a = 0; a < hq; ++a) {
+            int64_t b0 = cu_seqlens[s], n = cu_seqlens[s + 1] - b0;
+            if (n <= 0) continue;
+            int c = kv_head_of(a, hq, hkv, q_to_kv);
+            double *sc = (double *)malloc(sizeof(double) * (size_t)n * 2);
+            double *qr = (double *)malloc(sizeof(double) * (size_t)d * 2);
+            if (!sc || !qr) { err = 1; free(sc); free(qr); continue; }
+            double *pr = sc + n, *kr = qr + d;
+            for (int64_t i = 0; i < n; ++i) {
+                int64_t gi = b0 + i;
+                if (row_sel && !row_sel[gi]) continue;
+                double p = positions ? (double)positions[gi] : (double)i;
+                rope_vec(q + (gi * hq + a) * d, d, p, rope_base, qr);
+                for (int64_t j = 0; j <= i; ++j) {
+                    double pj = positions ? (double)positions[b0 + j] : (double)j;
+                    rope_vec(k + ((b0 + j) * hkv + c) * d, d, pj, rope_base, kr);
+                    double acc = 0.0;
+                    for (int e = 0; e < d; ++e) acc += qr[e] * kr[e];
+                    sc[j] = acc * scale;
+                }
+                softmax_row(sc, i + 1, pr);
+                int64_t m = i + 1, count = 0;
+                double head = 0.0, tail = 0.0;
+                for (int64_t j = 1; j <= m; ++j) { /* 1-based, as the paper writes the sums */
+                    double pj = pr[j - 1];
+                    if (pj > epsilon) ++count;
+                    if (j <= t_head) head += pj;
+                    if (j >= m - tail_back) tail += pj;
+                }
+                double *o = stats_out + (gi * hq + a) * 3;
+                o[0] = (double)count / (double)m;
+                o[1] = head;
+                o[2] = tail;
+            }
+            free(sc);
+            free(qr);
+        }
+    return err ? ORC_NO_MEM : ORC_OK;
+}
+
+/*
+ * One selection step of beam search (the paper decodes with beam search, beam size 20: Appendix, implementation
+ * details).  For every sequence b with `beams` live beams and `vocab` tokens, candidate (w, t) scores
+ * beam_scores[b, w] + token_logprobs[b, w, t]; the `beams` best candidates are kept, best first, equal scores in order
+ * of the candidate index w * vocab + t.  The sum is taken in fp32 (the inputs' precision: the comparison that decides
+ * an index must see the same numbers on every implementation).  A NaN candidate never wins.
+ *   parent_out[b, r] = b * beams + w of pick r (a stream index), token_out[b, r] = t, score_out[b, r] = the score;
+ *   -1 / -1 / -inf when a sequence has fewer candidates than beams.
+ * Written as the definition: `beams` rounds, each taking the best candidate not taken before.
+ */
+int oracle_beam_topk(const float *beam_scores, const float *token_logprobs, int32_t batch, int32_t beams, int32_t vocab,
+                     int32_t *parent_out, int32_t *token_out, float *score_out)
+{
+    if (!token_logprobs || !parent_out || !token_out || !score_out || batch <= 0 || beams <= 0 || vocab <= 0)
+        return ORC_BAD_ARG;
+    int64_t n = (int64_t)beams * vocab;
+    uint8_t *taken = (uint8_t *)malloc((size_t)n);
+    float *cand = (float *)malloc(sizeof(float) * (size_t)n);
+    if (!taken || !cand) { free(taken); free(cand); return ORC_NO_MEM; }
+    for (int b = 0; b < batch; ++b) {
+        for (int64_t c = 0; c < n; ++c) {
+            float bs = beam_scores ? beam_scores[(int64_t)b * beams + c / vocab] : 0.0f;
+            volatile float sum = token_logprobs[(int64_t)b * n + c] + bs; /* rounded to fp32 */
+            cand[c] = sum == sum ? sum : -INFINITY;
+            taken[c] = 0;
+        }
+        for (int r = 0; r < beams; ++r) {
+            int64_t best = -1;
+            for (int64_t c = 0; c < n; ++c)
+                if (!taken[c] && (best < 0 || cand[c] > cand[best])) best = c; /* first of equals: lowest index */
+            int64_t o = (int64_t)b * beams + r;
+            if (best < 0) { parent_out[o] = -1; token_out[o] = -1; score_out[o] = -INFINITY; continue; }
+            taken[best] = 1;
+            parent_out[o] = (int32_t)(b * beams + best / vocab);
+            token_out[o] = (int32_t)(best % vocab);
+            score_out[o] = cand[best];
+        }
+    }
+    free(taken);
+    free(cand);
+    return ORC_OK;
+}

@@ -170,6 +170,49 @@ def decode_attn(q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to
     return {"out": out, "lse": lse, "rowsum": rowsum}
 
 
+def attn_stats(q, k, cu_seqlens, positions=None, q_to_kv=None, scale: float = 0.0, rope_base: float = 10000.0,
+               row_sel=None, epsilon: float = 0.05, t_head: int = 3, tail_back: int = 3) -> np.ndarray:
+    """Sparsity, Sink_head, Sink_tail of the causal softmax rows: [T, Hq, 3] (NaN at rows not selected)."""
+    q, k = _f64(q), _f64(k)
+    cu = _i32(cu_seqlens)
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    assert k.shape == (T, hkv, d) and cu[-1] == T
+    sel = None if row_sel is None else np.ascontiguousarray(np.asarray(row_sel, dtype=np.uint8))
+    out = np.full((T, hq, 3), np.nan)
+    fn = lib().oracle_attn_stats
+    fn.restype = ctypes.c_int
+    rc = fn(_d(q), _d(k), _i(cu), _i(_i32(positions)), len(cu) - 1, hq, hkv, d, _i(_i32(q_to_kv)),
+            ctypes.c_double(scale), ctypes.c_double(rope_base), None if sel is None else sel.ctypes.data_as(c_bp),
+            ctypes.c_double(epsilon), t_head, tail_back, _d(out))
+    _check(rc, "attn_stats")
+    return out
+
+
+def beam_topk(beam_scores, token_logprobs, batch: int, beams: int, vocab: int) -> dict:
+    """One beam-search selection step: dict(parent [batch*beams] stream index, token, score), best first per sequence."""
+    lp = np.ascontiguousarray(np.asarray(token_logprobs, dtype=np.float32)).reshape(batch * beams, vocab)
+    bs = None if beam_scores is None else np.ascontiguousarray(np.asarray(beam_scores, dtype=np.float32))
+    parent = np.empty(batch * beams, dtype=np.int32)
+    token = np.empty(batch * beams, dtype=np.int32)
+    score = np.empty(batch * beams, dtype=np.float32)
+    c_fp = ctypes.POINTER(ctypes.c_float)
+    fn = lib().oracle_beam_topk
+    fn.restype = ctypes.c_int
+    rc = fn(None if bs is None else bs.ctypes.data_as(c_fp), lp.ctypes.data_as(c_fp), batch, beams, vocab, _i(parent),
+            _i(token), score.ctypes.data_as(c_fp))
+    _check(rc, "beam_topk")
+    return {"parent": parent, "token": token, "score": score}
+
+
+def beam_reorder_caches(parent, gen_k: np.ndarray, gen_v: np.ndarray) -> None:
+    """Beam search by the plain definition: new stream u continues its parent's history, so it takes a COPY of the
+    parent's generated cache (in place on gen_k / gen_v [S, gen_cap, Hkv, d])."""
+    parent = np.asarray(parent, dtype=np.int64)
+    gen_k[...] = gen_k[parent].copy()
+    gen_v[...] = gen_v[parent].copy()
+
+
 def cache_entries(n_layers: int, split_k: int, n: int, r: int, gen: int = 0) -> int:
     return int(lib().oracle_cache_entries(n_layers, split_k, n, r, gen))
 

@@ -27,7 +27,8 @@ EXPORTS = ["earn_last_error", "earn_version", "earn_prefill_attn", "earn_prefill
            "earn_compact_registers", "earn_decode_attn", "earn_decode_workspace_bytes", "earn_cache_entries",
            "earn_prefill_register_rows", "earn_prefill_register_rows_workspace_bytes", "earn_set_validation",
            "earn_set_tuning", "earn_decode_attn_static", "earn_prefill_attn_layers", "earn_decode_attn_layers",
-           "earn_decode_layers_workspace_bytes", "earn_decode_step_positions"]
+           "earn_decode_layers_workspace_bytes", "earn_decode_step_positions", "earn_attn_stats", "earn_beam_topk", "earn_beam_topk_workspace_bytes",
+           "earn_beam_reorder", "earn_decode_attn_beams"]
 EARN_STATIC_SCRATCH_BYTES = 8 << 20
 
 
@@ -77,6 +78,17 @@ def lib():
         L.earn_decode_layers_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), i32, i32, i32, i32, i32]
         L.earn_decode_step_positions.restype = ctypes.c_int
         L.earn_decode_step_positions.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+        L.earn_attn_stats.restype = ctypes.c_int
+        L.earn_attn_stats.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, i32, ctypes.c_float, i32, i32, vp, vp]
+        L.earn_beam_topk.restype = ctypes.c_int
+        L.earn_beam_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.earn_beam_topk_workspace_bytes.restype = sz
+        L.earn_beam_topk_workspace_bytes.argtypes = [i32, i32, i32]
+        L.earn_beam_reorder.restype = ctypes.c_int
+        L.earn_beam_reorder.argtypes = [vp, vp, vp, i32, i32, i32, vp]
+        L.earn_decode_attn_beams.restype = ctypes.c_int
+        L.earn_decode_attn_beams.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                             i32, i32, i32, vp, vp, sz, vp]
         L.earn_prefill_register_rows.restype = ctypes.c_int
         L.earn_prefill_register_rows.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp,
                                                  vp, sz, vp]
@@ -252,6 +264,40 @@ def bind_decode_step_positions(cu_seqlens, stream_to_seq, n_streams: int, batch:
                                gen_len) -> "BoundCall":
     args = (_ptr(cu_seqlens), _ptr(stream_to_seq), n_streams, batch, step, _ptr(q_pos), _ptr(gen_len))
     return BoundCall(lib().earn_decode_step_positions, args, (cu_seqlens, stream_to_seq, q_pos, gen_len))
+
+
+def earn_attn_stats(desc: AttnDesc, q_rows, k_rot, cu_seqlens, row_pos, batch: int, rows_per_seq: int, stats_out,
+                    epsilon: float = 0.05, t_head: int = 3, tail_back: int = 3) -> None:
+    _check(lib().earn_attn_stats(ctypes.byref(desc), _ptr(q_rows), _ptr(k_rot), _ptr(cu_seqlens), _ptr(row_pos), batch,
+                                 rows_per_seq, epsilon, t_head, tail_back, _ptr(stats_out), _stream()))
+
+
+def earn_beam_topk_workspace_bytes(batch: int, beams: int, vocab: int) -> int:
+    return int(lib().earn_beam_topk_workspace_bytes(batch, beams, vocab))
+
+
+def earn_beam_topk(beam_scores, token_logprobs, batch: int, beams: int, vocab: int, parent_out, token_out, score_out,
+                   workspace=None) -> None:
+    if workspace is None:
+        need = earn_beam_topk_workspace_bytes(batch, beams, vocab)
+        workspace = torch.empty(need, dtype=torch.uint8, device=token_logprobs.device) if need else None
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().earn_beam_topk(_ptr(beam_scores), _ptr(token_logprobs), batch, beams, vocab, _ptr(parent_out),
+                                _ptr(token_out), _ptr(score_out), _ptr(workspace), ws_bytes, _stream()))
+
+
+def earn_beam_reorder(parent, gen_src_in, gen_src_out, n_streams: int, gen_cap: int, step: int) -> None:
+    _check(lib().earn_beam_reorder(_ptr(parent), _ptr(gen_src_in), _ptr(gen_src_out), n_streams, gen_cap, step, _stream()))
+
+
+def earn_decode_attn_beams(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k,
+                           gen_v, gen_len, gen_src, gen_cap: int, n_streams: int, batch: int, max_shared_len: int, out,
+                           workspace=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().earn_decode_attn_beams(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos),
+                                        _ptr(shared_k), _ptr(shared_v), _ptr(shared_cu), _ptr(stream_to_seq), _ptr(gen_k),
+                                        _ptr(gen_v), _ptr(gen_len), _ptr(gen_src), gen_cap, n_streams, batch,
+                                        max_shared_len, _ptr(out), _ptr(workspace), ws_bytes, _stream()))
 
 
 def _layer_stride(t: Optional[torch.Tensor]) -> int:

@@ -54,7 +54,13 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
                   const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                   const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
                   int n_streams, int batch, int max_shared_len, void* out, void* workspace, size_t workspace_bytes,
-                  hipStream_t stream, const DecodeLayers* layers);
+                  hipStream_t stream, const DecodeLayers* layers, const int32_t* gen_src);
+size_t beam_topk_workspace_bytes(int batch, int beams, int vocab);
+int launch_beam_topk(const float* beam_scores, const float* logp, int batch, int beams, int vocab, int32_t* parent,
+                     int32_t* token, float* score, void* workspace, hipStream_t stream);
+int launch_beam_reorder(const int32_t* parent, const int32_t* src_in, int32_t* src_out, int n_streams, int gen_cap, int step,
+                        hipStream_t stream);
+int beam_topk_limits(int beams, int vocab, const char** why);
 size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, int batch, int max_shared_len,
                               int gen_cap, int n_layers);
 int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
@@ -63,6 +69,9 @@ int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* 
                          int n_streams, int batch, int max_shared_len, void* out, hipStream_t stream);
 int launch_step_positions(const int32_t* cu, const int32_t* stream_to_seq, int n_streams, int batch, int step,
                           int32_t* q_pos, int32_t* gen_len, hipStream_t stream);
+int launch_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const int32_t* cu_seqlens,
+                      const int32_t* row_pos, int batch, int rows_per_seq, float epsilon, int t_head, int tail_back,
+                      float* stats_out, hipStream_t stream);
 int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, const int32_t* cu_seqlens,
                      const int32_t* positions, int batch, int total_tokens, hipStream_t stream);
 int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
@@ -377,7 +386,66 @@ int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_ne
   if (rc != EARN_OK) return rc;
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
                        gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream,
-                       nullptr);
+                       nullptr, nullptr);
+}
+
+int earn_decode_attn_beams(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
+                           const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
+                           const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len,
+                           const int32_t* gen_src, int32_t gen_cap, int32_t n_streams, int32_t batch,
+                           int32_t max_shared_len, void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  const int rc = check_decode_args("earn_decode_attn_beams", desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu,
+                                   stream_to_seq, gen_k, gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, out,
+                                   stream);
+  if (rc != EARN_OK) return rc;
+  if (gen_src && g_validate.load(std::memory_order_relaxed)) {
+    std::vector<int32_t> src;
+    int rc2 = fetch_i32(gen_src, (size_t)n_streams * gen_cap, src, (hipStream_t)stream, "earn_decode_attn_beams");
+    if (rc2 != EARN_OK) return rc2;
+    for (size_t i = 0; i < src.size(); ++i)
+      if (src[i] < 0 || src[i] >= n_streams) {
+        set_error("earn_decode_attn_beams: gen_src[%zu] = %d outside [0, n_streams = %d)", i, src[i], n_streams);
+        return EARN_ERR_INVALID_ARG;
+      }
+  }
+  return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
+                       gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream,
+                       nullptr, gen_src);
+}
+
+size_t earn_beam_topk_workspace_bytes(int32_t batch, int32_t beams, int32_t vocab) {
+  const char* why;
+  if (batch <= 0 || beams <= 0 || vocab <= 0 || !beam_topk_limits(beams, vocab, &why)) return 0;
+  return beam_topk_workspace_bytes(batch, beams, vocab);
+}
+
+int earn_beam_topk(const float* beam_scores, const float* token_logprobs, int32_t batch, int32_t beams, int32_t vocab,
+                   int32_t* parent_out, int32_t* token_out, float* score_out, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+  g_err[0] = 0;
+  if (!token_logprobs || !parent_out || !token_out || !score_out || batch <= 0 || beams <= 0 || vocab <= 0 || batch > 65535) {
+    set_error("earn_beam_topk: NULL pointer or non-positive size (batch %d, beams %d, vocab %d)", batch, beams, vocab);
+    return EARN_ERR_INVALID_ARG;
+  }
+  const char* why = "";
+  if (!beam_topk_limits(beams, vocab, &why)) { set_error("earn_beam_topk: %s", why); return EARN_ERR_UNSUPPORTED; }
+  const size_t need = beam_topk_workspace_bytes(batch, beams, vocab);
+  if (need > workspace_bytes || (need > 0 && !workspace)) {
+    set_error("earn_beam_topk: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
+    return EARN_ERR_WORKSPACE_TOO_SMALL;
+  }
+  return launch_beam_topk(beam_scores, token_logprobs, batch, beams, vocab, parent_out, token_out, score_out, workspace,
+                          (hipStream_t)stream);
+}
+
+int earn_beam_reorder(const int32_t* parent, const int32_t* gen_src_in, int32_t* gen_src_out, int32_t n_streams,
+                      int32_t gen_cap, int32_t step, void* stream) {
+  g_err[0] = 0;
+  if (!parent || !gen_src_out || gen_src_out == gen_src_in || n_streams <= 0 || gen_cap <= 0 || step < 0 || step >= gen_cap) {
+    set_error("earn_beam_reorder: NULL or aliased table, or sizes out of range (n_streams %d, gen_cap %d, step %d)", n_streams, gen_cap, step);
+    return EARN_ERR_INVALID_ARG;
+  }
+  return launch_beam_reorder(parent, gen_src_in, gen_src_out, n_streams, gen_cap, step, (hipStream_t)stream);
 }
 
 size_t earn_decode_layers_workspace_bytes(const earn_attn_desc* desc, int32_t n_layers, int32_t n_streams, int32_t batch,
@@ -410,7 +478,7 @@ int earn_decode_attn_layers(const earn_attn_desc* desc, int32_t n_layers, const 
   const DecodeLayers layers = {n_layers, q_layer_stride, kv_new_layer_stride, shared_layer_stride, gen_layer_stride, out_layer_stride};
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
                        gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream,
-                       &layers);
+                       &layers, nullptr);
 }
 
 size_t earn_prefill_register_rows_workspace_bytes(const earn_attn_desc* desc, int32_t batch, int32_t max_seqlen,
@@ -471,6 +539,25 @@ int earn_prefill_register_rows(const earn_attn_desc* desc, const void* q_rows, c
   if (rc != EARN_OK) return rc;
   return launch_prefill_rows(desc, q_rows, k_rot_out, v, cu_seqlens, row_pos, batch, max_seqlen, rows_per_seq, out_rows,
                              workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int earn_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const int32_t* cu_seqlens,
+                    const int32_t* row_pos, int32_t batch, int32_t rows_per_seq, float epsilon, int32_t t_head,
+                    int32_t tail_back, float* stats_out, void* stream) {
+  g_err[0] = 0;
+  int rc = check_desc(desc, "earn_attn_stats");
+  if (rc != EARN_OK) return rc;
+  if (batch <= 0 || rows_per_seq <= 0 || !(epsilon >= 0.f) || t_head < 0 || tail_back < 0 ||
+      (long long)batch * rows_per_seq > 0x7fffffffLL || desc->n_q_heads > 65535) {
+    set_error("earn_attn_stats: batch (%d) and rows_per_seq (%d) must be positive, epsilon, t_head (%d) and tail_back (%d) non-negative", batch, rows_per_seq, t_head, tail_back);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (!q_rows || !k_rot || !cu_seqlens || !row_pos || !stats_out) {
+    set_error("earn_attn_stats: a required pointer is NULL");
+    return EARN_ERR_INVALID_ARG;
+  }
+  return launch_attn_stats(desc, q_rows, k_rot, cu_seqlens, row_pos, batch, rows_per_seq, epsilon, t_head, tail_back,
+                           stats_out, (hipStream_t)stream);
 }
 
 int64_t earn_cache_entries(int32_t n_layers, int32_t split_k, int64_t seq_len, int32_t n_registers, int64_t gen) {

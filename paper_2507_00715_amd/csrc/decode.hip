@@ -69,6 +69,10 @@ struct DecodeParams {
   const void* q; const void* k_new; const void* v_new; const int32_t* q_pos;
   const void* shared_k; const void* shared_v; const int32_t* shared_cu; const int32_t* stream_to_seq;
   void* gen_k; void* gen_v; const int32_t* gen_len;
+  // Beam search without cache copies (NULL = every stream reads its own rows): row g < gen_len[u] of stream u's generated
+  // cache lives in the physical slot (gen_src[u * gen_cap + g], g), i.e. in the cache rows of the stream that wrote it
+  // at step g, an ancestor of u; the append of this call still goes to the stream's own slot (u, gen_len[u]).
+  const int32_t* gen_src;
   void* out; float* part_o; float* part_ml;
   int gen_cap, n_streams, batch, hq, hkv, n_splits, chunk;  // chunk: keys per split (multiple of 64)
   int n_slots;    // partial-result slots per (stream, head) in the workspace (one per key split)
@@ -186,8 +190,14 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const DecodeL
         kr[i] = Row8<T>::load_raw(Kc + (long long)j * row_stride);
         vr[i] = Row8<T>::load_raw(Vc + (long long)j * row_stride);
       } else if (j < m_total - 1 && j < j_end) {
-        kr[i] = Row8<T>::load_raw(Gk + (long long)(j - ns) * row_stride);
-        vr[i] = Row8<T>::load_raw(Gv + (long long)(j - ns) * row_stride);
+        // the physical stream that holds logical row j - ns (an ancestor's slot under beam search)
+        long long from = 0;
+        if (p.gen_src) {
+          const int src = max(min(p.gen_src[(long long)u * p.gen_cap + (j - ns)], p.n_streams - 1), 0);
+          from = (long long)(src - u) * p.gen_cap * row_stride;
+        }
+        kr[i] = Row8<T>::load_raw(Gk + from + (long long)(j - ns) * row_stride);
+        vr[i] = Row8<T>::load_raw(Gv + from + (long long)(j - ns) * row_stride);
       } else {
         kr[i] = typename Row8<T>::Raw{};
         vr[i] = typename Row8<T>::Raw{};
@@ -653,8 +663,13 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
         const int u = sm.streams[si], g = sm.glen[si];
         const long long row0_of_u = (((long long)u * p.gen_cap) * p.hkv + c) * D + ch * 8;
         if (ri < g) {
-          kx = *(const u32x4*)((const __bf16*)lv.gen_k + row0_of_u + ri * kv_stride);
-          vx = *(const u32x4*)((const __bf16*)lv.gen_v + row0_of_u + ri * kv_stride);
+          long long from = row0_of_u;  // the physical stream that holds logical row ri (an ancestor's slot under beam search)
+          if (p.gen_src) {
+            const int src = max(min(p.gen_src[(long long)u * p.gen_cap + ri], p.n_streams - 1), 0);
+            from += (long long)(src - u) * p.gen_cap * kv_stride;
+          }
+          kx = *(const u32x4*)((const __bf16*)lv.gen_k + from + ri * kv_stride);
+          vx = *(const u32x4*)((const __bf16*)lv.gen_v + from + ri * kv_stride);
         } else if (ri == g) {
           const long long tok = ((long long)u * p.hkv + c) * D;
           float x[8], y[8];  // this unit's elements and their rotary partners (the unit half a row away)
@@ -1140,7 +1155,7 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
                   const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                   const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
                   int n_streams, int batch, int max_shared_len, void* out, void* workspace, size_t workspace_bytes,
-                  hipStream_t stream, const DecodeLayers* layers) {
+                  hipStream_t stream, const DecodeLayers* layers, const int32_t* gen_src) {
   const int hq = desc->n_q_heads, hkv = desc->n_kv_heads, d = desc->head_dim, gq = hq / hkv;
   const int n_layers = layers ? layers->n_layers : 1;
   if (gq > 8) { set_error("earn_decode_attn: more than 8 query heads per kv head is not supported"); return EARN_ERR_UNSUPPORTED; }
@@ -1156,7 +1171,7 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
   DecodeParams p;
   p.q = q; p.k_new = k_new; p.v_new = v_new; p.q_pos = q_pos;
   p.shared_k = shared_k; p.shared_v = shared_v; p.shared_cu = shared_cu; p.stream_to_seq = stream_to_seq;
-  p.gen_k = gen_k; p.gen_v = gen_v; p.gen_len = gen_len; p.out = out;
+  p.gen_k = gen_k; p.gen_v = gen_v; p.gen_len = gen_len; p.out = out; p.gen_src = gen_src;
   p.gen_cap = gen_cap; p.n_streams = n_streams; p.batch = batch; p.hq = hq; p.hkv = hkv;
   p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = 0; p.n_pass = pl.n_pass;
   const size_t need = decode_workspace_bytes(desc->dtype, hq, hkv, d, n_streams, batch, max_shared_len, gen_cap, n_layers);
@@ -1228,7 +1243,7 @@ int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* 
   const int rc = static_scratch_of_current_device(&ptr);
   if (rc != EARN_OK) return rc;
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
-                       gen_cap, n_streams, batch, max_shared_len, out, ptr, kStaticScratchBytes, stream, nullptr);
+                       gen_cap, n_streams, batch, max_shared_len, out, ptr, kStaticScratchBytes, stream, nullptr, nullptr);
 }
 
 // ---- causal attention of r chosen rows per sequence over the sequence's full-length keys, on the shared-cache kernel:
@@ -1283,7 +1298,7 @@ int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const vo
   DecodeParams p;
   p.q = q_rows; p.k_new = nullptr; p.v_new = nullptr; p.q_pos = row_pos;
   p.shared_k = k_rot; p.shared_v = v; p.shared_cu = cu_seqlens; p.stream_to_seq = nullptr;
-  p.gen_k = nullptr; p.gen_v = nullptr; p.gen_len = nullptr; p.out = out_rows;
+  p.gen_k = nullptr; p.gen_v = nullptr; p.gen_len = nullptr; p.out = out_rows; p.gen_src = nullptr;
   p.gen_cap = 0; p.n_streams = batch * rows_per_seq; p.batch = batch; p.hq = hq; p.hkv = hkv;
   p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = rows_per_seq; p.n_pass = n_pass;
   p.part_o = (float*)workspace;

@@ -437,3 +437,83 @@ def test_efficiency_example_printed_by_the_paper():
 def test_causal_flop_count():
     # one sequence of length m: 4 d Hq m(m+1)/2
     assert O.causal_attn_flops([100, 132], 4, 64) == 4 * 64 * 4 * (100 * 101 // 2 + 132 * 133 // 2)
+
+
+# ----------------------------------------------------------------------------------------------
+# attention-score statistics (Appendix: Sparsity, Sink_head, Sink_tail)
+# ----------------------------------------------------------------------------------------------
+def test_attention_statistics_closed_forms():
+    """Uniform rows (K = 0): p_j = 1/n, so Sparsity = [1/n > 0.05], Sink_head = min(3, n)/n, Sink_tail = min(4, n)/n
+    (T_t = n - 3 makes the tail window four keys wide, as the formula is printed).  Two-level rows: one key with score
+    c, all others 0, so p* = e^c / (e^c + n - 1) and the rest share 1 - p*."""
+    n, d = 40, 16
+    q = RNG.standard_normal((n, 2, d))
+    st = O.attn_stats(q, np.zeros((n, 1, d)), [0, n])
+    for i in range(n):
+        m = i + 1
+        np.testing.assert_allclose(st[i, :, 0], 1.0 if 1.0 / m > 0.05 else 0.0)
+        np.testing.assert_allclose(st[i, :, 1], min(3, m) / m, rtol=1e-12)
+        np.testing.assert_allclose(st[i, :, 2], min(4, m) / m, rtol=1e-12)
+    assert st[18, 0, 0] == 1.0 and st[19, 0, 0] == 0.0          # 1/19 > 0.05 >= 1/20: the comparison is strict
+    # two-level: without rotation, q = sqrt(d) e_0 scaled by c and key j* = e_0 give score c at j*, 0 elsewhere
+    c, jstar = 4.0, 30
+    q = np.zeros((n, 1, d)); q[:, 0, 0] = c * np.sqrt(d)
+    k = np.zeros((n, 1, d)); k[jstar, 0, 0] = 1.0
+    st = O.attn_stats(q, k, [0, n], rope_base=0.0)
+    i = n - 1
+    pstar = np.exp(c) / (np.exp(c) + n - 1)
+    rest = (1 - pstar) / (n - 1)
+    assert rest < 0.05 < pstar
+    np.testing.assert_allclose(st[i, 0], [1.0 / n, 3 * rest, 4 * rest], rtol=1e-12)          # j* = 31st key: in neither window
+    st2 = O.attn_stats(q, np.roll(k, n - 2 - jstar, axis=0), [0, n], rope_base=0.0)            # j* -> the (n-1)th key
+    np.testing.assert_allclose(st2[i, 0], [1.0 / n, 3 * rest, pstar + 3 * rest], rtol=1e-12)
+    st3 = O.attn_stats(q, np.roll(k, 1 - jstar, axis=0), [0, n], rope_base=0.0)                # j* -> the 2nd key
+    np.testing.assert_allclose(st3[i, 0], [1.0 / n, pstar + 2 * rest, 4 * rest], rtol=1e-12)
+    # other thresholds and windows
+    st4 = O.attn_stats(q, k, [0, n], rope_base=0.0, epsilon=rest / 2, t_head=0, tail_back=n)
+    np.testing.assert_allclose(st4[i, 0], [1.0, 0.0, 1.0], rtol=1e-12)
+
+
+def test_attention_statistics_follow_the_probabilities_of_the_attention_oracle():
+    """With rotation, grouped heads and a ragged batch: the statistics are those of the probabilities the (separately
+    pinned) attention oracle materialises; and the head map and the explicit scale reach this function as well."""
+    lens = [37, 9]
+    q, k, v, cu = rand_batch(lens, 4, 2, 32)
+    q *= 3.0
+    st = O.attn_stats(q, k, cu, scale=0.3)
+    for s in range(2):
+        for a in range(4):
+            p = O.prefill_attn(q, k, v, cu, scale=0.3, want_probs=(s, a))["probs"]
+            for i in range(lens[s]):
+                m = i + 1
+                row = p[i, :m]
+                want = [np.mean(row > 0.05), row[:3].sum(), row[max(m - 4, 0):].sum()]
+                np.testing.assert_allclose(st[cu[s] + i, a], want, rtol=0, atol=1e-12)
+    swapped = O.attn_stats(q, k, cu, q_to_kv=[1, 1, 0, 0], scale=0.3)
+    assert np.abs(swapped - st).max() > 1e-3
+
+
+# ----------------------------------------------------------------------------------------------
+# beam search selection (Appendix, implementation details: beam size 20)
+# ----------------------------------------------------------------------------------------------
+def test_beam_topk_equals_a_stable_sort_and_breaks_ties_by_index():
+    batch, beams, vocab = 3, 5, 37
+    lp = RNG.standard_normal((batch * beams, vocab)).astype(np.float32)
+    lp[2, 5] = lp[7, 30] = lp[7, 31] = 9.0                      # ties at the top, inside and across beams
+    lp[11] = -np.inf                                            # a dead beam
+    lp[4, 3] = np.nan                                           # never wins
+    bs = RNG.standard_normal(batch * beams).astype(np.float32)
+    res = O.beam_topk(bs, lp, batch, beams, vocab)
+    cand = (lp + bs[:, None]).astype(np.float32).reshape(batch, beams * vocab)   # the fp32 sum
+    cand = np.where(np.isnan(cand), -np.inf, cand)
+    for b in range(batch):
+        order = np.argsort(-cand[b], kind="stable")[:beams]     # library routine: descending, first of equals first
+        np.testing.assert_array_equal(res["parent"][b * beams:(b + 1) * beams], b * beams + order // vocab)
+        np.testing.assert_array_equal(res["token"][b * beams:(b + 1) * beams], order % vocab)
+        np.testing.assert_array_equal(res["score"][b * beams:(b + 1) * beams], cand[b][order])
+    # worked by hand: two beams, three tokens
+    r = O.beam_topk([0.0, -1.0], [[0.1, 0.5, 0.5], [2.0, 0.1, 1.5]], 1, 2, 3)
+    assert r["parent"].tolist() == [1, 0] and r["token"].tolist() == [0, 1] and r["score"].tolist() == [1.0, 0.5]
+    # fewer candidates than beams: the rest is empty
+    r = O.beam_topk(None, [[0.3], [0.1], [0.2]], 1, 3, 1)
+    assert r["parent"].tolist() == [0, 2, 1] and r["token"].tolist() == [0, 0, 0]
