@@ -433,6 +433,128 @@ def launch_floor_us(dev, launches: int = 200) -> float:
     return e0.elapsed_time(e1) * 1e3 / launches
 
 
+def beam_machinery(name: str, dev, beams: int = 20, vocabs=(256, 32000)) -> dict:
+    """Beam search at the paper's beam width on the shape of `name`: the selection step, the ancestor-table update, and
+    one decode layer (register cache and full-length cache) reading the generated rows through the table, next to the
+    same layer without the table and to the bytes a copy-based reorder of the generated caches would move."""
+    from paper_2507_00715_amd import binding as B
+    c = W.CONFIGS[name].replace(beams=beams)
+    w = W.Workload(c)
+    S, G, hq, hkv, d = w.n_streams, c.decode_steps, c.n_q_heads, c.n_kv_heads, c.head_dim
+    desc = B.make_desc(c.torch_dtype, hq, hkv, d, 0.0, c.rope_base)
+    rnd = lambda *shape: torch.randn(*shape, device=dev, dtype=c.torch_dtype)
+    i32 = lambda x: torch.tensor(list(x), dtype=torch.int32, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def us(fn, reps=20):
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    out = {"beams": beams, "streams": S}
+    parent, token = (torch.zeros(S, dtype=torch.int32, device=dev) for _ in range(2))
+    scores, new_scores = torch.zeros(S, device=dev), torch.zeros(S, device=dev)
+    for V in vocabs:
+        lp = torch.randn(S, V, device=dev)
+        ws = torch.empty(max(B.earn_beam_topk_workspace_bytes(c.batch, beams, V), 256), dtype=torch.uint8, device=dev)
+        t = us(lambda: B.earn_beam_topk(scores, lp, c.batch, beams, V, parent, token, new_scores, ws))
+        out[f"topk_vocab_{V}"] = {"us": t, "GBps": S * V * 4 / t / 1e3}
+    g = G // 2
+    src_a = torch.randint(0, S, (S, G), dtype=torch.int32, device=dev)
+    src_a = (src_a % beams + torch.arange(S, device=dev, dtype=torch.int32)[:, None] // beams * beams).contiguous()
+    src_b = torch.empty_like(src_a)
+    B.earn_beam_topk(scores, torch.randn(S, 256, device=dev), c.batch, beams, 256, parent, token, new_scores)
+    out["reorder_table"] = {"us": us(lambda: B.earn_beam_reorder(parent, src_a, src_b, S, G, g)), "bytes": 2 * S * G * 4}
+    out["copy_based_reorder_bytes_per_step"] = 2 * 2 * c.n_layers * S * g * hkv * d * c.elem_bytes   # K and V, read + write
+    q_pos, gen_len = i32(w.decode_positions(g)), i32([g] * S)
+    s2s = i32(w.stream_to_seq)
+    for label, lens in (("register_cache_layer", [c.r] * c.batch), ("full_cache_layer", w.seq_lengths)):
+        T = sum(lens)
+        cu = i32(np.concatenate([[0], np.cumsum(lens)]))
+        sk, sv = rnd(T, hkv, d), rnd(T, hkv, d)
+        q, kn, vn = rnd(S, hq, d), rnd(S, hkv, d), rnd(S, hkv, d)
+        gk, gv = rnd(S, G, hkv, d), rnd(S, G, hkv, d)
+        o = torch.empty(S, hq, d, dtype=c.torch_dtype, device=dev)
+        ws = torch.empty(max(B.earn_decode_workspace_bytes(desc, S, c.batch, max(lens), G), 256), dtype=torch.uint8, device=dev)
+        call = lambda table: B.earn_decode_attn_beams(desc, q, kn, vn, q_pos, sk, sv, cu, s2s, gk, gv, gen_len, table, G, S,
+                                                      c.batch, max(lens), o, ws)
+        out[label] = {"us_through_table": us(lambda: call(src_b)), "us_without_table": us(lambda: call(None))}
+    return out
+
+
+def decoder_layer(name: str, dev) -> dict:
+    """One whole decoder layer in the accounting of the paper's Appendix A.2 (Q/K/V projections with the rotation in
+    their epilogue, attention, output projection, two feed-forward projections with SiLU between; no norms or residual
+    adds, which the FLOP model leaves out too) at full length and on the compacted register rows, random weights:
+    the measured Gamma_attn = (k t_full + (N-k) t_registers) / (N t_full) next to the closed form of Section 3.3."""
+    from paper_2507_00715_amd import binding as B
+    c = W.CONFIGS[name]
+    w = W.Workload(c)
+    hq, hkv, d, N, kk = c.n_q_heads, c.n_kv_heads, c.head_dim, c.n_layers, c.split_k
+    dm = hq * d
+    df = 11008 if dm == 4096 else (int(dm * 2.6875) + 63) // 64 * 64      # the paper's typical values: d_h 4096, d_f 11008
+    bf = torch.bfloat16
+    g = torch.Generator(device=dev).manual_seed(1)
+    rnd = lambda *shape, sc=1.0: (torch.randn(*shape, device=dev, generator=g) * sc).to(bf)
+    w_qkv, w_o = rnd(dm, (hq + 2 * hkv) * d, sc=dm ** -0.5), rnd(hq * d, dm, sc=dm ** -0.5)
+    w_up, w_down = rnd(dm, df, sc=dm ** -0.5), rnd(df, dm, sc=df ** -0.5)
+    desc = B.make_desc(bf, hq, hkv, d, 0.0, c.rope_base)
+    desc0 = B.make_desc(bf, hq, hkv, d, 0.0, 0.0)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def ms(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    out = {"d_model": dm, "d_ffn": df}
+    r = c.r
+    cu_full = torch.tensor(w.cu_seqlens, dtype=torch.int32, device=dev)
+    cu_reg = torch.arange(0, c.batch * r + 1, r, dtype=torch.int32, device=dev)
+    pos_reg = torch.cat([torch.cat([torch.arange(c.n_head_reg), torch.arange(n - c.n_tail_reg, n)]) for n in w.seq_lengths]).to(torch.int32).to(dev)
+    totals = {}
+    for label, rows, cu, pos, maxlen in (("full_length", w.total_tokens, cu_full, None, w.max_seqlen),
+                                         ("register_rows", c.batch * r, cu_reg, pos_reg, r)):
+        x = rnd(rows, dm)
+        q, k, v = (torch.empty(rows, h_, d, dtype=bf, device=dev) for h_ in (hq, hkv, hkv))
+        o, y, hmid = torch.empty(rows, hq, d, dtype=bf, device=dev), torch.empty(rows, dm, dtype=bf, device=dev), torch.empty(rows, df, dtype=bf, device=dev)
+        t = {
+            "qkv_rope_project_ms": ms(lambda: B.earn_qkv_rope_project(desc, x, w_qkv, cu, pos, c.batch, q, k, v)),
+            "attention_ms": ms(lambda: B.earn_prefill_attn(desc0, q, k, v, cu, pos, c.batch, rows, maxlen, o, None, None, None)),
+            "out_projection_ms": ms(lambda: B.earn_linear(o.view(rows, hq * d), w_o, y)),
+            "ffn_up_silu_ms": ms(lambda: B.earn_linear(x, w_up, hmid, 1)),
+            "ffn_down_ms": ms(lambda: B.earn_linear(hmid, w_down, y)),
+        }
+        t["layer_ms"] = sum(t.values())
+        flops = {"qkv_rope_project": 2.0 * rows * dm * (hq + 2 * hkv) * d, "out_projection": 2.0 * rows * hq * d * dm,
+                 "ffn_up_silu": 2.0 * rows * dm * df, "ffn_down": 2.0 * rows * df * dm}
+        t["gemm_tflops"] = {k_: flops[k_] / (t[k_ + "_ms"] * 1e-3) / 1e12 for k_ in flops}
+        t["gemm_frac_of_bf16_peak"] = {k_: v_ / PEAK_BF16_TFLOPS for k_, v_ in t["gemm_tflops"].items()}
+        out[label] = t
+        totals[label] = t["layer_ms"]
+        del x, q, k, v, o, y, hmid
+    L = sum(w.seq_lengths) / c.batch
+
+    def f_layer(n):  # Appendix A.2: 4 n [n_h d_a (2 d_h + n) + d_h d_f]
+        return 4.0 * n * (hq * d * (2 * dm + n) + dm * df)
+    out["gamma_attn_measured"] = (kk * totals["full_length"] + (N - kk) * totals["register_rows"]) / (N * totals["full_length"])
+    out["gamma_attn_closed_form"] = kk / N + (1 - kk / N) * f_layer(r) / f_layer(L)
+    out["k_over_N"] = kk / N
+    out["speedup_measured_prefill_layers"] = 1.0 / out["gamma_attn_measured"]
+    torch.cuda.empty_cache()
+    return out
+
+
 def measured_peaks(dev) -> dict:
     """Ceilings measured in this process with the calibration micro-kernels of libearn_calib.so (plain loops, no
     attention code): what the published peaks come to on this machine under this power limit."""
@@ -586,6 +708,10 @@ def cpu_baseline(name: str, threads: int = 0, rows_target: int = 4096) -> dict:
                       f"{stride}th query row ({len(rows)} rows, {pairs:.3g} causal pairs)"}
 
 
+def cfg_has_decode(name: str) -> bool:
+    return W.CONFIGS[name].decode_steps > 0 and W.CONFIGS[name].dtype == "bf16"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -623,10 +749,12 @@ def main():
         one = cpu_baseline(args.workload, threads=1, rows_target=256)
         cpu["single_thread"] = {k_: one[k_] for k_ in ("value", "unit", "cores", "seconds", "sample")}
         cpu["other_oracle_functions"] = cpu_baseline_extras(args.workload)
+    cfg = W.CONFIGS[args.workload]
     floor_us = launch_floor_us(dev)
     peaks = measured_peaks(dev)
+    beams20 = beam_machinery(args.workload, dev) if cfg_has_decode(args.workload) else None
+    layer = decoder_layer(args.workload, dev) if cfg.dtype == "bf16" else None
 
-    cfg = W.CONFIGS[args.workload]
     traffic = measured_traffic(args.workload)
     pf = head["prefill_full_layer"]
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
@@ -654,6 +782,8 @@ def main():
         "phase_ms_per_step": head["phase_ms_per_step"],
         "per_layer_launch": head["per_layer_launch"],
         "attention_statistics": head["attention_statistics"],
+        "beam_search_width_20": beams20,
+        "decoder_layer_with_projections": layer,
         "launch_floor_us": floor_us,
         "last_full_layer_register_rows_only": head["last_full_layer_register_rows_only"],
         "attention_only_vs_vanilla": head["attention_only_vs_vanilla"],

@@ -112,6 +112,8 @@ int earn_set_tuning(const char* key, int32_t value);
  *   k_rot_out      [total_tokens, Hkv, d] or NULL: receives k' (this is what the layer's KV cache stores)
  *   lse_out        [total_tokens, Hq] fp32 or NULL: natural-log-sum-exp of each softmax row
  *   workspace      at least earn_prefill_workspace_bytes(...) bytes, 256-byte aligned; may be NULL when that is 0
+ * With the rotation switched off (rope_base <= 0) and k_rot_out == NULL the keys are read in place: no rotation pass, no
+ * workspace (the form used behind earn_qkv_rope_project, whose k_out already is the rotated cache).
  *
  * Errors: NULL required pointer, batch <= 0, total_tokens < 0, max_seqlen <= 0, Hq % Hkv != 0 -> INVALID_ARG;
  * head_dim not in {64,128} or unknown dtype -> UNSUPPORTED; workspace_bytes too small -> WORKSPACE_TOO_SMALL.
@@ -292,6 +294,32 @@ int earn_prefill_register_rows(const earn_attn_desc* desc, const void* q_rows, c
 /* Workspace earn_prefill_register_rows needs (bytes) for split-key partial results. 0 on invalid arguments. */
 size_t earn_prefill_register_rows_workspace_bytes(const earn_attn_desc* desc, int32_t batch, int32_t max_seqlen,
                                                   int32_t rows_per_seq);
+
+/*
+ * The dense projections of a decoder layer (paper Appendix A.2: per head, Q/K/V projections 3 x 2 L d_h d_a and the output
+ * projection 2 L d_a d_h; feed-forward block, two projections, 4 L d_h d_f), bf16 with fp32 accumulation.
+ *
+ * earn_qkv_rope_project: [rows, d_model] x [d_model, (Hq + 2 Hkv) d] -> Q, K, V, with the rotary embedding applied to the
+ * Q and K columns at each row's ORIGINAL position in the epilogue (same convention as earn_prefill_attn: half-split
+ * pairs, theta_e = rope_base^(-2e/d); rope_base <= 0: no rotation).  k_out is what the layer's key cache stores, so the
+ * attention entry points are then called with rope_base = 0 and, for the prefill, k_rot_out = NULL: they read q_out /
+ * k_out as they are and run no rotation pass.  Rows of the register-focused layers (Section 3.2) are the gathered hidden
+ * rows, with positions = pos_out of earn_compact_registers; decode rows are the new tokens with positions = q_pos.
+ *   x          device, [rows, d_model] bf16           w_qkv   device, [d_model, (Hq + 2 Hkv) d] bf16, row-major; columns:
+ *                                                             the Q heads, then the K heads, then the V heads
+ *   positions  device, [rows] int32 or NULL; NULL: row i of sequence s has position i - cu_seqlens[s] (cu_seqlens, batch
+ *              required then)
+ *   q_out      device, [rows, Hq, d];  k_out, v_out  device, [rows, Hkv, d]
+ * earn_linear: out[rows, n] = act(x[rows, k] w[k, n]), activation 0 = none, 1 = SiLU (x / (1 + e^-x)); bf16.
+ * Errors: NULL pointer, non-positive size, positions and cu_seqlens both NULL with rotation on -> INVALID_ARG;
+ * desc->dtype != EARN_BF16, an inner dimension that is not a multiple of 64, an output width that is not a multiple of
+ * 8, a weight matrix of 2 GiB or more -> UNSUPPORTED.  Enqueue on `stream`, allocate nothing.
+ */
+int earn_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void* w_qkv, int32_t rows, int32_t d_model,
+                          const int32_t* cu_seqlens, const int32_t* positions, int32_t batch, void* q_out, void* k_out,
+                          void* v_out, void* stream);
+int earn_linear(const void* x, const void* w, int32_t rows, int32_t k, int32_t n, int32_t activation, void* out,
+                void* stream);
 
 /*
  * Beam search around the decode step (paper Appendix, implementation details: inference decodes with beam search, beam

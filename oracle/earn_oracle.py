@@ -213,6 +213,30 @@ def beam_reorder_caches(parent, gen_k: np.ndarray, gen_v: np.ndarray) -> None:
     gen_v[...] = gen_v[parent].copy()
 
 
+def qkv_project(x, w_qkv, n_q_heads: int, n_kv_heads: int, head_dim: int, positions, rope_base: float = 10000.0) -> dict:
+    """The Q/K/V projections of a layer (Appendix A.2: X W per head) followed by the rotary embedding of Q and K at the
+    rows' original positions.  x [rows, d_model], w_qkv [d_model, (Hq + 2 Hkv) d] with the columns ordered Q heads, K
+    heads, V heads.  The matrix product is the library routine in fp64; the rotation is oracle_rope.
+    Returns dict(q [rows, Hq, d], k [rows, Hkv, d] (rotated: the cache), v [rows, Hkv, d])."""
+    x, w = _f64(x), _f64(w_qkv)
+    rows = x.shape[0]
+    hq, hkv, d = n_q_heads, n_kv_heads, head_dim
+    assert w.shape == (x.shape[1], (hq + 2 * hkv) * d)
+    y = x @ w
+    q = y[:, : hq * d].reshape(rows, hq, d)
+    k = y[:, hq * d: (hq + hkv) * d].reshape(rows, hkv, d)
+    v = y[:, (hq + hkv) * d:].reshape(rows, hkv, d)
+    pos = _i32(positions)
+    return {"q": rope(q, pos, rope_base), "k": rope(k, pos, rope_base), "v": np.ascontiguousarray(v)}
+
+
+def linear(x, w, activation: int = 0) -> np.ndarray:
+    """act(x w): activation 0 = none, 1 = SiLU, y / (1 + exp(-y)) (output projection and the two feed-forward
+    projections of Appendix A.2)."""
+    y = _f64(x) @ _f64(w)
+    return y / (1.0 + np.exp(-y)) if activation == 1 else y
+
+
 def cache_entries(n_layers: int, split_k: int, n: int, r: int, gen: int = 0) -> int:
     return int(lib().oracle_cache_entries(n_layers, split_k, n, r, gen))
 

@@ -28,7 +28,7 @@ EXPORTS = ["earn_last_error", "earn_version", "earn_prefill_attn", "earn_prefill
            "earn_prefill_register_rows", "earn_prefill_register_rows_workspace_bytes", "earn_set_validation",
            "earn_set_tuning", "earn_decode_attn_static", "earn_prefill_attn_layers", "earn_decode_attn_layers",
            "earn_decode_layers_workspace_bytes", "earn_decode_step_positions", "earn_attn_stats", "earn_beam_topk", "earn_beam_topk_workspace_bytes",
-           "earn_beam_reorder", "earn_decode_attn_beams"]
+           "earn_beam_reorder", "earn_decode_attn_beams", "earn_qkv_rope_project", "earn_linear"]
 EARN_STATIC_SCRATCH_BYTES = 8 << 20
 
 
@@ -89,6 +89,10 @@ def lib():
         L.earn_decode_attn_beams.restype = ctypes.c_int
         L.earn_decode_attn_beams.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
                                              i32, i32, i32, vp, vp, sz, vp]
+        L.earn_qkv_rope_project.restype = ctypes.c_int
+        L.earn_qkv_rope_project.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
+        L.earn_linear.restype = ctypes.c_int
+        L.earn_linear.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
         L.earn_prefill_register_rows.restype = ctypes.c_int
         L.earn_prefill_register_rows.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp,
                                                  vp, sz, vp]
@@ -298,6 +302,19 @@ def earn_decode_attn_beams(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, sha
                                         _ptr(shared_k), _ptr(shared_v), _ptr(shared_cu), _ptr(stream_to_seq), _ptr(gen_k),
                                         _ptr(gen_v), _ptr(gen_len), _ptr(gen_src), gen_cap, n_streams, batch,
                                         max_shared_len, _ptr(out), _ptr(workspace), ws_bytes, _stream()))
+
+
+def earn_qkv_rope_project(desc: AttnDesc, x, w_qkv, cu_seqlens, positions, batch: int, q_out, k_out, v_out) -> None:
+    rows, d_model = x.shape
+    _check(lib().earn_qkv_rope_project(ctypes.byref(desc), _ptr(x), _ptr(w_qkv), rows, d_model, _ptr(cu_seqlens),
+                                       _ptr(positions), batch, _ptr(q_out), _ptr(k_out), _ptr(v_out), _stream()))
+
+
+def earn_linear(x, w, out, activation: int = 0) -> None:
+    rows, k = x.shape
+    n = w.shape[1]
+    assert w.shape[0] == k and tuple(out.shape) == (rows, n)
+    _check(lib().earn_linear(_ptr(x), _ptr(w), rows, k, n, activation, _ptr(out), _stream()))
 
 
 def _layer_stride(t: Optional[torch.Tensor]) -> int:

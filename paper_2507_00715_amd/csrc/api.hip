@@ -72,6 +72,10 @@ int launch_step_positions(const int32_t* cu, const int32_t* stream_to_seq, int n
 int launch_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const int32_t* cu_seqlens,
                       const int32_t* row_pos, int batch, int rows_per_seq, float epsilon, int t_head, int tail_back,
                       float* stats_out, hipStream_t stream);
+int launch_linear(const void* x, const void* w, int rows, int k, int n, int activation, void* out, hipStream_t stream);
+int launch_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void* w_qkv, int rows, int d_model,
+                            const int32_t* cu_seqlens, const int32_t* positions, int batch, void* q_out, void* k_out,
+                            void* v_out, hipStream_t stream);
 int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, const int32_t* cu_seqlens,
                      const int32_t* positions, int batch, int total_tokens, hipStream_t stream);
 int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
@@ -558,6 +562,35 @@ int earn_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* 
   }
   return launch_attn_stats(desc, q_rows, k_rot, cu_seqlens, row_pos, batch, rows_per_seq, epsilon, t_head, tail_back,
                            stats_out, (hipStream_t)stream);
+}
+
+int earn_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void* w_qkv, int32_t rows, int32_t d_model,
+                          const int32_t* cu_seqlens, const int32_t* positions, int32_t batch, void* q_out, void* k_out,
+                          void* v_out, void* stream) {
+  g_err[0] = 0;
+  int rc = check_desc(desc, "earn_qkv_rope_project");
+  if (rc != EARN_OK) return rc;
+  if (desc->dtype != EARN_BF16) { set_error("earn_qkv_rope_project: bf16 only"); return EARN_ERR_UNSUPPORTED; }
+  if (!x || !w_qkv || !q_out || !k_out || !v_out || rows <= 0 || d_model <= 0) {
+    set_error("earn_qkv_rope_project: NULL pointer or non-positive size (rows %d, d_model %d)", rows, d_model);
+    return EARN_ERR_INVALID_ARG;
+  }
+  if (desc->rope_base > 0.f && !positions && (!cu_seqlens || batch <= 0)) {
+    set_error("earn_qkv_rope_project: positions is NULL and no cu_seqlens / batch to derive them from");
+    return EARN_ERR_INVALID_ARG;
+  }
+  return launch_qkv_rope_project(desc, x, w_qkv, rows, d_model, cu_seqlens, positions, batch, q_out, k_out, v_out,
+                                 (hipStream_t)stream);
+}
+
+int earn_linear(const void* x, const void* w, int32_t rows, int32_t k, int32_t n, int32_t activation, void* out,
+                void* stream) {
+  g_err[0] = 0;
+  if (!x || !w || !out || rows <= 0 || k <= 0 || n <= 0 || activation < 0 || activation > 1) {
+    set_error("earn_linear: NULL pointer, non-positive size or unknown activation %d", activation);
+    return EARN_ERR_INVALID_ARG;
+  }
+  return launch_linear(x, w, rows, k, n, activation, out, (hipStream_t)stream);
 }
 
 int64_t earn_cache_entries(int32_t n_layers, int32_t split_k, int64_t seq_len, int32_t n_registers, int64_t gen) {

@@ -290,7 +290,7 @@ __device__ __forceinline__ void pf_load_q(const PrefillParams& p, const __bf16* 
     u32x4 wl, wh;
 #pragma unroll
     for (int j = 0; j < 8; j += 2) {
-      const f32x4 c = cs4[j / 2];  // (cos, sin) of pairs j, j + 1
+      const f32x4 c = p.cs ? cs4[j / 2] : f32x4{1.f, 0.f, 1.f, 0.f};  // (cos, sin) of pairs j, j + 1; no table: no rotation
       const float x0 = (lo[j] * c[0] - hi[j] * c[1]) * p.scale_log2, y0 = (hi[j] * c[0] + lo[j] * c[1]) * p.scale_log2;
       const float x1 = (lo[j + 1] * c[2] - hi[j + 1] * c[3]) * p.scale_log2, y1 = (hi[j + 1] * c[2] + lo[j + 1] * c[3]) * p.scale_log2;
       wl[j / 2] = pack_bf16(x0, x1);
@@ -767,7 +767,9 @@ static size_t cs_table_bytes(const earn_attn_desc* desc, int total_tokens) {
   return ((size_t)total_tokens * (desc->head_dim / 2) * sizeof(f32x2) + 255) / 256 * 256;
 }
 // workspace layout: [rotated keys, unless the caller passes k_rot_out][cos/sin table]
+// Without rotation and without k_rot_out nothing is staged at all: the keys are read in place.
 size_t prefill_workspace_bytes(const earn_attn_desc* desc, int total_tokens, int have_k_rot_out) {
+  if (!(desc->rope_base > 0.f) && !have_k_rot_out) return 0;
   return (have_k_rot_out ? 0 : k_rot_bytes(desc, total_tokens)) + cs_table_bytes(desc, total_tokens);
 }
 
@@ -839,13 +841,15 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
     set_error("earn_prefill_attn: a sequence of %d rows exceeds the 2 GiB addressing range of one sequence", max_seqlen);
     return EARN_ERR_UNSUPPORTED;
   }
-  void* k_rot = k_rot_out ? k_rot_out : workspace;
-  f32x2* cs = cs_table_bytes(desc, total_tokens) ? (f32x2*)((char*)workspace + (k_rot_out ? 0 : k_rot_bytes(desc, total_tokens))) : nullptr;
+  // no rotation and no cache copy asked for: the keys (already rotated by their producer) are read where they are
+  const bool in_place = !(desc->rope_base > 0.f) && !k_rot_out;
+  const void* k_rot = in_place ? k : (k_rot_out ? k_rot_out : workspace);
+  f32x2* cs = !in_place && cs_table_bytes(desc, total_tokens) ? (f32x2*)((char*)workspace + (k_rot_out ? 0 : k_rot_bytes(desc, total_tokens))) : nullptr;
   PrefillParams p;
   p.cs = cs; p.row_pos = nullptr; p.rows_per_seq = 0;
   p.q = q; p.k_rot = k_rot; p.v = v; p.cu = cu_seqlens; p.positions = positions; p.out = out; p.lse = lse_out;
   p.batch = batch; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.max_seqlen = max_seqlen;
-  p.ls_q = layers ? layers->q : 0; p.ls_k_rot = ls_kr; p.ls_v = ls_k; p.ls_out = layers ? layers->out : 0;
+  p.ls_q = layers ? layers->q : 0; p.ls_k_rot = in_place ? ls_k : ls_kr; p.ls_v = ls_k; p.ls_out = layers ? layers->out : 0;
   p.ls_lse = layers ? layers->lse : 0;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
@@ -853,23 +857,29 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
   if (make_head_map(desc, &p.heads, "earn_prefill_attn") != EARN_OK) return EARN_ERR_UNSUPPORTED;
   const bool f32 = desc->dtype == EARN_F32;
   if (f32) {
-    if (d == 64) launch_rope_k<float, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
-    else launch_rope_k<float, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+    if (!in_place) {
+      if (d == 64) launch_rope_k<float, 64>(k, (void*)k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+      else launch_rope_k<float, 128>(k, (void*)k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+    }
     dim3 grid((max_seqlen + 63) / 64, p.hq, batch * n_layers);
     if (d == 64) hipLaunchKernelGGL((prefill_rows_kernel<float, 64>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((prefill_rows_kernel<float, 128>), grid, dim3(256), 0, stream, p);
   } else if (max_seqlen <= kTileKeys) {
     // register-only layers: every sequence is a single K/V tile
-    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
-    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+    if (!in_place) {
+      if (d == 64) launch_rope_k<__bf16, 64>(k, (void*)k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+      else launch_rope_k<__bf16, 128>(k, (void*)k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+    }
     p.n_qblk = 1;
     const long long pairs8 = ((long long)batch * p.hkv + kXcds - 1) / kXcds * kXcds;
     dim3 grid((unsigned)(pairs8 * (p.hq / p.hkv)), n_layers, 1);
     if (d == 64) hipLaunchKernelGGL((prefill_mfma_kernel<64, 2, 1>), grid, dim3(128), 0, stream, p);
     else hipLaunchKernelGGL((prefill_mfma_kernel<128, 2, 1>), grid, dim3(128), 0, stream, p);
   } else {
-    if (d == 64) launch_rope_k<__bf16, 64>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
-    else launch_rope_k<__bf16, 128>(k, k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+    if (!in_place) {
+      if (d == 64) launch_rope_k<__bf16, 64>(k, (void*)k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+      else launch_rope_k<__bf16, 128>(k, (void*)k_rot, cu_seqlens, positions, batch, total_tokens, p.hkv, p.rope, cs, stream, n_layers, ls_k, ls_kr);
+    }
     // 128-row workgroups (two per CU) in the plain schedule up to medium lengths, where the ends of a workgroup's
     // life (first tile's latency, output store) and the causal diagonal weigh most; the pipelined 256-row kernel beyond
     const int rows_set = tuning(kTunePrefillBlockRows, 0);

@@ -517,3 +517,41 @@ def test_beam_topk_equals_a_stable_sort_and_breaks_ties_by_index():
     # fewer candidates than beams: the rest is empty
     r = O.beam_topk(None, [[0.3], [0.1], [0.2]], 1, 3, 1)
     assert r["parent"].tolist() == [0, 2, 1] and r["token"].tolist() == [0, 0, 0]
+
+
+# ----------------------------------------------------------------------------------------------
+# projections (Appendix A.2)
+# ----------------------------------------------------------------------------------------------
+def test_qkv_projection_with_rotation():
+    rows, dm, hq, hkv, d = 23, 48, 4, 2, 16
+    x, w = RNG.standard_normal((rows, dm)), RNG.standard_normal((dm, (hq + 2 * hkv) * d))
+    pos = RNG.integers(0, 5000, size=rows)
+    res = O.qkv_project(x, w, hq, hkv, d, pos)
+    # library matmul in torch + the complex-multiplication form of the rotation
+    y = (torch.from_numpy(x) @ torch.from_numpy(w)).numpy()
+    np.testing.assert_allclose(res["q"], rope_complex(y[:, : hq * d].reshape(rows, hq, d), pos, 10000.0), rtol=0, atol=1e-9)
+    np.testing.assert_allclose(res["k"], rope_complex(y[:, hq * d: (hq + hkv) * d].reshape(rows, hkv, d), pos, 10000.0),
+                               rtol=0, atol=1e-9)
+    np.testing.assert_allclose(res["v"], y[:, (hq + hkv) * d:].reshape(rows, hkv, d), rtol=0, atol=1e-12)   # V is not rotated
+    # position 0 and rope_base 0: the plain product; a selector matrix: rotated copies of x's columns
+    plain = O.qkv_project(x, w, hq, hkv, d, np.zeros(rows, dtype=np.int32))
+    np.testing.assert_allclose(plain["q"].reshape(rows, -1), y[:, : hq * d], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(O.qkv_project(x, w, hq, hkv, d, pos, rope_base=0.0)["k"], plain["k"], rtol=0, atol=1e-12)
+    sel = np.zeros((dm, (hq + 2 * hkv) * d)); sel[:16, hq * d: hq * d + 16] = np.eye(16)   # K head 0 = x[:, :16]
+    np.testing.assert_allclose(O.qkv_project(x, sel, hq, hkv, d, pos)["k"][:, 0], O.rope(x[:, None, :16], pos)[:, 0], atol=1e-12)
+    # feeding the attention oracle rotated projections with its own rotation off = feeding it the raw projections
+    cu = [0, 10, 23]
+    p2 = np.concatenate([np.arange(10), np.arange(13)])
+    raw = O.qkv_project(x, w, hq, hkv, d, p2, rope_base=0.0)
+    rot = O.qkv_project(x, w, hq, hkv, d, p2)
+    a = O.prefill_attn(raw["q"], raw["k"], raw["v"], cu)["out"]
+    b = O.prefill_attn(rot["q"], rot["k"], rot["v"], cu, rope_base=0.0)["out"]
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-10)
+
+
+def test_linear_and_silu_equal_the_library_routines():
+    x, w = RNG.standard_normal((9, 32)), RNG.standard_normal((32, 24))
+    np.testing.assert_allclose(O.linear(x, w), torch.nn.functional.linear(torch.from_numpy(x), torch.from_numpy(w).T).numpy(),
+                               rtol=0, atol=1e-12)
+    want = torch.nn.functional.silu(torch.from_numpy(x) @ torch.from_numpy(w)).numpy()
+    np.testing.assert_allclose(O.linear(x, w, 1), want, rtol=0, atol=1e-12)
