@@ -555,6 +555,42 @@ def decoder_layer(name: str, dev) -> dict:
     return out
 
 
+def attention_backward(name: str, dev) -> dict:
+    """earn_attn_backward (vector-ALU form) on the register-focused layers of `name` (compacted sequences of r rows) and
+    on one full-length layer of small_gqa: time and the rate of its algorithmic FLOPs, 10 d per causal (query, key) pair
+    and head (five products of 2 d: QK^T, dO V^T, P^T dO, dS K, dS^T Q), against the fp32 vector peak."""
+    from paper_2507_00715_amd import binding as B
+    out = {}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for label, cname, compacted in (("register_layer", name, True), ("small_gqa_full_layer", "small_gqa", False)):
+        c = W.CONFIGS[cname]
+        w = W.Workload(c)
+        lens = [c.r] * c.batch if compacted else w.seq_lengths
+        T = sum(lens)
+        rnd = lambda h_: torch.randn(T, h_, c.head_dim, device=dev).to(c.torch_dtype)
+        q, k, v, go = rnd(c.n_q_heads), rnd(c.n_kv_heads), rnd(c.n_kv_heads), rnd(c.n_q_heads)
+        cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device=dev)
+        desc = B.make_desc(c.torch_dtype, c.n_q_heads, c.n_kv_heads, c.head_dim, 0.0, 0.0)
+        o = torch.empty_like(q)
+        lse = torch.empty(T, c.n_q_heads, dtype=torch.float32, device=dev)
+        B.earn_prefill_attn(desc, q, k, v, cu, None, c.batch, T, max(lens), o, None, lse, None)
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        ws = torch.empty(T * c.n_q_heads * 4 + 256, dtype=torch.uint8, device=dev)
+        call = lambda: B.earn_attn_backward(desc, q, k, v, o, lse, go, cu, c.batch, T, max(lens), dq, dk, dv, ws)
+        call()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / 5
+        flops = 10.0 * c.head_dim * c.n_q_heads * sum(n * (n + 1) // 2 for n in lens)
+        out[label] = {"workload": cname, "us": us, "tflops": flops / us / 1e6, "frac_of_fp32_vector_peak": flops / us / 1e6 / PEAK_F32_TFLOPS,
+                      "bound": "alu"}
+    return out
+
+
 def measured_peaks(dev) -> dict:
     """Ceilings measured in this process with the calibration micro-kernels of libearn_calib.so (plain loops, no
     attention code): what the published peaks come to on this machine under this power limit."""
@@ -754,6 +790,7 @@ def main():
     peaks = measured_peaks(dev)
     beams20 = beam_machinery(args.workload, dev) if cfg_has_decode(args.workload) else None
     layer = decoder_layer(args.workload, dev) if cfg.dtype == "bf16" else None
+    backward = attention_backward(args.workload, dev)
 
     traffic = measured_traffic(args.workload)
     pf = head["prefill_full_layer"]
@@ -784,6 +821,7 @@ def main():
         "attention_statistics": head["attention_statistics"],
         "beam_search_width_20": beams20,
         "decoder_layer_with_projections": layer,
+        "attention_backward": backward,
         "launch_floor_us": floor_us,
         "last_full_layer_register_rows_only": head["last_full_layer_register_rows_only"],
         "attention_only_vs_vanilla": head["attention_only_vs_vanilla"],

@@ -322,6 +322,27 @@ int earn_linear(const void* x, const void* w, int32_t rows, int32_t k, int32_t n
                 void* stream);
 
 /*
+ * Backward of the causal attention (paper Section 3.2, Training: the loss is differentiated through the same attention,
+ * over all tokens in layers l <= k and over register + target tokens in layers l > k; Eq. 3).  Inputs are the forward's,
+ * AS THE ATTENTION SAW THEM: q and k already rotated (q_out / k_out of earn_qkv_rope_project, or the k_rot_out of the
+ * forward), out and lse_out of earn_prefill_attn, and d_out = dLoss/dOut.  Computes
+ *   dq [total, Hq, d], dk, dv [total, Hkv, d]   (gradients with respect to the ROTATED q, k and to v; dk, dv summed over
+ *                                               the query heads of each kv head; the rotation's own backward belongs
+ *                                               to the projection's backward, which is not part of this library)
+ * in the tensors' element type, fp32 arithmetic.  For the register-focused layers pass the compacted tensors and cu_out.
+ * desc->rope_base must be <= 0 (nothing is rotated here); softmax_scale and q_to_kv as in the forward.
+ *   workspace: at least earn_attn_backward_workspace_bytes(desc, total_tokens) bytes (one float per (token, query head))
+ * Errors: NULL pointer, non-positive size -> INVALID_ARG; rope_base > 0 -> UNSUPPORTED; workspace -> WORKSPACE_TOO_SMALL.
+ * A first form on the vector ALU (no matrix cores): correct at any length, meant for the short sequences of the
+ * register-focused layers and for checking.
+ */
+int earn_attn_backward(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const void* out,
+                       const float* lse, const void* d_out, const int32_t* cu_seqlens, int32_t batch,
+                       int32_t total_tokens, int32_t max_seqlen, void* dq, void* dk, void* dv, void* workspace,
+                       size_t workspace_bytes, void* stream);
+size_t earn_attn_backward_workspace_bytes(const earn_attn_desc* desc, int32_t total_tokens);
+
+/*
  * Beam search around the decode step (paper Appendix, implementation details: inference decodes with beam search, beam
  * size 20).  The attention path has no logits; these calls take the per-beam token log-probabilities from the caller.
  *

@@ -395,3 +395,66 @@ int oracle_beam_topk(const float *beam_scores, const float *token_logprobs, int3
     free(cand);
     return ORC_OK;
 }
+
+/*
+ * Backward of the causal attention of Eq. 3 (what training, Section 3.2, differentiates through), for queries and keys
+ * AS THE ATTENTION SAW THEM (already rotated; this function rotates nothing).  For every sequence, query head a and its
+ * kv head c, with P the materialised causal softmax of scale * Q K^T:
+ *   dV += P^T dO;   dP = dO V^T;   dS = P o (dP - rowsum(dP o P));   dQ = scale dS K;   dK += scale dS^T Q
+ * (dK, dV sum over the query heads that share the kv head).  q, d_out, dq [T,Hq,d]; k, v, dk, dv [T,Hkv,d].
+ * The row sum is taken as rowsum(dP o P), the definition of the softmax Jacobian, not as rowsum(dO o O).
+ */
+int oracle_attn_backward(const double *q, const double *k, const double *v, const double *d_out,
+                         const int32_t *cu_seqlens, int32_t batch, int32_t hq, int32_t hkv, int32_t d,
+                         const int32_t *q_to_kv, double scale, double *dq, double *dk, double *dv)
+{
+    if (!q || !k || !v || !d_out || !cu_seqlens || !dq || !dk || !dv || batch <= 0) return ORC_BAD_ARG;
+    int rc = check_heads(hq, hkv, d, q_to_kv);
+    if (rc) return rc;
+    if (scale <= 0.0) scale = 1.0 / sqrt((double)d);
+    int64_t total = cu_seqlens[batch];
+    memset(dk, 0, sizeof(double) * (size_t)total * hkv * d);
+    memset(dv, 0, sizeof(double) * (size_t)total * hkv * d);
+    for (int s = 0; s < batch; ++s) {
+        int64_t b0 = cu_seqlens[s], n = cu_seqlens[s + 1] - b0;
+        if (n <= 0) continue;
+        double *sc = (double *)malloc(sizeof(double) * (size_t)n * 3);
+        if (!sc) return ORC_NO_MEM;
+        double *pr = sc + n, *dp = sc + 2 * n;
+        for (int a = 0; a < hq; ++a) {
+            int c = kv_head_of(a, hq, hkv, q_to_kv);
+            for (int64_t i = 0; i < n; ++i) {
+                const double *qi = q + ((b0 + i) * hq + a) * d, *gi = d_out + ((b0 + i) * hq + a) * d;
+                for (int64_t j = 0; j <= i; ++j) {
+                    const double *kj = k + ((b0 + j) * hkv + c) * d;
+                    double acc = 0.0;
+                    for (int e = 0; e < d; ++e) acc += qi[e] * kj[e];
+                    sc[j] = acc * scale;
+                }
+                softmax_row(sc, i + 1, pr);
+                double rowsum = 0.0;
+                for (int64_t j = 0; j <= i; ++j) {
+                    const double *vj = v + ((b0 + j) * hkv + c) * d;
+                    double acc = 0.0;
+                    for (int e = 0; e < d; ++e) acc += gi[e] * vj[e];
+                    dp[j] = acc;
+                    rowsum += acc * pr[j];
+                }
+                double *dqi = dq + ((b0 + i) * hq + a) * d;
+                for (int e = 0; e < d; ++e) dqi[e] = 0.0;
+                for (int64_t j = 0; j <= i; ++j) {
+                    double ds = pr[j] * (dp[j] - rowsum);
+                    const double *kj = k + ((b0 + j) * hkv + c) * d;
+                    double *dkj = dk + ((b0 + j) * hkv + c) * d, *dvj = dv + ((b0 + j) * hkv + c) * d;
+                    for (int e = 0; e < d; ++e) {
+                        dqi[e] += scale * ds * kj[e];
+                        dkj[e] += scale * ds * qi[e];
+                        dvj[e] += pr[j] * gi[e];
+                    }
+                }
+            }
+        }
+        free(sc);
+    }
+    return ORC_OK;
+}

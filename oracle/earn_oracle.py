@@ -237,6 +237,21 @@ def linear(x, w, activation: int = 0) -> np.ndarray:
     return y / (1.0 + np.exp(-y)) if activation == 1 else y
 
 
+def attn_backward(q, k, v, d_out, cu_seqlens, q_to_kv=None, scale: float = 0.0) -> dict:
+    """Gradients of the causal attention with respect to q, k (as the attention saw them: rotated) and v."""
+    q, k, v, g = _f64(q), _f64(k), _f64(v), _f64(d_out)
+    cu = _i32(cu_seqlens)
+    T, hq, d = q.shape
+    hkv = k.shape[1]
+    dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
+    fn = lib().oracle_attn_backward
+    fn.restype = ctypes.c_int
+    rc = fn(_d(q), _d(k), _d(v), _d(g), _i(cu), len(cu) - 1, hq, hkv, d, _i(_i32(q_to_kv)), ctypes.c_double(scale),
+            _d(dq), _d(dk), _d(dv))
+    _check(rc, "attn_backward")
+    return {"dq": dq, "dk": dk, "dv": dv}
+
+
 def cache_entries(n_layers: int, split_k: int, n: int, r: int, gen: int = 0) -> int:
     return int(lib().oracle_cache_entries(n_layers, split_k, n, r, gen))
 

@@ -28,7 +28,8 @@ EXPORTS = ["earn_last_error", "earn_version", "earn_prefill_attn", "earn_prefill
            "earn_prefill_register_rows", "earn_prefill_register_rows_workspace_bytes", "earn_set_validation",
            "earn_set_tuning", "earn_decode_attn_static", "earn_prefill_attn_layers", "earn_decode_attn_layers",
            "earn_decode_layers_workspace_bytes", "earn_decode_step_positions", "earn_attn_stats", "earn_beam_topk", "earn_beam_topk_workspace_bytes",
-           "earn_beam_reorder", "earn_decode_attn_beams", "earn_qkv_rope_project", "earn_linear"]
+           "earn_beam_reorder", "earn_decode_attn_beams", "earn_qkv_rope_project", "earn_linear", "earn_attn_backward",
+           "earn_attn_backward_workspace_bytes"]
 EARN_STATIC_SCRATCH_BYTES = 8 << 20
 
 
@@ -93,6 +94,11 @@ def lib():
         L.earn_qkv_rope_project.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
         L.earn_linear.restype = ctypes.c_int
         L.earn_linear.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
+        L.earn_attn_backward.restype = ctypes.c_int
+        L.earn_attn_backward.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp,
+                                         sz, vp]
+        L.earn_attn_backward_workspace_bytes.restype = sz
+        L.earn_attn_backward_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), i32]
         L.earn_prefill_register_rows.restype = ctypes.c_int
         L.earn_prefill_register_rows.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp,
                                                  vp, sz, vp]
@@ -315,6 +321,17 @@ def earn_linear(x, w, out, activation: int = 0) -> None:
     n = w.shape[1]
     assert w.shape[0] == k and tuple(out.shape) == (rows, n)
     _check(lib().earn_linear(_ptr(x), _ptr(w), rows, k, n, activation, _ptr(out), _stream()))
+
+
+def earn_attn_backward(desc: AttnDesc, q, k, v, out, lse, d_out, cu_seqlens, batch: int, total_tokens: int,
+                       max_seqlen: int, dq, dk, dv, workspace=None) -> None:
+    if workspace is None:
+        need = int(lib().earn_attn_backward_workspace_bytes(ctypes.byref(desc), total_tokens))
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check(lib().earn_attn_backward(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(d_out),
+                                    _ptr(cu_seqlens), batch, total_tokens, max_seqlen, _ptr(dq), _ptr(dk), _ptr(dv),
+                                    _ptr(workspace), ws_bytes, _stream()))
 
 
 def _layer_stride(t: Optional[torch.Tensor]) -> int:

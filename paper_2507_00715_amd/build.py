@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libearn.so")
 CALIB_LIB = os.path.join(HERE, "libearn_calib.so")   # the benchmark's calibration micro-kernels: not in libearn.so
-SOURCES = ["api.hip", "compact.hip", "decode.hip", "prefill.hip", "stats.hip", "beam.hip", "linear.hip"]
+SOURCES = ["api.hip", "compact.hip", "decode.hip", "prefill.hip", "stats.hip", "beam.hip", "linear.hip", "backward.hip"]
 CALIB_SOURCES = ["calib.hip"]
 # packed fp32 VALU ops are switched off for every device compilation (they have misbehaved on these machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -32,7 +32,7 @@ def _compile(src: str, extra) -> str:
 
 def build(extra_flags=(), verbose: bool = True) -> str:
     """Compile every source (always recompiles) and link libearn.so. Returns its path."""
-    with concurrent.futures.ThreadPoolExecutor(max_workers=8) as ex:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=9) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES + CALIB_SOURCES))
     n = len(SOURCES)
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs[:n]], check=True)

@@ -76,6 +76,10 @@ int launch_linear(const void* x, const void* w, int rows, int k, int n, int acti
 int launch_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void* w_qkv, int rows, int d_model,
                             const int32_t* cu_seqlens, const int32_t* positions, int batch, void* q_out, void* k_out,
                             void* v_out, hipStream_t stream);
+size_t attn_backward_workspace_bytes(int hq, int total_tokens);
+int launch_attn_backward(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const void* out,
+                         const float* lse, const void* d_out, const int32_t* cu_seqlens, int batch, int total_tokens,
+                         int max_seqlen, void* dq, void* dk, void* dv, void* workspace, hipStream_t stream);
 int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, const int32_t* cu_seqlens,
                      const int32_t* positions, int batch, int total_tokens, hipStream_t stream);
 int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
@@ -591,6 +595,42 @@ int earn_linear(const void* x, const void* w, int32_t rows, int32_t k, int32_t n
     return EARN_ERR_INVALID_ARG;
   }
   return launch_linear(x, w, rows, k, n, activation, out, (hipStream_t)stream);
+}
+
+size_t earn_attn_backward_workspace_bytes(const earn_attn_desc* desc, int32_t total_tokens) {
+  if (check_desc(desc, "earn_attn_backward_workspace_bytes") != EARN_OK || total_tokens <= 0) return 0;
+  return attn_backward_workspace_bytes(desc->n_q_heads, total_tokens);
+}
+
+int earn_attn_backward(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const void* out,
+                       const float* lse, const void* d_out, const int32_t* cu_seqlens, int32_t batch,
+                       int32_t total_tokens, int32_t max_seqlen, void* dq, void* dk, void* dv, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  g_err[0] = 0;
+  int rc = check_desc(desc, "earn_attn_backward");
+  if (rc != EARN_OK) return rc;
+  if (desc->rope_base > 0.f) {
+    set_error("earn_attn_backward: takes rotated q and k and rotates nothing: set rope_base <= 0");
+    return EARN_ERR_UNSUPPORTED;
+  }
+  if (!q || !k || !v || !out || !lse || !d_out || !cu_seqlens || !dq || !dk || !dv || batch <= 0 || total_tokens <= 0 ||
+      max_seqlen <= 0) {
+    set_error("earn_attn_backward: NULL pointer or non-positive size (batch %d, total_tokens %d, max_seqlen %d)", batch, total_tokens, max_seqlen);
+    return EARN_ERR_INVALID_ARG;
+  }
+  const size_t need = attn_backward_workspace_bytes(desc->n_q_heads, total_tokens);
+  if (need > workspace_bytes || !workspace) {
+    set_error("earn_attn_backward: workspace too small (%zu bytes given, %zu needed)", workspace_bytes, need);
+    return EARN_ERR_WORKSPACE_TOO_SMALL;
+  }
+  if (g_validate.load(std::memory_order_relaxed)) {
+    std::vector<int32_t> cu;
+    if ((rc = fetch_i32(cu_seqlens, (size_t)batch + 1, cu, (hipStream_t)stream, "earn_attn_backward")) != EARN_OK) return rc;
+    if ((rc = validate_cu("earn_attn_backward", "cu_seqlens", cu, batch, total_tokens, max_seqlen)) != EARN_OK) return rc;
+  }
+  if (max_seqlen > total_tokens) max_seqlen = total_tokens;
+  return launch_attn_backward(desc, q, k, v, out, lse, d_out, cu_seqlens, batch, total_tokens, max_seqlen, dq, dk, dv,
+                              workspace, (hipStream_t)stream);
 }
 
 int64_t earn_cache_entries(int32_t n_layers, int32_t split_k, int64_t seq_len, int32_t n_registers, int64_t gen) {

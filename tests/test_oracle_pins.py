@@ -555,3 +555,34 @@ def test_linear_and_silu_equal_the_library_routines():
                                rtol=0, atol=1e-12)
     want = torch.nn.functional.silu(torch.from_numpy(x) @ torch.from_numpy(w)).numpy()
     np.testing.assert_allclose(O.linear(x, w, 1), want, rtol=0, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------------------------
+# backward of the attention (Section 3.2, Training)
+# ----------------------------------------------------------------------------------------------
+def test_attention_backward_equals_autograd_of_the_library_attention():
+    lens, hq, hkv, d = [1, 17, 40], 6, 2, 16
+    q, k, v, cu = rand_batch(lens, hq, hkv, d)
+    g = RNG.standard_normal(q.shape)
+    res = O.attn_backward(q, k, v, g, cu, scale=0.3)
+    for s in range(len(lens)):
+        sl = slice(cu[s], cu[s + 1])
+        tq = torch.from_numpy(q[sl]).clone().requires_grad_(True)
+        tk = torch.from_numpy(k[sl]).clone().requires_grad_(True)
+        tv = torch.from_numpy(v[sl]).clone().requires_grad_(True)
+        rep = lambda t: t.repeat_interleave(hq // hkv, dim=1).permute(1, 0, 2)[None]
+        o = torch.nn.functional.scaled_dot_product_attention(tq.permute(1, 0, 2)[None], rep(tk), rep(tv), is_causal=True, scale=0.3)
+        o.backward(torch.from_numpy(g[sl]).permute(1, 0, 2)[None])
+        np.testing.assert_allclose(res["dq"][sl], tq.grad.numpy(), rtol=0, atol=1e-11)
+        np.testing.assert_allclose(res["dk"][sl], tk.grad.numpy(), rtol=0, atol=1e-11)     # summed over the group's heads
+        np.testing.assert_allclose(res["dv"][sl], tv.grad.numpy(), rtol=0, atol=1e-11)
+    # a central difference of the forward oracle through one element of each input
+    f = lambda qq, kk, vv: float((O.prefill_attn(qq, kk, vv, cu, scale=0.3, rope_base=0.0)["out"] * g).sum())
+    for name, arr, grad, at in (("q", q, res["dq"], (30, 4, 3)), ("k", k, res["dk"], (20, 1, 7)), ("v", v, res["dv"], (5, 0, 2))):
+        hi, lo = arr.copy(), arr.copy()
+        hi[at] += 1e-5
+        lo[at] -= 1e-5
+        args = {"q": (hi, k, v), "k": (q, hi, v), "v": (q, k, hi)}[name], {"q": (lo, k, v), "k": (q, lo, v), "v": (q, k, lo)}[name]
+        assert abs((f(*args[0]) - f(*args[1])) / 2e-5 - grad[at]) < 1e-6, name
+    # the explicit head map reaches the backward as well
+    assert np.abs(O.attn_backward(q, k, v, g, cu, q_to_kv=[1, 1, 0, 0, 1, 0])["dk"] - O.attn_backward(q, k, v, g, cu)["dk"]).max() > 1e-3
