@@ -501,8 +501,9 @@ def decoder_layer(name: str, dev) -> dict:
     bf = torch.bfloat16
     g = torch.Generator(device=dev).manual_seed(1)
     rnd = lambda *shape, sc=1.0: (torch.randn(*shape, device=dev, generator=g) * sc).to(bf)
-    w_qkv, w_o = rnd(dm, (hq + 2 * hkv) * d, sc=dm ** -0.5), rnd(hq * d, dm, sc=dm ** -0.5)
-    w_up, w_down = rnd(dm, df, sc=dm ** -0.5), rnd(df, dm, sc=df ** -0.5)
+    # weights as [outputs, inputs]
+    w_qkv, w_o = rnd((hq + 2 * hkv) * d, dm, sc=dm ** -0.5), rnd(dm, hq * d, sc=dm ** -0.5)
+    w_up, w_down = rnd(df, dm, sc=dm ** -0.5), rnd(dm, df, sc=df ** -0.5)
     desc = B.make_desc(bf, hq, hkv, d, 0.0, c.rope_base)
     desc0 = B.make_desc(bf, hq, hkv, d, 0.0, 0.0)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -540,6 +541,9 @@ def decoder_layer(name: str, dev) -> dict:
                  "ffn_up_silu": 2.0 * rows * dm * df, "ffn_down": 2.0 * rows * df * dm}
         t["gemm_tflops"] = {k_: flops[k_] / (t[k_ + "_ms"] * 1e-3) / 1e12 for k_ in flops}
         t["gemm_frac_of_bf16_peak"] = {k_: v_ / PEAK_BF16_TFLOPS for k_, v_ in t["gemm_tflops"].items()}
+        # context only: the vendor library's GEMM (through torch.matmul) on the feed-forward shape, no activation
+        lib_ms = ms(lambda: torch.matmul(x, w_up.t(), out=hmid))
+        t["library_matmul_ffn_up_tflops"] = flops["ffn_up_silu"] / (lib_ms * 1e-3) / 1e12
         out[label] = t
         totals[label] = t["layer_ms"]
         del x, q, k, v, o, y, hmid

@@ -89,6 +89,7 @@ int earn_set_validation(int enabled);
  *   "decode_vec_wgs"        workgroups the vector decode kernel's key splits aim at (1024)
  *   "decode_vec_waves"      waves per workgroup of the vector decode kernel (1, 2 or 4)
  *   "compact_blocks"        16 KB blocks one compaction workgroup copies (1..4)
+ *   "linear_tile"           1 | 2: output tile of the projection GEMMs, 256 x 128 (1) or 256 x 256 (2); default by size
  */
 int earn_set_tuning(const char* key, int32_t value);
 
@@ -299,21 +300,23 @@ size_t earn_prefill_register_rows_workspace_bytes(const earn_attn_desc* desc, in
  * The dense projections of a decoder layer (paper Appendix A.2: per head, Q/K/V projections 3 x 2 L d_h d_a and the output
  * projection 2 L d_a d_h; feed-forward block, two projections, 4 L d_h d_f), bf16 with fp32 accumulation.
  *
- * earn_qkv_rope_project: [rows, d_model] x [d_model, (Hq + 2 Hkv) d] -> Q, K, V, with the rotary embedding applied to the
+ * earn_qkv_rope_project: [rows, d_model] x [(Hq + 2 Hkv) d, d_model]^T -> Q, K, V, with the rotary embedding applied to the
  * Q and K columns at each row's ORIGINAL position in the epilogue (same convention as earn_prefill_attn: half-split
  * pairs, theta_e = rope_base^(-2e/d); rope_base <= 0: no rotation).  k_out is what the layer's key cache stores, so the
  * attention entry points are then called with rope_base = 0 and, for the prefill, k_rot_out = NULL: they read q_out /
  * k_out as they are and run no rotation pass.  Rows of the register-focused layers (Section 3.2) are the gathered hidden
  * rows, with positions = pos_out of earn_compact_registers; decode rows are the new tokens with positions = q_pos.
- *   x          device, [rows, d_model] bf16           w_qkv   device, [d_model, (Hq + 2 Hkv) d] bf16, row-major; columns:
+ *   x          device, [rows, d_model] bf16           w_qkv   device, [(Hq + 2 Hkv) d, d_model] bf16, one row per output
+ *                                                             (the layout checkpoints keep a linear layer's weight in):
  *                                                             the Q heads, then the K heads, then the V heads
  *   positions  device, [rows] int32 or NULL; NULL: row i of sequence s has position i - cu_seqlens[s] (cu_seqlens, batch
  *              required then)
  *   q_out      device, [rows, Hq, d];  k_out, v_out  device, [rows, Hkv, d]
- * earn_linear: out[rows, n] = act(x[rows, k] w[k, n]), activation 0 = none, 1 = SiLU (x / (1 + e^-x)); bf16.
+ * earn_linear: out[rows, n] = act(x[rows, k] w[n, k]^T), activation 0 = none, 1 = SiLU (x / (1 + e^-x)); bf16; w holds
+ * one row of k inputs per output.
  * Errors: NULL pointer, non-positive size, positions and cu_seqlens both NULL with rotation on -> INVALID_ARG;
  * desc->dtype != EARN_BF16, an inner dimension that is not a multiple of 64, an output width that is not a multiple of
- * 8, a weight matrix of 2 GiB or more -> UNSUPPORTED.  Enqueue on `stream`, allocate nothing.
+ * 8, 256 rows of the inner dimension reaching 2 GiB -> UNSUPPORTED.  Enqueue on `stream`, allocate nothing.
  */
 int earn_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void* w_qkv, int32_t rows, int32_t d_model,
                           const int32_t* cu_seqlens, const int32_t* positions, int32_t batch, void* q_out, void* k_out,

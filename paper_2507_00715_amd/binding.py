@@ -311,15 +311,18 @@ def earn_decode_attn_beams(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, sha
 
 
 def earn_qkv_rope_project(desc: AttnDesc, x, w_qkv, cu_seqlens, positions, batch: int, q_out, k_out, v_out) -> None:
+    """w_qkv: [(Hq + 2 Hkv) d, d_model], outputs x inputs (the layout of a torch.nn.Linear weight)."""
     rows, d_model = x.shape
+    assert tuple(w_qkv.shape) == ((desc.n_q_heads + 2 * desc.n_kv_heads) * desc.head_dim, d_model)
     _check(lib().earn_qkv_rope_project(ctypes.byref(desc), _ptr(x), _ptr(w_qkv), rows, d_model, _ptr(cu_seqlens),
                                        _ptr(positions), batch, _ptr(q_out), _ptr(k_out), _ptr(v_out), _stream()))
 
 
 def earn_linear(x, w, out, activation: int = 0) -> None:
+    """w: [n, k], outputs x inputs (the layout of a torch.nn.Linear weight)."""
     rows, k = x.shape
-    n = w.shape[1]
-    assert w.shape[0] == k and tuple(out.shape) == (rows, n)
+    n = w.shape[0]
+    assert w.shape[1] == k and tuple(out.shape) == (rows, n)
     _check(lib().earn_linear(_ptr(x), _ptr(w), rows, k, n, activation, _ptr(out), _stream()))
 
 

@@ -201,7 +201,7 @@ int earn_set_validation(int enabled) { return g_validate.exchange(enabled ? 1 : 
 
 int earn_set_tuning(const char* key, int32_t value) {
   static const char* const names[kTuneCount] = {"prefill_block_rows", "decode_mfma_min_len", "decode_mfma_short_wgs",
-                                                "decode_mfma_wgs", "decode_vec_wgs", "decode_vec_waves", "compact_blocks"};
+                                                "decode_mfma_wgs", "decode_vec_wgs", "decode_vec_waves", "compact_blocks", "linear_tile"};
   g_err[0] = 0;
   for (int i = 0; key && i < kTuneCount; ++i)
     if (strcmp(key, names[i]) == 0) { g_tuning[i].store(value > 0 ? value : 0, std::memory_order_relaxed); return EARN_OK; }

@@ -48,8 +48,10 @@ struct DecodeLayers { int n_layers; long long q, kv_new, shared, gen, out; };
 struct PrefillLayers { int n_layers; long long q, kv, out, k_rot, lse; };
 
 // launch-shape overrides (earn_set_tuning); 0 = default
+constexpr int kXcds = 8;  // accelerator complex dies, each with a private L2; consecutive workgroup ids go to them in turn
+
 enum Tuning { kTunePrefillBlockRows, kTuneDecMfmaMinLen, kTuneDecMfmaShortWgs, kTuneDecMfmaWgs, kTuneDecVecWgs,
-              kTuneDecVecWaves, kTuneCompactBlocks, kTuneCount };
+              kTuneDecVecWaves, kTuneCompactBlocks, kTuneLinearTile, kTuneCount };
 int tuning(Tuning t, int dflt);
 
 __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) { return __uint_as_float(((unsigned int)b) << 16); }

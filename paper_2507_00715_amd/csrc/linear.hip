@@ -1,18 +1,18 @@
 // The dense projections around the attention (paper Appendix A.2: per layer, Q/K/V/output projections 8 L d_h d_a FLOPs
 // per head and the feed-forward block 4 L d_h d_f) as one bf16 matrix-core GEMM kernel with two epilogues:
-//   earn_qkv_rope_project  [rows, d_model] x [d_model, (Hq + 2 Hkv) d]: rotates the Q and K columns at each token's
+//   earn_qkv_rope_project  [rows, d_model] x [(Hq + 2 Hkv) d, d_model]^T: rotates the Q and K columns at each token's
 //                          ORIGINAL position in the epilogue and writes Q, the rotated K (= the layer's key cache) and V
 //                          straight into their [rows, heads, d] tensors, so the attention that follows needs no rotation
 //                          pass of its own (it is then called with rotation switched off);
-//   earn_linear            [rows, k] x [k, n] with an optional SiLU (output projection, feed-forward matrices).
+//   earn_linear            [rows, k] x [n, k]^T with an optional SiLU (output projection, feed-forward matrices).
+// Weights are [outputs][inputs], the inner dimension contiguous (the layout checkpoints store them in): activations and
+// weights then both deliver MFMA fragments as plain 16-byte LDS reads, 8 consecutive inner indices per lane.
 //
-// Tiling.  The kernel computes C^T = W^T X^T with v_mfma_f32_32x32x16_bf16, the same shape as the second product of the
-// attention kernels (O^T = V^T P^T): the weight tile [64 k][128 n] plays V (kept in its natural layout, read with
-// transposing LDS reads as the A operand), the activation tile [256 rows][64 k] supplies the B operand.  The transposing
-// reads deliver the inner index of a 16-step in the order {4 hf .. 4 hf + 3, 8 + 4 hf .. 8 + 4 hf + 3} per half wave, so
-// the activation fragments are read in the same order: two 8-byte reads instead of one 16-byte read.  A workgroup of 4 waves owns 256 rows x 128 columns; each wave 64 rows x 128 columns (8 accumulator
-// tiles), so every weight fragment read feeds two MFMAs.  Tiles stream from global memory straight into a ring of three
-// LDS stages (two tiles in flight); rows past the end of the activations read as zeros through the buffer descriptor.
+// Tiling.  The kernel computes C^T = W X^T with v_mfma_f32_32x32x16_bf16: the weight tile [128 n][64 k] supplies the A
+// operand, the activation tile [256 rows][64 k] the B operand.  A workgroup of 4 waves owns 256 rows x 128 columns; each
+// wave 64 rows x 128 columns (8 accumulator tiles), so every weight fragment read feeds two MFMAs.  Tiles stream from
+// global memory straight into a ring of three LDS stages (two tiles in flight); rows past the end of the activations
+// and weight rows past the last output read as zeros through the buffer descriptors.
 // The accumulator layout gives a lane ONE row and, per 32-column block, columns 8 j + 4 hf + (0..3): the two elements of
 // a rotary pair (e, e + d/2) sit in the same lane, two (d = 128) or one (d = 64) column blocks apart, so the rotation
 // is lane-private.
@@ -23,7 +23,17 @@
 
 namespace earn {
 
-constexpr int kLinRows = 256, kLinCols = 128, kLinK = 64, kLinStages = 3, kLinWaves = 4;
+constexpr int kLinRows = 256;  // rows of a workgroup's tile
+constexpr int kLinPatchRows = 4, kLinPatchCols = 8, kLinPatch = kLinPatchRows * kLinPatchCols;  // tiles an XCD works on together
+constexpr int kLinKMultiple = 64;  // the inner dimension must be a multiple of this
+
+// chunk swizzle of a tile whose rows hold KT inner indices (KT / 8 chunks of 16 bytes): 64 -> the attention tiles' own
+// pattern; 32 -> four rows share 256 bytes of LDS, and rows 4 apart must land on different chunk positions
+template <int KT>
+__device__ __forceinline__ int lin_swz(int row) {
+  if constexpr (KT == 64) return swz<64>(row);
+  else return (row >> 2) & 3;
+}
 
 struct LinearParams {
   const __bf16* x; const __bf16* w;
@@ -35,103 +45,159 @@ struct LinearParams {
   RopeTable rope;
 };
 
-template <int EPI, int D>
-__global__ __launch_bounds__(64 * kLinWaves, 1) void linear_kernel(LinearParams p) {
+// RB: 32-row blocks per wave (the tile's 256 rows are shared by 8 / RB row groups of waves); WC: 128-column groups of
+// the tile (waves = 8 / RB x WC); KT: inner indices per LDS stage; STAGES: LDS ring depth (STAGES - 1 tiles in flight)
+template <int EPI, int D, int RB, int WC, int KT, int STAGES>
+__global__ __launch_bounds__(64 * (8 / RB) * WC, 1) void linear_kernel(LinearParams p) {
+  constexpr int WR = 8 / RB;
+  constexpr int kLinCols = 128 * WC, kLinWaves = WR * WC, kLinStages = STAGES, kLinK = KT;
+  constexpr int CPR = KT / 8, RPI = kWave / CPR;  // chunks per tile row, tile rows per load instruction
   __shared__ __bf16 smx[kLinStages][kLinRows * kLinK];   // 32 KB per stage
-  __shared__ __bf16 smw[kLinStages][kLinK * kLinCols];   // 16 KB per stage
+  __shared__ __bf16 smw[kLinStages][kLinCols * kLinK];   // 16 KB per stage and column group
   const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int wr = wave % WR, wc = wave / WR;              // this wave's 32 RB rows and 128 columns of the tile
   const int r32 = lane & 31, hf = lane >> 5;
-  // column tiles vary fastest: the workgroups that run together share the activation rows in L2
-  const int n_ct = (p.n + kLinCols - 1) / kLinCols;
-  const int ct = blockIdx.x % n_ct, rt = blockIdx.x / n_ct;
-  const int m0 = rt * kLinRows, n0 = ct * kLinCols;
+  // Workgroup -> tile.  Consecutive workgroup ids go to the 8 XCDs in turn, each with an L2 of its own and 32 CUs: the
+  // 32 workgroups an XCD runs side by side are given a patch of kLinPatchRows x kLinPatchCols tiles, so that the XCD
+  // fetches 4 activation and 8 weight tile slices per step for 32 workgroups instead of one of each per workgroup.
+  const int n_ct = (p.n + kLinCols - 1) / kLinCols, n_rt = (p.rows + kLinRows - 1) / kLinRows;
+  // The tile rows and columns are dealt to the patches in equal shares (a patch is up to 4 x 8 tiles, not exactly):
+  // patches of equal work keep the XCDs, which take them in turn, busy for the same time.
+  const int n_pc = (n_ct + kLinPatchCols - 1) / kLinPatchCols, n_pr = (n_rt + kLinPatchRows - 1) / kLinPatchRows;
+  const int xcd = blockIdx.x % kXcds, i_in_xcd = blockIdx.x / kXcds;
+  const int patch = (i_in_xcd / kLinPatch) * kXcds + xcd, within = i_in_xcd % kLinPatch;
+  const int pr = patch / n_pc, pc = patch % n_pc;
+  if (pr >= n_pr) return;
+  const int rt = (int)((long long)pr * n_rt / n_pr) + within % kLinPatchRows;
+  const int ct = (int)((long long)pc * n_ct / n_pc) + within / kLinPatchRows;
+  if (rt >= (int)((long long)(pr + 1) * n_rt / n_pr) || ct >= (int)((long long)(pc + 1) * n_ct / n_pc)) return;
+  const int m0 = rt * kLinRows, n0_wg = ct * kLinCols, n0 = n0_wg + 128 * wc;
   const int n_kt = p.k / kLinK;
+  static_assert(STAGES >= 2 && STAGES <= 5);
 
   // ---- staging ----
-  const int x_pitch = p.k * 2, w_pitch = p.n * 2;  // bytes
-  const int rows_here = min(kLinRows, p.rows - m0);
+  const int x_pitch = p.k * 2;  // bytes, of activation and weight rows alike
+  const int rows_here = min(kLinRows, p.rows - m0), cols_here = min(kLinCols, p.n - n0_wg);
   const u32x4 x_rsrc = raw_buffer(p.x + (long long)m0 * p.k, rows_here * x_pitch);
-  // weights: rows kt*64.. of all columns from n0 on; the range ends with the matrix (columns past n are never stored)
-  const long long w_bytes = (long long)p.k * w_pitch - (long long)n0 * 2;
-  const u32x4 w_rsrc = raw_buffer(p.w + n0, (int)(w_bytes < 0x7fffffffLL ? w_bytes : 0x7fffffffLL));
-  constexpr int XI = kLinRows * (kLinK / 8) / kWave / kLinWaves;   // 8 instructions per wave and tile
-  constexpr int WI = kLinK * (kLinCols / 8) / kWave / kLinWaves;   // 4
+  const u32x4 w_rsrc = raw_buffer(p.w + (long long)n0_wg * p.k, cols_here * x_pitch);
+  constexpr int XI = kLinRows * (kLinK / 8) / kWave / kLinWaves;   // instructions per wave and tile
+  constexpr int WI = kLinCols * (kLinK / 8) / kWave / kLinWaves;
+  static_assert(XI >= 1 && WI >= 1);
   int x_voff[XI], w_voff[WI];
 #pragma unroll
   for (int i = 0; i < XI; ++i) {
-    const int row = 8 * (wave + kLinWaves * i) + lane / 8;          // 8 rows of 8 units per instruction
-    x_voff[i] = row * x_pitch + ((lane % 8) ^ swz<64>(row)) * 16;
+    const int row = RPI * (wave + kLinWaves * i) + lane / CPR;
+    x_voff[i] = row * x_pitch + ((lane % CPR) ^ lin_swz<KT>(row)) * 16;
   }
 #pragma unroll
   for (int i = 0; i < WI; ++i) {
-    const int row = 4 * (wave + kLinWaves * i) + lane / 16;         // 4 rows of 16 units per instruction
-    w_voff[i] = row * w_pitch + ((lane % 16) ^ swz<128>(row)) * 16;
+    const int row = RPI * (wave + kLinWaves * i) + lane / CPR;
+    w_voff[i] = row * x_pitch + ((lane % CPR) ^ lin_swz<KT>(row)) * 16;
   }
   const unsigned lds_x = (unsigned)(size_t)(lds_void_ptr)&smx[0][0], lds_w = (unsigned)(size_t)(lds_void_ptr)&smw[0][0];
-  auto issue_tile = [&](int kt) {
+  constexpr int LPT = XI + WI;  // loads per wave and tile
+  // load j (0 .. LPT-1) of this wave's share of tile kt
+  auto issue_part = [&](int kt, int j) {
     const unsigned sx = lds_x + (unsigned)((kt % kLinStages) * kLinRows * kLinK * 2);
     const unsigned sw = lds_w + (unsigned)((kt % kLinStages) * kLinK * kLinCols * 2);
 #pragma unroll
-    for (int i = 0; i < XI; ++i) dma16_to_lds(x_rsrc, sx + (unsigned)((wave + kLinWaves * i) * 1024), x_voff[i] + kt * (kLinK * 2));
+    for (int i = 0; i < XI; ++i)
+      if (j == i) dma16_to_lds(x_rsrc, sx + (unsigned)((wave + kLinWaves * i) * 1024), x_voff[i] + kt * (kLinK * 2));
 #pragma unroll
-    for (int i = 0; i < WI; ++i) dma16_to_lds(w_rsrc, sw + (unsigned)((wave + kLinWaves * i) * 1024), w_voff[i] + kt * kLinK * w_pitch);
+    for (int i = 0; i < WI; ++i)
+      if (j == XI + i) dma16_to_lds(w_rsrc, sw + (unsigned)((wave + kLinWaves * i) * 1024), w_voff[i] + kt * (kLinK * 2));
   };
-  constexpr int LPT = XI + WI;  // loads per wave and tile
-  issue_tile(0);
-  if (n_kt > 1) issue_tile(1);
-
-  FragOffsets<128> fw;   // weight fragments: transposing reads on rows of 128 columns
-  fw.init(lane);
-  // activation fragments: row r32 of a 32-row block, inner indices 16 ks + {4 hf + (0..3), 8 + 4 hf + (0..3)}: the two
-  // halves sit in the 16-byte chunks 2 ks and 2 ks + 1 (swizzled), 8 hf bytes in
-  const int x_base = r32 * kLinK + 4 * hf, x_chunk = swz<64>(r32) << 3;
-  f32x16 acc[2][4];
+  auto issue_tile = [&](int kt) {
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
+    for (int j = 0; j < LPT; ++j) issue_part(kt, j);
+  };
+#pragma unroll
+  for (int t = 0; t < kLinStages - 1; ++t)
+    if (t < n_kt) issue_tile(t);
+
+  // fragments of both tiles: row r32 of a 32-row block, inner indices 16 ks + 8 hf + (0..7), i.e. the 16-byte chunk
+  // 2 ks + hf of the row (swizzled)
+  const int frag_base = r32 * KT + ((hf ^ lin_swz<KT>(r32)) << 3);
+  auto frag = [&](int ks) { return frag_base ^ (ks << 4); };
+  f32x16 acc[RB][4];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[rb][db][i] = 0.f;
 
-  for (int kt = 0; kt < n_kt; ++kt) {
-    // tile kt has landed (loads complete in order: at most the next tile's are still in flight); behind the barrier nobody
-    // reads tile kt-1 any more, whose stage tile kt+2 now fills
-    if (kt + 1 < n_kt) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
+  // Tile kt has landed when at most the loads of the later tiles already issued are still in flight (they complete in
+  // order); behind the barrier nobody reads tile kt-1 any more, whose stage the next tile to be requested fills.
+  auto await_tile = [&](int kt) {
+    const int later = min(kLinStages - 2, n_kt - 1 - kt);
+    if (later >= 3) wait_vmcnt<3 * LPT>(); else if (later == 2) wait_vmcnt<2 * LPT>(); else if (later == 1) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
     asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): this wave's fragment reads of the tile before are complete
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kt + 2 < n_kt) issue_tile(kt + 2);
-    const __bf16* sx = smx[kt % kLinStages] + wave * 64 * kLinK;
-    const __bf16* sw = smw[kt % kLinStages];
-    bf16x8 xf[2][2], wf[2][4];
-    auto fetch = [&](int ks, int buf) {
+  };
+  bf16x8 xf[2][RB], wf[2][4];
+  // fragment f (0 .. RB + 3: the activation blocks, then the weight blocks) of step ks of tile kt
+  auto fetch_one = [&](int kt, int ks, int buf, int f) {
+    const __bf16* sx = smx[kt % kLinStages] + wr * (32 * RB) * kLinK;
+    const __bf16* sw = smw[kt % kLinStages] + wc * 128 * kLinK;
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        const bf16x4 a = *(const bf16x4*)(sx + rb * 32 * kLinK + x_base + (x_chunk ^ (ks << 4)));
-        const bf16x4 b = *(const bf16x4*)(sx + rb * 32 * kLinK + x_base + (x_chunk ^ (ks << 4) ^ 8));
-        xf[buf][rb] = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+    for (int rb = 0; rb < RB; ++rb)
+      if (f == rb) xf[buf][rb] = *(const bf16x8*)(sx + rb * 32 * kLinK + frag(ks));
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+      if (f == RB + db) wf[buf][db] = *(const bf16x8*)(sw + db * 32 * kLinK + frag(ks));
+  };
+  auto fetch = [&](int kt, int ks, int buf) {
+#pragma unroll
+    for (int f = 0; f < RB + 4; ++f) fetch_one(kt, ks, buf, f);
+  };
+  // One step's products.  The loads of the tile that may be requested since the last barrier (stage_kt; none if past
+  // the end) are dealt out between the MFMAs, one behind every second one, `call` counting the steps since that barrier:
+  // requesting them takes issue cycles, which are free while the matrix core works off the product just issued.
+  // next_ks >= 0: the fragments of step next_ks of tile next_kt are requested into the other buffer on the way, one
+  // behind each of the first MFMAs
+  auto multiply = [&](int buf, int call, int stage_kt, int next_kt, int next_ks) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        acc[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][db], xf[buf][rb], acc[rb][db], 0, 0, 0);
+        const int m = db * RB + rb;
+        if (next_ks >= 0 && m < RB + 4) fetch_one(next_kt, next_ks, buf ^ 1, m);
+        if ((m & 1) && stage_kt < n_kt) issue_part(stage_kt, call * (2 * RB) + m / 2);
+        __builtin_amdgcn_sched_barrier(0);
       }
+  };
+  // The barrier between two tiles sits in front of the LAST step's products of the tile that ends: its fragments are in
+  // registers by then, and its MFMAs run while the first fragments of the next tile make their way out of LDS (right
+  // behind a barrier all waves ask for fragments at once).
+  constexpr int KS = kLinK / 16;
+  static_assert(KS % 2 == 0);  // the fragment buffers alternate: step 0 of every tile uses buffer 0
+  static_assert(KS * 2 * RB >= LPT, "a tile's loads are all requested within one tile's steps");
+  static_assert(4 * RB >= RB + 4, "a step has at least as many MFMAs as fragments");
+  await_tile(0);
 #pragma unroll
-      for (int db = 0; db < 4; ++db) wf[buf][db] = read_v_fragment<128>(sw, fw, db, ks);
-    };
-    fetch(0, 0);
+  for (int j = 0; j < 2 * RB; ++j)
+    if (kLinStages - 1 < n_kt) issue_part(kLinStages - 1, j);  // the share of the step that precedes the loop
+  fetch(0, 0, 0);
+  for (int kt = 0; kt < n_kt; ++kt) {
 #pragma unroll
-    for (int ks = 0; ks < kLinK / 16; ++ks) {
-      if (ks + 1 < kLinK / 16) fetch(ks + 1, (ks + 1) & 1);   // the next step's fragments arrive behind this step's MFMAs
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-          acc[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks & 1][db], xf[ks & 1][rb], acc[rb][db], 0, 0, 0);
+    for (int ks = 0; ks + 1 < KS; ++ks)   // step ks multiplies buffer ks & 1 while the other one takes step ks + 1
+      multiply(ks & 1, ks + 1, kt + kLinStages - 1, kt, ks + 1);
+    if (kt + 1 < n_kt) {
+      await_tile(kt + 1);
+      fetch(kt + 1, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
+    multiply((KS - 1) & 1, 0, kt + kLinStages, 0, -1);  // (behind the last tile there is no barrier and nothing to request)
   }
 
   // ---- epilogue: lane (r32, hf) holds, of row m0 + 64 wave + 32 rb + r32, columns n0 + 32 db + 8 j + 4 hf + (0..3) ----
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    const int m = m0 + wave * 64 + rb * 32 + r32;
+  for (int rb = 0; rb < RB; ++rb) {
+    const int m = m0 + wr * (32 * RB) + rb * 32 + r32;
     if (m >= p.rows) continue;
     if constexpr (EPI == 0) {
 #pragma unroll
@@ -200,16 +266,35 @@ __global__ __launch_bounds__(64 * kLinWaves, 1) void linear_kernel(LinearParams 
 
 static int check_linear_shape(const char* who, long long rows, int k, int n) {
   if (rows <= 0 || k <= 0 || n <= 0) { set_error("%s: rows, k and n must be positive", who); return EARN_ERR_INVALID_ARG; }
-  if (k % kLinK != 0 || n % 8 != 0) {
+  if (k % kLinKMultiple != 0 || n % 8 != 0) {
     set_error("%s: the inner dimension (%d) must be a multiple of 64 and the output width (%d) a multiple of 8", who, k, n);
     return EARN_ERR_UNSUPPORTED;
   }
-  if ((long long)kLinRows * k * 2 >= (1ll << 31) || (long long)k * n * 2 >= (1ll << 31)) {
-    set_error("%s: a %d x %d weight matrix or a 256-row block of %d columns exceeds the 2 GiB addressing range", who, k, n, k);
+  if ((long long)kLinRows * k * 2 >= (1ll << 31)) {
+    set_error("%s: a 256-row block of %d columns exceeds the 2 GiB addressing range", who, k);
     return EARN_ERR_UNSUPPORTED;
   }
   if (rows > 0x7fffffffLL - kLinRows) { set_error("%s: too many rows", who); return EARN_ERR_UNSUPPORTED; }
   return EARN_OK;
+}
+
+// template arguments and threads of the 256 x 256 form
+#define LIN_WIDE 2, 2, 64, 2
+#define LIN_WIDE_THREADS 512
+// 256 x 256 tiles (8 waves, two per SIMD, two LDS stages) unless there are too few of them to matter; 256 x 128 tiles
+// (4 waves, three stages) then, twice as many workgroups
+static bool linear_wide_tile(long long rows, int n) {
+  const int set = tuning(kTuneLinearTile, 0);
+  if (set == 1) return false;
+  if (set == 2) return true;
+  return ((rows + kLinRows - 1) / kLinRows) * ((n + 255) / 256) >= 64;
+}
+
+// workgroups: whole patches, a multiple of 8 of them (one per XCD and round); workgroups outside the matrix leave at once
+static long long linear_grid(long long rows, int n, int cols) {
+  const long long n_pr = ((rows + kLinRows - 1) / kLinRows + kLinPatchRows - 1) / kLinPatchRows;
+  const long long n_pc = ((n + cols - 1) / cols + kLinPatchCols - 1) / kLinPatchCols;
+  return (n_pr * n_pc + kXcds - 1) / kXcds * kXcds * kLinPatch;
 }
 
 int launch_linear(const void* x, const void* w, int rows, int k, int n, int activation, void* out, hipStream_t stream) {
@@ -218,9 +303,12 @@ int launch_linear(const void* x, const void* w, int rows, int k, int n, int acti
   LinearParams p;
   memset(&p, 0, sizeof(p));
   p.x = (const __bf16*)x; p.w = (const __bf16*)w; p.rows = rows; p.k = k; p.n = n; p.out = (__bf16*)out; p.activation = activation;
-  const long long grid = (long long)((rows + kLinRows - 1) / kLinRows) * ((n + kLinCols - 1) / kLinCols);
+  const bool wide = linear_wide_tile(rows, n);
+  const int cols = wide ? 256 : 128;
+  const long long grid = linear_grid(rows, n, cols);
   if (grid > 0x7fffffffLL) { set_error("earn_linear: grid too large"); return EARN_ERR_UNSUPPORTED; }
-  hipLaunchKernelGGL((linear_kernel<0, 128>), dim3((unsigned)grid), dim3(64 * kLinWaves), 0, stream, p);
+  if (wide) hipLaunchKernelGGL((linear_kernel<0, 128, LIN_WIDE>), dim3((unsigned)grid), dim3(LIN_WIDE_THREADS), 0, stream, p);
+  else hipLaunchKernelGGL((linear_kernel<0, 128, 2, 1, 64, 3>), dim3((unsigned)grid), dim3(256), 0, stream, p);
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
 }
 
@@ -237,10 +325,17 @@ int launch_qkv_rope_project(const earn_attn_desc* desc, const void* x, const voi
   p.cu = cu_seqlens; p.positions = positions; p.batch = batch;
   p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.head_dim = desc->head_dim;
   p.rope = make_rope_table(desc->rope_base, desc->head_dim);
-  const long long grid = (long long)((rows + kLinRows - 1) / kLinRows) * ((n + kLinCols - 1) / kLinCols);
+  const bool wide = linear_wide_tile(rows, n);
+  const int cols = wide ? 256 : 128;
+  const long long grid = linear_grid(rows, n, cols);
   if (grid > 0x7fffffffLL) { set_error("earn_qkv_rope_project: grid too large"); return EARN_ERR_UNSUPPORTED; }
-  if (desc->head_dim == 64) hipLaunchKernelGGL((linear_kernel<1, 64>), dim3((unsigned)grid), dim3(64 * kLinWaves), 0, stream, p);
-  else hipLaunchKernelGGL((linear_kernel<1, 128>), dim3((unsigned)grid), dim3(64 * kLinWaves), 0, stream, p);
+  if (desc->head_dim == 64) {
+    if (wide) hipLaunchKernelGGL((linear_kernel<1, 64, LIN_WIDE>), dim3((unsigned)grid), dim3(LIN_WIDE_THREADS), 0, stream, p);
+    else hipLaunchKernelGGL((linear_kernel<1, 64, 2, 1, 64, 3>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+  } else {
+    if (wide) hipLaunchKernelGGL((linear_kernel<1, 128, LIN_WIDE>), dim3((unsigned)grid), dim3(LIN_WIDE_THREADS), 0, stream, p);
+    else hipLaunchKernelGGL((linear_kernel<1, 128, 2, 1, 64, 3>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+  }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
 }
 

@@ -242,7 +242,6 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
 // ------------------------------------------------------------------------------------------------------------------
 // bf16 MFMA flash attention
 // ------------------------------------------------------------------------------------------------------------------
-constexpr int kXcds = 8;         // accelerator complex dies, each with a private L2
 
 // ---- workgroup -> (sequence, kv head, query block, head of the group), XCD aware ----
 // Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  Id (x, k) = the k-th

@@ -24,6 +24,11 @@ def rnd(g, *shape, scale=1.0):
     return (torch.randn(*shape, generator=g) * scale).to(BF)
 
 
+def wt(w):
+    """The library takes weights as [outputs, inputs]; the oracle's matrices here are [inputs, outputs]."""
+    return w.t().contiguous().to(DEV)
+
+
 QKV_CASES = [
     # hq, hkv, d, d_model, sequence lengths, explicit positions
     (8, 2, 128, 256, [300, 61, 100], False),        # 12 heads x 128 = 1536 columns, ragged last row tile
@@ -33,8 +38,17 @@ QKV_CASES = [
 ]
 
 
+@pytest.fixture(params=[1, 2], ids=["tile256x128", "tile256x256"])
+def tile(request):
+    """Both tile shapes of the GEMM kernel, whatever the library would pick for the size."""
+    B = _B()
+    B.earn_set_tuning("linear_tile", request.param)
+    yield request.param
+    B.earn_set_tuning("linear_tile", 0)
+
+
 @pytest.mark.parametrize("hq,hkv,d,dm,lens,explicit", QKV_CASES)
-def test_qkv_projection_matches_oracle(hq, hkv, d, dm, lens, explicit):
+def test_qkv_projection_matches_oracle(hq, hkv, d, dm, lens, explicit, tile):
     B = _B()
     rows, batch = sum(lens), len(lens)
     g = torch.Generator().manual_seed(rows + dm)
@@ -47,7 +61,7 @@ def test_qkv_projection_matches_oracle(hq, hkv, d, dm, lens, explicit):
     q = torch.full((rows, hq, d), float("nan"), dtype=BF, device=DEV)
     k = torch.full((rows, hkv, d), float("nan"), dtype=BF, device=DEV)
     v = torch.full((rows, hkv, d), float("nan"), dtype=BF, device=DEV)
-    B.earn_qkv_rope_project(desc, x.to(DEV), w.to(DEV), None if explicit else torch.from_numpy(cu).to(DEV),
+    B.earn_qkv_rope_project(desc, x.to(DEV), wt(w), None if explicit else torch.from_numpy(cu).to(DEV),
                             torch.from_numpy(pos).to(DEV) if explicit else None, batch, q, k, v)
     torch.cuda.synchronize()
     ref = O.qkv_project(W.to_f64(x), W.to_f64(w), hq, hkv, d, pos)
@@ -56,7 +70,7 @@ def test_qkv_projection_matches_oracle(hq, hkv, d, dm, lens, explicit):
     check_attn(v, ref["v"], BF, "v")
     # rotation off: the plain product
     desc0 = B.make_desc(BF, hq, hkv, d, rope_base=0.0)
-    B.earn_qkv_rope_project(desc0, x.to(DEV), w.to(DEV), None, None, batch, q, k, v)
+    B.earn_qkv_rope_project(desc0, x.to(DEV), wt(w), None, None, batch, q, k, v)
     torch.cuda.synchronize()
     ref0 = O.qkv_project(W.to_f64(x), W.to_f64(w), hq, hkv, d, pos, rope_base=0.0)
     check_attn(q, ref0["q"], BF, "q without rotation")
@@ -65,12 +79,12 @@ def test_qkv_projection_matches_oracle(hq, hkv, d, dm, lens, explicit):
 
 @pytest.mark.parametrize("rows,k,n,act", [(300, 256, 512, 0), (1000, 4096, 136, 1), (7, 64, 8, 1), (513, 128, 1000, 0),
                                            (256, 1024, 128, 1)])
-def test_linear_matches_oracle(rows, k, n, act):
+def test_linear_matches_oracle(rows, k, n, act, tile):
     B = _B()
     g = torch.Generator().manual_seed(rows + k + n)
     x, w = rnd(g, rows, k), rnd(g, k, n, scale=k ** -0.5)
     out = torch.full((rows + 1, n), float("nan"), dtype=BF, device=DEV)
-    B.earn_linear(x.to(DEV), w.to(DEV), out[:rows], act)
+    B.earn_linear(x.to(DEV), wt(w), out[:rows], act)
     torch.cuda.synchronize()
     ref = O.linear(W.to_f64(x), W.to_f64(w), act)
     got = out[:rows].cpu().double().numpy()
@@ -83,7 +97,7 @@ def test_linear_matches_oracle(rows, k, n, act):
 def test_projection_argument_errors():
     B = _B()
     x = torch.zeros(8, 64, dtype=BF, device=DEV)
-    w = torch.zeros(64, 4 * 64, dtype=BF, device=DEV)
+    w = torch.zeros(4 * 64, 64, dtype=BF, device=DEV)
     q, k = torch.zeros(8, 2, 64, dtype=BF, device=DEV), torch.zeros(8, 1, 64, dtype=BF, device=DEV)
     desc = B.make_desc(BF, 2, 1, 64)
     with pytest.raises(B.EarnError) as e:
@@ -93,7 +107,7 @@ def test_projection_argument_errors():
         B.earn_qkv_rope_project(B.make_desc(torch.float32, 2, 1, 64), x, w, None, torch.zeros(8, dtype=torch.int32, device=DEV), 1, q, k, k.clone())
     assert e.value.code == B.EARN_ERR_UNSUPPORTED
     with pytest.raises(B.EarnError) as e:
-        B.earn_linear(torch.zeros(8, 96, dtype=BF, device=DEV), torch.zeros(96, 64, dtype=BF, device=DEV), torch.zeros(8, 64, dtype=BF, device=DEV))
+        B.earn_linear(torch.zeros(8, 96, dtype=BF, device=DEV), torch.zeros(64, 96, dtype=BF, device=DEV), torch.zeros(8, 64, dtype=BF, device=DEV))
     assert e.value.code == B.EARN_ERR_UNSUPPORTED and "multiple of 64" in str(e.value)
     with pytest.raises(B.EarnError) as e:
         B.earn_linear(x, w, torch.zeros(8, 256, dtype=BF, device=DEV), activation=5)
@@ -119,7 +133,7 @@ def test_projection_fed_path_matches_oracle(hq, hkv, d, dm, lens):
     e = lambda n_, hh: torch.empty(n_, hh, d, dtype=BF, device=DEV)
     # layer 0: project, attend (no rotation pass, keys in place: no workspace)
     q0, k0, v0, o0 = e(rows, hq), e(rows, hkv), e(rows, hkv), e(rows, hq)
-    B.earn_qkv_rope_project(desc, dx, w0.to(DEV), dcu, None, batch, q0, k0, v0)
+    B.earn_qkv_rope_project(desc, dx, wt(w0), dcu, None, batch, q0, k0, v0)
     assert B.earn_prefill_workspace_bytes(desc0, batch, rows, max(lens), False) == 0
     B.earn_prefill_attn(desc0, q0, k0, v0, dcu, None, batch, rows, max(lens), o0, None, None, None)
     # compaction of the hidden rows only; layer 1 projects from them at the original positions
@@ -128,7 +142,7 @@ def test_projection_fed_path_matches_oracle(hq, hkv, d, dm, lens):
     cu_c = torch.empty(batch + 1, dtype=torch.int32, device=DEV)
     B.earn_compact_registers([dx], [x_c], dcu, batch, h, t, idx, pos, cu_c)
     q1, k1, v1, o1 = e(batch * r, hq), e(batch * r, hkv), e(batch * r, hkv), e(batch * r, hq)
-    B.earn_qkv_rope_project(desc, x_c, w1.to(DEV), None, pos, batch, q1, k1, v1)
+    B.earn_qkv_rope_project(desc, x_c, wt(w1), None, pos, batch, q1, k1, v1)
     B.earn_prefill_attn(desc0, q1, k1, v1, cu_c, pos, batch, batch * r, r, o1, None, None, None)
     # decode step 0 of both layers: the new tokens' hidden rows, projected at position n_s
     S = batch
@@ -138,7 +152,7 @@ def test_projection_fed_path_matches_oracle(hq, hkv, d, dm, lens):
     outs = []
     for wl, kc, vc, scu, mlen in ((w0, k0, v0, dcu, max(lens)), (w1, k1, v1, cu_c, r)):
         dq, dk, dv = e(S, hq), e(S, hkv), e(S, hkv)
-        B.earn_qkv_rope_project(desc, xd.to(DEV), wl.to(DEV), None, q_pos, batch, dq, dk, dv)
+        B.earn_qkv_rope_project(desc, xd.to(DEV), wt(wl), None, q_pos, batch, dq, dk, dv)
         gk, gv = torch.zeros(S, 2, hkv, d, dtype=BF, device=DEV), torch.zeros(S, 2, hkv, d, dtype=BF, device=DEV)
         od = e(S, hq)
         ws = torch.empty(max(B.earn_decode_workspace_bytes(desc0, S, batch, mlen, 2), 256), dtype=torch.uint8, device=DEV)
