@@ -39,14 +39,6 @@ __device__ __forceinline__ void dma16_to_lds(u32x4 rsrc, unsigned lds_addr, int 
                : "s"(lds_addr), "v"(voff), "s"(rsrc)
                : "memory");
 }
-// The same with 4 bytes per lane (lane l's word goes to lds_addr + 4 l): used to pull lines into L2 ahead of time, the
-// words themselves landing in a scrap area.
-__device__ __forceinline__ void dma4_to_lds(u32x4 rsrc, unsigned lds_addr, int voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
-               :
-               : "s"(lds_addr), "v"(voff), "s"(rsrc)
-               : "memory");
-}
 // Raw (unstrided, unswizzled) buffer descriptor over [base, base + bytes): accesses are range checked against `bytes`.
 __device__ __forceinline__ u32x4 raw_buffer(const void* base, int bytes) {
   const unsigned long long a = (unsigned long long)base;
