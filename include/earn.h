@@ -187,8 +187,9 @@ int earn_decode_step_positions(const int32_t* cu_seqlens, const int32_t* stream_
  *   shared_k, shared_v [shared_total, Hkv, d]; shared_k already rotated (k_rot_out of the prefill)
  *   shared_cu          [batch+1] int32
  *   stream_to_seq      [n_streams] int32 or NULL (= identity, requires n_streams == batch); a sequence may hold any
- *                      number of streams, none included, but at most 1024 (device-side precondition; the host rejects
- *                      what it can tell from n_streams and batch alone: n_streams - batch + 1 > 1024 -> UNSUPPORTED)
+ *                      number of streams, none included, but at most 1024 (device-side precondition, checked exactly in
+ *                      the validation mode; streams of a sequence beyond its first 1024 get no output.  The host
+ *                      rejects what it can tell from n_streams and batch alone: n_streams > 1024 batch -> UNSUPPORTED)
  *   gen_k, gen_v       [n_streams, gen_cap, Hkv, d]; slot gen_len[u] of stream u is written by this call
  *   gen_len            [n_streams] int32, 0 <= gen_len[u] < gen_cap
  *   max_shared_len     upper bound on shared_cu[s+1] - shared_cu[s]

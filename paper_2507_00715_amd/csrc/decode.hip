@@ -1164,8 +1164,10 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
     set_error("earn_decode_attn: a shared cache of %d rows exceeds the 2 GiB addressing range of one sequence", max_shared_len);
     return EARN_ERR_UNSUPPORTED;
   }
-  if (pl.mfma && n_streams - batch + 1 > kMaxStreamsPerSeq) {
-    set_error("earn_decode_attn: more than %d streams may share one sequence", kMaxStreamsPerSeq);
+  // (what the host can tell without reading stream_to_seq: with more than 1024 streams per sequence ON AVERAGE some
+  // sequence must exceed the limit; the exact check is part of the validation mode)
+  if (pl.mfma && n_streams > (long long)kMaxStreamsPerSeq * batch) {
+    set_error("earn_decode_attn: more than %d streams would share one sequence", kMaxStreamsPerSeq);
     return EARN_ERR_UNSUPPORTED;
   }
   DecodeParams p;

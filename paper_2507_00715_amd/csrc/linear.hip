@@ -281,13 +281,18 @@ static int check_linear_shape(const char* who, long long rows, int k, int n) {
 // template arguments and threads of the 256 x 256 form
 #define LIN_WIDE 2, 2, 64, 2
 #define LIN_WIDE_THREADS 512
-// 256 x 256 tiles (8 waves, two per SIMD, two LDS stages) unless there are too few of them to matter; 256 x 128 tiles
-// (4 waves, three stages) then, twice as many workgroups
+// 256 x 256 tiles (8 waves, two per SIMD, two LDS stages) or 256 x 128 tiles (4 waves, three stages), whichever needs
+// less time by a simple count: one workgroup per CU at a time, rounds of 256 workgroups, a narrow tile taking about 0.62
+// of a wide one's time (measured on large matrices: half the products at a lower rate).  Large matrices take the wide
+// tile; a few hundred rows take whichever fills the last round better.
 static bool linear_wide_tile(long long rows, int n) {
   const int set = tuning(kTuneLinearTile, 0);
   if (set == 1) return false;
   if (set == 2) return true;
-  return ((rows + kLinRows - 1) / kLinRows) * ((n + 255) / 256) >= 64;
+  const long long n_rt = (rows + kLinRows - 1) / kLinRows;
+  const long long wide = n_rt * ((n + 255) / 256), narrow = n_rt * ((n + 127) / 128);
+  const int cus = 256;
+  return (double)((wide + cus - 1) / cus) <= 0.62 * (double)((narrow + cus - 1) / cus);
 }
 
 // workgroups: whole patches, a multiple of 8 of them (one per XCD and round); workgroups outside the matrix leave at once

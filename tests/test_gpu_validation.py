@@ -112,7 +112,7 @@ def test_decode_validation(validating):
 def test_decode_validation_counts_streams_per_sequence(validating):
     B = validating
     hq, hkv, d, batch, gen_cap = 2, 2, 64, 30, 1
-    S = 1025 + 28                      # the host cannot tell from n_streams and batch alone: S - batch + 1 = 1024
+    S = 1025 + 28                      # the host cannot tell from n_streams and batch alone (S <= 1024 * batch)
     z = lambda *s: torch.zeros(*s, dtype=BF, device=DEV)
     q, kn, sk = z(S, hq, d), z(S, hkv, d), z(batch * 200, hkv, d)
     gk = z(S, gen_cap, hkv, d)
