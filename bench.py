@@ -524,17 +524,26 @@ def decoder_layer(name: str, dev) -> dict:
     cu_reg = torch.arange(0, c.batch * r + 1, r, dtype=torch.int32, device=dev)
     pos_reg = torch.cat([torch.cat([torch.arange(c.n_head_reg), torch.arange(n - c.n_tail_reg, n)]) for n in w.seq_lengths]).to(torch.int32).to(dev)
     totals = {}
+    S = c.batch * max(c.beams, 1)
+    pos_dec = torch.tensor([n for n in w.seq_lengths for _ in range(max(c.beams, 1))], dtype=torch.int32, device=dev)
+    # few-row products split their inner dimension through this buffer (earn_linear_workspace_bytes)
+    lin_ws = torch.empty(max([B.earn_linear_workspace_bytes(rows_, k_, n_) for rows_ in (c.batch * r, S)
+                              for k_, n_ in ((dm, (hq + 2 * hkv) * d), (hq * d, dm), (dm, df), (df, dm))] + [256]),
+                         dtype=torch.uint8, device=dev)
     for label, rows, cu, pos, maxlen in (("full_length", w.total_tokens, cu_full, None, w.max_seqlen),
-                                         ("register_rows", c.batch * r, cu_reg, pos_reg, r)):
+                                         ("register_rows", c.batch * r, cu_reg, pos_reg, r),
+                                         ("decode_rows", S, None, pos_dec, 0)):
         x = rnd(rows, dm)
         q, k, v = (torch.empty(rows, h_, d, dtype=bf, device=dev) for h_ in (hq, hkv, hkv))
         o, y, hmid = torch.empty(rows, hq, d, dtype=bf, device=dev), torch.empty(rows, dm, dtype=bf, device=dev), torch.empty(rows, df, dtype=bf, device=dev)
+        reps = 3 if rows > 4096 else 20
         t = {
-            "qkv_rope_project_ms": ms(lambda: B.earn_qkv_rope_project(desc, x, w_qkv, cu, pos, c.batch, q, k, v)),
-            "attention_ms": ms(lambda: B.earn_prefill_attn(desc0, q, k, v, cu, pos, c.batch, rows, maxlen, o, None, None, None)),
-            "out_projection_ms": ms(lambda: B.earn_linear(o.view(rows, hq * d), w_o, y)),
-            "ffn_up_silu_ms": ms(lambda: B.earn_linear(x, w_up, hmid, 1)),
-            "ffn_down_ms": ms(lambda: B.earn_linear(hmid, w_down, y)),
+            "qkv_rope_project_ms": ms(lambda: B.earn_qkv_rope_project(desc, x, w_qkv, cu, pos, c.batch, q, k, v, lin_ws), reps),
+            # (the decode rows' attention is the decode step measured above: not repeated here)
+            "attention_ms": ms(lambda: B.earn_prefill_attn(desc0, q, k, v, cu, pos, c.batch, rows, maxlen, o, None, None, None), reps) if maxlen else 0.0,
+            "out_projection_ms": ms(lambda: B.earn_linear(o.view(rows, hq * d), w_o, y, 0, lin_ws), reps),
+            "ffn_up_silu_ms": ms(lambda: B.earn_linear(x, w_up, hmid, 1, lin_ws), reps),
+            "ffn_down_ms": ms(lambda: B.earn_linear(hmid, w_down, y, 0, lin_ws), reps),
         }
         t["layer_ms"] = sum(t.values())
         flops = {"qkv_rope_project": 2.0 * rows * dm * (hq + 2 * hkv) * d, "out_projection": 2.0 * rows * hq * d * dm,
@@ -542,8 +551,13 @@ def decoder_layer(name: str, dev) -> dict:
         t["gemm_tflops"] = {k_: flops[k_] / (t[k_ + "_ms"] * 1e-3) / 1e12 for k_ in flops}
         t["gemm_frac_of_bf16_peak"] = {k_: v_ / PEAK_BF16_TFLOPS for k_, v_ in t["gemm_tflops"].items()}
         # context only: the vendor library's GEMM (through torch.matmul) on the feed-forward shape, no activation
-        lib_ms = ms(lambda: torch.matmul(x, w_up.t(), out=hmid))
+        lib_ms = ms(lambda: torch.matmul(x, w_up.t(), out=hmid), reps)
         t["library_matmul_ffn_up_tflops"] = flops["ffn_up_silu"] / (lib_ms * 1e-3) / 1e12
+        if rows <= 4096:  # few rows: the weights' bytes are what moves; HBM roofline of the four products together
+            wbytes = 2.0 * (dm * (hq + 2 * hkv) * d + hq * d * dm + 2 * dm * df)
+            gemm_ms = t["layer_ms"] - t["attention_ms"]
+            t["weights_GBps"] = wbytes / (gemm_ms * 1e-3) / 1e9
+            t["weights_frac_of_hbm_peak"] = t["weights_GBps"] / PEAK_HBM_GBPS
         out[label] = t
         totals[label] = t["layer_ms"]
         del x, q, k, v, o, y, hmid

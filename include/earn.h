@@ -90,6 +90,7 @@ int earn_set_validation(int enabled);
  *   "decode_vec_waves"      waves per workgroup of the vector decode kernel (1, 2 or 4)
  *   "compact_blocks"        16 KB blocks one compaction workgroup copies (1..4)
  *   "linear_tile"           1 | 2: output tile of the projection GEMMs, 256 x 128 (1) or 256 x 256 (2); default by size
+ *   "linear_splits"         splits of the inner dimension when a workspace is given (default by size; 1 = none)
  */
 int earn_set_tuning(const char* key, int32_t value);
 
@@ -315,15 +316,21 @@ size_t earn_prefill_register_rows_workspace_bytes(const earn_attn_desc* desc, in
  *   q_out      device, [rows, Hq, d];  k_out, v_out  device, [rows, Hkv, d]
  * earn_linear: out[rows, n] = act(x[rows, k] w[n, k]^T), activation 0 = none, 1 = SiLU (x / (1 + e^-x)); bf16; w holds
  * one row of k inputs per output.
+ *   workspace  device, optional (NULL / 0: never needed for a correct result).  A product with few rows (register rows,
+ *              decode rows) has too few output tiles to occupy the GPU; given earn_linear_workspace_bytes(rows, k, n)
+ *              bytes (256-byte aligned; 0 when the product is large enough as it is) the inner dimension is split over
+ *              more workgroups, fp32 partial sums pass through the workspace and a second kernel adds them and applies
+ *              the epilogue.  Same results up to fp32 summation order.  For earn_qkv_rope_project, n = (Hq + 2 Hkv) d.
  * Errors: NULL pointer, non-positive size, positions and cu_seqlens both NULL with rotation on -> INVALID_ARG;
  * desc->dtype != EARN_BF16, an inner dimension that is not a multiple of 64, an output width that is not a multiple of
  * 8, 256 rows of the inner dimension reaching 2 GiB -> UNSUPPORTED.  Enqueue on `stream`, allocate nothing.
  */
 int earn_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void* w_qkv, int32_t rows, int32_t d_model,
                           const int32_t* cu_seqlens, const int32_t* positions, int32_t batch, void* q_out, void* k_out,
-                          void* v_out, void* stream);
+                          void* v_out, void* workspace, size_t workspace_bytes, void* stream);
 int earn_linear(const void* x, const void* w, int32_t rows, int32_t k, int32_t n, int32_t activation, void* out,
-                void* stream);
+                void* workspace, size_t workspace_bytes, void* stream);
+size_t earn_linear_workspace_bytes(int32_t rows, int32_t k, int32_t n);
 
 /*
  * Backward of the causal attention (paper Section 3.2, Training: the loss is differentiated through the same attention,

@@ -28,7 +28,7 @@ EXPORTS = ["earn_last_error", "earn_version", "earn_prefill_attn", "earn_prefill
            "earn_prefill_register_rows", "earn_prefill_register_rows_workspace_bytes", "earn_set_validation",
            "earn_set_tuning", "earn_decode_attn_static", "earn_prefill_attn_layers", "earn_decode_attn_layers",
            "earn_decode_layers_workspace_bytes", "earn_decode_step_positions", "earn_attn_stats", "earn_beam_topk", "earn_beam_topk_workspace_bytes",
-           "earn_beam_reorder", "earn_decode_attn_beams", "earn_qkv_rope_project", "earn_linear", "earn_attn_backward",
+           "earn_beam_reorder", "earn_decode_attn_beams", "earn_qkv_rope_project", "earn_linear", "earn_linear_workspace_bytes", "earn_attn_backward",
            "earn_attn_backward_workspace_bytes"]
 EARN_STATIC_SCRATCH_BYTES = 8 << 20
 
@@ -91,9 +91,11 @@ def lib():
         L.earn_decode_attn_beams.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
                                              i32, i32, i32, vp, vp, sz, vp]
         L.earn_qkv_rope_project.restype = ctypes.c_int
-        L.earn_qkv_rope_project.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
+        L.earn_qkv_rope_project.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
         L.earn_linear.restype = ctypes.c_int
-        L.earn_linear.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp]
+        L.earn_linear.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.earn_linear_workspace_bytes.restype = sz
+        L.earn_linear_workspace_bytes.argtypes = [i32, i32, i32]
         L.earn_attn_backward.restype = ctypes.c_int
         L.earn_attn_backward.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp,
                                          sz, vp]
@@ -310,20 +312,37 @@ def earn_decode_attn_beams(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, sha
                                         max_shared_len, _ptr(out), _ptr(workspace), ws_bytes, _stream()))
 
 
-def earn_qkv_rope_project(desc: AttnDesc, x, w_qkv, cu_seqlens, positions, batch: int, q_out, k_out, v_out) -> None:
+def earn_linear_workspace_bytes(rows: int, k: int, n: int) -> int:
+    return int(lib().earn_linear_workspace_bytes(rows, k, n))
+
+
+def _linear_workspace(rows: int, k: int, n: int, workspace, device):
+    """workspace = "auto": allocate what a few-row product wants (one-off calls; loops pass their own buffer)."""
+    if isinstance(workspace, str):
+        need = earn_linear_workspace_bytes(rows, k, n)
+        workspace = torch.empty(need, dtype=torch.uint8, device=device) if need else None
+    return workspace, (0 if workspace is None else workspace.numel() * workspace.element_size())
+
+
+def earn_qkv_rope_project(desc: AttnDesc, x, w_qkv, cu_seqlens, positions, batch: int, q_out, k_out, v_out,
+                          workspace="auto") -> None:
     """w_qkv: [(Hq + 2 Hkv) d, d_model], outputs x inputs (the layout of a torch.nn.Linear weight)."""
     rows, d_model = x.shape
-    assert tuple(w_qkv.shape) == ((desc.n_q_heads + 2 * desc.n_kv_heads) * desc.head_dim, d_model)
+    n = (desc.n_q_heads + 2 * desc.n_kv_heads) * desc.head_dim
+    assert tuple(w_qkv.shape) == (n, d_model)
+    workspace, ws_bytes = _linear_workspace(rows, d_model, n, workspace, x.device)
     _check(lib().earn_qkv_rope_project(ctypes.byref(desc), _ptr(x), _ptr(w_qkv), rows, d_model, _ptr(cu_seqlens),
-                                       _ptr(positions), batch, _ptr(q_out), _ptr(k_out), _ptr(v_out), _stream()))
+                                       _ptr(positions), batch, _ptr(q_out), _ptr(k_out), _ptr(v_out), _ptr(workspace),
+                                       ws_bytes, _stream()))
 
 
-def earn_linear(x, w, out, activation: int = 0) -> None:
+def earn_linear(x, w, out, activation: int = 0, workspace="auto") -> None:
     """w: [n, k], outputs x inputs (the layout of a torch.nn.Linear weight)."""
     rows, k = x.shape
     n = w.shape[0]
     assert w.shape[1] == k and tuple(out.shape) == (rows, n)
-    _check(lib().earn_linear(_ptr(x), _ptr(w), rows, k, n, activation, _ptr(out), _stream()))
+    workspace, ws_bytes = _linear_workspace(rows, k, n, workspace, x.device)
+    _check(lib().earn_linear(_ptr(x), _ptr(w), rows, k, n, activation, _ptr(out), _ptr(workspace), ws_bytes, _stream()))
 
 
 def earn_attn_backward(desc: AttnDesc, q, k, v, out, lse, d_out, cu_seqlens, batch: int, total_tokens: int,

@@ -72,10 +72,12 @@ int launch_step_positions(const int32_t* cu, const int32_t* stream_to_seq, int n
 int launch_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const int32_t* cu_seqlens,
                       const int32_t* row_pos, int batch, int rows_per_seq, float epsilon, int t_head, int tail_back,
                       float* stats_out, hipStream_t stream);
-int launch_linear(const void* x, const void* w, int rows, int k, int n, int activation, void* out, hipStream_t stream);
+int launch_linear(const void* x, const void* w, int rows, int k, int n, int activation, void* out, void* workspace,
+                  size_t workspace_bytes, hipStream_t stream);
+size_t linear_workspace_bytes(long long rows, int k, int n);
 int launch_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void* w_qkv, int rows, int d_model,
                             const int32_t* cu_seqlens, const int32_t* positions, int batch, void* q_out, void* k_out,
-                            void* v_out, hipStream_t stream);
+                            void* v_out, void* workspace, size_t workspace_bytes, hipStream_t stream);
 size_t attn_backward_workspace_bytes(int hq, int total_tokens);
 int launch_attn_backward(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const void* out,
                          const float* lse, const void* d_out, const int32_t* cu_seqlens, int batch, int total_tokens,
@@ -201,7 +203,7 @@ int earn_set_validation(int enabled) { return g_validate.exchange(enabled ? 1 : 
 
 int earn_set_tuning(const char* key, int32_t value) {
   static const char* const names[kTuneCount] = {"prefill_block_rows", "decode_mfma_min_len", "decode_mfma_short_wgs",
-                                                "decode_mfma_wgs", "decode_vec_wgs", "decode_vec_waves", "compact_blocks", "linear_tile"};
+                                                "decode_mfma_wgs", "decode_vec_wgs", "decode_vec_waves", "compact_blocks", "linear_tile", "linear_splits"};
   g_err[0] = 0;
   for (int i = 0; key && i < kTuneCount; ++i)
     if (strcmp(key, names[i]) == 0) { g_tuning[i].store(value > 0 ? value : 0, std::memory_order_relaxed); return EARN_OK; }
@@ -570,7 +572,7 @@ int earn_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* 
 
 int earn_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void* w_qkv, int32_t rows, int32_t d_model,
                           const int32_t* cu_seqlens, const int32_t* positions, int32_t batch, void* q_out, void* k_out,
-                          void* v_out, void* stream) {
+                          void* v_out, void* workspace, size_t workspace_bytes, void* stream) {
   g_err[0] = 0;
   int rc = check_desc(desc, "earn_qkv_rope_project");
   if (rc != EARN_OK) return rc;
@@ -584,17 +586,19 @@ int earn_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void*
     return EARN_ERR_INVALID_ARG;
   }
   return launch_qkv_rope_project(desc, x, w_qkv, rows, d_model, cu_seqlens, positions, batch, q_out, k_out, v_out,
-                                 (hipStream_t)stream);
+                                 workspace, workspace_bytes, (hipStream_t)stream);
 }
 
+size_t earn_linear_workspace_bytes(int32_t rows, int32_t k, int32_t n) { return linear_workspace_bytes(rows, k, n); }
+
 int earn_linear(const void* x, const void* w, int32_t rows, int32_t k, int32_t n, int32_t activation, void* out,
-                void* stream) {
+                void* workspace, size_t workspace_bytes, void* stream) {
   g_err[0] = 0;
   if (!x || !w || !out || rows <= 0 || k <= 0 || n <= 0 || activation < 0 || activation > 1) {
     set_error("earn_linear: NULL pointer, non-positive size or unknown activation %d", activation);
     return EARN_ERR_INVALID_ARG;
   }
-  return launch_linear(x, w, rows, k, n, activation, out, (hipStream_t)stream);
+  return launch_linear(x, w, rows, k, n, activation, out, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
 size_t earn_attn_backward_workspace_bytes(const earn_attn_desc* desc, int32_t total_tokens) {

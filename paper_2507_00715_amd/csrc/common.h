@@ -51,7 +51,7 @@ struct PrefillLayers { int n_layers; long long q, kv, out, k_rot, lse; };
 constexpr int kXcds = 8;  // accelerator complex dies, each with a private L2; consecutive workgroup ids go to them in turn
 
 enum Tuning { kTunePrefillBlockRows, kTuneDecMfmaMinLen, kTuneDecMfmaShortWgs, kTuneDecMfmaWgs, kTuneDecVecWgs,
-              kTuneDecVecWaves, kTuneCompactBlocks, kTuneLinearTile, kTuneCount };
+              kTuneDecVecWaves, kTuneCompactBlocks, kTuneLinearTile, kTuneLinearSplits, kTuneCount };
 int tuning(Tuning t, int dflt);
 
 __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) { return __uint_as_float(((unsigned int)b) << 16); }

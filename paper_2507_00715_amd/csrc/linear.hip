@@ -18,13 +18,14 @@
 // is lane-private.
 #include <string.h>
 
+#include <algorithm>
+
 #include "common.h"
 #include "mfma_tiles.h"
 
 namespace earn {
 
 constexpr int kLinRows = 256;  // rows of a workgroup's tile
-constexpr int kLinPatchRows = 4, kLinPatchCols = 8, kLinPatch = kLinPatchRows * kLinPatchCols;  // tiles an XCD works on together
 constexpr int kLinKMultiple = 64;  // the inner dimension must be a multiple of this
 
 // chunk swizzle of a tile whose rows hold KT inner indices (KT / 8 chunks of 16 bytes): 64 -> the attention tiles' own
@@ -42,6 +43,11 @@ struct LinearParams {
   __bf16* out; int activation;
   __bf16* q_out; __bf16* k_out; __bf16* v_out;
   const int32_t* cu; const int32_t* positions; int batch, hq, hkv, head_dim;
+  // inner dimension split over grid rows (few output rows: too few tiles to fill the GPU otherwise): split z takes
+  // K-tiles [z * split_tiles, (z + 1) * split_tiles) and writes its fp32 sums to partial[z][rows][n]; a second kernel
+  // adds the splits and applies the epilogue.  n_split == 1: no partials, the kernel finishes the outputs itself.
+  float* partial; int n_split, split_tiles;
+  int patch_rows, patch_cols;  // tiles an XCD works on together (see the kernel's workgroup -> tile mapping)
   RopeTable rope;
 };
 
@@ -58,21 +64,24 @@ __global__ __launch_bounds__(64 * (8 / RB) * WC, 1) void linear_kernel(LinearPar
   const int wr = wave % WR, wc = wave / WR;              // this wave's 32 RB rows and 128 columns of the tile
   const int r32 = lane & 31, hf = lane >> 5;
   // Workgroup -> tile.  Consecutive workgroup ids go to the 8 XCDs in turn, each with an L2 of its own and 32 CUs: the
-  // 32 workgroups an XCD runs side by side are given a patch of kLinPatchRows x kLinPatchCols tiles, so that the XCD
-  // fetches 4 activation and 8 weight tile slices per step for 32 workgroups instead of one of each per workgroup.
+  // 32 workgroups an XCD runs side by side are given a patch of patch_rows x patch_cols (4 x 8, host's choice) tiles, so
+  // that the XCD fetches 4 activation and 8 weight tile slices per step for 32 workgroups instead of one of each per
+  // workgroup.  (Few tiles: smaller patches, down to single tiles, so that every XCD gets some.)
   const int n_ct = (p.n + kLinCols - 1) / kLinCols, n_rt = (p.rows + kLinRows - 1) / kLinRows;
   // The tile rows and columns are dealt to the patches in equal shares (a patch is up to 4 x 8 tiles, not exactly):
   // patches of equal work keep the XCDs, which take them in turn, busy for the same time.
-  const int n_pc = (n_ct + kLinPatchCols - 1) / kLinPatchCols, n_pr = (n_rt + kLinPatchRows - 1) / kLinPatchRows;
+  const int n_pc = (n_ct + p.patch_cols - 1) / p.patch_cols, n_pr = (n_rt + p.patch_rows - 1) / p.patch_rows;
+  const int slots = p.patch_rows * p.patch_cols;
   const int xcd = blockIdx.x % kXcds, i_in_xcd = blockIdx.x / kXcds;
-  const int patch = (i_in_xcd / kLinPatch) * kXcds + xcd, within = i_in_xcd % kLinPatch;
+  const int patch = (i_in_xcd / slots) * kXcds + xcd, within = i_in_xcd % slots;
   const int pr = patch / n_pc, pc = patch % n_pc;
   if (pr >= n_pr) return;
-  const int rt = (int)((long long)pr * n_rt / n_pr) + within % kLinPatchRows;
-  const int ct = (int)((long long)pc * n_ct / n_pc) + within / kLinPatchRows;
+  const int rt = (int)((long long)pr * n_rt / n_pr) + within % p.patch_rows;
+  const int ct = (int)((long long)pc * n_ct / n_pc) + within / p.patch_rows;
   if (rt >= (int)((long long)(pr + 1) * n_rt / n_pr) || ct >= (int)((long long)(pc + 1) * n_ct / n_pc)) return;
   const int m0 = rt * kLinRows, n0_wg = ct * kLinCols, n0 = n0_wg + 128 * wc;
-  const int n_kt = p.k / kLinK;
+  const int kt0 = blockIdx.y * p.split_tiles;                    // first K-tile of this workgroup's share of the inner dimension
+  const int n_kt = min(p.k / kLinK - kt0, p.split_tiles);
   static_assert(STAGES >= 2 && STAGES <= 5);
 
   // ---- staging ----
@@ -96,16 +105,17 @@ __global__ __launch_bounds__(64 * (8 / RB) * WC, 1) void linear_kernel(LinearPar
   }
   const unsigned lds_x = (unsigned)(size_t)(lds_void_ptr)&smx[0][0], lds_w = (unsigned)(size_t)(lds_void_ptr)&smw[0][0];
   constexpr int LPT = XI + WI;  // loads per wave and tile
+  auto k_byte = [&](int kt) { return (kt0 + kt) * (kLinK * 2); };  // byte offset of K-tile kt inside a row
   // load j (0 .. LPT-1) of this wave's share of tile kt
   auto issue_part = [&](int kt, int j) {
     const unsigned sx = lds_x + (unsigned)((kt % kLinStages) * kLinRows * kLinK * 2);
     const unsigned sw = lds_w + (unsigned)((kt % kLinStages) * kLinK * kLinCols * 2);
 #pragma unroll
     for (int i = 0; i < XI; ++i)
-      if (j == i) dma16_to_lds(x_rsrc, sx + (unsigned)((wave + kLinWaves * i) * 1024), x_voff[i] + kt * (kLinK * 2));
+      if (j == i) dma16_to_lds(x_rsrc, sx + (unsigned)((wave + kLinWaves * i) * 1024), x_voff[i] + k_byte(kt));
 #pragma unroll
     for (int i = 0; i < WI; ++i)
-      if (j == XI + i) dma16_to_lds(w_rsrc, sw + (unsigned)((wave + kLinWaves * i) * 1024), w_voff[i] + kt * (kLinK * 2));
+      if (j == XI + i) dma16_to_lds(w_rsrc, sw + (unsigned)((wave + kLinWaves * i) * 1024), w_voff[i] + k_byte(kt));
   };
   auto issue_tile = [&](int kt) {
 #pragma unroll
@@ -199,6 +209,17 @@ __global__ __launch_bounds__(64 * (8 / RB) * WC, 1) void linear_kernel(LinearPar
   for (int rb = 0; rb < RB; ++rb) {
     const int m = m0 + wr * (32 * RB) + rb * 32 + r32;
     if (m >= p.rows) continue;
+    if (p.n_split > 1) {  // this split's sums, as they are
+      float* dst = p.partial + ((long long)blockIdx.y * p.rows + m) * p.n;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int col = n0 + 32 * db + 8 * j + 4 * hf;
+          if (col < p.n) *(f32x4*)(dst + col) = f32x4{acc[rb][db][4 * j], acc[rb][db][4 * j + 1], acc[rb][db][4 * j + 2], acc[rb][db][4 * j + 3]};
+        }
+      continue;
+    }
     if constexpr (EPI == 0) {
 #pragma unroll
       for (int db = 0; db < 4; ++db)
@@ -264,6 +285,80 @@ __global__ __launch_bounds__(64 * (8 / RB) * WC, 1) void linear_kernel(LinearPar
   }
 }
 
+// Second kernel of a split product: adds the splits' sums and applies the epilogue.  One thread per row and group of 4
+// columns (EPI 0) or per row, head and group of 4 rotary pairs (EPI 1: the 4 low-half columns and their partners d/2 on).
+template <int EPI>
+__global__ __launch_bounds__(256) void linear_reduce_kernel(LinearParams p) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long slice = (long long)p.rows * p.n;
+  auto sum4 = [&](long long at) {
+    f32x4 a = *(const f32x4*)(p.partial + at);
+    for (int z = 1; z < p.n_split; ++z) {
+      const f32x4 b = *(const f32x4*)(p.partial + z * slice + at);
+      a[0] += b[0]; a[1] += b[1]; a[2] += b[2]; a[3] += b[3];
+    }
+    return a;
+  };
+  if constexpr (EPI == 0) {
+    const int groups = p.n / 4;
+    if (t >= (long long)p.rows * groups) return;
+    const int m = (int)(t / groups), col = (int)(t % groups) * 4;
+    f32x4 c = sum4((long long)m * p.n + col);
+    if (p.activation == 1) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) c[e] = c[e] / (1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * c[e]));  // SiLU
+    }
+    *(u32x2*)(p.out + (long long)m * p.n + col) = u32x2{pack_bf16(c[0], c[1]), pack_bf16(c[2], c[3])};
+  } else {
+    const int d = p.head_dim, per_head = d / 8, heads = p.hq + 2 * p.hkv;
+    if (t >= (long long)p.rows * heads * per_head) return;
+    const int g = (int)(t % per_head), head = (int)((t / per_head) % heads), m = (int)(t / ((long long)per_head * heads));
+    const long long at = (long long)m * p.n + (long long)head * d + 4 * g;
+    const f32x4 a = sum4(at), b = sum4(at + d / 2);
+    __bf16* dst;
+    bool rotate = p.rope.enabled;
+    if (head < p.hq) dst = p.q_out + ((long long)m * p.hq + head) * d;
+    else if (head < p.hq + p.hkv) dst = p.k_out + ((long long)m * p.hkv + (head - p.hq)) * d;
+    else { dst = p.v_out + ((long long)m * p.hkv + (head - p.hq - p.hkv)) * d; rotate = false; }
+    float lo[4], hi[4];
+    const float pos = !rotate ? 0.f : (float)(p.positions ? p.positions[m] : m - p.cu[find_seq(p.cu, p.batch, m)]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float sn = 0.f, cs = 1.f;
+      if (rotate) sincos_turns_fast(rope_turns(pos, p.rope.hi[4 * g + e], p.rope.lo[4 * g + e]), &sn, &cs);
+      lo[e] = a[e] * cs - b[e] * sn;
+      hi[e] = b[e] * cs + a[e] * sn;
+    }
+    *(u32x2*)(dst + 4 * g) = u32x2{pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3])};
+    *(u32x2*)(dst + 4 * g + d / 2) = u32x2{pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
+  }
+}
+
+// Splits of the inner dimension for a product with few output rows.  Without a split such a product has one workgroup
+// per 128 columns, a fraction of the CUs, each streaming its slice of the weights alone at the rate one workgroup's few
+// tiles in flight allow; with z splits there are z times as many, at the price of z * rows * n fp32 partial sums written
+// and read again.  The workgroups hold most of a CU's LDS (one per CU at a time), so z is the largest count that still
+// fits ONE round of 256 workgroups; at least 4 K-tiles per split, the partial sums no larger than the weights, and
+// within the workspace given.  Measured (160 rows, k = 4096): 4096 outputs 56 -> 23 us, 6144 outputs 57 -> 28 us; with
+// 86 or more tiles (11008 outputs) the unsplit launch already draws what this access pattern gets from HBM (128-byte
+// pieces of rows 8 KB apart: about 1.5 TB/s) and splitting only adds the partial sums.
+static int linear_splits(long long rows, int k, int n, size_t workspace_bytes) {
+  const long long tiles = ((rows + kLinRows - 1) / kLinRows) * ((n + 127) / 128);
+  long long z = tiles <= 64 ? 256 / tiles : (tiles <= 128 && k >= 8192 ? 2 : 1);
+  z = std::min<long long>(z, k / 64 / 4);
+  z = std::min<long long>(z, k / (2 * rows));
+  z = std::min<long long>(z, 16);
+  const int forced = tuning(kTuneLinearSplits, 0);
+  if (forced > 0) z = std::min<long long>(forced, std::max(1, k / 64));
+  while (z > 1 && (size_t)z * rows * n * sizeof(float) > workspace_bytes) --z;
+  return (int)std::max<long long>(z, 1);
+}
+size_t linear_workspace_bytes(long long rows, int k, int n) {
+  if (rows <= 0 || k <= 0 || n <= 0 || k % kLinKMultiple != 0) return 0;
+  const int z = linear_splits(rows, k, n, ~(size_t)0);
+  return z > 1 ? ((size_t)z * rows * n * sizeof(float) + 255) / 256 * 256 : 0;
+}
+
 static int check_linear_shape(const char* who, long long rows, int k, int n) {
   if (rows <= 0 || k <= 0 || n <= 0) { set_error("%s: rows, k and n must be positive", who); return EARN_ERR_INVALID_ARG; }
   if (k % kLinKMultiple != 0 || n % 8 != 0) {
@@ -296,30 +391,57 @@ static bool linear_wide_tile(long long rows, int n) {
 }
 
 // workgroups: whole patches, a multiple of 8 of them (one per XCD and round); workgroups outside the matrix leave at once
-static long long linear_grid(long long rows, int n, int cols) {
-  const long long n_pr = ((rows + kLinRows - 1) / kLinRows + kLinPatchRows - 1) / kLinPatchRows;
-  const long long n_pc = ((n + cols - 1) / cols + kLinPatchCols - 1) / kLinPatchCols;
-  return (n_pr * n_pc + kXcds - 1) / kXcds * kXcds * kLinPatch;
+// Patch shape: 4 x 8 tiles when that leaves every XCD at least two patches, else the largest of 2 x 4, 1 x 2 and single
+// tiles that does.
+static long long linear_grid(long long rows, int n, int cols, int* patch_rows, int* patch_cols) {
+  const long long n_rt = (rows + kLinRows - 1) / kLinRows, n_ct = (n + cols - 1) / cols;
+  static const int shapes[4][2] = {{4, 8}, {2, 4}, {1, 2}, {1, 1}};
+  long long patches = 0;
+  for (int i = 0; i < 4; ++i) {
+    *patch_rows = shapes[i][0]; *patch_cols = shapes[i][1];
+    patches = ((n_rt + *patch_rows - 1) / *patch_rows) * ((n_ct + *patch_cols - 1) / *patch_cols);
+    if (patches >= 2 * kXcds) break;
+  }
+  return (patches + kXcds - 1) / kXcds * kXcds * (*patch_rows * *patch_cols);
 }
 
-int launch_linear(const void* x, const void* w, int rows, int k, int n, int activation, void* out, hipStream_t stream) {
+// tile shape, splits and grid of one product; fills the split fields of p
+struct LinearLaunch { bool wide; int splits; dim3 grid; };
+static int plan_linear(const char* who, LinearParams& p, void* workspace, size_t workspace_bytes, LinearLaunch* out) {
+  const int splits = workspace ? linear_splits(p.rows, p.k, p.n, workspace_bytes) : 1;
+  const bool wide = splits == 1 && linear_wide_tile(p.rows, p.n);
+  const long long grid = linear_grid(p.rows, p.n, wide ? 256 : 128, &p.patch_rows, &p.patch_cols);
+  if (grid > 0x7fffffffLL) { set_error("%s: grid too large", who); return EARN_ERR_UNSUPPORTED; }
+  const int k_tiles = p.k / 64;
+  p.n_split = splits;
+  p.split_tiles = (k_tiles + splits - 1) / splits;
+  p.n_split = (k_tiles + p.split_tiles - 1) / p.split_tiles;  // no empty split
+  p.partial = p.n_split > 1 ? (float*)workspace : nullptr;
+  out->wide = wide; out->splits = p.n_split; out->grid = dim3((unsigned)grid, (unsigned)p.n_split, 1);
+  return EARN_OK;
+}
+
+int launch_linear(const void* x, const void* w, int rows, int k, int n, int activation, void* out, void* workspace,
+                  size_t workspace_bytes, hipStream_t stream) {
   int rc = check_linear_shape("earn_linear", rows, k, n);
   if (rc != EARN_OK) return rc;
   LinearParams p;
   memset(&p, 0, sizeof(p));
   p.x = (const __bf16*)x; p.w = (const __bf16*)w; p.rows = rows; p.k = k; p.n = n; p.out = (__bf16*)out; p.activation = activation;
-  const bool wide = linear_wide_tile(rows, n);
-  const int cols = wide ? 256 : 128;
-  const long long grid = linear_grid(rows, n, cols);
-  if (grid > 0x7fffffffLL) { set_error("earn_linear: grid too large"); return EARN_ERR_UNSUPPORTED; }
-  if (wide) hipLaunchKernelGGL((linear_kernel<0, 128, LIN_WIDE>), dim3((unsigned)grid), dim3(LIN_WIDE_THREADS), 0, stream, p);
-  else hipLaunchKernelGGL((linear_kernel<0, 128, 2, 1, 64, 3>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+  LinearLaunch ll;
+  if ((rc = plan_linear("earn_linear", p, workspace, workspace_bytes, &ll)) != EARN_OK) return rc;
+  if (ll.wide) hipLaunchKernelGGL((linear_kernel<0, 128, LIN_WIDE>), ll.grid, dim3(LIN_WIDE_THREADS), 0, stream, p);
+  else hipLaunchKernelGGL((linear_kernel<0, 128, 2, 1, 64, 3>), ll.grid, dim3(256), 0, stream, p);
+  if (ll.splits > 1) {
+    const long long threads = (long long)rows * (n / 4);
+    hipLaunchKernelGGL((linear_reduce_kernel<0>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, p);
+  }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
 }
 
 int launch_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void* w_qkv, int rows, int d_model,
                             const int32_t* cu_seqlens, const int32_t* positions, int batch, void* q_out, void* k_out,
-                            void* v_out, hipStream_t stream) {
+                            void* v_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
   const int n = (desc->n_q_heads + 2 * desc->n_kv_heads) * desc->head_dim;
   int rc = check_linear_shape("earn_qkv_rope_project", rows, d_model, n);
   if (rc != EARN_OK) return rc;
@@ -330,16 +452,18 @@ int launch_qkv_rope_project(const earn_attn_desc* desc, const void* x, const voi
   p.cu = cu_seqlens; p.positions = positions; p.batch = batch;
   p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.head_dim = desc->head_dim;
   p.rope = make_rope_table(desc->rope_base, desc->head_dim);
-  const bool wide = linear_wide_tile(rows, n);
-  const int cols = wide ? 256 : 128;
-  const long long grid = linear_grid(rows, n, cols);
-  if (grid > 0x7fffffffLL) { set_error("earn_qkv_rope_project: grid too large"); return EARN_ERR_UNSUPPORTED; }
+  LinearLaunch ll;
+  if ((rc = plan_linear("earn_qkv_rope_project", p, workspace, workspace_bytes, &ll)) != EARN_OK) return rc;
   if (desc->head_dim == 64) {
-    if (wide) hipLaunchKernelGGL((linear_kernel<1, 64, LIN_WIDE>), dim3((unsigned)grid), dim3(LIN_WIDE_THREADS), 0, stream, p);
-    else hipLaunchKernelGGL((linear_kernel<1, 64, 2, 1, 64, 3>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+    if (ll.wide) hipLaunchKernelGGL((linear_kernel<1, 64, LIN_WIDE>), ll.grid, dim3(LIN_WIDE_THREADS), 0, stream, p);
+    else hipLaunchKernelGGL((linear_kernel<1, 64, 2, 1, 64, 3>), ll.grid, dim3(256), 0, stream, p);
   } else {
-    if (wide) hipLaunchKernelGGL((linear_kernel<1, 128, LIN_WIDE>), dim3((unsigned)grid), dim3(LIN_WIDE_THREADS), 0, stream, p);
-    else hipLaunchKernelGGL((linear_kernel<1, 128, 2, 1, 64, 3>), dim3((unsigned)grid), dim3(256), 0, stream, p);
+    if (ll.wide) hipLaunchKernelGGL((linear_kernel<1, 128, LIN_WIDE>), ll.grid, dim3(LIN_WIDE_THREADS), 0, stream, p);
+    else hipLaunchKernelGGL((linear_kernel<1, 128, 2, 1, 64, 3>), ll.grid, dim3(256), 0, stream, p);
+  }
+  if (ll.splits > 1) {
+    const long long threads = (long long)rows * (desc->n_q_heads + 2 * desc->n_kv_heads) * (desc->head_dim / 8);
+    hipLaunchKernelGGL((linear_reduce_kernel<1>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, p);
   }
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
 }

@@ -35,6 +35,8 @@ QKV_CASES = [
     (14, 2, 64, 896, [17, 530], False),             # d = 64: two heads per column tile; 18 heads = 1152 columns (9 tiles)
     (4, 4, 128, 64, [40], True),                    # one k-tile, explicit positions (compacted register rows)
     (6, 2, 64, 192, [5, 1, 250], True),
+    (8, 2, 128, 2048, [40, 17], True),              # few rows, long inner dimension: split over workgroups when allowed
+    (14, 2, 64, 1024, [33], False),
 ]
 
 
@@ -47,8 +49,21 @@ def tile(request):
     B.earn_set_tuning("linear_tile", 0)
 
 
+@pytest.fixture(params=["auto", None, 3], ids=["split-if-few-rows", "no-workspace", "three-splits"])
+def ws(request):
+    """With a workspace a few-row product splits its inner dimension (partial sums + a second kernel); without, never.
+    The third form forces three splits whatever the size (an inner dimension of fewer K-tiles takes one split per tile)."""
+    if request.param == 3:
+        B = _B()
+        B.earn_set_tuning("linear_splits", 3)
+        yield "auto"
+        B.earn_set_tuning("linear_splits", 0)
+    else:
+        yield request.param
+
+
 @pytest.mark.parametrize("hq,hkv,d,dm,lens,explicit", QKV_CASES)
-def test_qkv_projection_matches_oracle(hq, hkv, d, dm, lens, explicit, tile):
+def test_qkv_projection_matches_oracle(hq, hkv, d, dm, lens, explicit, tile, ws):
     B = _B()
     rows, batch = sum(lens), len(lens)
     g = torch.Generator().manual_seed(rows + dm)
@@ -62,7 +77,7 @@ def test_qkv_projection_matches_oracle(hq, hkv, d, dm, lens, explicit, tile):
     k = torch.full((rows, hkv, d), float("nan"), dtype=BF, device=DEV)
     v = torch.full((rows, hkv, d), float("nan"), dtype=BF, device=DEV)
     B.earn_qkv_rope_project(desc, x.to(DEV), wt(w), None if explicit else torch.from_numpy(cu).to(DEV),
-                            torch.from_numpy(pos).to(DEV) if explicit else None, batch, q, k, v)
+                            torch.from_numpy(pos).to(DEV) if explicit else None, batch, q, k, v, workspace=ws)
     torch.cuda.synchronize()
     ref = O.qkv_project(W.to_f64(x), W.to_f64(w), hq, hkv, d, pos)
     check_attn(q, ref["q"], BF, "q")
@@ -70,7 +85,7 @@ def test_qkv_projection_matches_oracle(hq, hkv, d, dm, lens, explicit, tile):
     check_attn(v, ref["v"], BF, "v")
     # rotation off: the plain product
     desc0 = B.make_desc(BF, hq, hkv, d, rope_base=0.0)
-    B.earn_qkv_rope_project(desc0, x.to(DEV), wt(w), None, None, batch, q, k, v)
+    B.earn_qkv_rope_project(desc0, x.to(DEV), wt(w), None, None, batch, q, k, v, workspace=ws)
     torch.cuda.synchronize()
     ref0 = O.qkv_project(W.to_f64(x), W.to_f64(w), hq, hkv, d, pos, rope_base=0.0)
     check_attn(q, ref0["q"], BF, "q without rotation")
@@ -78,13 +93,13 @@ def test_qkv_projection_matches_oracle(hq, hkv, d, dm, lens, explicit, tile):
 
 
 @pytest.mark.parametrize("rows,k,n,act", [(300, 256, 512, 0), (1000, 4096, 136, 1), (7, 64, 8, 1), (513, 128, 1000, 0),
-                                           (256, 1024, 128, 1)])
-def test_linear_matches_oracle(rows, k, n, act, tile):
+                                           (256, 1024, 128, 1), (40, 2048, 328, 1), (160, 4096, 256, 0)])
+def test_linear_matches_oracle(rows, k, n, act, tile, ws):
     B = _B()
     g = torch.Generator().manual_seed(rows + k + n)
     x, w = rnd(g, rows, k), rnd(g, k, n, scale=k ** -0.5)
     out = torch.full((rows + 1, n), float("nan"), dtype=BF, device=DEV)
-    B.earn_linear(x.to(DEV), wt(w), out[:rows], act)
+    B.earn_linear(x.to(DEV), wt(w), out[:rows], act, workspace=ws)
     torch.cuda.synchronize()
     ref = O.linear(W.to_f64(x), W.to_f64(w), act)
     got = out[:rows].cpu().double().numpy()
