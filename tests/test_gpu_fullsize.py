@@ -274,3 +274,109 @@ def test_full_size_decode_sampled_streams(name, mode):
         check_attn(gk[u, step][kvh], ogk[0, step], BF, f"{name}/{mode} stream {u} appended key")
         assert torch.equal(gv[u, step].cpu(), w.decode_tensor("v", layer, step, streams=[u])[0])
         del sl
+
+
+@pytest.mark.parametrize("mode", ["full", "registers"])
+def test_full_size_decode_layer_batched_as_benchmarked(mode):
+    """The launch configuration bench.py times on the headline workload: one decode step of ALL full-cache layers (k of
+    them) or ALL register-cache layers (N - k) in ONE layer-batched launch at full size; sampled (layer, stream, head)
+    rows against the oracle, the appended cache rows included."""
+    B = _B()
+    cfg = W.CONFIGS["long_beam"]
+    w = W.Workload(cfg)
+    layers = list(range(cfg.split_k)) if mode == "full" else list(range(cfg.split_k, cfg.n_layers))
+    L = len(layers)
+    step = cfg.decode_steps // 2
+    G, S = cfg.decode_steps, w.n_streams
+    if mode == "full":
+        lens, coords_dev = w.seq_lengths, w.token_coords(DEV)
+    else:
+        lens = [cfg.r] * cfg.batch
+        ref_c = O.compact_registers(None, np.asarray(w.cu_seqlens, dtype=np.int32), cfg.n_head_reg, cfg.n_tail_reg)
+        seq = torch.repeat_interleave(torch.arange(cfg.batch), cfg.r)
+        coords_dev = (seq.to(DEV), torch.from_numpy(ref_c["pos"]).long().to(DEV))
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    stack = lambda f: torch.stack([f(l) for l in layers])
+    sk = stack(lambda l: w.prefill_tensor("k", l, coords=coords_dev))
+    sv = stack(lambda l: w.prefill_tensor("v", l, coords=coords_dev))
+    q = stack(lambda l: w.decode_tensor("q", l, step, device=DEV))
+    kn = stack(lambda l: w.decode_tensor("k", l, step, device=DEV))
+    vn = stack(lambda l: w.decode_tensor("v", l, step, device=DEV))
+    gk = torch.zeros(L, S, G, cfg.n_kv_heads, cfg.head_dim, dtype=cfg.torch_dtype, device=DEV)
+    gv = torch.zeros_like(gk)
+    for i, l in enumerate(layers):
+        for g in range(step):
+            gk[i, :, g] = w.decode_tensor("k", l, g, device=DEV)
+            gv[i, :, g] = w.decode_tensor("v", l, g, device=DEV)
+    i32 = lambda a: torch.tensor(list(a), dtype=torch.int32, device=DEV)
+    q_pos = w.decode_positions(step)
+    out = torch.full_like(q, float("nan"))
+    desc = B.make_desc(cfg.torch_dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, 0.0, cfg.rope_base)
+    B.earn_decode_attn_layers(desc, q, kn, vn, i32(q_pos), sk, sv, i32(cu), i32(w.stream_to_seq), gk, gv, i32([step] * S), G,
+                              S, cfg.batch, max(lens), out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+
+    rng = np.random.default_rng(300 + L)
+    gq = cfg.n_q_heads // cfg.n_kv_heads
+    for i in sorted({0, L - 1, int(rng.integers(0, L))}):
+        l = layers[i]
+        for u in sorted({0, S - 1, int(rng.integers(0, S))}):
+            s = w.stream_to_seq[u]
+            n = lens[s]
+            heads = sorted({0, cfg.n_q_heads - 1, int(rng.integers(0, cfg.n_q_heads))})
+            kvh = sorted({a // gq for a in heads})
+            if mode == "full":
+                cs = w.token_coords("cpu", seqs=[s])
+            else:
+                cs = (torch.full((cfg.r,), s, dtype=torch.int64), torch.from_numpy(ref_c["pos"][s * cfg.r:(s + 1) * cfg.r]).long())
+            skc = W.to_f64(w.prefill_tensor("k", l, coords=cs, heads=kvh))
+            svc = W.to_f64(w.prefill_tensor("v", l, coords=cs, heads=kvh))
+            qc = W.to_f64(w.decode_tensor("q", l, step, streams=[u])[:, heads])
+            knc = W.to_f64(w.decode_tensor("k", l, step, streams=[u])[:, kvh])
+            vnc = W.to_f64(w.decode_tensor("v", l, step, streams=[u])[:, kvh])
+            ogk = np.zeros((1, G, len(kvh), cfg.head_dim))
+            ogv = np.zeros_like(ogk)
+            for g in range(step):
+                ogk[0, g] = W.to_f64(w.decode_tensor("k", l, g, streams=[u])[:, kvh])[0]
+                ogv[0, g] = W.to_f64(w.decode_tensor("v", l, g, streams=[u])[:, kvh])[0]
+            ref = O.decode_attn(qc, knc, vnc, [q_pos[u]], skc, svc, [0, n], None, ogk, ogv, [step],
+                                q_to_kv=[kvh.index(a // gq) for a in heads], rope_base=cfg.rope_base)
+            check_attn(out[i, u][heads], ref["out"][0], BF, f"long_beam/{mode} batched layer {l} stream {u}")
+            check_attn(gk[i, u, step][kvh], ogk[0, step], BF, f"long_beam/{mode} batched layer {l} stream {u} appended key")
+            assert torch.equal(gv[i, u, step].cpu(), w.decode_tensor("v", l, step, streams=[u])[0])
+
+
+def test_full_size_register_prefill_layer_batched_as_benchmarked():
+    """The register-focused prefill layers k..N-1 of the headline workload in ONE layer-batched launch, as bench.py times
+    them: compacted sequences of r rows at their original positions; every row of sampled (layer, sequence) pairs against
+    the oracle, outputs, rotated keys (the caches) and log-sum-exps."""
+    B = _B()
+    cfg = W.CONFIGS["long_beam"]
+    w = W.Workload(cfg)
+    layers = list(range(cfg.split_k, cfg.n_layers))
+    L, r, batch = len(layers), cfg.r, cfg.batch
+    ref_c = O.compact_registers(None, np.asarray(w.cu_seqlens, dtype=np.int32), cfg.n_head_reg, cfg.n_tail_reg)
+    seq = torch.repeat_interleave(torch.arange(batch), r)
+    coords_dev = (seq.to(DEV), torch.from_numpy(ref_c["pos"]).long().to(DEV))
+    stack = lambda what: torch.stack([w.prefill_tensor(what, l, coords=coords_dev) for l in layers])
+    q, k, v = stack("q"), stack("k"), stack("v")
+    out, krot = torch.full_like(q, float("nan")), torch.full_like(k, float("nan"))
+    lse = torch.full((L, batch * r, cfg.n_q_heads), float("nan"), dtype=torch.float32, device=DEV)
+    i32 = lambda a: torch.tensor(np.asarray(a), dtype=torch.int32, device=DEV)
+    desc = B.make_desc(cfg.torch_dtype, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, 0.0, cfg.rope_base)
+    B.earn_prefill_attn_layers(desc, q, k, v, i32(ref_c["cu"]), i32(ref_c["pos"]), batch, batch * r, r, out, krot, lse)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(krot.float()).all() and torch.isfinite(lse).all()
+    rng = np.random.default_rng(77)
+    for i in sorted({0, L - 1, int(rng.integers(0, L))}):
+        for s in sorted({0, batch - 1, int(rng.integers(0, batch))}):
+            cs = (torch.full((r,), s, dtype=torch.int64), torch.from_numpy(ref_c["pos"][s * r:(s + 1) * r]).long())
+            f = lambda what: W.to_f64(w.prefill_tensor(what, layers[i], coords=cs))
+            ref = O.prefill_attn(f("q"), f("k"), f("v"), [0, r], positions=ref_c["pos"][s * r:(s + 1) * r],
+                                 rope_base=cfg.rope_base)
+            sl = slice(s * r, (s + 1) * r)
+            check_attn(out[i, sl], ref["out"], BF, f"layer {layers[i]} sequence {s} out")
+            check_attn(krot[i, sl], ref["k_rot"], BF, f"layer {layers[i]} sequence {s} rotated keys")
+            got_lse = lse[i, sl].cpu().double().numpy()
+            assert (np.abs(got_lse - ref["lse"]) <= 5e-2 + 1e-2 * np.abs(ref["lse"])).all()
