@@ -196,3 +196,37 @@ def test_projection_fed_path_matches_oracle(hq, hkv, d, dm, lens):
         rd = O.decode_attn(pd["q"], pd["k"], pd["v"], qp, pc["k"], pc["v"], scu, None, ogk, ogv, [0] * S, rope_base=0.0)
         check_attn(od, rd["out"], BF, "decode")
         check_attn(gk[:, 0], ogk[:, 0], BF, "appended key")
+
+
+def test_full_size_projections_sampled_rows():
+    """The headline workload's projection sizes (132096 rows, d_model 4096, d_ffn 11008, 32 + 2 x 8 heads of 128), in the
+    256 x 256 tile form the library picks for them: sampled rows (tile corners, the last row, random rows) of the
+    feed-forward product with SiLU and of the Q/K/V projection with rotation against the oracle."""
+    B = _B()
+    cfg = W.CONFIGS["long_beam"]
+    w_ = W.Workload(cfg)
+    rows, dm, df, hq, hkv, d = w_.total_tokens, 4096, 11008, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    g = torch.Generator(device=DEV).manual_seed(5)
+    x = torch.randn(rows, dm, device=DEV, generator=g).to(BF)
+    w_up = (torch.randn(df, dm, device=DEV, generator=g) * dm ** -0.5).to(BF)
+    w_qkv = (torch.randn((hq + 2 * hkv) * d, dm, device=DEV, generator=g) * dm ** -0.5).to(BF)
+    rng = np.random.default_rng(11)
+    sample = sorted({0, 255, 256, 1023, 1024, rows - 257, rows - 1, *[int(r) for r in rng.integers(0, rows, size=24)]})
+    xs = W.to_f64(x[sample].cpu())
+    # feed-forward up-projection with SiLU
+    hmid = torch.empty(rows, df, dtype=BF, device=DEV)
+    B.earn_linear(x, w_up, hmid, 1, None)
+    torch.cuda.synchronize()
+    ref = O.linear(xs, W.to_f64(w_up.cpu()).T, 1)
+    check_attn(hmid[sample].cpu()[:, None, :], ref[:, None, :], BF, "ffn up + SiLU, sampled rows")
+    del hmid
+    # Q/K/V projection with rotation at the tokens' positions
+    pos = np.concatenate([np.arange(n) for n in w_.seq_lengths]).astype(np.int32)
+    cu = torch.tensor(w_.cu_seqlens, dtype=torch.int32, device=DEV)
+    q, k, v = (torch.empty(rows, h_, d, dtype=BF, device=DEV) for h_ in (hq, hkv, hkv))
+    B.earn_qkv_rope_project(B.make_desc(BF, hq, hkv, d, 0.0, cfg.rope_base), x, w_qkv, cu, None, cfg.batch, q, k, v, None)
+    torch.cuda.synchronize()
+    ref = O.qkv_project(xs, W.to_f64(w_qkv.cpu()).T, hq, hkv, d, pos[sample], rope_base=cfg.rope_base)
+    check_attn(q[sample], ref["q"], BF, "q, sampled rows")
+    check_attn(k[sample], ref["k"], BF, "k, sampled rows")
+    check_attn(v[sample], ref["v"], BF, "v, sampled rows")
