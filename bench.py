@@ -10,7 +10,8 @@ The timed steps run in the harness throughput mode: the synthetic layers are ind
 register-only prefill layers and, per decode step, the k full-cache layers and the N-k register-cache layers each go
 out as ONE layer-batched launch (earn_prefill_attn_layers / earn_decode_attn_layers); the full-length prefill layers
 stay one launch per layer.  The same steps with one launch per layer (the form a real model needs, where layer l+1
-depends on layer l) are timed right after and reported under "per_layer_launch".
+depends on layer l) are timed right after and reported under "per_layer_launch", and once more with those per-layer
+launches replayed from HIP graphs ("per_layer_launch_graph").
 
 Prints ONE JSON line.  `value` is the prefill-attention rate in algorithmic causal TFLOP/s
 (4*d*Hq*sum_s m_s(m_s+1)/2 per layer, summed over all N prefill launches, divided by the time the prefill
@@ -170,7 +171,16 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
     dec_full_b = [path.bind_decode_full_layers(dq[g][:kk], dk[g][:kk], dv[g][:kk]) for g in range(G)]
     dec_reg_b = [path.bind_decode_register_layers(dq[g][kk:], dk[g][kk:], dv[g][kk:]) for g in range(G)]
 
-    def one_step(tm: PhaseTimer | None, batched: bool):
+    # the per-layer launches of the launch-bound phases recorded into HIP graphs (one replay per phase and decode step);
+    # the calls read what the prefill and the compaction wrote (caches, compacted bounds and positions): run those first
+    from paper_2507_00715_amd.pipeline import capture_graph
+    path.prefill(q, k, v, x)
+    torch.cuda.synchronize()
+    reg_prefill_g = capture_graph(reg_prefill) if N > kk else None
+    dec_full_g = [capture_graph([steps_pos[g]] + dec[g][:kk]) for g in range(G)]
+    dec_reg_g = [capture_graph(dec[g][kk:]) if N > kk else None for g in range(G)]
+
+    def one_step(tm: PhaseTimer | None, batched, graphs: bool = False):
         ph = (lambda n: tm.start(n)) if tm else (lambda n: None)
         pe = (lambda n: tm.stop(n)) if tm else (lambda n: None)
         ph("prefill_full")
@@ -181,42 +191,52 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
         path.compact(x, q, k, v)
         pe("compact")
         ph("prefill_reg")
-        if batched:
+        if graphs:
+            if reg_prefill_g is not None:
+                reg_prefill_g.replay()
+        elif batched:
             reg_prefill_b()
         else:
             for call in reg_prefill:
                 call()
         pe("prefill_reg")
         for g in range(G):
-            steps_pos[g]()
+            if not graphs:
+                steps_pos[g]()
             ph("decode_full")
-            if batched:
+            if graphs:
+                dec_full_g[g].replay()           # (the step's position update is its first node)
+            elif batched:
                 dec_full_b[g]()
             else:
                 for l in range(kk):
                     dec[g][l]()
             pe("decode_full")
             ph("decode_reg")
-            if batched:
+            if graphs:
+                if dec_reg_g[g] is not None:
+                    dec_reg_g[g].replay()
+            elif batched:
                 dec_reg_b[g]()
             else:
                 for l in range(kk, N):
                     dec[g][l]()
             pe("decode_reg")
 
-    def timed(batched: bool, n_steps: int):
+    def timed(batched: bool, n_steps: int, graphs: bool = False):
         for _ in range(warmup):
-            one_step(None, batched)
+            one_step(None, batched, graphs)
         torch.cuda.synchronize()
         tm = PhaseTimer()
         t0 = time.perf_counter()
         for _ in range(n_steps):
-            one_step(tm, batched)
+            one_step(tm, batched, graphs)
         torch.cuda.synchronize()
         return tm.totals_ms(), time.perf_counter() - t0
 
     ms, wall = timed(True, steps)
     ms_pl, wall_pl = timed(False, steps)
+    ms_gr, wall_gr = timed(False, steps, graphs=True)
     alg = algorithmic_counts(w)
 
     # The same N layers the vanilla way (Section 3.3's baseline: every layer full length), measured: N full-length
@@ -337,6 +357,12 @@ def run_workload(name: str, steps: int, warmup: int, dev) -> dict:
     pl = figures(ms_pl, wall_pl)
     res["per_layer_launch"] = {k_: pl[k_] for k_ in ("ms_per_step", "prefill_tflops", "prefill_register_layer", "decode",
                                                      "phase_ms_per_step")}
+    gr = figures(ms_gr, wall_gr)
+    res["per_layer_launch_graph"] = {k_: gr[k_] for k_ in ("ms_per_step", "prefill_tflops", "prefill_register_layer", "decode",
+                                                           "phase_ms_per_step")}
+    res["per_layer_launch_graph"]["note"] = ("the per-layer launches of the register prefill and of every decode step "
+                                             "replayed from HIP graphs (one launch per layer inside, the form a real "
+                                             "model needs)")
     full_ms = res["prefill_full_layer"]["ms_per_launch"]
     res["last_full_layer_register_rows_only"] = None if rows_only is None else {
         "ms_per_launch": rows_only, "full_layer_ms_per_launch": full_ms,
@@ -836,6 +862,7 @@ def main():
         "prefill_register_layer": head["prefill_register_layer"],
         "phase_ms_per_step": head["phase_ms_per_step"],
         "per_layer_launch": head["per_layer_launch"],
+        "per_layer_launch_graph": head["per_layer_launch_graph"],
         "attention_statistics": head["attention_statistics"],
         "beam_search_width_20": beams20,
         "decoder_layer_with_projections": layer,

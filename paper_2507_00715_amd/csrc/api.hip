@@ -85,8 +85,8 @@ int launch_attn_backward(const earn_attn_desc* desc, const void* q, const void* 
 int launch_rope_keys(const earn_attn_desc* desc, const void* k, void* k_rot, const int32_t* cu_seqlens,
                      const int32_t* positions, int batch, int total_tokens, hipStream_t stream);
 int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
-                            const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen,
-                            int rows_per_seq, void* out_rows, hipStream_t stream);
+                            const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int total_tokens,
+                            int max_seqlen, int rows_per_seq, void* out_rows, hipStream_t stream);
 size_t prefill_rows_workspace_bytes(int hq, int hkv, int d, int batch, int max_seqlen, int rows_per_seq);
 int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
                         const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen, int rows_per_seq,
@@ -537,8 +537,8 @@ int earn_prefill_register_rows(const earn_attn_desc* desc, const void* q_rows, c
   if (desc->dtype == EARN_F32) {
     rc = launch_rope_keys(desc, k, k_rot_out, cu_seqlens, nullptr, batch, total_tokens, (hipStream_t)stream);
     if (rc != EARN_OK) return rc;
-    return launch_prefill_rows_f32(desc, q_rows, k_rot_out, v, cu_seqlens, row_pos, batch, max_seqlen, rows_per_seq,
-                                   out_rows, (hipStream_t)stream);
+    return launch_prefill_rows_f32(desc, q_rows, k_rot_out, v, cu_seqlens, row_pos, batch, total_tokens, max_seqlen,
+                                   rows_per_seq, out_rows, (hipStream_t)stream);
   }
   const size_t need = prefill_rows_workspace_bytes(desc->n_q_heads, desc->n_kv_heads, desc->head_dim, batch, max_seqlen, rows_per_seq);
   if (need > workspace_bytes || (need > 0 && !workspace)) {

@@ -32,6 +32,7 @@ struct PrefillParams {
   const f32x2* cs;  // [tokens][d/2] (cos, sin) of every token's rotary angles, written by rope_k_kernel (bf16 paths)
   void* out; float* lse;
   int batch, hq, hkv, max_seqlen;
+  int total;   // rows of the packed tensors
   int n_qblk;  // query blocks of the longest sequence
   // chosen-rows mode of the vector kernel (rows_per_seq > 0): q and out hold rows_per_seq rows per sequence in
   // compacted order, row m of sequence s being token row_pos[s * rows_per_seq + m] (ascending) of the sequence
@@ -44,6 +45,14 @@ struct PrefillParams {
   RopeTable rope;
   HeadMap heads;
 };
+
+// Bounds of sequence s as the kernels use them: whatever cu_seqlens holds, rows [b0, b0 + n) lie inside the packed
+// tensors and n within the length the launch was sized (and its 32-bit offsets checked) for.  A corrupt or not yet
+// written cu_seqlens then gives wrong values, never an access outside the tensors.
+__device__ __forceinline__ void pf_seq_bounds(const PrefillParams& p, int s, int& b0, int& n) {
+  b0 = min(max(p.cu[s], 0), p.total);
+  n = min(min(max(p.cu[s + 1] - b0, 0), p.total - b0), p.max_seqlen);
+}
 
 template <typename P>
 __device__ __forceinline__ P* pf_layer_ptr(P* base, long long stride, int layer) {
@@ -157,16 +166,18 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   const int slot = blockIdx.y, s = blockIdx.z % p.batch;  // slot: the query heads in kv-head order
   const PfLayer lv = pf_layer_view(p, blockIdx.z / p.batch);
   const int a = head_of_slot(p.heads, slot);
-  const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
+  int b0, n;
+  pf_seq_bounds(p, s, b0, n);
   const int row0 = blockIdx.x * 64;
   const int r = p.rows_per_seq;           // 0: every row of the sequence
   const int n_rows = r > 0 ? r : n;
-  if (row0 >= n_rows) return;
+  if (row0 >= n_rows || n <= 0) return;
   const int qt = threadIdx.x & 3;
   const int mrow = row0 + (threadIdx.x >> 2);                  // row of the sequence's row list
   const bool row_ok = mrow < n_rows;
   const int mc = row_ok ? mrow : n_rows - 1;
-  const int ic = r > 0 ? p.row_pos[s * r + mc] : mc;           // its token index: it sees keys 0 .. ic
+  // its token index: it sees keys 0 .. ic (a row_pos outside the sequence is held inside it: wrong values, no stray access)
+  const int ic = r > 0 ? min(max(p.row_pos[s * r + mc], 0), n - 1) : mc;
   const long long io = r > 0 ? (long long)s * r + mc : (long long)b0 + mc;  // its row in q / out / lse
   const int c = slot / (p.hq / p.hkv);
   const T* qrow = (const T*)lv.q + (io * p.hq + a) * D;
@@ -187,7 +198,7 @@ __global__ __launch_bounds__(256) void prefill_rows_kernel(PrefillParams p) {
   for (int e = 0; e < E; ++e) { ol[e] = 0.f; oh[e] = 0.f; }
   // all rows of a wave walk the keys together up to the wave's last row
   const int wave_last_row = min(n_rows - 1, row0 + (int)(threadIdx.x / kWave) * 16 + 15);
-  const int wave_last = r > 0 ? p.row_pos[s * r + wave_last_row] : wave_last_row;
+  const int wave_last = r > 0 ? min(max(p.row_pos[s * r + wave_last_row], 0), n - 1) : wave_last_row;
   const T* kbase = (const T*)lv.k_rot + ((long long)b0 * p.hkv + c) * D;
   const T* vbase = (const T*)lv.v + ((long long)b0 * p.hkv + c) * D;
   const long long rs = (long long)p.hkv * D;
@@ -267,8 +278,7 @@ __device__ __forceinline__ PfBlock pf_map_block(const PrefillParams& p, int bloc
   const int s = pair / p.hkv;
   b.c = pair % p.hkv;
   b.a = head_of_slot(p.heads, b.c * gq + rem % gq);
-  b.b0 = p.cu[s];
-  b.n = p.cu[s + 1] - b.b0;
+  pf_seq_bounds(p, s, b.b0, b.n);
   b.q0 = qblk * block_rows;
   b.valid = b.q0 < b.n;
   return b;
@@ -786,13 +796,14 @@ static void launch_rope_k(const void* k, void* k_rot, const int32_t* cu, const i
 
 // fp32: the chosen rows of every sequence (q_rows, out_rows: [batch * r, Hq, d]) against the rotated keys, vector kernel
 int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
-                            const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen,
-                            int rows_per_seq, void* out_rows, hipStream_t stream) {
+                            const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int total_tokens,
+                            int max_seqlen, int rows_per_seq, void* out_rows, hipStream_t stream) {
   const int d = desc->head_dim;
   PrefillParams p;
   p.cs = nullptr; p.row_pos = row_pos; p.rows_per_seq = rows_per_seq;
   p.q = q_rows; p.k_rot = k_rot; p.v = v; p.cu = cu_seqlens; p.positions = nullptr; p.out = out_rows; p.lse = nullptr;
   p.batch = batch; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.max_seqlen = max_seqlen; p.n_qblk = 1;
+  p.total = total_tokens;
   p.ls_q = p.ls_k_rot = p.ls_v = p.ls_out = p.ls_lse = 0;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = scale * 1.4426950408889634f;
@@ -848,6 +859,7 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
   p.cs = cs; p.row_pos = nullptr; p.rows_per_seq = 0;
   p.q = q; p.k_rot = k_rot; p.v = v; p.cu = cu_seqlens; p.positions = positions; p.out = out; p.lse = lse_out;
   p.batch = batch; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads; p.max_seqlen = max_seqlen;
+  p.total = total_tokens;
   p.ls_q = layers ? layers->q : 0; p.ls_k_rot = in_place ? ls_k : ls_kr; p.ls_v = ls_k; p.ls_out = layers ? layers->out : 0;
   p.ls_lse = layers ? layers->lse : 0;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);

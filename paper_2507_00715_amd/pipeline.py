@@ -28,6 +28,27 @@ import torch
 from . import binding as B
 
 
+def capture_graph(calls) -> "torch.cuda.CUDAGraph":
+    """Record a sequence of launches into a HIP graph and return it; `replay()` then enqueues the whole sequence with
+    one call.  For the launch-bound stretches of the path in the form a real model needs them (layer l+1 reads what
+    layer l wrote, so the layers cannot share a launch): a decode step is N small launches per step, each costing more
+    host time than GPU time.  `calls` are objects that only enqueue kernels on the current stream on buffers that stay
+    where they are (BoundCall objects, or the path's methods with fixed arguments): the entry points allocate nothing
+    and do not synchronise, and none of them clears memory with a memset node.  The validation mode (which copies to
+    the host) must be off."""
+    side = torch.cuda.Stream()                       # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                    # one eager pass first: nothing lazy is left for the capture
+        for c in calls:
+            c()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for c in calls:
+            c()
+    return graph
+
+
 class EarnPath:
     def __init__(self, *, n_layers: int, split_k: int, n_head_reg: int, n_tail_reg: int, n_q_heads: int,
                  n_kv_heads: int, head_dim: int, dtype: torch.dtype, cu_seqlens: Sequence[int],
@@ -52,9 +73,11 @@ class EarnPath:
         # one stream per sequence in order: the library takes "no map" and saves every decode workgroup a dependent load
         identity = list(stream_to_seq) == list(range(self.batch))
         self.stream_to_seq = None if identity else torch.tensor(list(stream_to_seq), dtype=i32, device=dev)
-        self.idx = torch.empty(self.Tc, dtype=i32, device=dev)
-        self.pos = torch.empty(self.Tc, dtype=i32, device=dev)
-        self.cu_c = torch.empty(self.batch + 1, dtype=i32, device=dev)
+        # written by the compaction; valid (if not yet meaningful) before it has run, so that a call bound to them can be
+        # launched at any time: the library trusts cu_seqlens arrays
+        self.idx = torch.zeros(self.Tc, dtype=i32, device=dev)
+        self.pos = torch.zeros(self.Tc, dtype=i32, device=dev)
+        self.cu_c = torch.arange(0, (self.batch + 1) * self.r, self.r, dtype=i32, device=dev)
         e = lambda *shape: torch.empty(shape, dtype=dtype, device=dev)
         N, k = self.N, self.k
         rows_layer = k - 1 if self.rows_only else -1
