@@ -16,8 +16,12 @@
  *     non-decreasing, n_s >= h+t, 0 <= gen_len < gen_cap, stream_to_seq in [0, batch), positions >= 0) are
  *     PRECONDITIONS and are NOT checked by a normal call.  What the kernels do guard: gen_len is clamped into
  *     [0, gen_cap) before the cache append and the walk over the generated rows, stream_to_seq is clamped into
- *     [0, batch), and the compaction clamps a source row into its sequence (an empty sequence yields zero rows);
- *     the VALUES of cu_seqlens / shared_cu are trusted: wrong bounds there read or write outside the tensors.
+ *     [0, batch), the compaction clamps a source row into its sequence (an empty sequence yields zero rows), and the
+ *     prefill entry points, which are told total_tokens, hold every sequence's bounds inside [0, total_tokens], its
+ *     length within max_seqlen and (earn_prefill_register_rows) every row_pos inside its sequence: wrong values
+ *     there give wrong results, no stray access.  The decode and compaction entry points are not told how many rows
+ *     their tensors hold: the VALUES of shared_cu / cu_seqlens are trusted there, and wrong bounds read or write
+ *     outside the tensors.
  *     earn_set_validation(1) switches on a debug mode in which every call first copies these arrays to the host,
  *     checks them and returns EARN_ERR_INVALID_ARG before any kernel is launched;
  *   - return value: EARN_OK or a negative error code; earn_last_error() returns a thread-local message.
