@@ -19,9 +19,9 @@
  *     [0, batch), the compaction clamps a source row into its sequence (an empty sequence yields zero rows), and the
  *     prefill entry points, which are told total_tokens, hold every sequence's bounds inside [0, total_tokens], its
  *     length within max_seqlen and (earn_prefill_register_rows) every row_pos inside its sequence: wrong values
- *     there give wrong results, no stray access.  The decode and compaction entry points are not told how many rows
- *     their tensors hold: the VALUES of shared_cu / cu_seqlens are trusted there, and wrong bounds read or write
- *     outside the tensors.
+ *     there give wrong results, no stray access.  The same holds for the decode entry points (shared_cu against
+ *     shared_total and max_shared_len), the compaction, the statistics and the backward (cu_seqlens against
+ *     total_tokens): wrong VALUES in these arrays give wrong results, never an access outside the tensors.
  *     earn_set_validation(1) switches on a debug mode in which every call first copies these arrays to the host,
  *     checks them and returns EARN_ERR_INVALID_ARG before any kernel is launched;
  *   - return value: EARN_OK or a negative error code; earn_last_error() returns a thread-local message.
@@ -149,17 +149,18 @@ size_t earn_prefill_workspace_bytes(const earn_attn_desc* desc, int32_t batch, i
  *                  dst[i] is [batch*(h+t), row_bytes[i]] bytes; 16-byte aligned; n_tensors may be 0 (indices only)
  *   row_bytes      HOST array, each a positive multiple of 16
  *   cu_seqlens     [batch+1] int32 (device)
+ *   total_tokens   rows of every src[i] (>= cu_seqlens[batch]); source rows are held inside it
  *   idx_out        [batch*(h+t)] int32 or NULL: source row of every kept row
  *   pos_out        [batch*(h+t)] int32 or NULL: original position p of every kept row
  *   cu_out         [batch+1] int32 or NULL: cu_out[s] = s*(h+t)
  *
  * Precondition (device data): n_s >= h + t for every s.  n_s == h + t is the identity permutation.
- * Errors: batch <= 0, h < 0, t < 0, h + t == 0, n_tensors < 0 or > EARN_MAX_COMPACT_TENSORS, NULL src/dst/row_bytes
+ * Errors: batch <= 0, total_tokens < 0, h < 0, t < 0, h + t == 0, n_tensors < 0 or > EARN_MAX_COMPACT_TENSORS, NULL src/dst/row_bytes
  * with n_tensors > 0, a NULL or misaligned tensor pointer, row_bytes not a positive multiple of 16 -> INVALID_ARG.
  */
 int earn_compact_registers(int32_t n_tensors, const void* const* src, void* const* dst, const int64_t* row_bytes,
-                           const int32_t* cu_seqlens, int32_t batch, int32_t n_head_reg, int32_t n_tail_reg,
-                           int32_t* idx_out, int32_t* pos_out, int32_t* cu_out, void* stream);
+                           const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t n_head_reg,
+                           int32_t n_tail_reg, int32_t* idx_out, int32_t* pos_out, int32_t* cu_out, void* stream);
 
 /*
  * Positions of decode step `step` (the reading of Section 3.2's decoding bullet that this library takes: a generated
@@ -198,6 +199,7 @@ int earn_decode_step_positions(const int32_t* cu_seqlens, const int32_t* stream_
  *   gen_k, gen_v       [n_streams, gen_cap, Hkv, d]; slot gen_len[u] of stream u is written by this call
  *   gen_len            [n_streams] int32, 0 <= gen_len[u] < gen_cap
  *   max_shared_len     upper bound on shared_cu[s+1] - shared_cu[s]
+ *   shared_total       rows of shared_k / shared_v (>= shared_cu[batch]); sequence bounds are held inside it
  *   out                [n_streams, Hq, d]
  *   workspace          at least earn_decode_workspace_bytes(...) bytes, 256-byte aligned
  *
@@ -208,7 +210,7 @@ int earn_decode_step_positions(const int32_t* cu_seqlens, const int32_t* stream_
 int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
                      const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                      const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int32_t gen_cap,
-                     int32_t n_streams, int32_t batch, int32_t max_shared_len, void* out, void* workspace,
+                     int32_t n_streams, int32_t batch, int32_t max_shared_len, int32_t shared_total, void* out, void* workspace,
                      size_t workspace_bytes, void* stream);
 
 /* Workspace earn_decode_attn needs (bytes) for split-key partial results. 0 on invalid desc. */
@@ -240,7 +242,7 @@ int earn_decode_attn_layers(const earn_attn_desc* desc, int32_t n_layers, const 
                             const void* shared_k, const void* shared_v, int64_t shared_layer_stride,
                             const int32_t* shared_cu, const int32_t* stream_to_seq, void* gen_k, void* gen_v,
                             int64_t gen_layer_stride, const int32_t* gen_len, int32_t gen_cap, int32_t n_streams,
-                            int32_t batch, int32_t max_shared_len, void* out, int64_t out_layer_stride, void* workspace,
+                            int32_t batch, int32_t max_shared_len, int32_t shared_total, void* out, int64_t out_layer_stride, void* workspace,
                             size_t workspace_bytes, void* stream);
 size_t earn_decode_layers_workspace_bytes(const earn_attn_desc* desc, int32_t n_layers, int32_t n_streams,
                                           int32_t batch, int32_t max_shared_len, int32_t gen_cap);
@@ -267,7 +269,7 @@ int earn_decode_attn_static(const earn_attn_desc* desc, const void* q, const voi
                             const int32_t* q_pos, const void* shared_k, const void* shared_v,
                             const int32_t* shared_cu, const int32_t* stream_to_seq, void* gen_k, void* gen_v,
                             const int32_t* gen_len, int32_t gen_cap, int32_t n_streams, int32_t batch,
-                            int32_t max_shared_len, void* out, void* stream);
+                            int32_t max_shared_len, int32_t shared_total, void* out, void* stream);
 
 /*
  * Prefill attention of the LAST full-length layer (layer k-1) at the register rows only.
@@ -396,7 +398,7 @@ int earn_decode_attn_beams(const earn_attn_desc* desc, const void* q, const void
                            const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                            const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len,
                            const int32_t* gen_src, int32_t gen_cap, int32_t n_streams, int32_t batch,
-                           int32_t max_shared_len, void* out, void* workspace, size_t workspace_bytes, void* stream);
+                           int32_t max_shared_len, int32_t shared_total, void* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Attention-score statistics of chosen query rows (paper Appendix, "Quantitative Measurements of Attention Score
@@ -411,12 +413,13 @@ int earn_decode_attn_beams(const earn_attn_desc* desc, const void* q, const void
  *   q_rows     device, [batch*r, Hq, d], un-rotated      k_rot      device, [total_tokens, Hkv, d], rotated
  *   cu_seqlens device, [batch+1]                         row_pos    device, [batch*r], each inside its sequence
  *   stats_out  device, [batch*r, Hq, 3] fp32
- * Errors: NULL pointer, batch <= 0, rows_per_seq <= 0, epsilon < 0, t_head < 0, tail_back < 0 -> INVALID_ARG; desc as
+ *   total_tokens  rows of k_rot (>= cu_seqlens[batch]); sequence bounds are held inside it
+ * Errors: NULL pointer, batch <= 0, total_tokens < 0, rows_per_seq <= 0, epsilon < 0, t_head < 0, tail_back < 0 -> INVALID_ARG; desc as
  * for earn_prefill_attn.  Enqueues on `stream`, allocates nothing.
  */
 int earn_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const int32_t* cu_seqlens,
-                    const int32_t* row_pos, int32_t batch, int32_t rows_per_seq, float epsilon, int32_t t_head,
-                    int32_t tail_back, float* stats_out, void* stream);
+                    const int32_t* row_pos, int32_t batch, int32_t total_tokens, int32_t rows_per_seq, float epsilon,
+                    int32_t t_head, int32_t tail_back, float* stats_out, void* stream);
 
 /*
  * KV-cache entries per attention head one sequence holds under EARN (paper Section 3.3, "KV Cache Size":

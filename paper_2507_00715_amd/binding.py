@@ -61,26 +61,27 @@ def lib():
         L.earn_prefill_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), i32, i32, i32, i32]
         L.earn_compact_registers.restype = ctypes.c_int
         L.earn_compact_registers.argtypes = [i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
-                                             ctypes.POINTER(ctypes.c_int64), vp, i32, i32, i32, vp, vp, vp, vp]
+                                             ctypes.POINTER(ctypes.c_int64), vp, i32, i32, i32, i32, vp, vp, vp, vp]
         L.earn_decode_attn.restype = ctypes.c_int
         L.earn_decode_attn.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
-                                       i32, i32, vp, vp, sz, vp]
+                                       i32, i32, i32, vp, vp, sz, vp]
         L.earn_decode_attn_static.restype = ctypes.c_int
         L.earn_decode_attn_static.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
-                                              i32, i32, i32, vp, vp]
+                                              i32, i32, i32, i32, vp, vp]
         i64 = ctypes.c_int64
         L.earn_prefill_attn_layers.restype = ctypes.c_int
         L.earn_prefill_attn_layers.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, i64, vp, vp, i64, vp, vp, i32, i32, i32,
                                                vp, i64, vp, i64, vp, i64, vp, sz, vp]
         L.earn_decode_attn_layers.restype = ctypes.c_int
         L.earn_decode_attn_layers.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, i64, vp, vp, i64, vp, vp, vp, i64, vp,
-                                              vp, vp, vp, i64, vp, i32, i32, i32, i32, vp, i64, vp, sz, vp]
+                                              vp, vp, vp, i64, vp, i32, i32, i32, i32, i32, vp, i64, vp, sz, vp]
         L.earn_decode_layers_workspace_bytes.restype = sz
         L.earn_decode_layers_workspace_bytes.argtypes = [ctypes.POINTER(AttnDesc), i32, i32, i32, i32, i32]
         L.earn_decode_step_positions.restype = ctypes.c_int
         L.earn_decode_step_positions.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
         L.earn_attn_stats.restype = ctypes.c_int
-        L.earn_attn_stats.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, i32, ctypes.c_float, i32, i32, vp, vp]
+        L.earn_attn_stats.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, i32, i32, i32, ctypes.c_float, i32, i32, vp,
+                                      vp]
         L.earn_beam_topk.restype = ctypes.c_int
         L.earn_beam_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
         L.earn_beam_topk_workspace_bytes.restype = sz
@@ -89,7 +90,7 @@ def lib():
         L.earn_beam_reorder.argtypes = [vp, vp, vp, i32, i32, i32, vp]
         L.earn_decode_attn_beams.restype = ctypes.c_int
         L.earn_decode_attn_beams.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32,
-                                             i32, i32, i32, vp, vp, sz, vp]
+                                             i32, i32, i32, i32, vp, vp, sz, vp]
         L.earn_qkv_rope_project.restype = ctypes.c_int
         L.earn_qkv_rope_project.argtypes = [ctypes.POINTER(AttnDesc), vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, sz, vp]
         L.earn_linear.restype = ctypes.c_int
@@ -132,6 +133,11 @@ def _ptr(t: Optional[torch.Tensor]):
         return None
     assert t.is_cuda and t.is_contiguous(), "libearn takes contiguous device tensors"
     return ctypes.c_void_p(t.data_ptr())
+
+
+def _rows(t: Optional[torch.Tensor], dim: int = 0) -> int:
+    """Rows of a packed tensor as the library is told them (0 for None): the bound it holds sequence bounds inside."""
+    return 0 if t is None else int(t.shape[dim])
 
 
 def _stream():
@@ -189,7 +195,8 @@ def earn_compact_registers(src: Sequence[torch.Tensor], dst: Sequence[torch.Tens
     rb_arr = (ctypes.c_int64 * max(n, 1))(*row_bytes)
     for t in list(src) + list(dst):
         assert t.is_cuda and t.is_contiguous()
-    _check(lib().earn_compact_registers(n, src_arr, dst_arr, rb_arr, _ptr(cu_seqlens), batch, n_head_reg, n_tail_reg,
+    total = min(t.shape[0] for t in src) if n else 0x7fffffff   # no tensors: indices only, nothing is read
+    _check(lib().earn_compact_registers(n, src_arr, dst_arr, rb_arr, _ptr(cu_seqlens), batch, total, n_head_reg, n_tail_reg,
                                         _ptr(idx_out), _ptr(pos_out), _ptr(cu_out), _stream()))
 
 
@@ -215,7 +222,7 @@ def earn_decode_attn(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, shared_v,
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().earn_decode_attn(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos), _ptr(shared_k),
                                   _ptr(shared_v), _ptr(shared_cu), _ptr(stream_to_seq), _ptr(gen_k), _ptr(gen_v),
-                                  _ptr(gen_len), gen_cap, n_streams, batch, max_shared_len, _ptr(out),
+                                  _ptr(gen_len), gen_cap, n_streams, batch, max_shared_len, _rows(shared_k), _ptr(out),
                                   _ptr(workspace), ws_bytes, _stream()))
 
 
@@ -226,7 +233,7 @@ def earn_decode_attn_static(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, sh
     _check(lib().earn_decode_attn_static(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos),
                                          _ptr(shared_k), _ptr(shared_v), _ptr(shared_cu), _ptr(stream_to_seq),
                                          _ptr(gen_k), _ptr(gen_v), _ptr(gen_len), gen_cap, n_streams, batch,
-                                         max_shared_len, _ptr(out), _stream()))
+                                         max_shared_len, _rows(shared_k), _ptr(out), _stream()))
 
 
 class BoundCall:
@@ -251,8 +258,8 @@ def bind_decode_attn(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, shared_v,
     """earn_decode_attn with the same arguments, marshalled once (see BoundCall)."""
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     tensors = (q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len)
-    args = (ctypes.byref(desc), *[_ptr(t) for t in tensors], gen_cap, n_streams, batch, max_shared_len, _ptr(out),
-            _ptr(workspace), ws_bytes)
+    args = (ctypes.byref(desc), *[_ptr(t) for t in tensors], gen_cap, n_streams, batch, max_shared_len, _rows(shared_k),
+            _ptr(out), _ptr(workspace), ws_bytes)
     return BoundCall(lib().earn_decode_attn, args, (desc, tensors, out, workspace))
 
 
@@ -281,7 +288,7 @@ def bind_decode_step_positions(cu_seqlens, stream_to_seq, n_streams: int, batch:
 def earn_attn_stats(desc: AttnDesc, q_rows, k_rot, cu_seqlens, row_pos, batch: int, rows_per_seq: int, stats_out,
                     epsilon: float = 0.05, t_head: int = 3, tail_back: int = 3) -> None:
     _check(lib().earn_attn_stats(ctypes.byref(desc), _ptr(q_rows), _ptr(k_rot), _ptr(cu_seqlens), _ptr(row_pos), batch,
-                                 rows_per_seq, epsilon, t_head, tail_back, _ptr(stats_out), _stream()))
+                                 _rows(k_rot), rows_per_seq, epsilon, t_head, tail_back, _ptr(stats_out), _stream()))
 
 
 def earn_beam_topk_workspace_bytes(batch: int, beams: int, vocab: int) -> int:
@@ -309,7 +316,7 @@ def earn_decode_attn_beams(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, sha
     _check(lib().earn_decode_attn_beams(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos),
                                         _ptr(shared_k), _ptr(shared_v), _ptr(shared_cu), _ptr(stream_to_seq), _ptr(gen_k),
                                         _ptr(gen_v), _ptr(gen_len), _ptr(gen_src), gen_cap, n_streams, batch,
-                                        max_shared_len, _ptr(out), _ptr(workspace), ws_bytes, _stream()))
+                                        max_shared_len, _rows(shared_k), _ptr(out), _ptr(workspace), ws_bytes, _stream()))
 
 
 def earn_linear_workspace_bytes(rows: int, k: int, n: int) -> int:
@@ -410,8 +417,8 @@ def bind_decode_attn_layers(desc: AttnDesc, q, k_new, v_new, q_pos, shared_k, sh
     args = (ctypes.byref(desc), n_layers, _layers_ptr(q), _layer_stride(q), _layers_ptr(k_new), _layers_ptr(v_new),
             _layer_stride(k_new), _ptr(q_pos), _layers_ptr(shared_k), _layers_ptr(shared_v), _layer_stride(shared_k),
             _ptr(shared_cu), _ptr(stream_to_seq), _layers_ptr(gen_k), _layers_ptr(gen_v), _layer_stride(gen_k),
-            _ptr(gen_len), gen_cap, n_streams, batch, max_shared_len, _layers_ptr(out), _layer_stride(out),
-            _ptr(workspace), ws_bytes)
+            _ptr(gen_len), gen_cap, n_streams, batch, max_shared_len, _rows(shared_k, 1), _layers_ptr(out),
+            _layer_stride(out), _ptr(workspace), ws_bytes)
     return BoundCall(lib().earn_decode_attn_layers, args, (desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu,
                                                            stream_to_seq, gen_k, gen_v, gen_len, out, workspace))
 

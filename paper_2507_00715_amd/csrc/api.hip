@@ -43,8 +43,8 @@ RopeTable make_rope_table(float base, int head_dim) {
 }
 
 int launch_compact(int n_tensors, const void* const* src, void* const* dst, const int64_t* row_bytes,
-                   const int32_t* cu_seqlens, int batch, int h, int t, int32_t* idx_out, int32_t* pos_out,
-                   int32_t* cu_out, hipStream_t stream);
+                   const int32_t* cu_seqlens, int batch, int total_tokens, int h, int t, int32_t* idx_out,
+                   int32_t* pos_out, int32_t* cu_out, hipStream_t stream);
 int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
                    const int32_t* positions, int batch, int total_tokens, int max_seqlen, void* out, void* k_rot_out,
                    float* lse_out, void* workspace, size_t workspace_bytes, hipStream_t stream,
@@ -53,8 +53,8 @@ size_t prefill_workspace_bytes(const earn_attn_desc* desc, int total_tokens, int
 int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
                   const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                   const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
-                  int n_streams, int batch, int max_shared_len, void* out, void* workspace, size_t workspace_bytes,
-                  hipStream_t stream, const DecodeLayers* layers, const int32_t* gen_src);
+                  int n_streams, int batch, int max_shared_len, int shared_total, void* out, void* workspace,
+                  size_t workspace_bytes, hipStream_t stream, const DecodeLayers* layers, const int32_t* gen_src);
 size_t beam_topk_workspace_bytes(int batch, int beams, int vocab);
 int launch_beam_topk(const float* beam_scores, const float* logp, int batch, int beams, int vocab, int32_t* parent,
                      int32_t* token, float* score, void* workspace, hipStream_t stream);
@@ -66,12 +66,12 @@ size_t decode_workspace_bytes(int dtype, int hq, int hkv, int d, int n_streams, 
 int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
                          const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                          const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
-                         int n_streams, int batch, int max_shared_len, void* out, hipStream_t stream);
+                         int n_streams, int batch, int max_shared_len, int shared_total, void* out, hipStream_t stream);
 int launch_step_positions(const int32_t* cu, const int32_t* stream_to_seq, int n_streams, int batch, int step,
                           int32_t* q_pos, int32_t* gen_len, hipStream_t stream);
 int launch_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const int32_t* cu_seqlens,
-                      const int32_t* row_pos, int batch, int rows_per_seq, float epsilon, int t_head, int tail_back,
-                      float* stats_out, hipStream_t stream);
+                      const int32_t* row_pos, int batch, int total_tokens, int rows_per_seq, float epsilon, int t_head,
+                      int tail_back, float* stats_out, hipStream_t stream);
 int launch_linear(const void* x, const void* w, int rows, int k, int n, int activation, void* out, void* workspace,
                   size_t workspace_bytes, hipStream_t stream);
 size_t linear_workspace_bytes(long long rows, int k, int n);
@@ -89,8 +89,8 @@ int launch_prefill_rows_f32(const earn_attn_desc* desc, const void* q_rows, cons
                             int max_seqlen, int rows_per_seq, void* out_rows, hipStream_t stream);
 size_t prefill_rows_workspace_bytes(int hq, int hkv, int d, int batch, int max_seqlen, int rows_per_seq);
 int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
-                        const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen, int rows_per_seq,
-                        void* out_rows, void* workspace, size_t workspace_bytes, hipStream_t stream);
+                        const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int total_tokens, int max_seqlen,
+                        int rows_per_seq, void* out_rows, void* workspace, size_t workspace_bytes, hipStream_t stream);
 
 static std::atomic<int> g_tuning[kTuneCount];
 int tuning(Tuning t, int dflt) {
@@ -168,11 +168,15 @@ static int validate_positions(const char* who, const char* name, const std::vect
 
 static int validate_decode(const char* who, const int32_t* q_pos, const int32_t* shared_cu, const int32_t* stream_to_seq,
                            const int32_t* gen_len, int gen_cap, int n_streams, int batch, int max_shared_len,
-                           hipStream_t stream) {
+                           int shared_total, hipStream_t stream) {
   std::vector<int32_t> cu, qp, gl, s2s;
   int rc;
   if ((rc = fetch_i32(shared_cu, (size_t)batch + 1, cu, stream, who)) != EARN_OK) return rc;
   if ((rc = validate_cu(who, "shared_cu", cu, batch, -1, max_shared_len)) != EARN_OK) return rc;
+  if (cu[batch] > shared_total) {
+    set_error("%s: shared_cu[batch] = %d, more than the %d rows of the shared tensors", who, cu[batch], shared_total);
+    return EARN_ERR_INVALID_ARG;
+  }
   if ((rc = fetch_i32(q_pos, (size_t)n_streams, qp, stream, who)) != EARN_OK) return rc;
   if ((rc = validate_positions(who, "q_pos", qp)) != EARN_OK) return rc;
   if ((rc = fetch_i32(gen_len, (size_t)n_streams, gl, stream, who)) != EARN_OK) return rc;
@@ -285,10 +289,10 @@ int earn_prefill_attn_layers(const earn_attn_desc* desc, int32_t n_layers, const
 }
 
 int earn_compact_registers(int32_t n_tensors, const void* const* src, void* const* dst, const int64_t* row_bytes,
-                           const int32_t* cu_seqlens, int32_t batch, int32_t n_head_reg, int32_t n_tail_reg,
-                           int32_t* idx_out, int32_t* pos_out, int32_t* cu_out, void* stream) {
+                           const int32_t* cu_seqlens, int32_t batch, int32_t total_tokens, int32_t n_head_reg,
+                           int32_t n_tail_reg, int32_t* idx_out, int32_t* pos_out, int32_t* cu_out, void* stream) {
   g_err[0] = 0;
-  if (batch <= 0) { set_error("earn_compact_registers: batch must be positive"); return EARN_ERR_INVALID_ARG; }
+  if (batch <= 0 || total_tokens < 0) { set_error("earn_compact_registers: batch must be positive, total_tokens non-negative"); return EARN_ERR_INVALID_ARG; }
   if (n_head_reg < 0 || n_tail_reg < 0 || n_head_reg + n_tail_reg == 0) {
     set_error("earn_compact_registers: register counts must be non-negative and not both zero (h=%d, t=%d)", n_head_reg, n_tail_reg);
     return EARN_ERR_INVALID_ARG;
@@ -320,8 +324,8 @@ int earn_compact_registers(int32_t n_tensors, const void* const* src, void* cons
         return EARN_ERR_INVALID_ARG;
       }
   }
-  return launch_compact(n_tensors, src, dst, row_bytes, cu_seqlens, batch, n_head_reg, n_tail_reg, idx_out, pos_out,
-                        cu_out, (hipStream_t)stream);
+  return launch_compact(n_tensors, src, dst, row_bytes, cu_seqlens, batch, total_tokens, n_head_reg, n_tail_reg, idx_out,
+                        pos_out, cu_out, (hipStream_t)stream);
 }
 
 int earn_decode_step_positions(const int32_t* cu_seqlens, const int32_t* stream_to_seq, int32_t n_streams,
@@ -351,12 +355,13 @@ static int check_decode_args(const char* who, const earn_attn_desc* desc, const 
                              const void* v_new, const int32_t* q_pos, const void* shared_k, const void* shared_v,
                              const int32_t* shared_cu, const int32_t* stream_to_seq, void* gen_k, void* gen_v,
                              const int32_t* gen_len, int32_t gen_cap, int32_t n_streams, int32_t batch,
-                             int32_t max_shared_len, void* out, void* stream) {
+                             int32_t max_shared_len, int32_t shared_total, void* out, void* stream) {
   g_err[0] = 0;
   int rc = check_desc(desc, who);
   if (rc != EARN_OK) return rc;
-  if (n_streams <= 0 || batch <= 0 || gen_cap <= 0 || max_shared_len < 0) {
-    set_error("%s: n_streams (%d), batch (%d), gen_cap (%d) must be positive and max_shared_len (%d) non-negative", who, n_streams, batch, gen_cap, max_shared_len);
+  if (n_streams <= 0 || batch <= 0 || gen_cap <= 0 || max_shared_len < 0 || shared_total < 0) {
+    set_error("%s: n_streams (%d), batch (%d), gen_cap (%d) must be positive, max_shared_len (%d) and shared_total (%d) non-negative",
+              who, n_streams, batch, gen_cap, max_shared_len, shared_total);
     return EARN_ERR_INVALID_ARG;
   }
   if (!q || !k_new || !v_new || !q_pos || !shared_cu || !gen_k || !gen_v || !gen_len || !out) {
@@ -367,7 +372,7 @@ static int check_decode_args(const char* who, const earn_attn_desc* desc, const 
   if (!stream_to_seq && n_streams != batch) { set_error("%s: stream_to_seq is NULL but n_streams (%d) != batch (%d)", who, n_streams, batch); return EARN_ERR_INVALID_ARG; }
   if (g_validate.load(std::memory_order_relaxed) &&
       (rc = validate_decode(who, q_pos, shared_cu, stream_to_seq, gen_len, gen_cap, n_streams, batch, max_shared_len,
-                            (hipStream_t)stream)) != EARN_OK)
+                            shared_total, (hipStream_t)stream)) != EARN_OK)
     return rc;
   return EARN_OK;
 }
@@ -376,26 +381,26 @@ int earn_decode_attn_static(const earn_attn_desc* desc, const void* q, const voi
                             const int32_t* q_pos, const void* shared_k, const void* shared_v,
                             const int32_t* shared_cu, const int32_t* stream_to_seq, void* gen_k, void* gen_v,
                             const int32_t* gen_len, int32_t gen_cap, int32_t n_streams, int32_t batch,
-                            int32_t max_shared_len, void* out, void* stream) {
+                            int32_t max_shared_len, int32_t shared_total, void* out, void* stream) {
   const int rc = check_decode_args("earn_decode_attn_static", desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu,
-                                   stream_to_seq, gen_k, gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, out,
+                                   stream_to_seq, gen_k, gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, shared_total, out,
                                    stream);
   if (rc != EARN_OK) return rc;
   return launch_decode_static(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v,
-                              gen_len, gen_cap, n_streams, batch, max_shared_len, out, (hipStream_t)stream);
+                              gen_len, gen_cap, n_streams, batch, max_shared_len, shared_total, out, (hipStream_t)stream);
 }
 
 int earn_decode_attn(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
                      const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                      const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int32_t gen_cap,
-                     int32_t n_streams, int32_t batch, int32_t max_shared_len, void* out, void* workspace,
+                     int32_t n_streams, int32_t batch, int32_t max_shared_len, int32_t shared_total, void* out, void* workspace,
                      size_t workspace_bytes, void* stream) {
   const int rc = check_decode_args("earn_decode_attn", desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu,
-                                   stream_to_seq, gen_k, gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, out,
+                                   stream_to_seq, gen_k, gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, shared_total, out,
                                    stream);
   if (rc != EARN_OK) return rc;
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
-                       gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream,
+                       gen_cap, n_streams, batch, max_shared_len, shared_total, out, workspace, workspace_bytes, (hipStream_t)stream,
                        nullptr, nullptr);
 }
 
@@ -403,9 +408,9 @@ int earn_decode_attn_beams(const earn_attn_desc* desc, const void* q, const void
                            const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                            const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len,
                            const int32_t* gen_src, int32_t gen_cap, int32_t n_streams, int32_t batch,
-                           int32_t max_shared_len, void* out, void* workspace, size_t workspace_bytes, void* stream) {
+                           int32_t max_shared_len, int32_t shared_total, void* out, void* workspace, size_t workspace_bytes, void* stream) {
   const int rc = check_decode_args("earn_decode_attn_beams", desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu,
-                                   stream_to_seq, gen_k, gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, out,
+                                   stream_to_seq, gen_k, gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, shared_total, out,
                                    stream);
   if (rc != EARN_OK) return rc;
   if (gen_src && g_validate.load(std::memory_order_relaxed)) {
@@ -419,7 +424,7 @@ int earn_decode_attn_beams(const earn_attn_desc* desc, const void* q, const void
       }
   }
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
-                       gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream,
+                       gen_cap, n_streams, batch, max_shared_len, shared_total, out, workspace, workspace_bytes, (hipStream_t)stream,
                        nullptr, gen_src);
 }
 
@@ -472,11 +477,11 @@ int earn_decode_attn_layers(const earn_attn_desc* desc, int32_t n_layers, const 
                             const void* shared_k, const void* shared_v, int64_t shared_layer_stride,
                             const int32_t* shared_cu, const int32_t* stream_to_seq, void* gen_k, void* gen_v,
                             int64_t gen_layer_stride, const int32_t* gen_len, int32_t gen_cap, int32_t n_streams,
-                            int32_t batch, int32_t max_shared_len, void* out, int64_t out_layer_stride, void* workspace,
+                            int32_t batch, int32_t max_shared_len, int32_t shared_total, void* out, int64_t out_layer_stride, void* workspace,
                             size_t workspace_bytes, void* stream) {
   const char* who = "earn_decode_attn_layers";
   int rc = check_decode_args(who, desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k,
-                             gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, out, stream);
+                             gen_v, gen_len, gen_cap, n_streams, batch, max_shared_len, shared_total, out, stream);
   if (rc != EARN_OK) return rc;
   if (n_layers <= 0 || n_layers > 65535) { set_error("%s: n_layers (%d) outside [1, 65535]", who, n_layers); return EARN_ERR_INVALID_ARG; }
   if ((rc = check_layer_stride(who, "q_layer_stride", q_layer_stride, n_layers)) != EARN_OK ||
@@ -487,7 +492,7 @@ int earn_decode_attn_layers(const earn_attn_desc* desc, int32_t n_layers, const 
     return rc;
   const DecodeLayers layers = {n_layers, q_layer_stride, kv_new_layer_stride, shared_layer_stride, gen_layer_stride, out_layer_stride};
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
-                       gen_cap, n_streams, batch, max_shared_len, out, workspace, workspace_bytes, (hipStream_t)stream,
+                       gen_cap, n_streams, batch, max_shared_len, shared_total, out, workspace, workspace_bytes, (hipStream_t)stream,
                        &layers, nullptr);
 }
 
@@ -547,17 +552,17 @@ int earn_prefill_register_rows(const earn_attn_desc* desc, const void* q_rows, c
   }
   rc = launch_rope_keys(desc, k, k_rot_out, cu_seqlens, nullptr, batch, total_tokens, (hipStream_t)stream);
   if (rc != EARN_OK) return rc;
-  return launch_prefill_rows(desc, q_rows, k_rot_out, v, cu_seqlens, row_pos, batch, max_seqlen, rows_per_seq, out_rows,
-                             workspace, workspace_bytes, (hipStream_t)stream);
+  return launch_prefill_rows(desc, q_rows, k_rot_out, v, cu_seqlens, row_pos, batch, total_tokens, max_seqlen, rows_per_seq,
+                             out_rows, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
 int earn_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const int32_t* cu_seqlens,
-                    const int32_t* row_pos, int32_t batch, int32_t rows_per_seq, float epsilon, int32_t t_head,
-                    int32_t tail_back, float* stats_out, void* stream) {
+                    const int32_t* row_pos, int32_t batch, int32_t total_tokens, int32_t rows_per_seq, float epsilon,
+                    int32_t t_head, int32_t tail_back, float* stats_out, void* stream) {
   g_err[0] = 0;
   int rc = check_desc(desc, "earn_attn_stats");
   if (rc != EARN_OK) return rc;
-  if (batch <= 0 || rows_per_seq <= 0 || !(epsilon >= 0.f) || t_head < 0 || tail_back < 0 ||
+  if (batch <= 0 || total_tokens < 0 || rows_per_seq <= 0 || !(epsilon >= 0.f) || t_head < 0 || tail_back < 0 ||
       (long long)batch * rows_per_seq > 0x7fffffffLL || desc->n_q_heads > 65535) {
     set_error("earn_attn_stats: batch (%d) and rows_per_seq (%d) must be positive, epsilon, t_head (%d) and tail_back (%d) non-negative", batch, rows_per_seq, t_head, tail_back);
     return EARN_ERR_INVALID_ARG;
@@ -566,8 +571,8 @@ int earn_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* 
     set_error("earn_attn_stats: a required pointer is NULL");
     return EARN_ERR_INVALID_ARG;
   }
-  return launch_attn_stats(desc, q_rows, k_rot, cu_seqlens, row_pos, batch, rows_per_seq, epsilon, t_head, tail_back,
-                           stats_out, (hipStream_t)stream);
+  return launch_attn_stats(desc, q_rows, k_rot, cu_seqlens, row_pos, batch, total_tokens, rows_per_seq, epsilon, t_head,
+                           tail_back, stats_out, (hipStream_t)stream);
 }
 
 int earn_qkv_rope_project(const earn_attn_desc* desc, const void* x, const void* w_qkv, int32_t rows, int32_t d_model,

@@ -15,7 +15,7 @@ struct BwdParams {
   const void* q; const void* k; const void* v; const void* out; const float* lse; const void* d_out;
   const int32_t* cu; float* dsum;  // D [tokens, Hq]
   void* dq; void* dk; void* dv;
-  int batch, hq, hkv;
+  int batch, hq, hkv, total, max_seqlen;
   float scale, scale_log2;
   HeadMap heads;
 };
@@ -88,7 +88,8 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(BwdParams p) {
   constexpr int Q4 = D / 4;
   const int slot = blockIdx.y, s = blockIdx.z;
   const int a = head_of_slot(p.heads, slot), c = slot / (p.hq / p.hkv);
-  const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
+  int b0, n;
+  clamped_bounds(p.cu, s, p.total, p.max_seqlen, b0, n);
   const int row0 = blockIdx.x * 64;
   if (row0 >= n) return;
   const int qt = threadIdx.x & 3;
@@ -133,7 +134,8 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(BwdParams p) {
   constexpr int Q4 = D / 4;
   const int c = blockIdx.y, s = blockIdx.z;
   const int gq = p.hq / p.hkv;
-  const int b0 = p.cu[s], n = p.cu[s + 1] - b0;
+  int b0, n;
+  clamped_bounds(p.cu, s, p.total, p.max_seqlen, b0, n);
   const int key0 = blockIdx.x * 64;
   if (key0 >= n) return;
   const int qt = threadIdx.x & 3;
@@ -190,6 +192,7 @@ int launch_attn_backward(const earn_attn_desc* desc, const void* q, const void* 
   BwdParams p;
   p.q = q; p.k = k; p.v = v; p.out = out; p.lse = lse; p.d_out = d_out; p.cu = cu_seqlens; p.dsum = (float*)workspace;
   p.dq = dq; p.dk = dk; p.dv = dv; p.batch = batch; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads;
+  p.total = total_tokens; p.max_seqlen = max_seqlen;
   const int d = desc->head_dim;
   p.scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);
   p.scale_log2 = p.scale * 1.4426950408889634f;

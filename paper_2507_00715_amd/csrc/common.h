@@ -48,6 +48,14 @@ struct DecodeLayers { int n_layers; long long q, kv_new, shared, gen, out; };
 struct PrefillLayers { int n_layers; long long q, kv, out, k_rot, lse; };
 
 // launch-shape overrides (earn_set_tuning); 0 = default
+// Bounds of packed sequence s as the kernels use them: whatever cu holds, rows [b0, b0 + n) lie inside the `total` rows
+// of the tensors and n within `max_len` (the length the launch was sized for).  A corrupt or not yet written cu then
+// gives wrong values, never an access outside the tensors.
+__device__ __forceinline__ void clamped_bounds(const int32_t* cu, int s, int total, int max_len, int& b0, int& n) {
+  b0 = min(max(cu[s], 0), total);
+  n = min(min(max(cu[s + 1] - b0, 0), total - b0), max_len);
+}
+
 constexpr int kXcds = 8;  // accelerator complex dies, each with a private L2; consecutive workgroup ids go to them in turn
 
 enum Tuning { kTunePrefillBlockRows, kTuneDecMfmaMinLen, kTuneDecMfmaShortWgs, kTuneDecMfmaWgs, kTuneDecVecWgs,

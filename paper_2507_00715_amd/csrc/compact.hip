@@ -22,9 +22,10 @@ constexpr int kCompactBlocksPerWg = 4;  // blocks (kCompactThreads * kCompactUnr
 
 // source row of compacted row m; a sequence shorter than h + t (a violated precondition) has its rows clamped into the
 // sequence, an empty one yields -1 (no row)
-__device__ __forceinline__ int source_row(const int32_t* __restrict__ cu, int m, int r, int h, int t, int* pos) {
+__device__ __forceinline__ int source_row(const int32_t* __restrict__ cu, int total, int m, int r, int h, int t, int* pos) {
   int s = m / r, j = m - s * r;
-  int b0 = cu[s], n = cu[s + 1] - b0;
+  int b0, n;
+  clamped_bounds(cu, s, total, total, b0, n);
   int p = j < h ? j : n - t + (j - h);
   p = max(min(p, n - 1), 0);
   *pos = p;
@@ -32,7 +33,7 @@ __device__ __forceinline__ int source_row(const int32_t* __restrict__ cu, int m,
 }
 
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactArgs args, const int32_t* __restrict__ cu,
-                                                                  int batch, int h, int t, int rows_out,
+                                                                  int batch, int total, int h, int t, int rows_out,
                                                                   int32_t* __restrict__ idx_out,
                                                                   int32_t* __restrict__ pos_out,
                                                                   int32_t* __restrict__ cu_out, int n_tensors) {
@@ -52,7 +53,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactArgs ar
     const unsigned int n_blocks = gridDim.x - args.first_block[n_tensors];
     for (int m = block_in_tensor * kCompactThreads + threadIdx.x; m < rows_out; m += n_blocks * kCompactThreads) {
       int pos;
-      int idx = source_row(cu, m, r, h, t, &pos);
+      int idx = source_row(cu, total, m, r, h, t, &pos);
       if (idx_out) idx_out[m] = idx;
       if (pos_out) pos_out[m] = pos;
     }
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactArgs ar
         int m = (int)(u[i] / upr);
         unsigned int off = (unsigned int)(u[i] - (long long)m * upr);
         int pos;
-        long long row = source_row(cu, m, r, h, t, &pos);
+        long long row = source_row(cu, total, m, r, h, t, &pos);
         v[i] = row >= 0 ? __builtin_nontemporal_load(src + row * upr + off) : u32x4{0u, 0u, 0u, 0u};
       }
     }
@@ -106,8 +107,8 @@ int launch_step_positions(const int32_t* cu, const int32_t* stream_to_seq, int n
 }
 
 int launch_compact(int n_tensors, const void* const* src, void* const* dst, const int64_t* row_bytes,
-                   const int32_t* cu_seqlens, int batch, int h, int t, int32_t* idx_out, int32_t* pos_out,
-                   int32_t* cu_out, hipStream_t stream) {
+                   const int32_t* cu_seqlens, int batch, int total_tokens, int h, int t, int32_t* idx_out,
+                   int32_t* pos_out, int32_t* cu_out, hipStream_t stream) {
   CompactArgs args;
   const long long rows_out = (long long)batch * (h + t);
   const long long per_block = (long long)kCompactThreads * kCompactUnroll;
@@ -140,7 +141,7 @@ int launch_compact(int n_tensors, const void* const* src, void* const* dst, cons
   if (gi < 1) gi = 1;
   if (gi > 256) gi = 256;
   dim3 grid(blocks + (unsigned)gi, 1, 1);
-  hipLaunchKernelGGL(compact_kernel, grid, dim3(kCompactThreads), 0, stream, args, cu_seqlens, batch, h, t,
+  hipLaunchKernelGGL(compact_kernel, grid, dim3(kCompactThreads), 0, stream, args, cu_seqlens, batch, total_tokens, h, t,
                      (int)rows_out, idx_out, pos_out, cu_out, n_tensors);
   return hipGetLastError() == hipSuccess ? EARN_OK : EARN_ERR_HIP;
 }

@@ -75,6 +75,7 @@ struct DecodeParams {
   const int32_t* gen_src;
   void* out; float* part_o; float* part_ml;
   int gen_cap, n_streams, batch, hq, hkv, n_splits, chunk;  // chunk: keys per split (multiple of 64)
+  int shared_total, max_shared_len;  // rows of shared_k / shared_v; the longest cache the launch was sized for
   int n_slots;    // partial-result slots per (stream, head) in the workspace (one per key split)
   // Prefill of chosen rows with the decode machinery (0 = decode).  r > 0: the "streams" are r query rows per sequence
   // (stream s*r + i belongs to sequence s), q_pos[u] is the row's token index in its sequence, a row sees shared keys
@@ -91,6 +92,14 @@ struct DecodeParams {
   RopeTable rope;
   HeadMap heads;
 };
+
+// Bounds of sequence s's shared cache as the kernels use them: whatever shared_cu holds, rows [b0, b0 + ns) lie inside
+// the shared tensors and ns within the length the launch was sized (and its 32-bit offsets checked) for.  A corrupt or
+// not yet written shared_cu gives wrong values, never an access outside the tensors.
+__device__ __forceinline__ void shared_bounds(const DecodeParams& p, int s, int& b0, int& ns) {
+  b0 = min(max(p.shared_cu[s], 0), p.shared_total);
+  ns = min(min(max(p.shared_cu[s + 1] - b0, 0), p.shared_total - b0), p.max_shared_len);
+}
 
 template <typename P>
 __device__ __forceinline__ P* layer_ptr(P* base, long long stride, int layer) {
@@ -163,8 +172,8 @@ __device__ __forceinline__ void decode_rows(const DecodeParams& p, const DecodeL
   const int gq = p.hq / p.hkv;       // query heads per kv head
   const int sub = lane % LPK, kk = lane / LPK;
   const int s = p.stream_to_seq ? max(min(p.stream_to_seq[u], p.batch - 1), 0) : u;
-  const int b0 = p.shared_cu[s];
-  const int ns = p.shared_cu[s + 1] - b0;
+  int b0, ns;
+  shared_bounds(p, s, b0, ns);
   const int g = clamp_gen_len(p.gen_len[u], p.gen_cap);
   const int m_total = ns + g + 1;    // shared rows, earlier generated rows, the new token
   const float pos = (float)p.q_pos[u];
@@ -536,7 +545,8 @@ __global__ __launch_bounds__(256 * C, 1) void decode_shared_mfma_kernel(DecodePa
   };
   const bool causal = p.causal_rows > 0;
   if (wave == 0 && p.stream_to_seq && !causal) fetch_lists(0);
-  const int b0 = p.shared_cu[s], ns = p.shared_cu[s + 1] - b0;
+  int b0, ns;
+  shared_bounds(p, s, b0, ns);
   const int j_begin = z * p.chunk;
   const int j_end = min(ns, j_begin + p.chunk);
   const int n_keys = max(j_end - j_begin, 0);
@@ -1154,8 +1164,8 @@ static void launch_decode_t(DecodeParams& p, const DecodePlan& pl, int gq, hipSt
 int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
                   const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                   const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
-                  int n_streams, int batch, int max_shared_len, void* out, void* workspace, size_t workspace_bytes,
-                  hipStream_t stream, const DecodeLayers* layers, const int32_t* gen_src) {
+                  int n_streams, int batch, int max_shared_len, int shared_total, void* out, void* workspace,
+                  size_t workspace_bytes, hipStream_t stream, const DecodeLayers* layers, const int32_t* gen_src) {
   const int hq = desc->n_q_heads, hkv = desc->n_kv_heads, d = desc->head_dim, gq = hq / hkv;
   const int n_layers = layers ? layers->n_layers : 1;
   if (gq > 8) { set_error("earn_decode_attn: more than 8 query heads per kv head is not supported"); return EARN_ERR_UNSUPPORTED; }
@@ -1175,6 +1185,7 @@ int launch_decode(const earn_attn_desc* desc, const void* q, const void* k_new, 
   p.shared_k = shared_k; p.shared_v = shared_v; p.shared_cu = shared_cu; p.stream_to_seq = stream_to_seq;
   p.gen_k = gen_k; p.gen_v = gen_v; p.gen_len = gen_len; p.out = out; p.gen_src = gen_src;
   p.gen_cap = gen_cap; p.n_streams = n_streams; p.batch = batch; p.hq = hq; p.hkv = hkv;
+  p.shared_total = shared_total; p.max_shared_len = max_shared_len;
   p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = 0; p.n_pass = pl.n_pass;
   const size_t need = decode_workspace_bytes(desc->dtype, hq, hkv, d, n_streams, batch, max_shared_len, gen_cap, n_layers);
   if (need > workspace_bytes || (need > 0 && !workspace)) {
@@ -1233,7 +1244,7 @@ static int static_scratch_of_current_device(void** ptr) {
 int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* k_new, const void* v_new,
                          const int32_t* q_pos, const void* shared_k, const void* shared_v, const int32_t* shared_cu,
                          const int32_t* stream_to_seq, void* gen_k, void* gen_v, const int32_t* gen_len, int gen_cap,
-                         int n_streams, int batch, int max_shared_len, void* out, hipStream_t stream) {
+                         int n_streams, int batch, int max_shared_len, int shared_total, void* out, hipStream_t stream) {
   const size_t need = decode_workspace_bytes(desc->dtype, desc->n_q_heads, desc->n_kv_heads, desc->head_dim, n_streams,
                                              batch, max_shared_len, gen_cap, 1);
   if (need > kStaticScratchBytes) {
@@ -1245,7 +1256,8 @@ int launch_decode_static(const earn_attn_desc* desc, const void* q, const void* 
   const int rc = static_scratch_of_current_device(&ptr);
   if (rc != EARN_OK) return rc;
   return launch_decode(desc, q, k_new, v_new, q_pos, shared_k, shared_v, shared_cu, stream_to_seq, gen_k, gen_v, gen_len,
-                       gen_cap, n_streams, batch, max_shared_len, out, ptr, kStaticScratchBytes, stream, nullptr, nullptr);
+                       gen_cap, n_streams, batch, max_shared_len, shared_total, out, ptr, kStaticScratchBytes, stream, nullptr,
+                       nullptr);
 }
 
 // ---- causal attention of r chosen rows per sequence over the sequence's full-length keys, on the shared-cache kernel:
@@ -1278,8 +1290,8 @@ size_t prefill_rows_workspace_bytes(int hq, int hkv, int d, int batch, int max_s
 }
 
 int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const void* v,
-                        const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int max_seqlen, int rows_per_seq,
-                        void* out_rows, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+                        const int32_t* cu_seqlens, const int32_t* row_pos, int batch, int total_tokens, int max_seqlen,
+                        int rows_per_seq, void* out_rows, void* workspace, size_t workspace_bytes, hipStream_t stream) {
   const int hq = desc->n_q_heads, hkv = desc->n_kv_heads, d = desc->head_dim, gq = hq / hkv;
   if (desc->dtype != EARN_BF16) { set_error("earn_prefill_register_rows: bf16 only"); return EARN_ERR_UNSUPPORTED; }
   if (rows_per_seq > kMaxStreamsPerSeq) {
@@ -1302,6 +1314,7 @@ int launch_prefill_rows(const earn_attn_desc* desc, const void* q_rows, const vo
   p.shared_k = k_rot; p.shared_v = v; p.shared_cu = cu_seqlens; p.stream_to_seq = nullptr;
   p.gen_k = nullptr; p.gen_v = nullptr; p.gen_len = nullptr; p.out = out_rows; p.gen_src = nullptr;
   p.gen_cap = 0; p.n_streams = batch * rows_per_seq; p.batch = batch; p.hq = hq; p.hkv = hkv;
+  p.shared_total = total_tokens; p.max_shared_len = max_seqlen;
   p.n_splits = pl.n_splits; p.n_slots = pl.n_slots; p.chunk = pl.chunk; p.causal_rows = rows_per_seq; p.n_pass = n_pass;
   p.part_o = (float*)workspace;
   p.part_ml = p.part_o + (size_t)p.n_streams * hq * p.n_slots * d;

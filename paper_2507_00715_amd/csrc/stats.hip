@@ -11,7 +11,7 @@ namespace earn {
 
 struct StatsParams {
   const void* q_rows; const void* k_rot; const int32_t* cu; const int32_t* row_pos; float* out;
-  int batch, rows_per_seq, hq, hkv, t_head, tail_back;
+  int batch, total, rows_per_seq, hq, hkv, t_head, tail_back;
   float scale_log2, epsilon;
   RopeTable rope;
   HeadMap heads;
@@ -43,7 +43,16 @@ __global__ __launch_bounds__(256) void attn_stats_kernel(StatsParams p) {
   const int m = blockIdx.x, c = blockIdx.y;
   const int gq = p.hq / p.hkv;
   const int s = m / p.rows_per_seq;
-  const int b0 = p.cu[s], n_seq = p.cu[s + 1] - b0;
+  int b0, n_seq;
+  clamped_bounds(p.cu, s, p.total, p.total, b0, n_seq);
+  if (n_seq <= 0) {  // an empty sequence has no keys: its rows report zeros
+    const int gq0 = p.hq / p.hkv;
+    if ((int)threadIdx.x < gq0) {
+      float* o = p.out + ((long long)m * p.hq + head_of_slot(p.heads, c * gq0 + threadIdx.x)) * 3;
+      o[0] = 0.f; o[1] = 0.f; o[2] = 0.f;
+    }
+    return;
+  }
   const int pos = max(min(p.row_pos[m], n_seq - 1), 0);  // the row's token index = rotary position: keys 0 .. pos
   const int n = pos + 1;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
@@ -183,11 +192,11 @@ static void launch_stats_t(const StatsParams& p, dim3 grid, hipStream_t stream) 
 }
 
 int launch_attn_stats(const earn_attn_desc* desc, const void* q_rows, const void* k_rot, const int32_t* cu_seqlens,
-                      const int32_t* row_pos, int batch, int rows_per_seq, float epsilon, int t_head, int tail_back,
-                      float* stats_out, hipStream_t stream) {
+                      const int32_t* row_pos, int batch, int total_tokens, int rows_per_seq, float epsilon, int t_head,
+                      int tail_back, float* stats_out, hipStream_t stream) {
   StatsParams p;
   p.q_rows = q_rows; p.k_rot = k_rot; p.cu = cu_seqlens; p.row_pos = row_pos; p.out = stats_out;
-  p.batch = batch; p.rows_per_seq = rows_per_seq; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads;
+  p.batch = batch; p.total = total_tokens; p.rows_per_seq = rows_per_seq; p.hq = desc->n_q_heads; p.hkv = desc->n_kv_heads;
   p.t_head = t_head; p.tail_back = tail_back; p.epsilon = epsilon;
   const int d = desc->head_dim;
   const float scale = desc->softmax_scale > 0.f ? desc->softmax_scale : 1.0f / sqrtf((float)d);

@@ -74,7 +74,7 @@ def test_compact_argument_errors():
 
     def call(n=1, src=256, dst=512, rb=32, cu=fake, batch=2, h=1, t=1):
         s, d, r = (vp * 1)(src), (vp * 1)(dst), (ctypes.c_int64 * 1)(rb)
-        return lib.earn_compact_registers(n, s, d, r, cu, batch, h, t, None, None, None, None)
+        return lib.earn_compact_registers(n, s, d, r, cu, batch, 1024, h, t, None, None, None, None)
 
     assert call(batch=0) == B.EARN_ERR_INVALID_ARG
     assert call(h=0, t=0) == B.EARN_ERR_INVALID_ARG
@@ -85,7 +85,7 @@ def test_compact_argument_errors():
     assert call(src=None) == B.EARN_ERR_INVALID_ARG
     assert call(cu=None) == B.EARN_ERR_INVALID_ARG
     assert call(n=B.EARN_MAX_COMPACT_TENSORS + 1) == B.EARN_ERR_INVALID_ARG
-    assert lib.earn_compact_registers(1, None, None, None, fake, 2, 1, 1, None, None, None, None) == B.EARN_ERR_INVALID_ARG
+    assert lib.earn_compact_registers(1, None, None, None, fake, 2, 1024, 1, 1, None, None, None, None) == B.EARN_ERR_INVALID_ARG
 
 
 def test_decode_argument_errors():
@@ -95,7 +95,7 @@ def test_decode_argument_errors():
     def call(desc=None, q=fake, s2s=fake, gen_cap=4, S=2, batch=2, maxlen=8, ws=None, ws_bytes=0):
         desc = desc or _desc()
         return lib.earn_decode_attn(ctypes.byref(desc), q, fake, fake, fake, fake, fake, fake, s2s, fake, fake, fake,
-                                    gen_cap, S, batch, maxlen, fake, ws, ws_bytes, None)
+                                    gen_cap, S, batch, maxlen, 1 << 20, fake, ws, ws_bytes, None)
 
     assert call(desc=_desc(d=32)) == B.EARN_ERR_UNSUPPORTED
     assert call(q=None) == B.EARN_ERR_INVALID_ARG

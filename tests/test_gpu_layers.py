@@ -136,7 +136,7 @@ def test_layer_argument_errors():
                                         None, 512, None, 0, None, 0, None) == B.EARN_ERR_INVALID_ARG  # k_rot_out required
     dcall = lambda n_layers=2, gs=4096: lib.earn_decode_attn_layers(
         ctypes.byref(desc), n_layers, fake, 1024, fake, fake, 512, fake, fake, fake, 4096, fake, None, fake, fake, gs, fake,
-        4, 2, 2, 100000, fake, 1024, None, 0, None)
+        4, 2, 2, 100000, 200000, fake, 1024, None, 0, None)
     assert dcall(n_layers=70000) == B.EARN_ERR_INVALID_ARG
     assert dcall(gs=-16) == B.EARN_ERR_INVALID_ARG
     assert dcall() == B.EARN_ERR_WORKSPACE_TOO_SMALL
