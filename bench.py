@@ -651,6 +651,9 @@ def measured_peaks(dev) -> dict:
     L.earn_calib_attention_mix.argtypes = [vp, ctypes.c_int, vp]
     L.earn_calib_attention_mix_flops.restype = ctypes.c_double
     L.earn_calib_attention_mix_flops.argtypes = [ctypes.c_int]
+    L.earn_calib_attention_mix_rows.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
+    L.earn_calib_attention_mix_rows_flops.restype = ctypes.c_double
+    L.earn_calib_attention_mix_rows_flops.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
     L.earn_calib_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     L.earn_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     sink = torch.zeros(int(L.earn_calib_sink_floats()), dtype=torch.float32, device=dev)
@@ -681,6 +684,13 @@ def measured_peaks(dev) -> dict:
         out[label] = L.earn_calib_mfma_flops(it_mfma) / (ms * 1e-3) / 1e12
     ms = best_ms(lambda: L.earn_calib_attention_mix(vp(sink.data_ptr()), it_mix, stream()))
     out["attention_tile_mix_random_operands_tflops"] = L.earn_calib_attention_mix_flops(it_mix) / (ms * 1e-3) / 1e12
+    # the same tile mix in the wave shapes a prefill kernel can take: 32 query rows per wave on one or two waves per
+    # SIMD (two = the long-sequence kernel), and 64 rows per wave on one wave per SIMD (half the LDS fragment reads)
+    for label, rb, wgs in (("tile_mix_32_rows_per_wave_2_waves_per_simd_tflops", 1, 2),
+                           ("tile_mix_32_rows_per_wave_1_wave_per_simd_tflops", 1, 1),
+                           ("tile_mix_64_rows_per_wave_1_wave_per_simd_tflops", 2, 1)):
+        ms = best_ms(lambda: L.earn_calib_attention_mix_rows(vp(sink.data_ptr()), it_mix, rb, wgs, stream()))
+        out[label] = L.earn_calib_attention_mix_rows_flops(it_mix, rb, wgs) / (ms * 1e-3) / 1e12
     ms = best_ms(lambda: L.earn_calib_read(vp(a.data_ptr()), nbytes, vp(word.data_ptr()), stream()))
     out["hbm_read_GBps"] = nbytes / (ms * 1e-3) / 1e9
     ms = best_ms(lambda: L.earn_calib_copy(vp(b.data_ptr()), vp(a.data_ptr()), nbytes, stream()))

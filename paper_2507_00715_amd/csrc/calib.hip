@@ -117,6 +117,83 @@ __global__ __launch_bounds__(kThreads) void attention_mix_kernel(float* __restri
   sink[t] = r;
 }
 
+// The same tile for a wave that owns RB blocks of 32 query rows: every K and V^T fragment read from LDS feeds RB
+// matrix products, so LDS reads per product fall by RB while the wave's registers grow by about RB (RB = 2 needs more
+// than 256 registers per lane, i.e. one wave per SIMD).  The caller picks the workgroups per CU: RB = 1 with two
+// workgroups per CU is the shape of the long-sequence prefill kernel (two waves per SIMD), RB = 2 with one workgroup
+// per CU is the alternative with half the fragment reads.
+template <int RB>
+__global__ __launch_bounds__(kThreads, RB == 1 ? 2 : 1) void attention_mix_rows_kernel(float* __restrict__ sink, int iters) {
+  __shared__ u32x4 lds[2048];
+  for (int i = threadIdx.x; i < 2048; i += kThreads) lds[i] = __builtin_bit_cast(u32x4, operand(blockIdx.x * 2048 + i, true));
+  __syncthreads();
+  const unsigned t = blockIdx.x * kThreads + threadIdx.x;
+  bf16x8 q[RB][8];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[rb][i] = operand(t * 16 + rb * 8 + i, true);
+  f32x16 o[RB][4], s[RB][2];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) o[rb][i][j] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+    const int base = (it * 64 + threadIdx.x) & 1023;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s[rb][kb][j] = -40.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 kf = __builtin_bit_cast(bf16x8, lds[(base + 64 * (kb * 8 + ks)) & 2047]);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) s[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, q[rb][ks], s[rb][kb], 0, 0, 0);
+      }
+    }
+    u32x4 w[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int r = 8 * (kk & 1) + 2 * j;
+          f32x2 e = {__builtin_amdgcn_exp2f(s[rb][kk >> 1][r] * 0.01f), __builtin_amdgcn_exp2f(s[rb][kk >> 1][r + 1] * 0.01f)};
+          w[rb][kk][j] = __builtin_bit_cast(unsigned, __builtin_convertvector(e, bf16x2));
+        }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const u32x4 v = lds[(base + 1024 + 64 * (kk * 4 + db)) & 2047];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+          o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v), __builtin_bit_cast(bf16x8, w[rb][kk]), o[rb][db], 0, 0, 0);
+      }
+    if ((it & 63) == 63) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) o[rb][i][j] *= 0x1p-20f;
+    }
+  }
+  float r = 0.f;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) r += o[rb][i][j];
+  sink[t] = r;
+}
+
 constexpr int kUnroll = 8;
 __global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src, unsigned* __restrict__ sink, size_t n) {
   u32x4 acc = {0u, 0u, 0u, 0u};
@@ -162,6 +239,19 @@ int earn_calib_attention_mix(float* sink, int iters, void* stream) {
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 double earn_calib_attention_mix_flops(int iters) { return (double)kWgs * (kThreads / 64) * iters * 32 * 2.0 * 32 * 32 * 16; }
+// the tile mix with row_blocks (1 | 2) blocks of 32 query rows per wave, on wgs_per_cu (1 | 2 | 4) workgroups per CU;
+// matrix-core FLOPs of one launch = earn_calib_attention_mix_rows_flops(...)
+int earn_calib_attention_mix_rows(float* sink, int iters, int row_blocks, int wgs_per_cu, void* stream) {
+  if (!sink || iters <= 0 || iters > (1 << 20) || (row_blocks != 1 && row_blocks != 2) ||
+      (wgs_per_cu != 1 && wgs_per_cu != 2 && wgs_per_cu != 4) || (row_blocks == 2 && wgs_per_cu != 1) || (row_blocks == 1 && wgs_per_cu == 4))
+    return -1;
+  if (row_blocks == 1) hipLaunchKernelGGL((attention_mix_rows_kernel<1>), dim3(256 * wgs_per_cu), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);
+  else hipLaunchKernelGGL((attention_mix_rows_kernel<2>), dim3(256 * wgs_per_cu), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+double earn_calib_attention_mix_rows_flops(int iters, int row_blocks, int wgs_per_cu) {
+  return 256.0 * wgs_per_cu * (kThreads / 64) * iters * 32 * row_blocks * 2.0 * 32 * 32 * 16;
+}
 // streaming read of `bytes` (multiple of 16) from src; sink: one device word
 int earn_calib_read(const void* src, size_t bytes, unsigned* sink, void* stream) {
   if (!src || !sink || bytes % 16) return -1;
