@@ -39,7 +39,20 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3     # fp32 vector
 PEAK_HBM_GBPS = 8000.0      # HBM3E
 HEADLINE = "long_beam"
-DOMINANT_KERNEL = "prefill_pipe_kernel + rope_k_kernel (one full-length causal layer)"
+
+
+def dominant_kernel(cfg, w) -> tuple:
+    """Name of the kernel a full-length prefill layer of this workload runs (the library picks by dtype and by the
+    lengths: register-sized, medium or long sequences), and the roofline that bounds it."""
+    if cfg.dtype != "bf16":
+        return "prefill_rows_kernel + rope_k_kernel (one full-length causal layer, vector ALU)", "alu"
+    if w.max_seqlen <= 64:
+        name = "prefill_mfma_kernel<D,2,1>"
+    elif w.max_seqlen <= 3072 or w.total_tokens // cfg.batch <= 2048:
+        name = "prefill_mfma_kernel<D,4,2>"
+    else:
+        name = "prefill_pipe_kernel<D,8>"
+    return name + " + rope_k_kernel (one full-length causal layer)", "mfma"
 
 
 def measured_traffic(name: str):
@@ -849,6 +862,7 @@ def main():
     traffic = measured_traffic(args.workload)
     pf = head["prefill_full_layer"]
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    dominant = dominant_kernel(cfg, W.Workload(cfg))
     line = {
         "metric": METRIC,
         "value": head["prefill_tflops"],
@@ -858,7 +872,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": dict(head["workload"], launch_mode=head["launch_mode"]),
-        "roofline": {"kernel": DOMINANT_KERNEL, "bound": "mfma",
+        "roofline": {"kernel": dominant[0], "bound": dominant[1],
                      "achieved": pf["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": pf["tflops"] / peak,
                      "traffic": None if traffic is None else traffic["fetch_bytes"] + traffic["write_bytes"],
                      "traffic_detail": traffic,

@@ -66,7 +66,7 @@ def make_desc(B, dtype, hq, hkv, d, o):
 PREFILL_SHAPES = [
     (BF, 8, 2, 128, [40, 16, 64]),          # one K/V tile per sequence: the register-layer kernel
     (BF, 14, 2, 64, [300, 61, 1000]),       # 128-row workgroups
-    (BF, 4, 2, 128, [3300, 200]),           # past 3072 rows: the pipelined kernel
+    (BF, 4, 2, 128, [3300, 1000]),          # long on average (mean > 2048 rows): the pipelined kernel
     (F32, 6, 2, 64, [130, 70]),             # vector kernel
 ]
 

@@ -36,7 +36,7 @@ def sample_rows(n, h, t, rng, n_random=24):
     return sorted(rows)
 
 
-@pytest.mark.parametrize("name", BF16_CONFIGS)
+@pytest.mark.parametrize("name", BF16_CONFIGS + ["hstu_prefill"])
 def test_full_layer_prefill_sampled_rows(name):
     B = _B()
     cfg = W.CONFIGS[name]

@@ -26,7 +26,7 @@ def i32(x):
 PREFILL_CASES = [
     (BF, 8, 2, 128, [40, 16, 64], 5, True),     # register-sized sequences, explicit positions
     (BF, 14, 2, 64, [300, 61, 1000], 3, False),  # 128-row workgroups
-    (BF, 4, 2, 128, [3300, 200], 2, False),      # pipelined kernel
+    (BF, 4, 2, 128, [3300, 1000], 2, False),     # pipelined kernel (sequences long on average)
     (F32, 6, 2, 64, [130, 70], 4, True),         # vector kernel
 ]
 

@@ -1,7 +1,8 @@
-"""Parity of the long-sequence (software-pipelined) prefill kernel on a RAGGED batch: the longest sequence is past the
-length at which earn_prefill_attn switches to 256-row workgroups, the others end inside a workgroup, inside a wave's
-32 rows, inside a 64-key tile, or are shorter than one tile.  A few key rows are scaled up (outliers), so the running
-softmax reference jumps and the exact-recompute path of the kernel runs too.
+"""Parity of both full-length bf16 prefill kernels (256-row workgroups, software pipelined; 128-row workgroups, plain
+schedule) on a RAGGED batch with sequences of more than 4000 rows: the others end inside a workgroup, inside a wave's
+32 rows, inside a 64-key tile, or are shorter than one tile.  (By itself earn_prefill_attn gives such a batch, short
+on average, to the 128-row form; the tuning key selects either.)  A few key rows are scaled up (outliers), so the
+running softmax reference jumps and the exact-recompute path of the kernels runs too.
 
 Attention outputs are checked against the fp64 oracle on sampled rows (every row of the short sequences); inputs are
 drawn on the GPU and again on the CPU from the same counter-based generator.
@@ -28,14 +29,23 @@ def _B():
 
 # outlier keys 8 times the usual scale move the row maxima by a few binary orders (the stale reference absorbs that);
 # 24 times moves them by dozens: the kernel has to re-reference in the middle of a sequence (exact path)
+@pytest.mark.parametrize("block_rows", [256, 128])
 @pytest.mark.parametrize("head_dim,outlier_scale", [(128, 8.0), (64, 8.0), (128, 24.0), (64, 24.0)])
-def test_pipelined_prefill_ragged_batch_with_outliers(head_dim, outlier_scale):
+def test_pipelined_prefill_ragged_batch_with_outliers(head_dim, outlier_scale, block_rows):
     B = _B()
+    B.earn_set_tuning("prefill_block_rows", block_rows)
+    try:
+        _ragged_batch_with_outliers(B, head_dim, outlier_scale)
+    finally:
+        B.earn_set_tuning("prefill_block_rows", 0)
+
+
+def _ragged_batch_with_outliers(B, head_dim, outlier_scale):
     cfg = W.CONFIGS["mid_mha"].replace(name="ragged_long", config_id=41, batch=len(HISTORY), len_dist=("list", HISTORY),
                                        n_head_reg=8, n_tail_reg=8, n_q_heads=4, n_kv_heads=2, head_dim=head_dim,
                                        outlier_prob=0.05, outlier_scale=outlier_scale)
     w = W.Workload(cfg)
-    assert w.max_seqlen > 3072  # the pipelined kernel's range
+    assert w.max_seqlen > 3072
     coords = w.token_coords(DEV)
     q, k, v = (w.prefill_tensor(t, 0, coords=coords) for t in "qkv")
     out = torch.full_like(q, float("nan"))
