@@ -377,15 +377,44 @@ __device__ __forceinline__ void pf_store_row(__bf16* orow /* row + 4 hf */, cons
 //              double buffer, and the small footprint lets 4 workgroups share a CU, which is what hides the
 //              load -> rotate -> multiply latency chain of these tiny problems.
 // ------------------------------------------------------------------------------------------------------------------
+//
+// Life-cycle timers, compiled in only with -DEARN_PF_TIMELINE (paper_2507_00715_amd/timeline.py builds that variant
+// into a library of its own and prints where a workgroup's life goes).  Thread 0 of every workgroup stamps the 100 MHz
+// wall clock into 8 words of a caller-provided buffer: 0 entry, 1 block known, 2 queries, cos/sin rows and first K/V
+// tile arrived (this stamp waits for them, which the normal build does only at the first barrier), 3 first tile done,
+// 4 all tiles done, 5 output stores issued; 6 the CU, 7 the block's tile count (0: block beyond its sequence).  In the
+// normal build the macros are empty.
+#ifdef EARN_PF_TIMELINE
+__device__ long long* g_pf_timeline;
+__device__ int g_pf_timeline_slots;
+#define PF_TIMELINE(code) code
+#define PF_STAMP(i)                                                                                    \
+  do {                                                                                                 \
+    const long long pf_wg = (long long)blockIdx.y * gridDim.x + blockIdx.x;                            \
+    if (threadIdx.x == 0 && g_pf_timeline && pf_wg < g_pf_timeline_slots) g_pf_timeline[pf_wg * 8 + (i)] = wall_clock64(); \
+  } while (0)
+#else
+#define PF_TIMELINE(code)
+#define PF_STAMP(i)
+#endif
 template <int D, int WAVES, int STAGES>
 __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_kernel(PrefillParams p) {
   constexpr int kBlockRows = 32 * WAVES;
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   __shared__ __bf16 smk[STAGES][kTileKeys * D];  // tile t+1 arrives while tile t is read
   __shared__ __bf16 smv[STAGES][kTileKeys * D];
+  PF_STAMP(0);
 
   const PfBlock blk = pf_map_block(p, kBlockRows);
+  PF_TIMELINE({
+    const long long pf_wg = (long long)blockIdx.y * gridDim.x + blockIdx.x;
+    if (threadIdx.x == 0 && g_pf_timeline && pf_wg < g_pf_timeline_slots) {
+      g_pf_timeline[pf_wg * 8 + 6] = __smid();
+      g_pf_timeline[pf_wg * 8 + 7] = blk.valid ? (min(blk.q0 + kBlockRows, blk.n) + kTileKeys - 1) / kTileKeys : 0;
+    }
+  })
   if (!blk.valid) return;
+  PF_STAMP(1);
   const PfLayer lv = pf_layer_view(p, blockIdx.y);
   const int b0 = blk.b0, n = blk.n;
   // the wave index is the same in all 64 lanes: say so, and everything derived from it (the wave's query window, its
@@ -425,6 +454,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
   }
   FragOffsets<D> fo;
   fo.init(lane);
+  PF_TIMELINE(__builtin_amdgcn_s_waitcnt(0x0F70);)  // vmcnt(0)
+  PF_STAMP(2);
 
   f32x16 o[DB], neg_m;  // neg_m: -m in every register, the start value of the steady-state score accumulators
 #pragma unroll
@@ -522,7 +553,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
     if (!exact) break;
     exact_tile(t, synced);
     ++t;
+    PF_TIMELINE(if (t == 1) PF_STAMP(3);)
   }
+  PF_STAMP(4);
 
   if (!wave_active) return;
   const int qi = qw + r32;
@@ -530,6 +563,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 1 : 2) void prefill_mfma_k
   if (qi >= n) return;
   pf_store_row<D>((__bf16*)lv.out + ((long long)(b0 + qi) * p.hq + blk.a) * D + 4 * hf, o, 1.f / ltot);
   if (lv.lse && hf == 0) lv.lse[(long long)(b0 + qi) * p.hq + blk.a] = (mrow + __builtin_log2f(ltot)) * 0.6931471805599453f;
+  PF_STAMP(5);
 }
 
 // ------------------------------------------------------------------------------------------------------------------
@@ -914,3 +948,11 @@ int launch_prefill(const earn_attn_desc* desc, const void* q, const void* k, con
 }
 
 }  // namespace earn
+
+#ifdef EARN_PF_TIMELINE
+// buf: device memory of slots * 8 64-bit words, zeroed by the caller; NULL switches the timers off
+extern "C" int earn_debug_set_timeline(void* buf, int slots) {
+  if (hipMemcpyToSymbol(HIP_SYMBOL(earn::g_pf_timeline_slots), &slots, sizeof(slots)) != hipSuccess) return EARN_ERR_HIP;
+  return hipMemcpyToSymbol(HIP_SYMBOL(earn::g_pf_timeline), &buf, sizeof(buf)) == hipSuccess ? EARN_OK : EARN_ERR_HIP;
+}
+#endif
