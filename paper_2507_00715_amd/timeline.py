@@ -23,11 +23,11 @@ TIMELINE_LIB = os.path.join(earn_build.HERE, "libearn_timeline.so")
 TICK_US = 0.01  # the wall clock of the device counts at 100 MHz
 
 
-def build_timeline_library() -> str:
+def build_timeline_library(force: bool = False) -> str:
     """Compile prefill.hip with the timers and link it with the normal build's other objects (built first if absent).
-    Kept when it is newer than every source."""
+    Kept, unless `force`, when it is newer than every source."""
     sources = [os.path.join(earn_build.CSRC, f) for f in os.listdir(earn_build.CSRC) if f.endswith((".hip", ".h"))]
-    if os.path.exists(TIMELINE_LIB) and all(os.path.getmtime(TIMELINE_LIB) >= os.path.getmtime(f) for f in sources):
+    if not force and os.path.exists(TIMELINE_LIB) and all(os.path.getmtime(TIMELINE_LIB) >= os.path.getmtime(f) for f in sources):
         return TIMELINE_LIB
     objs = [os.path.join(earn_build.CSRC, s.replace(".hip", ".o")) for s in earn_build.SOURCES]
     if not all(os.path.exists(o) and os.path.getmtime(o) >= max(os.path.getmtime(f) for f in sources) for o in objs):
